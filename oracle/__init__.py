@@ -1,0 +1,198 @@
+"""Python face of the CPU oracle (`mohge_oracle.c`).
+
+TEST INFRASTRUCTURE ONLY: imported by `tests/`, by the smoke check and by the
+benchmark's cpu_baseline leg.  Nothing here touches the HIP library, and the HIP
+library never touches this.  All results are float64 numpy arrays computed by the
+plain C loops; this file only marshals arguments.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mohge_oracle.c")
+_LIB = os.path.join(_HERE, "libmohge_oracle.so")
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (OpenMP over independent tokens / pairs)."""
+    if force or not os.path.exists(_LIB):
+        cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared",
+               "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Cfg(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("n_groups", C.c_int32),
+                ("n_per_group", C.c_int32), ("d_ff", C.POINTER(C.c_int32)),
+                ("k_groups", C.c_int32), ("k_experts", C.c_int32),
+                ("select_mode", C.c_int32), ("aux_freq_norm", C.c_int32),
+                ("alpha_g", C.c_double), ("alpha_e", C.c_double), ("eps", C.c_double)]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        _lib = C.CDLL(_LIB)
+        _lib.oracle_num_threads.restype = C.c_int
+        for name in ("oracle_route", "oracle_permute", "oracle_expert_ffn", "oracle_combine",
+                     "oracle_aux_loss"):
+            getattr(_lib, name).restype = C.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def _cfg(w, aux_freq_norm: int = 1, alpha_g=None, alpha_e=None):
+    dff = (C.c_int32 * w.n_groups)(*w.d_ff)
+    c = _Cfg(w.T, w.d, w.n_groups, w.experts_per_group, dff, w.k_groups, w.k_experts,
+             w.select_mode, aux_freq_norm,
+             float(w.alpha_g if alpha_g is None else alpha_g),
+             float(w.alpha_e if alpha_e is None else alpha_e), float(w.eps))
+    c._keep = dff
+    return c
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"{what}: oracle rejected the configuration (code {rc})")
+
+
+def route(w, x, w_group, w_expert, bias=None):
+    """Section 3.2.  Returns dict(group_idx, expert_idx, gates, gs, es1, margin)."""
+    lib = _load()
+    c = _cfg(w)
+    x, w_group, w_expert = _f32(x), _f32(w_group), _f32(w_expert)
+    assert x.shape == (w.T, w.d) and w_group.shape == (w.n_groups, w.d)
+    assert w_expert.shape == (w.n_experts, w.d)
+    bias = None if bias is None else _f32(bias)
+    out = dict(
+        group_idx=np.empty((w.T, w.k_groups), np.int32),
+        expert_idx=np.empty((w.T, w.k_experts), np.int32),
+        gates=np.empty((w.T, w.k_experts), np.float64),
+        gs=np.empty((w.T, w.n_groups), np.float64),
+        es1=np.empty((w.T, w.n_experts), np.float64),
+        margin=np.empty((w.T,), np.float64),
+    )
+    _check(lib.oracle_route(C.byref(c), _p(x), _p(w_group), _p(w_expert), _p(bias),
+                            _p(out["group_idx"]), _p(out["expert_idx"]), _p(out["gates"]),
+                            _p(out["gs"]), _p(out["es1"]), _p(out["margin"])), "route")
+    return out
+
+
+def permute(w, expert_idx):
+    """Stable bucketing of the (token, slot) pairs by expert."""
+    lib = _load()
+    c = _cfg(w)
+    expert_idx = np.ascontiguousarray(expert_idx, dtype=np.int32)
+    assert expert_idx.shape == (w.T, w.k_experts)
+    P, Ne = w.n_pairs, w.n_experts
+    out = dict(counts=np.empty(Ne, np.int32), offsets=np.empty(Ne + 1, np.int32),
+               perm=np.empty(P, np.int32), inv_perm=np.empty(P, np.int32))
+    _check(lib.oracle_permute(C.byref(c), _p(expert_idx), _p(out["counts"]), _p(out["offsets"]),
+                              _p(out["perm"]), _p(out["inv_perm"])), "permute")
+    return out
+
+
+def _ptr_array(arrs: Sequence[np.ndarray]):
+    keep = [_f32(a) for a in arrs]
+    arr = (C.c_void_p * len(keep))(*[a.ctypes.data for a in keep])
+    return arr, keep
+
+
+def expert_ffn(w, x, w_gate: List[np.ndarray], w_up: List[np.ndarray], w_down: List[np.ndarray],
+               pair_token, pair_expert, want_h: bool = False):
+    """E_e(x_t) for the listed pairs.  Returns y_pairs [n, d] (and h [n, max F] if asked)."""
+    lib = _load()
+    c = _cfg(w)
+    x = _f32(x)
+    pg, kg = _ptr_array(w_gate)
+    pu, ku = _ptr_array(w_up)
+    pd, kd = _ptr_array(w_down)
+    for g in range(w.n_groups):
+        assert kg[g].shape == (w.experts_per_group, w.d_ff[g], w.d)
+        assert ku[g].shape == (w.experts_per_group, w.d_ff[g], w.d)
+        assert kd[g].shape == (w.experts_per_group, w.d, w.d_ff[g])
+    pair_token = np.ascontiguousarray(pair_token, dtype=np.int32)
+    pair_expert = np.ascontiguousarray(pair_expert, dtype=np.int32)
+    n = pair_token.shape[0]
+    assert pair_expert.shape == (n,)
+    assert n == 0 or (0 <= pair_token.min() and pair_token.max() < w.T)
+    assert n == 0 or (0 <= pair_expert.min() and pair_expert.max() < w.n_experts)
+    y = np.empty((n, w.d), np.float64)
+    fmax = max(w.d_ff)
+    h = np.zeros((n, fmax), np.float64) if want_h else None
+    _check(lib.oracle_expert_ffn(C.byref(c), _p(x), pg, pu, pd, C.c_int64(n), _p(pair_token),
+                                 _p(pair_expert), _p(y), _p(h), C.c_int64(fmax)), "expert_ffn")
+    return (y, h) if want_h else y
+
+
+def combine(w, y_pairs, gates):
+    """y[q] = sum_slot gates[q, slot] * y_pairs[q*K_e + slot] for the n_tok rows given."""
+    lib = _load()
+    c = _cfg(w)
+    gates = np.ascontiguousarray(gates, dtype=np.float64)
+    n_tok = gates.shape[0]
+    y_pairs = np.ascontiguousarray(y_pairs, dtype=np.float64)
+    assert y_pairs.shape == (n_tok * w.k_experts, w.d)
+    y = np.empty((n_tok, w.d), np.float64)
+    _check(lib.oracle_combine(C.byref(c), C.c_int64(n_tok), _p(y_pairs), _p(gates), _p(y)),
+           "combine")
+    return y
+
+
+def aux_loss(w, gs, es1, group_idx, expert_idx, aux_freq_norm: int = 1, alpha_g=None,
+             alpha_e=None):
+    """Sections 3.3 and 3.4.2.  Returns dict(L_G, L_E, f_G, p_G, f_E, p_E)."""
+    lib = _load()
+    c = _cfg(w, aux_freq_norm, alpha_g, alpha_e)
+    gs = np.ascontiguousarray(gs, dtype=np.float64)
+    es1 = np.ascontiguousarray(es1, dtype=np.float64)
+    group_idx = np.ascontiguousarray(group_idx, dtype=np.int32)
+    expert_idx = np.ascontiguousarray(expert_idx, dtype=np.int32)
+    assert gs.shape == (w.T, w.n_groups) and es1.shape == (w.T, w.n_experts)
+    losses = np.empty(2, np.float64)
+    Ng, Ne = w.n_groups, w.n_experts
+    stats = np.empty(2 * Ng + 2 * Ne, np.float64)
+    _check(lib.oracle_aux_loss(C.byref(c), _p(gs), _p(es1), _p(group_idx), _p(expert_idx),
+                               _p(losses), _p(stats)), "aux_loss")
+    return dict(L_G=float(losses[0]), L_E=float(losses[1]), f_G=stats[:Ng].copy(),
+                p_G=stats[Ng:2 * Ng].copy(), f_E=stats[2 * Ng:2 * Ng + Ne].copy(),
+                p_E=stats[2 * Ng + Ne:].copy())
+
+
+def layer(w, inp, tokens=None):
+    """Forward pass of the layer for all tokens, or for the listed token ids.
+
+    Returns dict with the routing of ALL tokens (`route`), the permutation, and
+    `y` [len(tokens), d] float64 for the requested tokens, plus `y_pairs`.
+    """
+    r = route(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias)
+    perm = permute(w, r["expert_idx"])
+    tok = np.arange(w.T, dtype=np.int32) if tokens is None else np.asarray(tokens, np.int32)
+    pair_token = np.repeat(tok, w.k_experts)
+    pair_expert = r["expert_idx"][tok].reshape(-1)
+    y_pairs = expert_ffn(w, inp.x.f32, [t.f32 for t in inp.w_gate], [t.f32 for t in inp.w_up],
+                         [t.f32 for t in inp.w_down], pair_token, pair_expert)
+    y = combine(w, y_pairs, r["gates"][tok])
+    return dict(route=r, permute=perm, tokens=tok, y_pairs=y_pairs, y=y)
