@@ -1,0 +1,164 @@
+"""Benchmark of the MoHGE layer forward pass on one MI355X.
+
+A step is one pass of the whole hot path (route -> permute -> expert FFN up/down ->
+combine) over one batch of seeded synthetic input already resident in HBM.  Prints ONE
+JSON line: whole-layer tokens/s, the roofline of the dominant kernel (live HIP-event
+timing), and the CPU oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_MFMA_BF16 = 2.5e15     # FLOP/s, dense bf16, MI355X
+PEAK_HBM = 8.0e12           # B/s
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (profiles/), scaled by the same counters on a copy kernel of known size; None until
+# measured for that workload.
+MEASURED_TRAFFIC = {}
+
+
+def event_time(fn, iters, torch):
+    """Average milliseconds per call of fn(), HIP events on the stream the kernels use."""
+    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    stop.record()
+    stop.synchronize()
+    return start.elapsed_time(stop) / iters
+
+
+def cpu_baseline(w, inp, budget_s=12.0):
+    """The oracle as it stands on a bounded sample: the first n tokens of the workload
+    through route -> permute -> experts -> combine, n sized to about `budget_s` seconds."""
+    import numpy as np
+    import oracle
+    from synth import LayerInputs, Tensor
+
+    def run(n):
+        sw = w.replace(T=n)
+        sub = LayerInputs(sw, Tensor(inp.x.f32[:n]), inp.w_group, inp.w_expert, inp.w_gate, inp.w_up,
+                          inp.w_down, inp.expert_logit_bias)
+        t0 = time.perf_counter()
+        oracle.layer(sw, sub)
+        return time.perf_counter() - t0
+
+    n = min(w.T, 16)
+    t = run(n)
+    per_tok = t / n
+    n2 = int(max(n, min(w.T, budget_s / max(per_tok, 1e-9))))
+    if n2 > n:
+        t = run(n2)
+        n = n2
+    return {"value": n / t, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"first {n} of {w.T} tokens through the whole layer (fp64 C oracle, OpenMP), {t:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="mid_prefill")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2604_23108_amd as M
+    from synth import WORKLOADS, generate
+    from gpu_harness import DeviceLayer
+
+    w = WORKLOADS[args.workload]
+    inp = generate(w)
+    dl = DeviceLayer(w, inp, training=False)
+    L, cfg, x = dl.layer, dl.cfg, dl.x
+
+    def step():
+        L.forward(x)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-call timing with HIP events (state from the last step is valid input for each call)
+    it = max(10, args.steps)
+    calls = {
+        "route": lambda: M.mohge_route(cfg, x, L.w_group, L.w_expert, L.bias, L.group_idx, L.expert_idx, L.gates, L.gs, L.es1),
+        "permute": lambda: M.mohge_permute(cfg, L.expert_idx, L.counts, L.offsets, L.perm, L.inv_perm, None, None, L.ws_permute),
+        "ffn_up": lambda: M.mohge_expert_ffn_up(cfg, x, L.perm, L.offsets, L.w13, L.ws_ffn),
+        "ffn_down": lambda: M.mohge_expert_ffn_down(cfg, L.ws_ffn, L.offsets, L.w2, L.y_perm),
+        "combine": lambda: M.mohge_combine(cfg, L.y_perm, L.inv_perm, L.gates, L.y),
+    }
+    call_ms = {k: event_time(f, it, torch) for k, f in calls.items()}
+
+    counts = L.counts.cpu().numpy().astype(np.int64)
+    F_e = np.repeat(np.asarray(w.d_ff, np.int64), w.experts_per_group)
+    elt = 2 if w.dtype == "bf16" else 4
+    flops_up = float((counts * 4 * w.d * F_e).sum())
+    flops_down = float((counts * 2 * w.d * F_e).sum())
+    touched = counts > 0
+    bytes_up = float((touched * 2 * w.d * F_e * elt).sum() + w.T * w.d * elt + (counts * F_e * elt).sum())
+    bytes_down = float((touched * w.d * F_e * elt).sum() + (counts * F_e * elt).sum() + w.n_pairs * w.d * elt)
+    P = w.n_pairs
+    bytes_route = float(w.T * w.d * elt + (w.n_experts + w.n_groups) * w.d * 4 + w.T * (w.k_groups * 4 + w.k_experts * 8))
+    bytes_combine = float((P + w.T) * w.d * elt + P * 8)
+
+    decode = w.T <= 32
+    if decode:
+        ach = bytes_up / (call_ms["ffn_up"] * 1e-3)
+        roof = {"kernel": "ffn_skinny_kernel<up> (mohge_expert_ffn_up)", "bound": "hbm",
+                "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": ach / PEAK_HBM,
+                "traffic": MEASURED_TRAFFIC.get(args.workload)}
+    else:
+        ach = flops_up / (call_ms["ffn_up"] * 1e-3)
+        roof = {"kernel": "ffn_tile_kernel<up> (mohge_expert_ffn_up)", "bound": "mfma",
+                "achieved": ach / 1e12, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
+                "frac": ach / PEAK_MFMA_BF16, "traffic": MEASURED_TRAFFIC.get(args.workload)}
+    t_ffn = (call_ms["ffn_up"] + call_ms["ffn_down"]) * 1e-3
+    parts = {
+        "call_ms": {k: round(v, 5) for k, v in call_ms.items()},
+        "ffn_up_down_tflops": (flops_up + flops_down) / t_ffn / 1e12,
+        "ffn_up_down_frac_mfma": (flops_up + flops_down) / t_ffn / PEAK_MFMA_BF16,
+        "ffn_up_down_gbs": (bytes_up + bytes_down) / t_ffn / 1e9,
+        "ffn_up_down_frac_hbm": (bytes_up + bytes_down) / t_ffn / PEAK_HBM,
+        "route_gbs": bytes_route / (call_ms["route"] * 1e-3) / 1e9,
+        "route_tflops_f32": 2.0 * w.T * w.d * (w.n_experts + w.n_groups) / (call_ms["route"] * 1e-3) / 1e12,
+        "combine_gbs": bytes_combine / (call_ms["combine"] * 1e-3) / 1e9,
+        "count_min": int(counts.min()), "count_max": int(counts.max()),
+    }
+    out = {
+        "metric": "MoHGE layer tokens/sec + expert-FFN % bf16 MFMA peak (decode: % HBM BW)",
+        "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "T": w.T, "d": w.d, "groups_x_experts": f"{w.n_groups}x{w.experts_per_group}",
+                   "d_ff": list(w.d_ff), "k_groups": w.k_groups, "k_experts": w.k_experts,
+                   "select_mode": "per_group" if w.select_mode == 1 else "global", "seed": w.seed},
+        "roofline": roof,
+        "parts": parts,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,180 @@
+/*
+ * mohge.h — C boundary of the MI355X (gfx950) implementation of one MoHGE layer
+ * (Mixture of Heterogeneous Grouped Experts): forward pass on one GPU's share of
+ * the experts, plus the two auxiliary losses of the training variant.
+ *
+ * Notation follows the paper (section 3):
+ *   T    tokens in the call,            d    hidden size,
+ *   N_g  expert groups,                 N    experts per group (held by this GPU),
+ *   N_e = N_g*N experts, expert e = g*N + i (group-major, 0-based),
+ *   F_g  SwiGLU intermediate width of every expert of group g (section 3.1),
+ *   K_g  groups kept per token (3.2.1), K_e experts kept per token (3.2.2),
+ *   P = T*K_e (token, slot) pairs, pair p = t*K_e + slot.
+ *
+ * Conventions for every call
+ *   - Returns MOHGE_OK (0) or a negative error code; mohge_last_error() gives the
+ *     message of the last failing call on the calling thread.
+ *   - "DEVICE" pointers are device memory owned by the caller; the library never
+ *     allocates, frees or keeps them.  "HOST" pointers are read during the call only.
+ *   - DEVICE pointers must be 16-byte aligned (MOHGE_EALIGN otherwise).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls
+ *     only enqueue kernels: no host synchronisation, no device-to-host copy.  The
+ *     tile schedules of the expert networks are derived on the device from `offsets`.
+ *   - Activations and expert weights are fp32 or bf16 as `dtype` says; router
+ *     weights, gates, scores and losses are always fp32; indices are int32.
+ *   - All matrices are row-major with the innermost (reduction) dimension contiguous.
+ *   - Limits: 1 <= N_g <= 16, N_e <= 256, d % 64 == 0, F_g % 64 == 0, T*K_e < 2^31.
+ *     With the All-size Group-decoupling Allocation (section 3.4.1) a GPU holds the
+ *     same expert indices i of every group, so its share is itself an N_g x N layer
+ *     and `experts_per_group` is the local count.
+ */
+#ifndef MOHGE_H
+#define MOHGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  MOHGE_OK = 0,
+  MOHGE_EINVAL = -1,      /* configuration outside the documented limits            */
+  MOHGE_ENULL = -2,       /* a required pointer is NULL                             */
+  MOHGE_EALIGN = -3,      /* a device pointer is not 16-byte aligned                */
+  MOHGE_EWORKSPACE = -4,  /* workspace smaller than mohge_workspace_size()          */
+  MOHGE_EHIP = -5         /* the HIP runtime reported an error at launch            */
+};
+
+enum { MOHGE_SELECT_GLOBAL = 0, MOHGE_SELECT_PER_GROUP = 1 };
+enum { MOHGE_F32 = 0, MOHGE_BF16 = 1 };
+enum { MOHGE_CALL_PERMUTE = 0, MOHGE_CALL_EXPERT_FFN = 1, MOHGE_CALL_AUX_LOSS = 2 };
+
+typedef struct mohge_config {
+  int32_t T;                  /* tokens                                              */
+  int32_t d;                  /* hidden size                                         */
+  int32_t n_groups;           /* N_g                                                 */
+  int32_t experts_per_group;  /* N                                                   */
+  const int32_t* d_ff;        /* HOST [N_g]: F_g                                     */
+  int32_t k_groups;           /* K_g, 1..N_g                                         */
+  int32_t k_experts;          /* K_e, 1..K_g*N                                       */
+  int32_t select_mode;        /* MOHGE_SELECT_GLOBAL: K_e best ES'' over all kept
+                                 groups (section 3.2.2, step 2);
+                                 MOHGE_SELECT_PER_GROUP: K_e/K_g best in each kept
+                                 group (K_e % K_g == 0, K_e/K_g <= N)               */
+  int32_t dtype;              /* MOHGE_F32 or MOHGE_BF16: x, expert weights, y       */
+  float alpha_g;              /* coefficient of L_G                                  */
+  float alpha_e;              /* coefficient of L_E                                  */
+  float eps;                  /* epsilon in the denominator of S^E (section 3.4.2)   */
+  int32_t aux_freq_norm;      /* 1: routing frequencies f carry 1/T; 0: as printed   */
+} mohge_config;
+
+/*
+ * Two-level router (section 3.2).
+ *   GS_{g,t}  = sigmoid(x_t . w_group[g])                          (3.2.1)
+ *   kept groups = the K_g largest (taken on the logit; ties to the lowest g)
+ *   ES'_{g,i,t} = softmax_i(x_t . w_expert[g*N+i] + bias) for kept g, else 0   (3.2.2 step 1)
+ *   ES'' = ES' * GS; kept experts per select_mode (ties to the lowest e)       (step 2)
+ *   gates = kept ES'' / sum of kept ES''                                        (step 3)
+ * In:  x DEVICE [T,d] (dtype), w_group DEVICE [N_g,d] f32, w_expert DEVICE [N_e,d]
+ *      f32, expert_logit_bias DEVICE [N_e] f32 or NULL.
+ * Out: group_idx DEVICE [T,K_g] and expert_idx DEVICE [T,K_e], ascending ids;
+ *      gates DEVICE [T,K_e] aligned with expert_idx; gs_out DEVICE [T,N_g] (GS) and
+ *      es1_out DEVICE [T,N_e] (ES', zero outside kept groups), each may be NULL.
+ * Logits are accumulated in fp32 (fp64 across 64-wide slices of d).
+ */
+int mohge_route(const mohge_config* cfg, const void* x, const float* w_group,
+                const float* w_expert, const float* expert_logit_bias, int32_t* group_idx,
+                int32_t* expert_idx, float* gates, float* gs_out, float* es1_out, void* stream);
+
+/*
+ * Token permutation: buckets the P pairs by expert in stable order (expert id, then
+ * pair id).  The paper implies dispatch without describing it; this is a stable
+ * counting sort, deterministic (bit-identical from run to run).
+ * In:  expert_idx DEVICE [T,K_e], values in [0, N_e).
+ * Out: counts DEVICE [N_e]; offsets DEVICE [N_e+1] (exclusive prefix sum, last = P);
+ *      perm DEVICE [P], perm[r] = p; inv_perm DEVICE [P], inv_perm[p] = r.
+ *      If x_perm != NULL (then x must be given): x_perm DEVICE [P,d] (dtype),
+ *      x_perm[r,:] = x[perm[r] / K_e, :].
+ * workspace DEVICE, at least mohge_workspace_size(cfg, MOHGE_CALL_PERMUTE) bytes.
+ */
+int mohge_permute(const mohge_config* cfg, const int32_t* expert_idx, int32_t* counts,
+                  int32_t* offsets, int32_t* perm, int32_t* inv_perm, const void* x,
+                  void* x_perm, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Expert networks on the bucketed tokens (section 3.1: every expert of group g has
+ * width F_g; the form is a SwiGLU feed-forward network without bias):
+ *   for sorted position r in [offsets[e], offsets[e+1]), expert e = g*N + i:
+ *     a = W_gate x_r, b = W_up x_r, h = a*sigmoid(a)*b, y_perm[r,:] = W_down h.
+ * In:  x DEVICE (dtype): if perm != NULL, [T,d] and row r reads x[perm[r]/K_e,:]
+ *      (gather fused into the operand load); if perm == NULL, [P,d] already permuted.
+ *      offsets DEVICE [N_e+1] as written by mohge_permute.
+ *      w13 HOST array [N_g] of DEVICE pointers; w13[g] is [N, 2*F_g, d]: for expert i
+ *      rows 0..F_g-1 are W_gate, rows F_g..2F_g-1 are W_up.
+ *      w2 HOST array [N_g] of DEVICE pointers; w2[g] is [N, d, F_g] (W_down).
+ * Out: y_perm DEVICE [P,d] (dtype).
+ * workspace DEVICE, at least mohge_workspace_size(cfg, MOHGE_CALL_EXPERT_FFN) bytes;
+ * it holds h between the two projections.
+ * bf16: products on the matrix cores with fp32 accumulation; h and y_perm are
+ * rounded to bf16 once each.  fp32: plain fp32 arithmetic.
+ */
+int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm,
+                     const int32_t* offsets, const void* const* w13, const void* const* w2,
+                     void* y_perm, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The two halves of mohge_expert_ffn as separate calls (same arguments, same kernels):
+ * mohge_expert_ffn_up writes h = SiLU(W_gate x) * (W_up x) for every sorted position
+ * into `h` (DEVICE, mohge_workspace_size(cfg, MOHGE_CALL_EXPERT_FFN) bytes, row r at
+ * element offset r * max_g F_g); mohge_expert_ffn_down reads it and writes y_perm.
+ * mohge_expert_ffn(…, workspace) is exactly up(…, workspace) followed by down(workspace, …).
+ */
+int mohge_expert_ffn_up(const mohge_config* cfg, const void* x, const int32_t* perm,
+                        const int32_t* offsets, const void* const* w13, void* h, size_t h_bytes,
+                        void* stream);
+int mohge_expert_ffn_down(const mohge_config* cfg, const void* h, const int32_t* offsets,
+                          const void* const* w2, void* y_perm, void* stream);
+
+/*
+ * Gated un-permute and combine (appendix, background: y = sum_i G_i(x) E_i(x)):
+ *   y[t,:] = sum_{slot<K_e} gates[t,slot] * y_perm[inv_perm[t*K_e+slot], :]
+ * accumulated in fp32 in slot order.
+ * In:  y_perm DEVICE [P,d] (dtype), inv_perm DEVICE [P], gates DEVICE [T,K_e].
+ * Out: y DEVICE [T,d] (dtype).
+ */
+int mohge_combine(const mohge_config* cfg, const void* y_perm, const int32_t* inv_perm,
+                  const float* gates, void* y, void* stream);
+
+/*
+ * Group-Wise Auxiliary Loss L_G (section 3.3) and Intra-Group Experts Auxiliary
+ * Loss L_E (section 3.4.2) over the T tokens of the call:
+ *   f^G_g = (N_g/K_g) * [1/T] * #{t : g kept},  p^G_g = (1/T) sum_t GS_{g,t}/sum_j GS_{j,t}
+ *   L_G = alpha_g * sum_g (F_g / max F) f^G_g p^G_g
+ *   f^E_e = (N/K_e) * [1/T] * #{t : e kept},
+ *   p^E_e = (1/T) sum_t ES'_{e,t} / (sum_{j in group} ES'_{j,t} + eps)
+ *   L_E = alpha_e * sum_e f^E_e p^E_e
+ * ([1/T] present when aux_freq_norm != 0.)
+ * In:  gs DEVICE [T,N_g], es1 DEVICE [T,N_e] (as written by mohge_route),
+ *      group_idx DEVICE [T,K_g], expert_idx DEVICE [T,K_e].
+ * Out: losses DEVICE [2] = (L_G, L_E); stats DEVICE [2*N_g + 2*N_e] = f^G, p^G, f^E,
+ *      p^E, or NULL.
+ * workspace DEVICE, at least mohge_workspace_size(cfg, MOHGE_CALL_AUX_LOSS) bytes.
+ * Sums over tokens are taken in fp64 in a fixed order (deterministic).
+ */
+int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
+                   const int32_t* group_idx, const int32_t* expert_idx, float* losses,
+                   float* stats, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of DEVICE workspace that call `which_call` (MOHGE_CALL_*) needs for `cfg`;
+ * 0 for an invalid configuration or call id. */
+size_t mohge_workspace_size(const mohge_config* cfg, int which_call);
+
+/* Message of the last error on this thread ("" if none); valid until the next call. */
+const char* mohge_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOHGE_H */

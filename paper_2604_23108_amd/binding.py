@@ -1,0 +1,235 @@
+"""ctypes binding of libmohge.so: argument marshalling only.
+
+Function names and argument order are those of `include/mohge.h`.  Tensors must live on
+the GPU; pointers are taken with `data_ptr()` and the current torch stream is passed as
+the HIP stream.  PyTorch is used for device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libmohge.so")
+
+SELECT_GLOBAL, SELECT_PER_GROUP = 0, 1
+F32, BF16 = 0, 1
+CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
+
+EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
+           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_workspace_size", "mohge_last_error"]
+
+
+class MohgeError(RuntimeError):
+    pass
+
+
+class _CConfig(C.Structure):
+    _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("n_groups", C.c_int32),
+                ("experts_per_group", C.c_int32), ("d_ff", C.POINTER(C.c_int32)),
+                ("k_groups", C.c_int32), ("k_experts", C.c_int32), ("select_mode", C.c_int32),
+                ("dtype", C.c_int32), ("alpha_g", C.c_float), ("alpha_e", C.c_float),
+                ("eps", C.c_float), ("aux_freq_norm", C.c_int32)]
+
+
+_lib = None
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise MohgeError(f"{_LIB_PATH} is missing: build it with "
+                             "`python -m paper_2604_23108_amd.build` (there is no fallback path)")
+        l = C.CDLL(_LIB_PATH)
+        for n in EXPORTS[:7]:
+            getattr(l, n).restype = C.c_int
+        l.mohge_workspace_size.restype = C.c_size_t
+        l.mohge_last_error.restype = C.c_char_p
+        _lib = l
+    return _lib
+
+
+class Config:
+    """Python mirror of `mohge_config`."""
+
+    def __init__(self, T: int, d: int, n_groups: int, experts_per_group: int, d_ff: Sequence[int],
+                 k_groups: int, k_experts: int, select_mode: int = SELECT_PER_GROUP,
+                 dtype: int = BF16, alpha_g: float = 1e-4, alpha_e: float = 2.5e-3,
+                 eps: float = 1e-9, aux_freq_norm: int = 1):
+        self.T, self.d, self.n_groups, self.experts_per_group = T, d, n_groups, experts_per_group
+        self.d_ff = tuple(int(f) for f in d_ff)
+        self.k_groups, self.k_experts, self.select_mode, self.dtype = k_groups, k_experts, select_mode, dtype
+        self.alpha_g, self.alpha_e, self.eps, self.aux_freq_norm = alpha_g, alpha_e, eps, aux_freq_norm
+        self._dff = (C.c_int32 * max(1, len(self.d_ff)))(*self.d_ff)
+        self._c = _CConfig(T, d, n_groups, experts_per_group, self._dff, k_groups, k_experts,
+                           select_mode, dtype, alpha_g, alpha_e, eps, aux_freq_norm)
+
+    @classmethod
+    def from_workload(cls, w, **kw) -> "Config":
+        args = dict(T=w.T, d=w.d, n_groups=w.n_groups, experts_per_group=w.experts_per_group,
+                    d_ff=w.d_ff, k_groups=w.k_groups, k_experts=w.k_experts,
+                    select_mode=w.select_mode, dtype=BF16 if w.dtype == "bf16" else F32,
+                    alpha_g=w.alpha_g, alpha_e=w.alpha_e, eps=w.eps)
+        args.update(kw)
+        return cls(**args)
+
+    @property
+    def n_experts(self) -> int:
+        return self.n_groups * self.experts_per_group
+
+    @property
+    def n_pairs(self) -> int:
+        return self.T * self.k_experts
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == BF16 else torch.float32
+
+    def ref(self):
+        return C.byref(self._c)
+
+
+def mohge_last_error() -> str:
+    return lib().mohge_last_error().decode()
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise MohgeError(f"{what} failed with code {rc}: {mohge_last_error()}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return C.c_void_p(0)
+    if not t.is_cuda:
+        raise MohgeError("tensors handed to the library must be on the GPU")
+    if not t.is_contiguous():
+        raise MohgeError("tensors handed to the library must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def mohge_workspace_size(cfg: Config, which_call: int) -> int:
+    return int(lib().mohge_workspace_size(cfg.ref(), C.c_int(which_call)))
+
+
+def mohge_route(cfg, x, w_group, w_expert, expert_logit_bias, group_idx, expert_idx, gates,
+                gs_out=None, es1_out=None):
+    _check(lib().mohge_route(cfg.ref(), _ptr(x), _ptr(w_group), _ptr(w_expert),
+                             _ptr(expert_logit_bias), _ptr(group_idx), _ptr(expert_idx),
+                             _ptr(gates), _ptr(gs_out), _ptr(es1_out), _stream()), "mohge_route")
+
+
+def mohge_permute(cfg, expert_idx, counts, offsets, perm, inv_perm, x, x_perm, workspace):
+    _check(lib().mohge_permute(cfg.ref(), _ptr(expert_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
+                               _ptr(inv_perm), _ptr(x), _ptr(x_perm), _ptr(workspace),
+                               C.c_size_t(workspace.numel() * workspace.element_size()), _stream()),
+           "mohge_permute")
+
+
+def _ptr_table(ts: Sequence[torch.Tensor]):
+    return (C.c_void_p * len(ts))(*[t.data_ptr() for t in ts])
+
+
+def mohge_expert_ffn(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], w2: Sequence[torch.Tensor],
+                     y_perm, workspace):
+    for t in list(w13) + list(w2):
+        _ptr(t)
+    _check(lib().mohge_expert_ffn(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13),
+                                  _ptr_table(w2), _ptr(y_perm), _ptr(workspace),
+                                  C.c_size_t(workspace.numel() * workspace.element_size()),
+                                  _stream()), "mohge_expert_ffn")
+
+
+def mohge_expert_ffn_up(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], h):
+    for t in w13:
+        _ptr(t)
+    _check(lib().mohge_expert_ffn_up(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13),
+                                     _ptr(h), C.c_size_t(h.numel() * h.element_size()), _stream()),
+           "mohge_expert_ffn_up")
+
+
+def mohge_expert_ffn_down(cfg, h, offsets, w2: Sequence[torch.Tensor], y_perm):
+    for t in w2:
+        _ptr(t)
+    _check(lib().mohge_expert_ffn_down(cfg.ref(), _ptr(h), _ptr(offsets), _ptr_table(w2),
+                                       _ptr(y_perm), _stream()), "mohge_expert_ffn_down")
+
+
+def mohge_combine(cfg, y_perm, inv_perm, gates, y):
+    _check(lib().mohge_combine(cfg.ref(), _ptr(y_perm), _ptr(inv_perm), _ptr(gates), _ptr(y),
+                               _stream()), "mohge_combine")
+
+
+def mohge_aux_loss(cfg, gs, es1, group_idx, expert_idx, losses, stats, workspace):
+    _check(lib().mohge_aux_loss(cfg.ref(), _ptr(gs), _ptr(es1), _ptr(group_idx), _ptr(expert_idx),
+                                _ptr(losses), _ptr(stats), _ptr(workspace),
+                                C.c_size_t(workspace.numel() * workspace.element_size()),
+                                _stream()), "mohge_aux_loss")
+
+
+def pack_w13(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor:
+    """Layout helper: [N,F,d] gate and up matrices -> the [N,2F,d] block the library reads
+    (gate rows first).  Pure data movement."""
+    return torch.cat([w_gate, w_up], dim=1).contiguous()
+
+
+class MoHGELayer:
+    """Holds the device buffers of one layer call and runs the five C calls in order.
+
+    All buffers are allocated once here (by torch); `forward()` allocates nothing and only
+    enqueues kernels on the current stream.
+    """
+
+    def __init__(self, cfg: Config, w_group, w_expert, w13: List[torch.Tensor],
+                 w2: List[torch.Tensor], expert_logit_bias=None, training: bool = False,
+                 device="cuda"):
+        self.cfg = cfg
+        self.w_group, self.w_expert, self.w13, self.w2 = w_group, w_expert, list(w13), list(w2)
+        self.bias = expert_logit_bias
+        self.training = training
+        T, P, Ne, Ng = cfg.T, cfg.n_pairs, cfg.n_experts, cfg.n_groups
+        i32 = dict(dtype=torch.int32, device=device)
+        f32 = dict(dtype=torch.float32, device=device)
+        self.group_idx = torch.empty((T, cfg.k_groups), **i32)
+        self.expert_idx = torch.empty((T, cfg.k_experts), **i32)
+        self.gates = torch.empty((T, cfg.k_experts), **f32)
+        self.gs = torch.empty((T, Ng), **f32) if training else None
+        self.es1 = torch.empty((T, Ne), **f32) if training else None
+        self.counts = torch.empty(Ne, **i32)
+        self.offsets = torch.empty(Ne + 1, **i32)
+        self.perm = torch.empty(max(P, 1), **i32)
+        self.inv_perm = torch.empty(max(P, 1), **i32)
+        self.y_perm = torch.empty((max(P, 1), cfg.d), dtype=cfg.torch_dtype, device=device)
+        self.y = torch.empty((T, cfg.d), dtype=cfg.torch_dtype, device=device)
+        u8 = dict(dtype=torch.uint8, device=device)
+        self.ws_permute = torch.empty(max(16, mohge_workspace_size(cfg, CALL_PERMUTE)), **u8)
+        self.ws_ffn = torch.empty(max(16, mohge_workspace_size(cfg, CALL_EXPERT_FFN)), **u8)
+        self.losses = torch.empty(2, **f32) if training else None
+        self.stats = torch.empty(2 * Ng + 2 * Ne, **f32) if training else None
+        self.ws_aux = torch.empty(max(16, mohge_workspace_size(cfg, CALL_AUX_LOSS)), **u8) if training else None
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        c = self.cfg
+        mohge_route(c, x, self.w_group, self.w_expert, self.bias, self.group_idx, self.expert_idx,
+                    self.gates, self.gs, self.es1)
+        mohge_permute(c, self.expert_idx, self.counts, self.offsets, self.perm, self.inv_perm,
+                      None, None, self.ws_permute)
+        mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws_ffn)
+        mohge_combine(c, self.y_perm, self.inv_perm, self.gates, self.y)
+        if self.training:
+            mohge_aux_loss(c, self.gs, self.es1, self.group_idx, self.expert_idx, self.losses,
+                           self.stats, self.ws_aux)
+        return self.y

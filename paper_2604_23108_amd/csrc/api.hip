@@ -1,0 +1,223 @@
+// Host side of the C boundary: argument checking, error strings, dispatch to launchers.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace mohge {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+
+int check_config(const mohge_config* c, LayerDesc* L) {
+  if (!c) { set_error("cfg is NULL"); return MOHGE_ENULL; }
+  if (!c->d_ff) { set_error("cfg->d_ff is NULL"); return MOHGE_ENULL; }
+  if (c->T < 0) { set_error("T = %d is negative", c->T); return MOHGE_EINVAL; }
+  if (c->d < 64 || c->d % 64) { set_error("d = %d must be a positive multiple of 64", c->d); return MOHGE_EINVAL; }
+  if (c->n_groups < 1 || c->n_groups > kMaxGroups) {
+    set_error("n_groups = %d outside 1..%d", c->n_groups, kMaxGroups); return MOHGE_EINVAL; }
+  if (c->experts_per_group < 1 || (int64_t)c->experts_per_group * c->n_groups > kMaxExperts) {
+    set_error("n_groups*experts_per_group = %lld outside 1..%d",
+              (long long)c->experts_per_group * c->n_groups, kMaxExperts); return MOHGE_EINVAL; }
+  if (c->k_groups < 1 || c->k_groups > c->n_groups) {
+    set_error("k_groups = %d outside 1..n_groups", c->k_groups); return MOHGE_EINVAL; }
+  if (c->k_experts < 1 || c->k_experts > c->k_groups * c->experts_per_group) {
+    set_error("k_experts = %d outside 1..k_groups*experts_per_group", c->k_experts); return MOHGE_EINVAL; }
+  if (c->select_mode == MOHGE_SELECT_PER_GROUP) {
+    if (c->k_experts % c->k_groups || c->k_experts / c->k_groups > c->experts_per_group) {
+      set_error("per-group selection needs k_experts %% k_groups == 0 and k_experts/k_groups <= experts_per_group");
+      return MOHGE_EINVAL; }
+  } else if (c->select_mode != MOHGE_SELECT_GLOBAL) {
+    set_error("select_mode = %d unknown", c->select_mode); return MOHGE_EINVAL; }
+  if (c->dtype != MOHGE_F32 && c->dtype != MOHGE_BF16) {
+    set_error("dtype = %d unknown", c->dtype); return MOHGE_EINVAL; }
+  if ((int64_t)c->T * c->k_experts >= (int64_t)1 << 31) {
+    set_error("T*k_experts does not fit int32"); return MOHGE_EINVAL; }
+  int fmax = 0;
+  for (int g = 0; g < c->n_groups; ++g) {
+    int F = c->d_ff[g];
+    if (F < 64 || F % 64) { set_error("d_ff[%d] = %d must be a positive multiple of 64", g, F); return MOHGE_EINVAL; }
+    if (F > fmax) fmax = F;
+  }
+  if (L) {
+    memset(L, 0, sizeof(*L));
+    L->T = c->T; L->d = c->d; L->Ng = c->n_groups; L->N = c->experts_per_group;
+    L->Ne = L->Ng * L->N; L->Kg = c->k_groups; L->Ke = c->k_experts; L->P = c->T * c->k_experts;
+    L->select_mode = c->select_mode; L->Fmax = fmax;
+    for (int g = 0; g < L->Ng; ++g) L->F[g] = c->d_ff[g];
+  }
+  return MOHGE_OK;
+}
+
+static int need(const void* p, const char* name, bool required = true) {
+  if (!p) {
+    if (!required) return MOHGE_OK;
+    set_error("%s is NULL", name);
+    return MOHGE_ENULL;
+  }
+  if (((uintptr_t)p) & 15) { set_error("%s is not 16-byte aligned", name); return MOHGE_EALIGN; }
+  return MOHGE_OK;
+}
+
+static int hip_rc(hipError_t e, const char* what) {
+  if (e == hipSuccess) return MOHGE_OK;
+  set_error("%s: %s", what, hipGetErrorString(e));
+  return MOHGE_EHIP;
+}
+
+}  // namespace mohge
+
+using namespace mohge;
+
+#define NEED(p) do { int rc_ = need((p), #p); if (rc_) return rc_; } while (0)
+#define OPT(p) do { int rc_ = need((p), #p, false); if (rc_) return rc_; } while (0)
+
+extern "C" {
+
+const char* mohge_last_error(void) { return g_err; }
+
+size_t mohge_workspace_size(const mohge_config* cfg, int which_call) {
+  LayerDesc L;
+  if (check_config(cfg, &L)) return 0;
+  switch (which_call) {
+    case MOHGE_CALL_PERMUTE: return permute_workspace_bytes(L);
+    case MOHGE_CALL_EXPERT_FFN: return ffn_workspace_bytes(L, cfg->dtype);
+    case MOHGE_CALL_AUX_LOSS: return aux_workspace_bytes(L);
+    default: set_error("unknown call id %d", which_call); return 0;
+  }
+}
+
+int mohge_route(const mohge_config* cfg, const void* x, const float* w_group,
+                const float* w_expert, const float* expert_logit_bias, int32_t* group_idx,
+                int32_t* expert_idx, float* gates, float* gs_out, float* es1_out, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(x); NEED(w_group); NEED(w_expert); OPT(expert_logit_bias);
+  NEED(group_idx); NEED(expert_idx); NEED(gates); OPT(gs_out); OPT(es1_out);
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_route(L, cfg->dtype, x, w_group, w_expert, expert_logit_bias, group_idx,
+                             expert_idx, gates, gs_out, es1_out, (hipStream_t)stream),
+                "mohge_route");
+}
+
+int mohge_permute(const mohge_config* cfg, const int32_t* expert_idx, int32_t* counts,
+                  int32_t* offsets, int32_t* perm, int32_t* inv_perm, const void* x,
+                  void* x_perm, void* workspace, size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(expert_idx); NEED(counts); NEED(offsets); NEED(perm); NEED(inv_perm);
+  OPT(x); OPT(x_perm); NEED(workspace);
+  if (x_perm && !x) { set_error("x_perm requested but x is NULL"); return MOHGE_ENULL; }
+  if (workspace_bytes < permute_workspace_bytes(L)) {
+    set_error("permute workspace: %zu bytes given, %zu needed", workspace_bytes,
+              permute_workspace_bytes(L));
+    return MOHGE_EWORKSPACE;
+  }
+  return hip_rc(launch_permute(L, cfg->dtype, expert_idx, counts, offsets, perm, inv_perm, x,
+                               x_perm, workspace, (hipStream_t)stream),
+                "mohge_permute");
+}
+
+int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm,
+                     const int32_t* offsets, const void* const* w13, const void* const* w2,
+                     void* y_perm, void* workspace, size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(x); OPT(perm); NEED(offsets); NEED(y_perm); NEED(workspace);
+  if (!w13 || !w2) { set_error("w13 / w2 pointer table is NULL"); return MOHGE_ENULL; }
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
+  for (int g = 0; g < L.Ng; ++g) {
+    NEED(w13[g]); NEED(w2[g]);
+    W.w13[g] = w13[g];
+    W.w2[g] = w2[g];
+  }
+  if (workspace_bytes < ffn_workspace_bytes(L, cfg->dtype)) {
+    set_error("expert_ffn workspace: %zu bytes given, %zu needed", workspace_bytes,
+              ffn_workspace_bytes(L, cfg->dtype));
+    return MOHGE_EWORKSPACE;
+  }
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_expert_ffn(L, cfg->dtype, x, perm, offsets, W, y_perm, workspace,
+                                  (hipStream_t)stream, 3),
+                "mohge_expert_ffn");
+}
+
+int mohge_expert_ffn_up(const mohge_config* cfg, const void* x, const int32_t* perm,
+                        const int32_t* offsets, const void* const* w13, void* h, size_t h_bytes,
+                        void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(x); OPT(perm); NEED(offsets); NEED(h);
+  if (!w13) { set_error("w13 pointer table is NULL"); return MOHGE_ENULL; }
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
+  for (int g = 0; g < L.Ng; ++g) { NEED(w13[g]); W.w13[g] = w13[g]; }
+  if (h_bytes < ffn_workspace_bytes(L, cfg->dtype)) {
+    set_error("expert_ffn_up: h has %zu bytes, %zu needed", h_bytes, ffn_workspace_bytes(L, cfg->dtype));
+    return MOHGE_EWORKSPACE;
+  }
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_expert_ffn(L, cfg->dtype, x, perm, offsets, W, nullptr, h,
+                                  (hipStream_t)stream, 1),
+                "mohge_expert_ffn_up");
+}
+
+int mohge_expert_ffn_down(const mohge_config* cfg, const void* h, const int32_t* offsets,
+                          const void* const* w2, void* y_perm, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(h); NEED(offsets); NEED(y_perm);
+  if (!w2) { set_error("w2 pointer table is NULL"); return MOHGE_ENULL; }
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
+  for (int g = 0; g < L.Ng; ++g) { NEED(w2[g]); W.w2[g] = w2[g]; }
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_expert_ffn(L, cfg->dtype, nullptr, nullptr, offsets, W, y_perm,
+                                  const_cast<void*>(h), (hipStream_t)stream, 2),
+                "mohge_expert_ffn_down");
+}
+
+int mohge_combine(const mohge_config* cfg, const void* y_perm, const int32_t* inv_perm,
+                  const float* gates, void* y, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(y_perm); NEED(inv_perm); NEED(gates); NEED(y);
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_combine(L, cfg->dtype, y_perm, inv_perm, gates, y, (hipStream_t)stream),
+                "mohge_combine");
+}
+
+int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
+                   const int32_t* group_idx, const int32_t* expert_idx, float* losses,
+                   float* stats, void* workspace, size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(gs); NEED(es1); NEED(group_idx); NEED(expert_idx); NEED(losses); OPT(stats);
+  NEED(workspace);
+  if (L.T < 1) { set_error("aux_loss needs T >= 1"); return MOHGE_EINVAL; }
+  if (workspace_bytes < aux_workspace_bytes(L)) {
+    set_error("aux_loss workspace: %zu bytes given, %zu needed", workspace_bytes,
+              aux_workspace_bytes(L));
+    return MOHGE_EWORKSPACE;
+  }
+  return hip_rc(launch_aux_loss(L, *cfg, gs, es1, group_idx, expert_idx, losses, stats, workspace,
+                                (hipStream_t)stream),
+                "mohge_aux_loss");
+}
+
+}  // extern "C"

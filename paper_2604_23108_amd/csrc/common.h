@@ -1,0 +1,64 @@
+// Internal declarations shared by the host entry points and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "mohge.h"
+
+namespace mohge {
+
+constexpr int kMaxGroups = 16;
+constexpr int kMaxExperts = 256;
+constexpr int kWave = 64;
+
+// Layer description passed by value to kernels (everything a kernel needs to map an
+// expert id to its group, width and weight block).
+struct LayerDesc {
+  int32_t T, d, Ng, N, Ne, Kg, Ke, P;
+  int32_t select_mode;
+  int32_t F[kMaxGroups];          // F_g
+  int32_t Fmax;
+};
+
+struct GroupPtrs {
+  const void* w13[kMaxGroups];    // [N, 2F_g, d]
+  const void* w2[kMaxGroups];     // [N, d, F_g]
+};
+
+void set_error(const char* fmt, ...);
+int check_config(const mohge_config* cfg, LayerDesc* out);
+
+// bf16 <-> fp32 on the device, bit level (round to nearest even on the way down)
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) {
+  return __uint_as_float(((uint32_t)b) << 16);
+}
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// launchers implemented in the kernel files; each returns a hipError_t from the launch
+hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const float* w_group,
+                        const float* w_expert, const float* bias, int32_t* group_idx,
+                        int32_t* expert_idx, float* gates, float* gs_out, float* es1_out,
+                        hipStream_t s);
+size_t permute_workspace_bytes(const LayerDesc& L);
+hipError_t launch_permute(const LayerDesc& L, int dtype, const int32_t* expert_idx,
+                          int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                          const void* x, void* x_perm, void* ws, hipStream_t s);
+size_t ffn_workspace_bytes(const LayerDesc& L, int dtype);
+hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const int32_t* perm,
+                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
+                             hipStream_t s, int stages);   // stages: bit 0 = up, bit 1 = down
+hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
+                          const int32_t* inv_perm, const float* gates, void* y, hipStream_t s);
+size_t aux_workspace_bytes(const LayerDesc& L);
+hipError_t launch_aux_loss(const LayerDesc& L, const mohge_config& cfg, const float* gs,
+                           const float* es1, const int32_t* group_idx, const int32_t* expert_idx,
+                           float* losses, float* stats, void* ws, hipStream_t s);
+
+}  // namespace mohge

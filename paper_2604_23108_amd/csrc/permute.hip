@@ -1,0 +1,211 @@
+// Token permutation for gfx950: a deterministic, stable counting sort of the
+// P = T*K_e (token, slot) pairs by expert id.
+//
+// The pair list is cut into wave segments of 512 consecutive pairs.  Every wave
+// (1) histograms its segment in LDS, (2) a scan turns the [segment][expert] counts
+// into the first output position of every (segment, expert), (3) every wave walks its
+// segment again 64 pairs at a time and ranks equal experts inside the 64 with ballots
+// (one ballot per bit of the expert id), so the order inside a bucket is the pair order.
+// Integer LDS atomics only feed counts, so nothing depends on execution order.
+// Up to 2048 pairs the three steps run in one single-workgroup kernel.
+#include "common.h"
+
+namespace mohge {
+
+constexpr int kSegPairs = 512;                 // pairs per wave segment
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlockPairs = kSegPairs * kWavesPerBlock;
+
+struct PermArgs {
+  const int32_t* eidx;
+  int32_t* counts;
+  int32_t* offsets;
+  int32_t* perm;
+  int32_t* inv_perm;
+  int32_t* seg_hist;   // [nseg][Ne], overwritten with segment bases by the scan
+  int P, Ne, nseg, nbits;
+};
+
+// lanes of the wave that are active and hold the same `key` as this lane
+__device__ __forceinline__ unsigned long long match_mask(int key, int nbits, bool active) {
+  unsigned long long m = __ballot(active);
+  for (int b = 0; b < nbits; ++b) {
+    const unsigned long long bal = __ballot((key >> b) & 1);
+    m &= ((key >> b) & 1) ? bal : ~bal;
+  }
+  return m;
+}
+
+// expert id of pair p, forced into [0, Ne) so that a corrupt input cannot index outside
+// the LDS tables (the result is then meaningless but every access stays in bounds)
+__device__ __forceinline__ int load_expert(const PermArgs& a, int p) {
+  const int e = a.eidx[p];
+  return e < 0 ? 0 : (e >= a.Ne ? a.Ne - 1 : e);
+}
+
+__device__ __forceinline__ void wave_histogram(const PermArgs& a, int seg, int lane, int* hist) {
+  const int p0 = seg * kSegPairs;
+  for (int i = 0; i < kSegPairs; i += 64) {
+    const int p = p0 + i + lane;
+    if (p < a.P) atomicAdd(&hist[load_expert(a, p)], 1);
+  }
+}
+
+// base[e] = first free output position for expert e in this segment (LDS, wave private)
+__device__ __forceinline__ void wave_scatter(const PermArgs& a, int seg, int lane, int* base) {
+  const int p0 = seg * kSegPairs;
+  for (int i = 0; i < kSegPairs; i += 64) {
+    const int p = p0 + i + lane;
+    const bool active = p < a.P;
+    const int e = active ? load_expert(a, p) : 0;
+    const unsigned long long m = match_mask(e, a.nbits, active);
+    const unsigned long long lt = (1ull << lane) - 1ull;
+    int r = 0;
+    if (active) {
+      r = base[e] + __popcll(m & lt);
+      a.perm[r] = p;
+      a.inv_perm[p] = r;
+    }
+    __syncthreads();
+    // the highest lane of each set of equal experts advances the bucket cursor
+    if (active && (m >> lane) == 1ull) base[e] = r + 1;
+    __syncthreads();
+  }
+}
+
+__global__ void __launch_bounds__(256) permute_hist_kernel(const PermArgs a) {
+  __shared__ int hist[kWavesPerBlock][kMaxExperts];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int e = threadIdx.x; e < kWavesPerBlock * kMaxExperts; e += blockDim.x) (&hist[0][0])[e] = 0;
+  __syncthreads();
+  const int seg = blockIdx.x * kWavesPerBlock + w;
+  if (seg < a.nseg) wave_histogram(a, seg, lane, hist[w]);
+  __syncthreads();
+  if (seg < a.nseg)
+    for (int e = lane; e < a.Ne; e += 64) a.seg_hist[(size_t)seg * a.Ne + e] = hist[w][e];
+}
+
+// One workgroup of 16 waves.  Wave v handles experts v, v+16, ...: an exclusive scan of
+// that expert's counts over the segments; then an exclusive scan over experts.
+__global__ void __launch_bounds__(1024) permute_scan_kernel(const PermArgs a) {
+  __shared__ int cnt[kMaxExperts + 1];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int e = w; e < a.Ne; e += 16) {
+    int carry = 0;
+    for (int s0 = 0; s0 < a.nseg; s0 += 64) {
+      const int s = s0 + lane;
+      const int v = (s < a.nseg) ? a.seg_hist[(size_t)s * a.Ne + e] : 0;
+      int incl = v;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += up;
+      }
+      if (s < a.nseg) a.seg_hist[(size_t)s * a.Ne + e] = carry + incl - v;
+      carry += __shfl(incl, 63, 64);
+    }
+    if (lane == 0) cnt[e] = carry;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int e = 0; e < a.Ne; ++e) {
+      const int c = cnt[e];
+      a.counts[e] = c;
+      a.offsets[e] = run;
+      run += c;
+    }
+    a.offsets[a.Ne] = run;
+  }
+}
+
+__global__ void __launch_bounds__(256) permute_scatter_kernel(const PermArgs a) {
+  __shared__ int base[kWavesPerBlock][kMaxExperts];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int seg = blockIdx.x * kWavesPerBlock + w;
+  const int segc = seg < a.nseg ? seg : a.nseg - 1;
+  for (int e = lane; e < a.Ne; e += 64) base[w][e] = a.seg_hist[(size_t)segc * a.Ne + e] + a.offsets[e];
+  __syncthreads();
+  // every wave runs the same number of rounds (pairs past P are inactive)
+  PermArgs b = a;
+  if (seg >= a.nseg) b.P = 0;
+  wave_scatter(b, seg, lane, base[w]);
+}
+
+// P <= kBlockPairs: histogram, scan and scatter in one workgroup.
+__global__ void __launch_bounds__(256) permute_small_kernel(const PermArgs a) {
+  __shared__ int hist[kWavesPerBlock][kMaxExperts];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int e = threadIdx.x; e < kWavesPerBlock * kMaxExperts; e += blockDim.x) (&hist[0][0])[e] = 0;
+  __syncthreads();
+  wave_histogram(a, w, lane, hist[w]);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int e = 0; e < a.Ne; ++e) {
+      int c = 0;
+      for (int ww = 0; ww < kWavesPerBlock; ++ww) {
+        const int h = hist[ww][e];
+        hist[ww][e] = run + c;      // becomes the base of (segment ww, expert e)
+        c += h;
+      }
+      a.counts[e] = c;
+      a.offsets[e] = run;
+      run += c;
+    }
+    a.offsets[a.Ne] = run;
+  }
+  __syncthreads();
+  wave_scatter(a, w, lane, hist[w]);
+}
+
+template <typename V>
+__global__ void __launch_bounds__(256) gather_rows_kernel(const V* __restrict__ x, V* __restrict__ xp,
+                                                          const int32_t* __restrict__ perm, int P,
+                                                          int Ke, int vec_per_row) {
+  // one wave per output row, 16 bytes per lane per step
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= P) return;
+  const int lane = threadIdx.x & 63;
+  const V* src = x + (size_t)(perm[r] / Ke) * vec_per_row;
+  V* dst = xp + (size_t)r * vec_per_row;
+  for (int i = lane; i < vec_per_row; i += 64) dst[i] = src[i];
+}
+
+size_t permute_workspace_bytes(const LayerDesc& L) {
+  const size_t nseg = ((size_t)L.P + kSegPairs - 1) / kSegPairs;
+  const size_t b = (nseg > 0 ? nseg : 1) * (size_t)L.Ne * sizeof(int32_t);
+  return (b + 255) / 256 * 256;
+}
+
+hipError_t launch_permute(const LayerDesc& L, int dtype, const int32_t* expert_idx,
+                          int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                          const void* x, void* x_perm, void* ws, hipStream_t s) {
+  PermArgs a;
+  a.eidx = expert_idx; a.counts = counts; a.offsets = offsets; a.perm = perm; a.inv_perm = inv_perm;
+  a.seg_hist = static_cast<int32_t*>(ws);
+  a.P = L.P; a.Ne = L.Ne;
+  a.nseg = (L.P + kSegPairs - 1) / kSegPairs;
+  a.nbits = 0;
+  while ((1 << a.nbits) < L.Ne) ++a.nbits;
+  if (L.P <= kBlockPairs) {
+    hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(256), 0, s, a);
+  } else {
+    const int nblk = (a.nseg + kWavesPerBlock - 1) / kWavesPerBlock;
+    hipLaunchKernelGGL(permute_hist_kernel, dim3(nblk), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL(permute_scatter_kernel, dim3(nblk), dim3(256), 0, s, a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (x_perm && L.P > 0) {
+    const int row_bytes = L.d * (dtype == MOHGE_BF16 ? 2 : 4);
+    hipLaunchKernelGGL((gather_rows_kernel<uint4>), dim3((L.P + 3) / 4), dim3(256), 0, s,
+                       static_cast<const uint4*>(x), static_cast<uint4*>(x_perm), perm, L.P, L.Ke,
+                       row_bytes / 16);
+    e = hipGetLastError();
+  }
+  return e;
+}
+
+}  // namespace mohge

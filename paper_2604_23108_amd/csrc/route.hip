@@ -1,0 +1,302 @@
+// Two-level router (section 3.2 of the paper) for gfx950.
+//
+// One workgroup owns 16*TM tokens.  Phase 1 computes the N_g + N_e logits of its
+// tokens with the fp32 matrix cores (v_mfma_f32_16x16x4_f32): tokens are the M
+// rows, router rows (group embeddings first, then expert embeddings) the N columns.
+// Each lane loads 8 consecutive hidden elements of "its" token / router row straight
+// from global memory -- this is already the operand layout the instruction wants, so
+// no LDS staging is needed.  The hidden dimension is split over the waves of the
+// workgroup; every wave folds its fp32 accumulators into fp64 totals after each 64
+// hidden elements, and the per-wave totals are added in fp64 in a fixed order.  This
+// keeps the logit error near 1e-7, which bit-exact top-k agreement with an fp64
+// reference needs.
+// Phase 2 runs one wavefront per token with lane <-> expert: group top-K_g by rank
+// counting, softmax inside kept groups, scaling by the group score, expert top-k by
+// rank counting, a ballot + popcount to assign ascending output slots, and a
+// cross-lane sum for the gate normalisation.
+#include "common.h"
+
+namespace mohge {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct RouteArgs {
+  const void* x;
+  const float* wg;
+  const float* we;
+  const float* bias;
+  int32_t* gidx;
+  int32_t* eidx;
+  float* gates;
+  float* gs;
+  float* es1;
+  int T, d, Ng, N, Ne, Kg, Ke, mode;
+  int NO;        // Ng + Ne
+  int NOpad;     // NO rounded up to a multiple of 16, plus 4 (row stride of lg)
+  int Nepad;     // Ne rounded up to 64
+  int kslice;    // hidden elements per wave
+  int region0;   // bytes of the first LDS region (partial totals / per-wave rows)
+};
+
+template <bool BF16>
+__device__ __forceinline__ void load8(const void* base, size_t elem_off, float (&v)[8]) {
+  if constexpr (BF16) {
+    const uint4 u = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(base) + elem_off);
+    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
+    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
+  } else {
+    const float4* p = reinterpret_cast<const float4*>(static_cast<const float*>(base) + elem_off);
+    const float4 a = p[0], b = p[1];
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+template <bool BF16, int TM, int TN>
+__global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int BT = 16 * TM, NC = 16 * TN;
+  const int NW = blockDim.x >> 6;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, q = lane >> 4;
+  const int t0 = blockIdx.x * BT;
+  double* part = reinterpret_cast<double*>(smem);                 // [BT][NC]
+  float* lg = reinterpret_cast<float*>(smem + a.region0);         // [BT][NOpad]
+
+  // ---- phase 1: logits ----------------------------------------------------
+  size_t xrow[TM];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    int t = t0 + 16 * tm + r;
+    xrow[tm] = (size_t)(t < a.T ? t : a.T - 1) * a.d;
+  }
+  for (int nc = 0; nc < a.NO; nc += NC) {
+    const float* wrow[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      int o = nc + 16 * tn + r;
+      if (o > a.NO - 1) o = a.NO - 1;
+      wrow[tn] = (o < a.Ng) ? a.wg + (size_t)o * a.d : a.we + (size_t)(o - a.Ng) * a.d;
+    }
+    f32x4 acc[TM][TN];
+    double tot[TM][TN][4];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) {
+        acc[tm][tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tot[tm][tn][i] = 0.0;
+      }
+    const int kbeg = w * a.kslice, kend = kbeg + a.kslice;
+    int step = 0;
+    for (int k = kbeg; k < kend; k += 32, ++step) {
+      float xa[TM][8], wb[TN][8];
+#pragma unroll
+      for (int tm = 0; tm < TM; ++tm) load8<BF16>(a.x, xrow[tm] + k + 8 * q, xa[tm]);
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) load8<false>(wrow[tn], (size_t)(k + 8 * q), wb[tn]);
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+          for (int tn = 0; tn < TN; ++tn)
+            acc[tm][tn] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[tm][j], wb[tn][j], acc[tm][tn], 0, 0, 0);
+      if ((step & 1) || k + 32 >= kend) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+          for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) tot[tm][tn][i] += (double)acc[tm][tn][i];
+            acc[tm][tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+          }
+      }
+    }
+    // Accumulator element i of lane (r, q) is token 4q+i, router row r of the 16x16
+    // tile.  The waves add their fp64 totals into LDS one after the other (fixed order).
+    for (int ww = 0; ww < NW; ++ww) {
+      if (w == ww) {
+#pragma unroll
+        for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+          for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              double* dst = &part[(size_t)(16 * tm + 4 * q + i) * NC + 16 * tn + r];
+              *dst = (ww == 0) ? tot[tm][tn][i] : *dst + tot[tm][tn][i];
+            }
+      }
+      __syncthreads();
+    }
+    for (int idx = threadIdx.x; idx < BT * NC; idx += blockDim.x) {
+      const int tl = idx / NC, ol = idx % NC;
+      if (nc + ol < a.NO) lg[tl * a.NOpad + nc + ol] = (float)part[idx];
+    }
+    __syncthreads();
+  }
+
+  // ---- phase 2: one wavefront per token, lane <-> expert ---------------------
+  float* zrow = reinterpret_cast<float*>(smem) + (size_t)w * 4 * a.Nepad;  // biased expert logits
+  float* e1row = zrow + a.Nepad;                                            // ES'
+  float* e2row = e1row + a.Nepad;                                           // ES''
+  float* krow = e2row + a.Nepad;                                            // selection key
+  const int klimit = (a.mode == MOHGE_SELECT_GLOBAL) ? a.Ke : a.Ke / a.Kg;
+  const int iters = (BT + NW - 1) / NW;
+  const float NEG_INF = -__builtin_inff();
+  for (int it = 0; it < iters; ++it) {
+    const int tl = it * NW + w;
+    const int t = t0 + tl;
+    const bool live = (tl < BT) && (t < a.T);
+    const float* lrow = lg + (size_t)(live ? tl : 0) * a.NOpad;
+
+    // group gating: rank of each group's logit (ties to the lower id)
+    const float zg = (lane < a.Ng) ? lrow[lane] : NEG_INF;
+    int grank = 0;
+    for (int g2 = 0; g2 < a.Ng; ++g2) {
+      const float z2 = lrow[g2];
+      grank += (z2 > zg) || (z2 == zg && g2 < lane);
+    }
+    const bool gsel = (lane < a.Ng) && (grank < a.Kg);
+    const unsigned long long gmask = __ballot(gsel);
+    if (live && lane < a.Ng) {
+      if (a.gs) a.gs[(size_t)t * a.Ng + lane] = 1.f / (1.f + expf(-zg));
+      if (gsel) {
+        // (a NaN logit could make more than K_g lanes qualify: never write past the row)
+        const int slot = __popcll(gmask & ((1ull << lane) - 1ull));
+        if (slot < a.Kg) a.gidx[(size_t)t * a.Kg + slot] = lane;
+      }
+    }
+
+    for (int e = lane; e < a.Ne; e += 64) zrow[e] = lrow[a.Ng + e] + (a.bias ? a.bias[e] : 0.f);
+    __syncthreads();
+
+    for (int e = lane; e < a.Ne; e += 64) {
+      const int g = e / a.N;
+      const bool in = (gmask >> g) & 1ull;
+      float e1 = 0.f, e2 = 0.f;
+      if (in) {
+        const float* zg_row = zrow + g * a.N;
+        float mx = NEG_INF;
+        for (int i = 0; i < a.N; ++i) mx = fmaxf(mx, zg_row[i]);
+        float sum = 0.f;
+        for (int i = 0; i < a.N; ++i) sum += expf(zg_row[i] - mx);
+        e1 = expf(zrow[e] - mx) / sum;
+        e2 = e1 * (1.f / (1.f + expf(-lrow[g])));
+      }
+      e1row[e] = e1;
+      e2row[e] = e2;
+      krow[e] = in ? ((a.mode == MOHGE_SELECT_GLOBAL) ? e2 : zrow[e]) : NEG_INF;
+    }
+    __syncthreads();
+
+    unsigned long long smask[4] = {0ull, 0ull, 0ull, 0ull};
+    float dsum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (64 * j < a.Ne) {
+        const int e = lane + 64 * j;
+        const bool valid = e < a.Ne;
+        const int g = valid ? e / a.N : 0;
+        const bool in = valid && ((gmask >> g) & 1ull);
+        bool sel = false;
+        if (in) {
+          const float key = krow[e];
+          int rank = 0;
+          if (a.mode == MOHGE_SELECT_GLOBAL) {
+            for (int e2i = 0; e2i < a.Ne; ++e2i) {
+              const float k2 = krow[e2i];
+              rank += (k2 > key) || (k2 == key && e2i < e);
+            }
+          } else {
+            for (int i = 0; i < a.N; ++i) {
+              const int e2i = g * a.N + i;
+              const float k2 = krow[e2i];
+              rank += (k2 > key) || (k2 == key && e2i < e);
+            }
+          }
+          sel = rank < klimit;
+        }
+        smask[j] = __ballot(sel);
+        if (sel) dsum += e2row[e];
+      }
+    }
+    const float D = wave_sum(dsum);
+    int base = 0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (64 * j < a.Ne) {
+        const int e = lane + 64 * j;
+        if (live && e < a.Ne) {
+          if (a.es1) a.es1[(size_t)t * a.Ne + e] = e1row[e];
+          if ((smask[j] >> lane) & 1ull) {
+            const int slot = base + __popcll(smask[j] & ((1ull << lane) - 1ull));
+            if (slot < a.Ke) {
+              a.eidx[(size_t)t * a.Ke + slot] = e;
+              a.gates[(size_t)t * a.Ke + slot] = e2row[e] / D;
+            }
+          }
+        }
+        base += __popcll(smask[j]);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+template <bool BF16, int TM>
+static hipError_t launch_tn(const RouteArgs& a, int TN, dim3 grid, dim3 block, size_t smem,
+                            hipStream_t s) {
+  switch (TN) {
+    case 1: hipLaunchKernelGGL((route_kernel<BF16, TM, 1>), grid, block, smem, s, a); break;
+    case 2: hipLaunchKernelGGL((route_kernel<BF16, TM, 2>), grid, block, smem, s, a); break;
+    case 3: hipLaunchKernelGGL((route_kernel<BF16, TM, 3>), grid, block, smem, s, a); break;
+    default: hipLaunchKernelGGL((route_kernel<BF16, TM, 5>), grid, block, smem, s, a); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const float* w_group,
+                        const float* w_expert, const float* bias, int32_t* group_idx,
+                        int32_t* expert_idx, float* gates, float* gs_out, float* es1_out,
+                        hipStream_t s) {
+  RouteArgs a;
+  a.x = x; a.wg = w_group; a.we = w_expert; a.bias = bias;
+  a.gidx = group_idx; a.eidx = expert_idx; a.gates = gates; a.gs = gs_out; a.es1 = es1_out;
+  a.T = L.T; a.d = L.d; a.Ng = L.Ng; a.N = L.N; a.Ne = L.Ne; a.Kg = L.Kg; a.Ke = L.Ke;
+  a.mode = L.select_mode;
+  a.NO = L.Ng + L.Ne;
+  a.NOpad = ((a.NO + 15) / 16) * 16 + 4;
+  a.Nepad = ((L.Ne + 63) / 64) * 64;
+  const int NW = (L.d % 256 == 0) ? 8 : (L.d % 128 == 0) ? 4 : 2;
+  a.kslice = L.d / NW;
+  const int tiles = (a.NO + 15) / 16;
+  const int TN = tiles <= 1 ? 1 : tiles == 2 ? 2 : tiles == 3 ? 3 : 5;
+  int TM = (L.T >= 16384) ? 2 : 1;
+  size_t smem = 0;
+  for (;; TM = 1) {
+    const size_t part_bytes = (size_t)16 * TM * 16 * TN * sizeof(double);
+    const size_t rows_bytes = (size_t)NW * 4 * a.Nepad * sizeof(float);
+    a.region0 = (int)(((part_bytes > rows_bytes ? part_bytes : rows_bytes) + 15) / 16 * 16);
+    smem = (size_t)a.region0 + (size_t)16 * TM * a.NOpad * sizeof(float);
+    if (smem <= 64 * 1024 || TM == 1) break;
+  }
+  const int BT = 16 * TM;
+  dim3 grid((L.T + BT - 1) / BT), block(64 * NW);
+  const bool bf = dtype == MOHGE_BF16;
+  if (TM == 2) return bf ? launch_tn<true, 2>(a, TN, grid, block, smem, s)
+                         : launch_tn<false, 2>(a, TN, grid, block, smem, s);
+  return bf ? launch_tn<true, 1>(a, TN, grid, block, smem, s)
+            : launch_tn<false, 1>(a, TN, grid, block, smem, s);
+}
+
+}  // namespace mohge

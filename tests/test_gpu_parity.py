@@ -1,0 +1,222 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.
+
+Bars: routing indices and the permutation bit-exact (tokens whose top-k margin in the
+oracle is below 1e-6 are excluded from index / output comparison and counted); gates
+within 1e-6; layer output max|err| <= 2e-2 * max|ref| in bf16 and <= 1e-4 in fp32;
+auxiliary losses within 1e-4 relative.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import SELECT_GLOBAL, SELECT_PER_GROUP, WORKLOADS, Workload, generate
+
+pytestmark = pytest.mark.gpu
+
+MARGIN = 1e-6
+
+
+def _dev():
+    from gpu_harness import DeviceLayer
+    return DeviceLayer
+
+
+def check_routing(w, out, ref, what=""):
+    keep = ref["margin"] >= MARGIN
+    n_excl = int((~keep).sum())
+    assert n_excl <= max(2, w.T // 500), f"{what}: {n_excl} tokens inside the margin"
+    assert (out["group_idx"][keep] == ref["group_idx"][keep]).all(), f"{what}: group ids differ"
+    assert (out["expert_idx"][keep] == ref["expert_idx"][keep]).all(), f"{what}: expert ids differ"
+    err = np.abs(out["gates"][keep] - ref["gates"][keep]).max() if keep.any() else 0.0
+    assert err <= 1e-6, f"{what}: gate error {err}"
+    return keep, n_excl
+
+
+def check_permutation(w, out):
+    # the permutation of whatever expert ids the GPU produced must be the stable bucket sort
+    p = oracle.permute(w, out["expert_idx"])
+    for k in ("counts", "offsets", "perm", "inv_perm"):
+        assert (out[k] == p[k]).all(), f"{k} differs"
+
+
+def check_output(w, inp, out, ref_route, keep, tokens, tol_rel=2e-2, tol_abs_f32=1e-4):
+    tokens = np.asarray([t for t in tokens if keep[t]], np.int32)
+    pair_token = np.repeat(tokens, w.k_experts)
+    pair_expert = ref_route["expert_idx"][tokens].reshape(-1)
+    y_pairs = oracle.expert_ffn(w, inp.x.f32, [t.f32 for t in inp.w_gate], [t.f32 for t in inp.w_up],
+                                [t.f32 for t in inp.w_down], pair_token, pair_expert)
+    y_ref = oracle.combine(w, y_pairs, ref_route["gates"][tokens])
+    # expert outputs, looked up through the GPU's own inverse permutation
+    pair_ids = (tokens[:, None] * w.k_experts + np.arange(w.k_experts)[None, :]).reshape(-1)
+    rows = torch.from_numpy(out["inv_perm"][pair_ids].astype(np.int64)).cuda()
+    y_perm_rows = out["y_perm"][rows].float().cpu().numpy()
+    if w.dtype == "bf16":
+        assert np.abs(y_perm_rows - y_pairs).max() <= tol_rel * np.abs(y_pairs).max()
+        err = np.abs(out["y"][tokens] - y_ref).max()
+        assert err <= tol_rel * np.abs(y_ref).max(), f"y error {err} vs max|ref| {np.abs(y_ref).max()}"
+    else:
+        assert np.abs(y_perm_rows - y_pairs).max() <= tol_abs_f32
+        assert np.abs(out["y"][tokens] - y_ref).max() <= tol_abs_f32
+    return float(np.abs(out["y"][tokens] - y_ref).max()), float(np.abs(y_ref).max())
+
+
+def full_check(w, tokens=None, scale_router=1.0):
+    inp = generate(w)
+    if scale_router != 1.0:
+        inp.w_group *= np.float32(scale_router)
+        inp.w_expert *= np.float32(scale_router)
+    dl = _dev()(w, inp, training=True)
+    out = dl.run()
+    ref = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias)
+    keep, n_excl = check_routing(w, out, ref, w.name)
+    check_permutation(w, out)
+    toks = np.arange(w.T) if tokens is None else tokens
+    check_output(w, inp, out, ref, keep, toks)
+    # scores and auxiliary losses
+    np.testing.assert_allclose(out["gs"], ref["gs"], atol=1e-6)
+    np.testing.assert_allclose(out["es1"][keep], ref["es1"][keep], atol=1e-6)
+    if n_excl == 0:
+        a = oracle.aux_loss(w, ref["gs"], ref["es1"], ref["group_idx"], ref["expert_idx"])
+        assert abs(out["losses"][0] - a["L_G"]) <= 1e-4 * abs(a["L_G"])
+        assert abs(out["losses"][1] - a["L_E"]) <= 1e-4 * abs(a["L_E"])
+        Ng, Ne = w.n_groups, w.n_experts
+        np.testing.assert_allclose(out["stats"][:Ng], a["f_G"], rtol=1e-5)
+        np.testing.assert_allclose(out["stats"][Ng:2 * Ng], a["p_G"], rtol=1e-5)
+        np.testing.assert_allclose(out["stats"][2 * Ng:2 * Ng + Ne], a["f_E"], rtol=1e-5, atol=1e-7)
+        np.testing.assert_allclose(out["stats"][2 * Ng + Ne:], a["p_E"], rtol=1e-5, atol=1e-7)
+    return out, ref
+
+
+# ---- configuration 1 in full ------------------------------------------------------------
+def test_tiny_f32_layer_all_tokens():
+    full_check(WORKLOADS["tiny_f32"])
+
+
+@pytest.mark.parametrize("mode", [SELECT_GLOBAL, SELECT_PER_GROUP])
+def test_tiny_f32_both_selection_modes_spread_router(mode):
+    full_check(WORKLOADS["tiny_f32"].replace(select_mode=mode, k_experts=4, T=77), scale_router=10.0)
+
+
+# ---- bf16, several row tiles with ragged tails, ragged column tiles ----------------------
+MID = Workload("mid_bf16", T=1500, d=256, n_groups=3, experts_per_group=4, d_ff=(64, 192, 320),
+               k_groups=2, k_experts=4, seed=21)
+
+
+@pytest.mark.parametrize("mode", [SELECT_GLOBAL, SELECT_PER_GROUP])
+def test_mid_bf16_tiled_path(mode):
+    full_check(MID.replace(select_mode=mode), scale_router=5.0)
+
+
+def test_mid_bf16_skewed_counts():
+    w = MID.replace(skew_beta=2.0, experts_per_group=8, seed=22, T=2100)
+    out, _ = full_check(w, scale_router=5.0)
+    c = out["counts"]
+    assert c.max() / max(1, c.min()) > 10
+
+
+def test_paper_shape_global_selection_eight_widths():
+    w = WORKLOADS["paper_1b"].replace(T=900, d=256)
+    full_check(w, tokens=np.arange(0, 900, 3), scale_router=8.0)
+
+
+# ---- decode-shaped: the weight-streaming path --------------------------------------------
+@pytest.mark.parametrize("T", [1, 7, 32])
+def test_decode_shaped_small(T):
+    w = Workload("dec", T=T, d=512, n_groups=4, experts_per_group=4, d_ff=(64, 128, 192, 256),
+                 k_groups=2, k_experts=4, seed=30 + T)
+    full_check(w, scale_router=4.0)
+
+
+def test_all_tokens_to_one_expert_decode_and_tiled():
+    # degenerate routing: a huge bias on one expert per group
+    for T in (32, 700):
+        w = Workload("one", T=T, d=128, n_groups=2, experts_per_group=4, d_ff=(64, 128), k_groups=2,
+                     k_experts=2, seed=40)
+        inp = generate(w)
+        bias = np.zeros(w.n_experts, np.float32)
+        bias[1] = 50.0
+        bias[6] = 50.0
+        inp.expert_logit_bias = bias
+        dl = _dev()(w, inp, training=False)
+        out = dl.run()
+        ref = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert, bias)
+        keep, _ = check_routing(w, out, ref)
+        assert out["counts"].tolist() == [0, T, 0, 0, 0, 0, T, 0]
+        check_permutation(w, out)
+        check_output(w, inp, out, ref, keep, np.arange(T))
+
+
+def test_empty_call_and_error_paths():
+    import paper_2604_23108_amd as M
+    w = MID.replace(T=0)
+    cfg = M.Config.from_workload(w)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    eidx = torch.empty((0, w.k_experts), **i32)
+    counts = torch.full((w.n_experts,), -1, **i32)
+    offsets = torch.full((w.n_experts + 1,), -1, **i32)
+    perm = torch.empty(4, **i32)
+    ws = torch.empty(4096, dtype=torch.uint8, device="cuda")
+    M.mohge_permute(cfg, eidx.reshape(-1).new_empty(4), counts, offsets, perm, perm.clone(), None, None, ws)
+    torch.cuda.synchronize()
+    assert (counts == 0).all() and (offsets == 0).all()
+    # workspace too small, misaligned pointer
+    w2 = MID
+    cfg2 = M.Config.from_workload(w2)
+    with pytest.raises(M.MohgeError, match="workspace"):
+        M.mohge_permute(cfg2, torch.zeros(w2.n_pairs, **i32), counts, offsets,
+                        torch.empty(w2.n_pairs, **i32), torch.empty(w2.n_pairs, **i32), None, None,
+                        torch.empty(16, dtype=torch.uint8, device="cuda"))
+    g = torch.empty(w2.T * w2.k_experts + 1, dtype=torch.float32, device="cuda")
+    with pytest.raises(M.MohgeError, match="aligned"):
+        M.mohge_combine(cfg2, torch.empty((w2.n_pairs, w2.d), dtype=torch.bfloat16, device="cuda"),
+                        torch.zeros(w2.n_pairs, **i32), g[1:],
+                        torch.empty((w2.T, w2.d), dtype=torch.bfloat16, device="cuda"))
+
+
+def test_x_perm_materialisation_and_prepermuted_ffn_input():
+    import paper_2604_23108_amd as M
+    w = MID.replace(T=600)
+    inp = generate(w)
+    dl = _dev()(w, inp, training=False)
+    out = dl.run()
+    L = dl.layer
+    x_perm = torch.empty((w.n_pairs, w.d), dtype=torch.bfloat16, device="cuda")
+    M.mohge_permute(dl.cfg, L.expert_idx, L.counts, L.offsets, L.perm, L.inv_perm, dl.x, x_perm, L.ws_permute)
+    torch.cuda.synchronize()
+    src = torch.from_numpy((out["perm"] // w.k_experts).astype(np.int64)).cuda()
+    assert torch.equal(x_perm, dl.x[src])
+    y_perm2 = torch.empty_like(L.y_perm)
+    M.mohge_expert_ffn(dl.cfg, x_perm, None, L.offsets, dl.w13, dl.w2, y_perm2, L.ws_ffn)
+    torch.cuda.synchronize()
+    assert torch.equal(y_perm2[:w.n_pairs], L.y_perm[:w.n_pairs])
+
+
+def test_runs_are_bit_identical():
+    w = MID.replace(T=1111)
+    inp = generate(w)
+    dl = _dev()(w, inp, training=True)
+    a = dl.run()
+    ya, la = a["y"].copy(), a["losses"].copy()
+    pa = a["perm"].copy()
+    b = dl.run()
+    assert (ya == b["y"]).all() and (la == b["losses"]).all() and (pa == b["perm"]).all()
+
+
+# ---- the named configurations at full size: routing in full, outputs on sampled tokens ---
+@pytest.mark.parametrize("name,n_sample", [("mid_prefill", 48), ("decode", 32), ("training", 32)])
+def test_full_size_configs_sampled(name, n_sample):
+    w = WORKLOADS[name]
+    rng = np.random.default_rng(123)
+    toks = np.sort(rng.choice(w.T, size=min(n_sample, w.T), replace=False))
+    full_check(w, tokens=toks)
+
+
+def test_full_size_large_prefill_skewed_sampled():
+    w = WORKLOADS["large_prefill_skewed"]
+    rng = np.random.default_rng(321)
+    toks = np.sort(rng.choice(w.T, size=24, replace=False))
+    out, _ = full_check(w, tokens=toks)
+    c = out["counts"]
+    assert c.sum() == w.n_pairs and c.max() / max(1, c.min()) > 10
