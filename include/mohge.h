@@ -171,6 +171,12 @@ int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
  * 0 for an invalid configuration or call id. */
 size_t mohge_workspace_size(const mohge_config* cfg, int which_call);
 
+/* Tuning hook for benchmarks: knob 0 / 1 selects the tile configuration (an index into
+ * the table in the tiled expert-FFN source) used by the up / down projection of the bf16
+ * prefill path.  Process-wide, not thread-safe, default 0 / 0.  Indices marked as probes
+ * in that table compute meaningless results and exist for bandwidth measurements only. */
+int mohge_tune(int knob, int value);
+
 /* Message of the last error on this thread ("" if none); valid until the next call. */
 const char* mohge_last_error(void);
 

@@ -6,7 +6,7 @@ if `libmohge.so` has not been built, loading fails.
 """
 from .binding import (  # noqa: F401
     MohgeError, Config, lib, lib_path, mohge_route, mohge_permute, mohge_expert_ffn, mohge_expert_ffn_up, mohge_expert_ffn_down,
-    mohge_combine, mohge_aux_loss, mohge_workspace_size, mohge_last_error, pack_w13,
+    mohge_combine, mohge_aux_loss, mohge_workspace_size, mohge_tune, mohge_last_error, pack_w13,
     MoHGELayer, CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS, SELECT_GLOBAL, SELECT_PER_GROUP,
     F32, BF16,
 )

@@ -20,7 +20,8 @@ F32, BF16 = 0, 1
 CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
-           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_workspace_size", "mohge_last_error"]
+           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_tune", "mohge_workspace_size",
+           "mohge_last_error"]
 
 
 class MohgeError(RuntimeError):
@@ -50,7 +51,7 @@ def lib():
             raise MohgeError(f"{_LIB_PATH} is missing: build it with "
                              "`python -m paper_2604_23108_amd.build` (there is no fallback path)")
         l = C.CDLL(_LIB_PATH)
-        for n in EXPORTS[:7]:
+        for n in EXPORTS[:8]:
             getattr(l, n).restype = C.c_int
         l.mohge_workspace_size.restype = C.c_size_t
         l.mohge_last_error.restype = C.c_char_p
@@ -119,6 +120,10 @@ def _ptr(t: Optional[torch.Tensor]):
 
 def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def mohge_tune(knob: int, value: int):
+    _check(lib().mohge_tune(C.c_int(knob), C.c_int(value)), "mohge_tune")
 
 
 def mohge_workspace_size(cfg: Config, which_call: int) -> int:

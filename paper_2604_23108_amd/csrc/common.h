@@ -37,8 +37,19 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f) {
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
+// two floats -> packed bf16 pair with the hardware conversion (v_cvt_pk_bf16_f32, round
+// to nearest even); `lo` lands in the low half
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const f32x2_t v = {lo, hi};
+  const bf16x2_t r = __builtin_convertvector(v, bf16x2_t);
+  return __builtin_bit_cast(uint32_t, r);
+}
+// SiLU(g) * u with the fast exp / reciprocal instructions (relative error ~1e-6, far
+// below the bf16 rounding that follows)
+__device__ __forceinline__ float swiglu(float g, float u) {
+  return g * u * __builtin_amdgcn_rcpf(1.f + __expf(-g));
 }
 
 // launchers implemented in the kernel files; each returns a hipError_t from the launch
@@ -56,6 +67,8 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
                              hipStream_t s, int stages);   // stages: bit 0 = up, bit 1 = down
 hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
                           const int32_t* inv_perm, const float* gates, void* y, hipStream_t s);
+int tune_tiled(int knob, int value);
+void tune_tiled_dbg(void* p);
 size_t aux_workspace_bytes(const LayerDesc& L);
 hipError_t launch_aux_loss(const LayerDesc& L, const mohge_config& cfg, const float* gs,
                            const float* es1, const int32_t* group_idx, const int32_t* expert_idx,
