@@ -127,8 +127,8 @@ int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm
 /*
  * The two halves of mohge_expert_ffn as separate calls (same arguments, same kernels):
  * mohge_expert_ffn_up writes h = SiLU(W_gate x) * (W_up x) for every sorted position
- * into `h` (DEVICE, mohge_workspace_size(cfg, MOHGE_CALL_EXPERT_FFN) bytes, row r at
- * element offset r * max_g F_g); mohge_expert_ffn_down reads it and writes y_perm.
+ * into `h` (DEVICE, mohge_workspace_size(cfg, MOHGE_CALL_EXPERT_FFN) bytes; the layout
+ * inside is the library's); mohge_expert_ffn_down reads it and writes y_perm.
  * mohge_expert_ffn(…, workspace) is exactly up(…, workspace) followed by down(workspace, …).
  */
 int mohge_expert_ffn_up(const mohge_config* cfg, const void* x, const int32_t* perm,
@@ -171,10 +171,9 @@ int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
  * 0 for an invalid configuration or call id. */
 size_t mohge_workspace_size(const mohge_config* cfg, int which_call);
 
-/* Tuning hook for benchmarks: knob 0 / 1 selects the tile configuration (an index into
- * the table in the tiled expert-FFN source) used by the up / down projection of the bf16
- * prefill path.  Process-wide, not thread-safe, default 0 / 0.  Indices marked as probes
- * in that table compute meaningless results and exist for bandwidth measurements only. */
+/* Tuning hook for benchmarks: knob 0 / 1 forces the token-tile height (64, 128, 192 or
+ * 256 rows; 0 = chosen per call from the routed counts) of the up / down projection of the
+ * bf16 prefill path.  Results do not depend on it.  Process-wide, not thread-safe. */
 int mohge_tune(int knob, int value);
 
 /* Message of the last error on this thread ("" if none); valid until the next call. */

@@ -33,6 +33,11 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = False) -> str:
+    global LIB, OBJDIR
+    if os.environ.get("MOHGE_PROBE"):      # instrumented build for timing probes, separate file
+        FLAGS.append("-DMOHGE_PROBE")
+        LIB = os.path.join(HERE, "libmohge_probe.so")
+        OBJDIR = os.path.join(HERE, "_build_probe")
     os.makedirs(OBJDIR, exist_ok=True)
     with cf.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(_compile, SOURCES))

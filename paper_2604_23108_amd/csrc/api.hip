@@ -83,8 +83,6 @@ extern "C" {
 
 const char* mohge_last_error(void) { return g_err; }
 
-int mohge_tune_dbg(void* p) { tune_tiled_dbg(p); return 0; }
-
 int mohge_tune(int knob, int value) {
   if (tune_tiled(knob, value)) { set_error("mohge_tune: knob %d / value %d out of range", knob, value); return MOHGE_EINVAL; }
   return MOHGE_OK;

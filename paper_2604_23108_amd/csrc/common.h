@@ -68,7 +68,7 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
 hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
                           const int32_t* inv_perm, const float* gates, void* y, hipStream_t s);
 int tune_tiled(int knob, int value);
-void tune_tiled_dbg(void* p);
+size_t tiled_sched_bytes(const LayerDesc& L);
 size_t aux_workspace_bytes(const LayerDesc& L);
 hipError_t launch_aux_loss(const LayerDesc& L, const mohge_config& cfg, const float* gs,
                            const float* es1, const int32_t* group_idx, const int32_t* expert_idx,

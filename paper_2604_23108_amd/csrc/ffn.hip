@@ -92,10 +92,14 @@ static hipError_t launch_ffn_f32(const LayerDesc& L, const void* x, const int32_
   return hipGetLastError();
 }
 
-// workspace: the hidden activations h, one row of max F_g per sorted position
+static bool use_skinny(const LayerDesc& L) { return L.T <= 32; }
+
+// workspace: the hidden activations h, one row of max F_g per sorted position; the tiled
+// matrix-core path keeps its tile schedules in front of them
 size_t ffn_workspace_bytes(const LayerDesc& L, int dtype) {
   const size_t elt = dtype == MOHGE_BF16 ? 2 : 4;
-  const size_t b = (size_t)(L.P > 0 ? L.P : 1) * L.Fmax * elt;
+  size_t b = (size_t)(L.P > 0 ? L.P : 1) * L.Fmax * elt;
+  if (dtype == MOHGE_BF16 && !use_skinny(L)) b += tiled_sched_bytes(L);
   return (b + 255) / 256 * 256;
 }
 
@@ -105,7 +109,7 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
   if (dtype == MOHGE_F32) return launch_ffn_f32(L, x, perm, offsets, W, y_perm, ws, s, stages);
   // With at most 32 tokens no expert can receive more than 32 rows: one pass of the
   // weight-streaming kernel covers it.  Otherwise the tiled matrix-core kernel.
-  if (L.T <= 32) return launch_ffn_skinny(L, x, perm, offsets, W, y_perm, ws, s, stages);
+  if (use_skinny(L)) return launch_ffn_skinny(L, x, perm, offsets, W, y_perm, ws, s, stages);
   return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages);
 }
 

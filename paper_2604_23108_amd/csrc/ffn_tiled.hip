@@ -7,17 +7,33 @@
 // ragged: the row count n_e comes from the router (device memory `offsets`), the width
 // F_g differs from group to group (it is N of the up and K of the down projection).
 //
-// Tile schedule, derived on the device: tile -> (expert, row tile, column tile) by a
-// wave-wide prefix sum over the experts' tile counts; workgroup ids are first folded so
-// that each of the 8 XCDs (own L2 each) walks a contiguous range of tiles, and inside
-// an expert row tiles vary fastest so that neighbours share the weight tile.
+// Schedule (device side, no host synchronisation).  A one-workgroup kernel turns
+// `offsets` into a list of tiles: up to 256 token rows x 256 weight rows (up: 128 W_gate +
+// the matching 128 W_up rows).  It picks the tile height (128, 192 or 256 rows) that needs
+// the fewest rounds over the compute units, orders tiles so that tiles sharing operands are
+// neighbours and the longest reductions come first, and cuts the list into 8 ranges of
+// equal cost, one per XCD (each XCD has its own L2).  The GEMM kernel is persistent: one
+// workgroup per compute unit, workgroup b serves XCD b%8 (the hardware hands workgroups
+// to XCDs round-robin) and walks that XCD's range with stride 32.
 //
-// Data path: global -> LDS with global_load_lds_dwordx4 (no staging registers), two
-// stages; 16-byte chunks are XOR-swizzled inside each 128-byte tile row so that the
-// ds_read_b128 operand reads do not collide on banks.  The token gather is fused: a
-// tile row's global address is taken through `perm`.  The MFMA is issued with the
-// weight fragment as the first operand so that a lane ends up with 4 consecutive
-// output features of one token, which pack into one 8-byte store.
+// Tile kernel.  8 waves as 2 (token) x 4 (weight) with wave tiles of 128 x 64; a wave owns
+// the 32-row token fragments {wm, wm+2, wm+4, wm+6}, so a tile with fewer rows keeps both
+// wave rows equally busy and simply runs fewer MFMAs (the inner loop is instantiated for
+// 1..4 active fragments).  Operands go global -> LDS with global_load_lds_dwordx4 (no
+// staging registers) in 128-byte row segments (BK = 64): the texture path handles about one
+// 128-byte line per two clocks however little of it is used, so 64-byte segments halve the
+// feed rate (measured 24 vs 57 B/clk per CU).  16-byte chunks are XOR-swizzled inside the
+// tile rows so that ds_read_b128 fragment reads are conflict free.  All 160 KB of LDS are
+// used, asymmetrically: two stages for the token operand (its rows are shared by all column
+// tiles of an expert and mostly hit in L2) and three for the weight operand (streamed from
+// HBM), which therefore is requested two stages ahead.  The token gather is fused: a tile
+// row's global address is taken through `perm`.
+// The inner loop is ordered by hand (pinned with sched_barrier): operand fragments of the
+// next 16-deep k-step are read from LDS into a second register set and the global -> LDS
+// requests are issued between the MFMAs of the current one; one barrier per stage.
+// The MFMA takes the weight fragment as first operand: a lane then holds 4 consecutive
+// output features of one token; the epilogue packs them to bf16 (hardware conversion),
+// transposes through a wave-private LDS patch and stores whole row segments.
 #include <type_traits>
 
 #include "common.h"
@@ -26,6 +42,25 @@ namespace mohge {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kBM = 256, kBN = 256, kBK = 64;
+constexpr int kStagesA = 2, kStagesB = 3;   // 32 KB parts: 2 token + 3 weight = all 160 KB of LDS
+constexpr int kWGM = 2, kWGN = 4;
+constexpr int kXcds = 8;
+
+struct TileRec {
+  int e;          // expert
+  int row_start;  // first sorted position of the tile
+  int rows;       // valid token rows (1..256)
+  int n0;         // first output column (up: hidden unit, down: feature of d)
+};
+
+struct SchedHeader {
+  int tile_rows;             // chosen tile height
+  int total;                 // number of tiles
+  int xcd_begin[kXcds + 1];  // tile ranges per XCD
+  int pad[5];
+};
 
 struct TileArgs {
   const uint16_t* A;          // up: x [T,d] (gathered through perm) or [P,d]; down: H [P,lda]
@@ -36,86 +71,117 @@ struct TileArgs {
   int lda, ldc;
   int Ke, Ng, N, Ne, d;
   int F[kMaxGroups];
-  int order[kMaxGroups];      // groups in visiting order
-  long long* dbg;             // timing probe only: 8 timestamps per workgroup, else NULL
+  int order[kMaxGroups];      // groups in visiting order (longest reduction first)
+  SchedHeader* hdr;
+  TileRec* recs;
+  long long* cpfx;            // cost of all tiles before tile i
+  int ncu;                    // compute units = persistent workgroups
+  int force_rows;             // 0 = choose, else 64/128/192/256
+#ifdef MOHGE_PROBE
+  long long* dbg;             // [workgroup][8]: cycle sums per phase, tile count
+#endif
 };
 
-template <int BM, int BN, bool UP>
-struct TileCoord {
-  int e, g, i, row0, rows, m0, n0, F;
-  bool valid;
+template <bool UP>
+struct Shape {
+  static constexpr int NCOLS_PER_TILE = UP ? kBN / 2 : kBN;
 };
 
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const int up = __shfl_up(v, off, 64);
-    if (lane >= off) v += up;
+// ---------------------------------------------------------------------------------------
+// schedule: one workgroup, thread v <-> expert at visiting position v
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ long long block_excl_scan(long long v, long long* sm, long long* total) {
+  // 256 threads, Hillis-Steele in LDS
+  const int t = threadIdx.x;
+  sm[t] = v;
+  __syncthreads();
+  for (int off = 1; off < 256; off <<= 1) {
+    const long long add = t >= off ? sm[t - off] : 0;
+    __syncthreads();
+    sm[t] += add;
+    __syncthreads();
   }
-  return v;
+  const long long incl = sm[t];
+  *total = sm[255];
+  __syncthreads();
+  return incl - v;
 }
 
-// Maps this workgroup to a tile.  Every wave computes it redundantly (no LDS, no barrier).
-template <int BM, int BN, bool UP>
-__device__ __forceinline__ TileCoord<BM, BN, UP> find_tile(const TileArgs& a, int lane) {
-  TileCoord<BM, BN, UP> tc;
-  tc.valid = false;
-  // tiles per expert, in visiting order v = position of (group order, expert in group)
-  int incl[4], ev[4], cntv[4];
-  int carry = 0;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    incl[c] = 0; ev[c] = 0; cntv[c] = 0;
-    if (64 * c < a.Ne) {
-      const int v = lane + 64 * c;
-      int tiles = 0;
-      if (v < a.Ne) {
-        const int g = a.order[v / a.N];
-        const int e = g * a.N + v % a.N;
-        const int cnt = a.offsets[e + 1] - a.offsets[e];
-        const int ncols = UP ? a.F[g] : a.d;
-        constexpr int NCOLS_PER_TILE = UP ? BN / 2 : BN;
-        tiles = ((cnt + BM - 1) / BM) * ((ncols + NCOLS_PER_TILE - 1) / NCOLS_PER_TILE);
-        ev[c] = e;
-        cntv[c] = cnt;
-      }
-      const int s = wave_incl_scan(tiles, lane);
-      incl[c] = carry + s;
-      carry += __shfl(s, 63, 64);
-    }
+template <bool UP>
+__global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs a) {
+  __shared__ long long sm[256];
+  __shared__ int s_rows;
+  constexpr int NCPT = Shape<UP>::NCOLS_PER_TILE;
+  const int v = threadIdx.x;
+  int e = 0, cnt = 0, nt = 0, kc = 0;
+  if (v < a.Ne) {
+    const int g = a.order[v / a.N];
+    e = g * a.N + v % a.N;
+    cnt = a.offsets[e + 1] - a.offsets[e];
+    const int ncols = UP ? a.F[g] : a.d;
+    nt = (ncols + NCPT - 1) / NCPT;
+    kc = (UP ? a.d : a.F[g]) / 64;
   }
-  const int total = carry;
-  // fold workgroup ids so that XCD x (which receives ids x, x+8, ...) gets a contiguous range
-  const int chunk = (total + 7) / 8;
-  const int xcd = blockIdx.x & 7, local = blockIdx.x >> 3;
-  const int tile = xcd * chunk + local;
-  if (local >= chunk || tile >= total) return tc;
-#pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    if (64 * c < a.Ne && !tc.valid) {
-      const unsigned long long m = __ballot(tile < incl[c]);
-      if (m) {
-        const int src = __ffsll((long long)m) - 1;
-        const int e = __shfl(ev[c], src, 64);
-        const int cnt = __shfl(cntv[c], src, 64);
-        const int hi = __shfl(incl[c], src, 64);
-        const int mt = (cnt + BM - 1) / BM;
-        const int g = e / a.N;
-        constexpr int NCOLS_PER_TILE = UP ? BN / 2 : BN;
-        const int ncols = UP ? a.F[g] : a.d;
-        const int nt = (ncols + NCOLS_PER_TILE - 1) / NCOLS_PER_TILE;
-        const int lo = hi - mt * nt;
-        const int rel = tile - lo;
-        tc.e = e; tc.g = g; tc.i = e % a.N; tc.F = a.F[g];
-        tc.row0 = a.offsets[e];
-        tc.rows = cnt;
-        tc.m0 = (rel % mt) * BM;
-        tc.n0 = (rel / mt) * NCOLS_PER_TILE;
-        tc.valid = true;
+  // tile height: fewest rounds over the compute units, weighted by tile cost
+  long long tot;
+  long long kmax = 0;
+  for (int g = 0; g < a.Ng; ++g) kmax = max(kmax, (long long)((UP ? a.d : a.F[g]) / 64));
+  float best = 0.f;
+  int best_rows = 256;
+  for (int h = 256; h >= 128; h -= 64) {
+    const long long w = (long long)((cnt + h - 1) / h) * nt * kc;
+    block_excl_scan(w, sm, &tot);
+    const long long rounds = (tot + (long long)a.ncu * kmax - 1) / ((long long)a.ncu * kmax);
+    const float est = (float)rounds * ((float)(h / 64) + 0.6f);
+    if (h == 256 || est < best) { best = est; best_rows = h; }
+  }
+  if (threadIdx.x == 0) s_rows = a.force_rows ? a.force_rows : best_rows;
+  __syncthreads();
+  const int h = s_rows;
+  const int mt = (cnt + h - 1) / h;
+  const int units = (cnt + 63) / 64;
+  long long ttot, ctot;
+  const long long tp = block_excl_scan((long long)mt * nt, sm, &ttot);
+  const long long cp = block_excl_scan((long long)units * nt * kc, sm, &ctot);
+  if (v < a.Ne) {
+    const int row0 = a.offsets[e];
+    for (int ni = 0; ni < nt; ++ni)
+      for (int mi = 0; mi < mt; ++mi) {
+        const long long idx = tp + (long long)ni * mt + mi;
+        TileRec r;
+        r.e = e;
+        r.row_start = row0 + mi * h;
+        r.rows = min(h, cnt - mi * h);
+        r.n0 = ni * NCPT;
+        a.recs[idx] = r;
+        const int before = min(mi * (h / 64), units);
+        a.cpfx[idx] = cp + ((long long)ni * units + before) * kc;
+      }
+  }
+  __threadfence();
+  __syncthreads();
+  if (threadIdx.x <= kXcds) {
+    const int x = threadIdx.x;
+    int lo = 0, hi = (int)ttot;                 // first tile whose preceding cost >= target
+    const long long target = (ctot * x + kXcds - 1) / kXcds;
+    if (x == kXcds) lo = (int)ttot;
+    else {
+      while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a.cpfx[mid] >= target) hi = mid; else lo = mid + 1;
       }
     }
+    a.hdr->xcd_begin[x] = lo;
   }
-  return tc;
+  if (threadIdx.x == 0) { a.hdr->tile_rows = h; a.hdr->total = (int)ttot; }
+}
+
+// ---------------------------------------------------------------------------------------
+// tile kernel
+// ---------------------------------------------------------------------------------------
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
 __device__ __forceinline__ void async_copy16(const void* gptr, void* lds_uniform_base) {
@@ -124,60 +190,61 @@ __device__ __forceinline__ void async_copy16(const void* gptr, void* lds_uniform
       (__attribute__((address_space(3))) void*)lds_uniform_base, 16, 0, 0);
 }
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
+#define MOHGE_PIN() __builtin_amdgcn_sched_barrier(0)
 
-// Probe modes for tuning runs (results are meaningless in the non-zero modes, every access
-// stays in bounds): 1 = global loads only in the prologue (matrix-core + LDS rate with a
-// perfect memory system), 2 = no matrix-core work (rate of the global -> LDS feed alone).
-enum { PROBE_NONE = 0, PROBE_NO_LOADS = 1, PROBE_NO_MFMA = 2 };
+// One tile with NACT active 32-row token fragments per wave (tile rows <= 64*NACT).
+#ifdef MOHGE_PROBE
+#define PROBE_T(i) ts[i] = __builtin_amdgcn_s_memtime()
+#else
+#define PROBE_T(i)
+#endif
 
-// BM x BN output tile (BM tokens, BN weight rows), BK reduction elements per stage, NST
-// LDS stages, WGM x WGN waves.
-template <int BM, int BN, int BK, int NST, int WGM, int WGN, bool UP, int PROBE>
-__global__ void __launch_bounds__(64 * WGM * WGN) ffn_tile_kernel(const TileArgs a) {
-  constexpr int NWAVES = WGM * WGN, NT = 64 * NWAVES;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wave tile: tokens x weight rows
+template <bool UP, int NACT>
+__device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, unsigned char* lds,
+                                         int lane, int w) {
+#ifdef MOHGE_PROBE
+  long long ts[6];
+#endif
+  PROBE_T(0);
+  constexpr int BM = kBM, BN = kBN, BK = kBK;
+  constexpr int WGM = kWGM, WGN = kWGN, NWAVES = WGM * WGN, NT = 64 * NWAVES;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MF = WTM / 32, NF = WTN / 32;
-  constexpr int CH = BK / 8;                      // 16-byte chunks per tile row
-  constexpr int ROWB = BK * 2;                    // bytes per tile row
-  constexpr int RPL = 64 / CH;                    // tile rows filled by one wave-wide load
-  constexpr int SH = (CH == 8) ? 1 : 2;           // swizzle: chunk ^= (row >> SH) & (CH-1)
-  constexpr int KK = BK / 16;
-  constexpr int A_LOADS = BM * CH / NT, B_LOADS = BN * CH / NT, LPS = A_LOADS + B_LOADS;
-  constexpr int STAGE_BYTES = (BM + BN) * ROWB;
-  static_assert(BM * CH % NT == 0 && BN * CH % NT == 0, "tile rows must divide over the waves");
+  constexpr int CH = BK / 8, ROWB = BK * 2, RPL = 64 / CH, SH = 1;   // 8 chunks, 128-byte rows
+  constexpr int KK = BK / 16;                                        // MFMA k-steps per stage
+  constexpr int B_LOADS = BN * CH / NT;
+  // wave-wide load j of the token part fills tile rows [64j, 64j+64): only NACT of them matter
+  constexpr int A_LOADS = NACT;
+  static_assert(BM * CH / NT == 4 && B_LOADS == 4, "load bookkeeping below assumes 4 + 4");
+  constexpr int PART = BM * ROWB;                 // 32 KB: one token part or one weight part
+  constexpr int NM = NACT * NF;     // MFMAs per k-step
+  constexpr int NR = NACT + NF;     // fragment reads per k-step
+  static_assert(NACT >= 1 && NACT <= MF, "active fragments");
   static_assert(!UP || NF % 2 == 0, "gate and up halves per wave");
-  static_assert(NST >= 2 && NST <= 4 && (NST - 2) * LPS < 64, "stage count");
-  extern __shared__ __align__(1024) unsigned char lds[];
+  // LDS map: token parts A0, A1 (two stages), then weight parts B0, B1, B2 (three stages)
+  auto a_part = [&](int stage) { return lds + (stage & 1) * PART; };
+  auto b_part = [&](int slot) { return lds + (kStagesA + slot) * PART; };
 
-  const int lane = threadIdx.x & 63;
-  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const TileCoord<BM, BN, UP> tc = find_tile<BM, BN, UP>(a, lane);
-  if (!tc.valid) return;
-  const int e_i = tc.i, g = tc.g, F = tc.F;
+  const int g = rec.e / a.N, e_i = rec.e % a.N, F = a.F[g];
   const int K = UP ? a.d : F;
-  const int rows_left = tc.rows - tc.m0;           // valid token rows in this tile (>= 1)
+  const int wm = w / WGN, wn = w % WGN;
 
-  // ---- global source pointers of this thread's 16-byte chunks -------------------
-  // load instruction j of wave w fills LDS tile rows (j*NWAVES + w)*RPL .. +RPL-1; lane l
-  // fills row l/CH, physical chunk l%CH, which holds logical chunk (l%CH) ^ swz(row).
+  // ---- global source pointers of this thread's 16-byte chunks -------------------------
+  // wave-wide load j fills tile rows (j*NWAVES + w)*RPL .. +RPL-1; lane l fills row l/CH,
+  // physical chunk l%CH, which holds logical chunk (l%CH) ^ ((row >> SH) & (CH-1)).
   const int lrow = lane / CH, lpos = lane % CH;
-  const uint16_t* a_src[A_LOADS];
-  const uint16_t* b_src[B_LOADS];
+  const uint16_t* src_a[A_LOADS];
+  const uint16_t* src_b[B_LOADS];
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
     const int row = (j * NWAVES + w) * RPL + lrow;
-    int rr = tc.m0 + row;
-    if (rr > tc.rows - 1) rr = tc.rows - 1;         // rows past the expert's end: any valid row
-    const int pos = tc.row0 + rr;
+    const int rr = row < rec.rows ? row : rec.rows - 1;     // rows past the end: any valid row
+    const int pos = rec.row_start + rr;
     long long src_row;
     if constexpr (UP) src_row = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
     else src_row = pos;
     const int chunk = lpos ^ ((row >> SH) & (CH - 1));
-    a_src[j] = a.A + src_row * a.lda + chunk * 8;
+    src_a[j] = a.A + src_row * a.lda + chunk * 8;
   }
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j) {
@@ -187,29 +254,28 @@ __global__ void __launch_bounds__(64 * WGM * WGN) ffn_tile_kernel(const TileArgs
     if constexpr (UP) {
       // tile rows [0, BN/2): W_gate rows n0.., rows [BN/2, BN): W_up rows n0..
       const int half = row >= BN / 2;
-      int f = tc.n0 + (row - half * (BN / 2));
+      int f = rec.n0 + (row - half * (BN / 2));
       if (f > F - 1) f = F - 1;
       wrow = (long long)e_i * 2 * F + (long long)half * F + f;
     } else {
-      int n = tc.n0 + row;
+      int n = rec.n0 + row;
       if (n > a.d - 1) n = a.d - 1;
       wrow = (long long)e_i * a.d + n;
     }
-    b_src[j] = a.W[g] + wrow * K + chunk * 8;
+    src_b[j] = a.W[g] + wrow * K + chunk * 8;
   }
+  const int ld_off = w * 1024;      // + j * NWAVES * 1024: wave-uniform destination inside a part
 
-  // ---- LDS read offsets of the MFMA operand fragments ----------------------------
+  // ---- LDS offsets of the MFMA operand fragments ---------------------------------------
   // fragment row = base + lane%32, logical chunk = 2*kk + lane/32
   const int frow = lane & 31, fh = lane >> 5;
   int foff[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk)
     foff[kk] = frow * ROWB + (((2 * kk + fh) ^ ((frow >> SH) & (CH - 1))) << 4);
-  const int wm = w / WGN, wn = w % WGN;
-  // token fragments live in the A part, weight fragments in the B part of a stage
-  int xbase[MF], wbase[NF];
+  int fbase[NR];     // token fragments first (interleaved over the wave rows), then weights
 #pragma unroll
-  for (int ti = 0; ti < MF; ++ti) xbase[ti] = (wm * WTM + ti * 32) * ROWB;
+  for (int ti = 0; ti < NACT; ++ti) fbase[ti] = ((ti * WGM + wm) * 32) * ROWB;
 #pragma unroll
   for (int fi = 0; fi < NF; ++fi) {
     int row;
@@ -219,432 +285,272 @@ __global__ void __launch_bounds__(64 * WGM * WGN) ffn_tile_kernel(const TileArgs
     } else {
       row = wn * WTN + fi * 32;
     }
-    wbase[fi] = BM * ROWB + row * ROWB;
+    fbase[NACT + fi] = row * ROWB;
   }
 
-  f32x16 acc[NF][MF];
+  f32x16 acc[NF][NACT];
 #pragma unroll
   for (int fi = 0; fi < NF; ++fi)
 #pragma unroll
-    for (int ti = 0; ti < MF; ++ti)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[fi][ti][r] = 0.f;
-
-  auto issue = [&](int stage, int k0) {
-    unsigned char* sb = lds + stage * STAGE_BYTES;
-#pragma unroll
-    for (int j = 0; j < A_LOADS; ++j)
-      async_copy16(a_src[j] + k0, sb + (j * NWAVES + w) * 1024);
-#pragma unroll
-    for (int j = 0; j < B_LOADS; ++j)
-      async_copy16(b_src[j] + k0, sb + BM * ROWB + (j * NWAVES + w) * 1024);
-  };
-
-  // NST-stage pipeline: stage kt+NST-1 is requested while stage kt is consumed
-  const int KT = K / BK;
-#pragma unroll
-  for (int s = 0; s < NST - 1; ++s)
-    if (s < KT) issue(s, s * BK);
-  for (int kt = 0; kt < KT; ++kt) {
-    // wait until this thread's loads of stage kt have landed: at most `ahead` later stages
-    // may still be in flight
-    int ahead = KT - 1 - kt;
-    if (ahead > NST - 2) ahead = NST - 2;
-    if (PROBE == PROBE_NO_LOADS && kt >= 1) ahead = 3;
-    if (ahead == 0) wait_vmcnt<0>();
-    else if (ahead == 1) wait_vmcnt<LPS>();
-    else if (ahead == 2) wait_vmcnt<(NST > 3 ? 2 * LPS : 0)>();
-    __syncthreads();
-    if (kt + NST - 1 < KT && (PROBE != PROBE_NO_LOADS))
-      issue((kt + NST - 1) % NST, (kt + NST - 1) * BK);
-    const unsigned char* sb = lds + (kt % NST) * STAGE_BYTES;
-    if constexpr (PROBE != PROBE_NO_MFMA) {
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        bf16x8 xf[MF], wf[NF];
-#pragma unroll
-        for (int ti = 0; ti < MF; ++ti) xf[ti] = *reinterpret_cast<const bf16x8*>(sb + xbase[ti] + foff[kk]);
-#pragma unroll
-        for (int fi = 0; fi < NF; ++fi) wf[fi] = *reinterpret_cast<const bf16x8*>(sb + wbase[fi] + foff[kk]);
-#pragma unroll
-        for (int fi = 0; fi < NF; ++fi)
-#pragma unroll
-          for (int ti = 0; ti < MF; ++ti)
-            acc[fi][ti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[fi], xf[ti], acc[fi][ti], 0, 0, 0);
-      }
-    }
-  }
-
-  // ---- epilogue: lane holds, per 32x32 block, token lane%32 and weight rows
-  // 8*(r/4) + 4*(lane/32) + r%4, i.e. 4 runs of 4 consecutive output features ---------
-  const int tok_l = lane & 31, fsub = (lane >> 5) * 4;
-  constexpr int NFo = UP ? NF / 2 : NF;
-  const int ncols = UP ? F : a.d;
-#pragma unroll
-  for (int ti = 0; ti < MF; ++ti) {
-    const int trow = wm * WTM + ti * 32 + tok_l;
-    if (trow >= rows_left) continue;
-    uint16_t* crow = a.C + (long long)(tc.row0 + tc.m0 + trow) * a.ldc;
-#pragma unroll
-    for (int fi = 0; fi < NFo; ++fi) {
-      const int cbase = tc.n0 + (UP ? wn * (WTN / 2) : wn * WTN) + fi * 32 + fsub;
-#pragma unroll
-      for (int blk = 0; blk < 4; ++blk) {
-        const int col = cbase + blk * 8;
-        float v[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          if constexpr (UP) {
-            const float gt = acc[fi][ti][blk * 4 + b], up = acc[fi + NF / 2][ti][blk * 4 + b];
-            v[b] = gt / (1.f + __expf(-gt)) * up;
-          } else {
-            v[b] = acc[fi][ti][blk * 4 + b];
-          }
-        }
-        if (col < ncols) {
-          uint2 o;
-          o.x = pack_bf16x2(v[0], v[1]);
-          o.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2*>(crow + col) = o;
-        }
-      }
-    }
-  }
-}
-
-// ------------------------------------------------------------------------------------
-// Second generation of the tile kernel: 256 x 256 tile, BK = 32, four LDS stages, and a
-// hand-ordered inner loop.  One workgroup barrier per stage sits in the MIDDLE of the
-// stage's matrix-core work: operand fragments for the next 16-deep slice are read from LDS
-// into a second register set while the current set feeds the MFMAs, and the global -> LDS
-// requests for the stage three ahead are issued between MFMAs, so that neither LDS latency
-// nor the barrier nor the address arithmetic of the loads leaves the matrix core idle.
-//   stage kt, first half : MFMA(set0) interleaved with ds_read(stage kt, k 16..31 -> set1)
-//   middle               : wait for this thread's loads of stage kt+1, barrier
-//   stage kt, second half: MFMA(set1) interleaved with ds_read(stage kt+1, k 0..15 -> set0)
-//                          and the loads of stage kt+3 (its buffer held stage kt-1, which
-//                          every wave has left once it passed the barrier)
-#define MOHGE_PIN() __builtin_amdgcn_sched_barrier(0)
-
-template <int WGM, int WGN, bool UP, int PROBE>
-__global__ void __launch_bounds__(64 * WGM * WGN) ffn_tile_kernel_v2(const TileArgs a) {
-  constexpr int BM = 256, BN = 256, BK = 32, NST = 4;
-  constexpr int NWAVES = WGM * WGN, NT = 64 * NWAVES;
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;
-  constexpr int MF = WTM / 32, NF = WTN / 32;
-  constexpr int CH = 4, ROWB = 64, RPL = 16, SH = 2;
-  constexpr int A_LOADS = BM * CH / NT, B_LOADS = BN * CH / NT, LPS = A_LOADS + B_LOADS;
-  constexpr int STAGE_BYTES = (BM + BN) * ROWB;
-  constexpr int NM = MF * NF;       // MFMAs per half stage
-  constexpr int NR = MF + NF;       // fragment reads per half stage
-  static_assert(!UP || NF % 2 == 0, "gate and up halves per wave");
-  static_assert(NR <= NM && LPS <= NM, "interleave slots");
-  extern __shared__ __align__(1024) unsigned char lds[];
-
-  const int lane = threadIdx.x & 63;
-  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  long long ts[8];
-  ts[0] = __builtin_amdgcn_s_memtime();
-  const TileCoord<BM, BN, UP> tc = find_tile<BM, BN, UP>(a, lane);
-  if (!tc.valid) return;
-  ts[1] = __builtin_amdgcn_s_memtime();
-  const int e_i = tc.i, g = tc.g, F = tc.F;
-  const int K = UP ? a.d : F;
-  const int rows_left = tc.rows - tc.m0;
-
-  const int lrow = lane / CH, lpos = lane % CH;
-  const uint16_t* src[LPS];
-#pragma unroll
-  for (int j = 0; j < A_LOADS; ++j) {
-    const int row = (j * NWAVES + w) * RPL + lrow;
-    int rr = tc.m0 + row;
-    if (rr > tc.rows - 1) rr = tc.rows - 1;
-    const int pos = tc.row0 + rr;
-    long long src_row;
-    if constexpr (UP) src_row = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
-    else src_row = pos;
-    const int chunk = lpos ^ ((row >> SH) & (CH - 1));
-    src[j] = a.A + src_row * a.lda + chunk * 8;
-  }
-#pragma unroll
-  for (int j = 0; j < B_LOADS; ++j) {
-    const int row = (j * NWAVES + w) * RPL + lrow;
-    const int chunk = lpos ^ ((row >> SH) & (CH - 1));
-    long long wrow;
-    if constexpr (UP) {
-      const int half = row >= BN / 2;
-      int f = tc.n0 + (row - half * (BN / 2));
-      if (f > F - 1) f = F - 1;
-      wrow = (long long)e_i * 2 * F + (long long)half * F + f;
-    } else {
-      int n = tc.n0 + row;
-      if (n > a.d - 1) n = a.d - 1;
-      wrow = (long long)e_i * a.d + n;
-    }
-    src[A_LOADS + j] = a.W[g] + wrow * K + chunk * 8;
-  }
-  // LDS destination (wave-uniform) of load j inside a stage
-  auto dst_off = [&](int j) {
-    return j < A_LOADS ? (j * NWAVES + w) * 1024 : BM * ROWB + ((j - A_LOADS) * NWAVES + w) * 1024;
-  };
-
-  const int frow = lane & 31, fh = lane >> 5;
-  int foff[2];
-#pragma unroll
-  for (int kk = 0; kk < 2; ++kk)
-    foff[kk] = frow * ROWB + (((2 * kk + fh) ^ ((frow >> SH) & (CH - 1))) << 4);
-  const int wm = w / WGN, wn = w % WGN;
-  int fbase[NR];     // token fragments first, then weight fragments
-#pragma unroll
-  for (int ti = 0; ti < MF; ++ti) fbase[ti] = (wm * WTM + ti * 32) * ROWB;
-#pragma unroll
-  for (int fi = 0; fi < NF; ++fi) {
-    int row;
-    if constexpr (UP) {
-      constexpr int NFh = NF / 2;
-      row = (fi < NFh) ? wn * (WTN / 2) + fi * 32 : BN / 2 + wn * (WTN / 2) + (fi - NFh) * 32;
-    } else {
-      row = wn * WTN + fi * 32;
-    }
-    fbase[MF + fi] = BM * ROWB + row * ROWB;
-  }
-
-  f32x16 acc[NF][MF];
-#pragma unroll
-  for (int fi = 0; fi < NF; ++fi)
-#pragma unroll
-    for (int ti = 0; ti < MF; ++ti)
+    for (int ti = 0; ti < NACT; ++ti)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[fi][ti][r] = 0.f;
 
   const int KT = K / BK;
-  auto issue_stage = [&](int st) {
-    unsigned char* sb = lds + (st & (NST - 1)) * STAGE_BYTES;
-#pragma unroll
-    for (int j = 0; j < LPS; ++j) async_copy16(src[j] + st * BK, sb + dst_off(j));
+  // fragment r of k-step kk of the stage whose parts are pa (tokens) / pb (weights)
+  auto read_frag = [&](const unsigned char* pa, const unsigned char* pb, int kk, int r) {
+    return *reinterpret_cast<const bf16x8*>((r < NACT ? pa : pb) + fbase[r] + foff[kk]);
   };
-  auto read_frag = [&](const unsigned char* sb, int kk, int r) {
-    return *reinterpret_cast<const bf16x8*>(sb + fbase[r] + foff[kk]);
+  auto issue_a = [&](int stage, int j) {
+    async_copy16(src_a[j] + stage * BK, a_part(stage) + j * NWAVES * 1024 + ld_off);
+  };
+  auto issue_b = [&](int stage, int slot, int j) {
+    async_copy16(src_b[j] + stage * BK, b_part(slot) + j * NWAVES * 1024 + ld_off);
   };
 
-  // prologue: request stages 0..2, wait for stage 0, read its first fragments
-  ts[2] = __builtin_amdgcn_s_memtime();
+  // prologue: request A(0), B(0), B(1); wait for A(0), B(0); read the first fragments
+  PROBE_T(1);
+  __syncthreads();                  // the previous tile's epilogue has left the LDS
 #pragma unroll
-  for (int st = 0; st < NST - 1; ++st)
-    if (st < KT) issue_stage(st);
-  if (KT >= 3) wait_vmcnt<2 * LPS>();
-  else if (KT == 2) wait_vmcnt<LPS>();
-  else wait_vmcnt<0>();
+  for (int j = 0; j < A_LOADS; ++j) issue_a(0, j);
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) issue_b(0, 0, j);
+  if (KT > 1) {
+#pragma unroll
+    for (int j = 0; j < B_LOADS; ++j) issue_b(1, 1, j);
+    wait_vmcnt<B_LOADS>();
+  } else {
+    wait_vmcnt<0>();
+  }
   __builtin_amdgcn_s_barrier();
   MOHGE_PIN();
-  ts[3] = __builtin_amdgcn_s_memtime();
+  PROBE_T(2);
   bf16x8 f0[NR], f1[NR];
 #pragma unroll
-  for (int r = 0; r < NR; ++r) f0[r] = read_frag(lds, 0, r);
+  for (int r = 0; r < NR; ++r) f0[r] = read_frag(a_part(0), b_part(0), 0, r);
 
-  // one half stage: NM MFMAs on `use`; after MFMA i the i-th fragment read into `nxt`; the
-  // last LPS MFMAs are each followed by one global -> LDS request when LOADS is set
-  auto half = [&](bf16x8 (&use)[NR], bf16x8 (&nxt)[NR], const unsigned char* sb_next, int kk_next,
-                  auto LOADS, int st_load) {
+  // One k-step: NM MFMAs on `use`; after MFMA i the extra instructions of this k-step are
+  // placed round-robin: first the NR fragment reads of the next k-step into `nxt`, then the
+  // global -> LDS requests handed in as `nld` callables.
+  auto kstep = [&](bf16x8 (&use)[NR], bf16x8 (&nxt)[NR], auto READ_NEXT, const unsigned char* pa,
+                   const unsigned char* pb, int kk_next, auto NLD, auto&& issue_one) {
+    constexpr bool RN = decltype(READ_NEXT)::value;
+    constexpr int NL = decltype(NLD)::value;
+    constexpr int NX = (RN ? NR : 0) + NL;
+    constexpr int PER = (NX + NM - 1) / NM;
 #pragma unroll
     for (int i = 0; i < NM; ++i) {
-      const int fi = i / MF, ti = i % MF;
-      if constexpr (PROBE != PROBE_NO_MFMA)
-        acc[fi][ti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(use[MF + fi], use[ti], acc[fi][ti], 0, 0, 0);
+      const int fi = i / NACT, ti = i % NACT;
+      acc[fi][ti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(use[NACT + fi], use[ti], acc[fi][ti], 0, 0, 0);
       MOHGE_PIN();
-      if (i < NR) {
-        if constexpr (PROBE != PROBE_NO_MFMA) nxt[i] = read_frag(sb_next, kk_next, i);
-        MOHGE_PIN();
-      }
-      if constexpr (decltype(LOADS)::value) {
-        if (i >= NM - LPS) {
-          const int j = i - (NM - LPS);
-          unsigned char* sb = lds + (st_load & (NST - 1)) * STAGE_BYTES;
-          async_copy16(src[j] + st_load * BK, sb + dst_off(j));
+#pragma unroll
+      for (int q = 0; q < PER; ++q) {
+        const int x = i * PER + q;
+        if (RN && x < NR) {
+          nxt[x] = read_frag(pa, pb, kk_next, x);
+          MOHGE_PIN();
+        } else if (x < NX) {
+          issue_one(x - (RN ? NR : 0));
           MOHGE_PIN();
         }
       }
     }
   };
 
-  auto stage = [&](int kt, auto LOADS) {
-    const unsigned char* sb = lds + (kt & (NST - 1)) * STAGE_BYTES;
-    const unsigned char* sbn = lds + ((kt + 1) & (NST - 1)) * STAGE_BYTES;
-    half(f0, f1, sb, 1, std::false_type{}, 0);
-    // stage kt+1 must be complete before anyone reads it in the second half
-    if (PROBE != PROBE_NO_LOADS) {
-      if (kt + 2 < KT) wait_vmcnt<LPS>();
-      else wait_vmcnt<0>();
+  // Stage kt: token part kt&1, weight slot `slot`.  While it runs, the token part of stage
+  // kt+1 (its buffer was freed by the barrier that ended stage kt-1) and the weight part of
+  // stage kt+2 (slot of stage kt-1) are requested, tokens first, so that "all but the newest
+  // B_LOADS requests have landed" certifies stage kt+1 at the end.
+  int slot = 0;
+  auto stage = [&](int kt, auto LA, auto LB, auto LAST) {
+    constexpr bool la = decltype(LA)::value, lb = decltype(LB)::value, last = decltype(LAST)::value;
+    const unsigned char* pa = a_part(kt);
+    const unsigned char* pb = b_part(slot);
+    const int slot1 = slot == kStagesB - 1 ? 0 : slot + 1;     // stage kt+1
+    const int slot2 = slot == 0 ? kStagesB - 1 : slot - 1;     // stage kt+2 (= freed slot of kt-1)
+    using c0 = std::integral_constant<int, 0>;
+    using cA = std::integral_constant<int, la ? A_LOADS : 0>;
+    using cB = std::integral_constant<int, lb ? B_LOADS : 0>;
+    kstep(f0, f1, std::true_type{}, pa, pb, 1, cA{}, [&](int j) { issue_a(kt + 1, j); });
+    kstep(f1, f0, std::true_type{}, pa, pb, 2, cB{}, [&](int j) { issue_b(kt + 2, slot2, j); });
+    kstep(f0, f1, std::true_type{}, pa, pb, 3, c0{}, [&](int) {});
+    kstep(f1, f0, std::false_type{}, pa, pb, 0, c0{}, [&](int) {});
+    if constexpr (!last) {
+      if constexpr (lb) wait_vmcnt<B_LOADS>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      MOHGE_PIN();
+#pragma unroll
+      for (int r = 0; r < NR; ++r) f0[r] = read_frag(a_part(kt + 1), b_part(slot1), 0, r);
+      MOHGE_PIN();
     }
-    __builtin_amdgcn_s_barrier();
-    MOHGE_PIN();
-    half(f1, f0, sbn, 0, LOADS, kt + NST - 1);
+    slot = slot1;
   };
 
-  int kt = 0;
-  if constexpr (PROBE != PROBE_NO_LOADS) {
-    for (; kt + NST - 1 < KT; ++kt) stage(kt, std::true_type{});
+  {
+    using T = std::true_type;
+    using Fa = std::false_type;
+    int kt = 0;
+    for (; kt + 2 < KT; ++kt) stage(kt, T{}, T{}, Fa{});
+    if (kt + 1 < KT) { stage(kt, T{}, Fa{}, Fa{}); ++kt; }
+    stage(kt, Fa{}, Fa{}, T{});
   }
-  for (; kt < KT; ++kt) stage(kt, std::false_type{});
-  ts[4] = __builtin_amdgcn_s_memtime();
+  PROBE_T(3);
 
   // ---- epilogue: accumulators -> bf16 -> a wave-private LDS patch -> 16-byte stores ------
   // A lane holds, per 32x32 block, token lane%32 and weight rows 8*(r/4) + 4*(lane/32) +
-  // r%4: runs of 4 consecutive output features.  Writing those straight to global memory
-  // scatters 8-byte pieces over 32 rows per instruction; instead every wave transposes its
-  // part through LDS (row stride padded by 16 bytes against bank conflicts) and stores whole
-  // 128- or 256-byte row segments.
+  // r%4: runs of 4 consecutive output features.  Every wave transposes its part through
+  // LDS (row stride padded by 16 bytes against bank conflicts) and stores row segments.
   __syncthreads();                     // all waves are done reading the stages
   {
     constexpr int OC = UP ? WTN / 2 : WTN;           // output features of this wave
     constexpr int RS = OC * 2 + 16;                  // LDS row stride in bytes
-    constexpr int TPP = (NWAVES * WTM * RS <= NST * STAGE_BYTES) ? WTM : WTM / 2;   // tokens per pass
-    constexpr int EPI_BYTES = TPP * RS;
+    constexpr int EPI_BYTES = 32 * RS;               // one 32-token fragment at a time
     constexpr int CPR = OC * 2 / 16;                 // 16-byte chunks per row
     constexpr int NFo = UP ? NF / 2 : NF;
-    static_assert(NWAVES * EPI_BYTES <= NST * STAGE_BYTES, "epilogue patch must fit the stage buffers");
-    static_assert(TPP * CPR % 64 == 0 && TPP % 32 == 0, "whole wave-wide copies");
+    static_assert(NWAVES * EPI_BYTES <= (kStagesA + kStagesB) * PART, "epilogue patch must fit the stage buffers");
+    static_assert(32 * CPR % 64 == 0, "whole wave-wide copies");
     unsigned char* my = lds + w * EPI_BYTES;
     const int tok_l = lane & 31, fsub = (lane >> 5) * 4;
     const int ncols = UP ? F : a.d;
-    const int col0 = tc.n0 + wn * OC;
+    const int col0 = rec.n0 + wn * OC;
 #pragma unroll
-    for (int pass = 0; pass < WTM / TPP; ++pass) {
+    for (int ti = 0; ti < NACT; ++ti) {
 #pragma unroll
-      for (int tl = 0; tl < TPP / 32; ++tl) {
-        const int ti = pass * (TPP / 32) + tl;
+      for (int fi = 0; fi < NFo; ++fi)
 #pragma unroll
-        for (int fi = 0; fi < NFo; ++fi)
+        for (int blk = 0; blk < 4; ++blk) {
+          float v[4];
 #pragma unroll
-          for (int blk = 0; blk < 4; ++blk) {
-            float v[4];
-#pragma unroll
-            for (int b = 0; b < 4; ++b) {
-              if constexpr (UP) v[b] = swiglu(acc[fi][ti][blk * 4 + b], acc[fi + NF / 2][ti][blk * 4 + b]);
-              else v[b] = acc[fi][ti][blk * 4 + b];
-            }
-            uint2 o;
-            o.x = pack_bf16x2(v[0], v[1]);
-            o.y = pack_bf16x2(v[2], v[3]);
-            *reinterpret_cast<uint2*>(my + (tl * 32 + tok_l) * RS + (fi * 32 + blk * 8 + fsub) * 2) = o;
+          for (int b = 0; b < 4; ++b) {
+            if constexpr (UP) v[b] = swiglu(acc[fi][ti][blk * 4 + b], acc[fi + NF / 2][ti][blk * 4 + b]);
+            else v[b] = acc[fi][ti][blk * 4 + b];
           }
-      }
+          uint2 o;
+          o.x = pack_bf16x2(v[0], v[1]);
+          o.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>(my + tok_l * RS + (fi * 32 + blk * 8 + fsub) * 2) = o;
+        }
 #pragma unroll
-      for (int it = 0; it < TPP * CPR / 64; ++it) {
+      for (int it = 0; it < 32 * CPR / 64; ++it) {
         const int idx = it * 64 + lane;
         const int row = idx / CPR, c = idx % CPR;
         const uint4 v = *reinterpret_cast<const uint4*>(my + row * RS + c * 16);
-        const int trow = wm * WTM + pass * TPP + row;
+        const int trow = (ti * WGM + wm) * 32 + row;
         const int col = col0 + c * 8;
-        if (trow < rows_left && col < ncols)
-          *reinterpret_cast<uint4*>(a.C + (long long)(tc.row0 + tc.m0 + trow) * a.ldc + col) = v;
+        if (trow < rec.rows && col < ncols)
+          *reinterpret_cast<uint4*>(a.C + (long long)(rec.row_start + trow) * a.ldc + col) = v;
       }
     }
   }
-  if (a.dbg) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    ts[5] = __builtin_amdgcn_s_memtime();
-    if (threadIdx.x == 0) {
-      for (int i = 0; i < 6; ++i) a.dbg[(size_t)blockIdx.x * 8 + i] = ts[i];
-      a.dbg[(size_t)blockIdx.x * 8 + 6] = KT;
-      a.dbg[(size_t)blockIdx.x * 8 + 7] = __builtin_amdgcn_s_getreg((4 << 0) | (8 << 6) | ((4 - 1) << 11));  // HW_ID bits: cu/se ids
-    }
+#ifdef MOHGE_PROBE
+  PROBE_T(4);
+  if (a.dbg && threadIdx.x == 0) {
+    long long* d = a.dbg + (size_t)blockIdx.x * 8;
+    for (int i = 0; i < 4; ++i) d[i] += ts[i + 1] - ts[i];
+    d[4] += 1;
+    d[5] += KT;
   }
-}
-
-template <int WGM, int WGN, bool UP, int PROBE = 0>
-static hipError_t launch_tile_v2(const TileArgs& a, int P, int maxcols, hipStream_t s) {
-  constexpr int BM = 256, BN = 256;
-  constexpr int NCOLS_PER_TILE = UP ? BN / 2 : BN;
-  constexpr size_t smem = (size_t)4 * (BM + BN) * 32 * 2;
-  auto kern = ffn_tile_kernel_v2<WGM, WGN, UP, PROBE>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  const long long mt_bound = (long long)P / BM + a.Ne;
-  const long long nt_max = (maxcols + NCOLS_PER_TILE - 1) / NCOLS_PER_TILE;
-  long long grid = mt_bound * nt_max;
-  grid = (grid + 7) / 8 * 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), smem, s, a);
-  return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int NST, int WGM, int WGN, bool UP, int PROBE = 0>
-static hipError_t launch_tile(const TileArgs& a, int P, int maxcols, hipStream_t s) {
-  constexpr int NCOLS_PER_TILE = UP ? BN / 2 : BN;
-  constexpr size_t smem = (size_t)NST * (BM + BN) * BK * 2;
-  static_assert(smem <= 160 * 1024, "LDS per workgroup");
-  auto kern = ffn_tile_kernel<BM, BN, BK, NST, WGM, WGN, UP, PROBE>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
-  // upper bound on the number of tiles: every expert adds at most one partial row tile
-  const long long mt_bound = (long long)P / BM + a.Ne;
-  const long long nt_max = (maxcols + NCOLS_PER_TILE - 1) / NCOLS_PER_TILE;
-  long long grid = mt_bound * nt_max;
-  grid = (grid + 7) / 8 * 8;
-  hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(64 * WGM * WGN), smem, s, a);
-  return hipGetLastError();
-}
-
-// tile configuration used by the up / down launch; changed through mohge_tune()
-static int g_variant[2] = {0, 0};
-static long long* g_dbg = nullptr;
-
-void tune_tiled_dbg(void* p) { g_dbg = static_cast<long long*>(p); }
-
-int tune_tiled(int knob, int value) {
-  if (knob < 0 || knob > 1 || value < 0 || value > 31) return -1;
-  g_variant[knob] = value;
-  return 0;
+#endif
 }
 
 template <bool UP>
-static hipError_t launch_variant(int v, const TileArgs& a, int P, int maxcols, hipStream_t s) {
-  switch (v) {
-    case 0: return launch_tile<256, 256, 64, 2, 2, 2, UP>(a, P, maxcols, s);
-    case 1: return launch_tile<256, 256, 32, 4, 2, 2, UP>(a, P, maxcols, s);
-    case 2: return launch_tile<256, 256, 64, 2, 2, 4, UP>(a, P, maxcols, s);
-    case 3: return launch_tile<256, 256, 32, 4, 2, 4, UP>(a, P, maxcols, s);
-    case 4: return launch_tile<256, 256, 32, 3, 2, 2, UP>(a, P, maxcols, s);
-    case 5: return launch_tile<256, 256, 64, 2, 4, 2, UP>(a, P, maxcols, s);
-    case 6: return launch_tile<256, 128, 64, 3, 2, 2, UP>(a, P, maxcols, s);
-    case 7: return launch_tile<128, 256, 64, 3, 2, 2, UP>(a, P, maxcols, s);
-    case 8: return launch_tile<128, 128, 64, 2, 2, 2, UP>(a, P, maxcols, s);
-    case 9: return launch_tile<256, 256, 64, 2, 2, 2, UP, PROBE_NO_LOADS>(a, P, maxcols, s);
-    case 10: return launch_tile<256, 256, 64, 2, 2, 2, UP, PROBE_NO_MFMA>(a, P, maxcols, s);
-    case 11: return launch_tile<256, 256, 32, 4, 2, 2, UP, PROBE_NO_MFMA>(a, P, maxcols, s);
-    case 12: return launch_tile<256, 256, 64, 2, 2, 4, UP, PROBE_NO_LOADS>(a, P, maxcols, s);
-    case 13: return launch_tile_v2<2, 2, UP>(a, P, maxcols, s);
-    case 14: return launch_tile_v2<4, 2, UP>(a, P, maxcols, s);
-    case 15: return launch_tile_v2<2, 4, UP>(a, P, maxcols, s);
-    case 16: return launch_tile_v2<2, 2, UP, PROBE_NO_LOADS>(a, P, maxcols, s);
-    case 17: return launch_tile_v2<4, 2, UP, PROBE_NO_LOADS>(a, P, maxcols, s);
-    case 18: return launch_tile_v2<2, 2, UP, PROBE_NO_MFMA>(a, P, maxcols, s);
-    default: return hipErrorInvalidValue;
+__global__ void __launch_bounds__(64 * kWGM * kWGN) ffn_tile_kernel(const TileArgs a) {
+  extern __shared__ __align__(1024) unsigned char lds[];
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds, nslot = gridDim.x / kXcds;
+  const int tbeg = a.hdr->xcd_begin[xcd], tend = a.hdr->xcd_begin[xcd + 1];
+  for (int t = tbeg + slot; t < tend; t += nslot) {
+    TileRec rec = a.recs[t];
+    rec.e = __builtin_amdgcn_readfirstlane(rec.e);
+    rec.row_start = __builtin_amdgcn_readfirstlane(rec.row_start);
+    rec.rows = __builtin_amdgcn_readfirstlane(rec.rows);
+    rec.n0 = __builtin_amdgcn_readfirstlane(rec.n0);
+    const int nact = (rec.rows + 63) / 64;
+    if (nact == 4) run_tile<UP, 4>(a, rec, lds, lane, w);
+    else if (nact == 3) run_tile<UP, 3>(a, rec, lds, lane, w);
+    else if (nact == 2) run_tile<UP, 2>(a, rec, lds, lane, w);
+    else run_tile<UP, 1>(a, rec, lds, lane, w);
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------
+static int g_force_rows[2] = {0, 0};
+#ifdef MOHGE_PROBE
+static long long* g_dbg = nullptr;
+extern "C" void mohge_probe_buffer(void* p) { g_dbg = static_cast<long long*>(p); }
+#endif
+
+int tune_tiled(int knob, int value) {
+  if (knob < 0 || knob > 1) return -1;
+  if (value != 0 && value != 64 && value != 128 && value != 192 && value != 256) return -1;
+  g_force_rows[knob] = value;
+  return 0;
+}
+
+static long long max_tiles(const LayerDesc& L, bool up) {
+  // smallest tile height 64 (forced) / 128 (chosen): every expert adds at most one partial tile
+  const long long mt = (long long)L.P / 64 + L.Ne;
+  const int ncols = up ? L.Fmax : L.d;
+  const int ncpt = up ? kBN / 2 : kBN;
+  return mt * ((ncols + ncpt - 1) / ncpt);
+}
+
+// bytes at the start of the workspace reserved for the two schedules
+size_t tiled_sched_bytes(const LayerDesc& L) {
+  size_t b = 0;
+  for (int up = 0; up < 2; ++up) {
+    const size_t n = (size_t)max_tiles(L, up);
+    b += 256 + (n * sizeof(TileRec) + 255) / 256 * 256 + (n * sizeof(long long) + 255) / 256 * 256;
+  }
+  return b;
+}
+
+static int num_cus() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0;
+    hipDeviceProp_t p;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess)
+      n = p.multiProcessorCount;
+    if (n < kXcds) n = 256;
+    n = n / kXcds * kXcds;
+  }
+  return n;
+}
+
+template <bool UP>
+static hipError_t launch_stage(TileArgs a, hipStream_t s) {
+  constexpr size_t smem = (size_t)(kStagesA * kBM + kStagesB * kBN) * kBK * 2;
+  auto kern = ffn_tile_kernel<UP>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL((ffn_schedule_kernel<UP>), dim3(1), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(kern, dim3(a.ncu), dim3(64 * kWGM * kWGN), smem, s, a);
+  return hipGetLastError();
 }
 
 hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* perm,
                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
                             hipStream_t s, int stages) {
+  unsigned char* base = static_cast<unsigned char*>(ws);
+  uint16_t* H = reinterpret_cast<uint16_t*>(base + tiled_sched_bytes(L));
   TileArgs up;
   up.A = static_cast<const uint16_t*>(x);
   up.perm = perm;
   up.offsets = offsets;
-  up.C = static_cast<uint16_t*>(ws);
+  up.C = H;
   up.lda = L.d; up.ldc = L.Fmax;
   up.Ke = L.Ke; up.Ng = L.Ng; up.N = L.N; up.Ne = L.Ne; up.d = L.d;
-  // visit groups by decreasing width so that the longest tiles are scheduled first
+  up.ncu = num_cus();
+  // visit groups by decreasing width: the down projection's longest reductions come first
   int order[kMaxGroups];
   for (int g = 0; g < kMaxGroups; ++g) order[g] = g;
   for (int i = 1; i < L.Ng; ++i)
@@ -656,18 +562,32 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
     up.order[g] = order[g];
     up.W[g] = static_cast<const uint16_t*>(W.w13[g]);
   }
-  up.dbg = g_dbg;
   TileArgs dn = up;
-  dn.A = static_cast<const uint16_t*>(ws);
+  dn.A = H;
   dn.perm = nullptr;
   dn.C = static_cast<uint16_t*>(y_perm);
   dn.lda = L.Fmax; dn.ldc = L.d;
   for (int g = 0; g < kMaxGroups; ++g) dn.W[g] = static_cast<const uint16_t*>(W.w2[g]);
-
+  // schedule areas: [header 256 B][records][cost prefix] for up, then the same for down
+  unsigned char* p = base;
+  for (int st = 0; st < 2; ++st) {
+    TileArgs& t = st == 0 ? up : dn;
+    const size_t n = (size_t)max_tiles(L, st == 0);
+    t.hdr = reinterpret_cast<SchedHeader*>(p);
+    p += 256;
+    t.recs = reinterpret_cast<TileRec*>(p);
+    p += (n * sizeof(TileRec) + 255) / 256 * 256;
+    t.cpfx = reinterpret_cast<long long*>(p);
+    p += (n * sizeof(long long) + 255) / 256 * 256;
+    t.force_rows = g_force_rows[st];
+#ifdef MOHGE_PROBE
+    t.dbg = g_dbg;
+#endif
+  }
   hipError_t e = hipSuccess;
-  if (stages & 1) e = launch_variant<true>(g_variant[0], up, L.P, L.Fmax, s);
+  if (stages & 1) e = launch_stage<true>(up, s);
   if (e != hipSuccess) return e;
-  if (stages & 2) e = launch_variant<false>(g_variant[1], dn, L.P, L.d, s);
+  if (stages & 2) e = launch_stage<false>(dn, s);
   return e;
 }
 

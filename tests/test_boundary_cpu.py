@@ -57,7 +57,8 @@ def test_null_pointers_and_workspace_sizes():
     assert "NULL" in M.mohge_last_error()
     assert M.lib().mohge_route(None, None, None, None, None, None, None, None, None, None, None) == -2
     P = 4096 * 4
-    assert M.mohge_workspace_size(cfg, M.CALL_EXPERT_FFN) == P * 1536 * 2
+    # hidden activations plus the tile schedules of the matrix-core path
+    assert P * 1536 * 2 <= M.mohge_workspace_size(cfg, M.CALL_EXPERT_FFN) <= P * 1536 * 2 + (1 << 20)
     assert M.mohge_workspace_size(cfg, M.CALL_PERMUTE) >= (P // 512) * 24 * 4
     assert M.mohge_workspace_size(cfg, M.CALL_AUX_LOSS) > 0
     assert M.mohge_workspace_size(cfg, 99) == 0
