@@ -11,10 +11,10 @@
 // `offsets` into a list of tiles: up to 256 token rows x 256 weight rows (up: 128 W_gate +
 // the matching 128 W_up rows).  It picks the tile height (128, 192 or 256 rows) that needs
 // the fewest rounds over the compute units, orders tiles so that tiles sharing operands are
-// neighbours and the longest reductions come first, and cuts the list into 8 ranges of
+// neighbours and every stretch of the list mixes all group widths, and cuts the list into 8 ranges of
 // equal cost, one per XCD (each XCD has its own L2).  The GEMM kernel is persistent: one
 // workgroup per compute unit, workgroup b serves XCD b%8 (the hardware hands workgroups
-// to XCDs round-robin) and walks that XCD's range with stride 32.
+// to XCDs round-robin) and draws tiles of that XCD's range from an atomic counter.
 //
 // Tile kernel.  8 waves as 2 (token) x 4 (weight) with wave tiles of 128 x 64; a wave owns
 // the 32-row token fragments {wm, wm+2, wm+4, wm+6}, so a tile with fewer rows keeps both
@@ -30,7 +30,9 @@
 // row's global address is taken through `perm`.
 // The inner loop is ordered by hand (pinned with sched_barrier): operand fragments of the
 // next 16-deep k-step are read from LDS into a second register set and the global -> LDS
-// requests are issued between the MFMAs of the current one; one barrier per stage.
+// requests are issued between the MFMAs of the current one; one barrier per stage, placed
+// after the third of its four k-steps so that the first fragments of the next stage are
+// read under MFMAs as well.
 // The MFMA takes the weight fragment as first operand: a lane then holds 4 consecutive
 // output features of one token; the epilogue packs them to bf16 (hardware conversion),
 // transposes through a wave-private LDS patch and stores whole row segments.
@@ -59,8 +61,10 @@ struct SchedHeader {
   int tile_rows;             // chosen tile height
   int total;                 // number of tiles
   int xcd_begin[kXcds + 1];  // tile ranges per XCD
-  int pad[5];
+  int counters[kXcds];       // next tile of each range not yet handed out
+  int pad[13];
 };
+static_assert(sizeof(SchedHeader) <= 256, "header area");
 
 struct TileArgs {
   const uint16_t* A;          // up: x [T,d] (gathered through perm) or [P,d]; down: H [P,lda]
@@ -69,12 +73,11 @@ struct TileArgs {
   const uint16_t* W[kMaxGroups];   // up: w13[g] [N,2F,d]; down: w2[g] [N,d,F]
   uint16_t* C;                // up: H [P,ldc]; down: y_perm [P,ldc]
   int lda, ldc;
-  int Ke, Ng, N, Ne, d;
+  int Ke, Ng, N, Ne, d, P;
   int F[kMaxGroups];
   int order[kMaxGroups];      // groups in visiting order (longest reduction first)
   SchedHeader* hdr;
   TileRec* recs;
-  long long* cpfx;            // cost of all tiles before tile i
   int ncu;                    // compute units = persistent workgroups
   int force_rows;             // 0 = choose, else 64/128/192/256
 #ifdef MOHGE_PROBE
@@ -88,92 +91,151 @@ struct Shape {
 };
 
 // ---------------------------------------------------------------------------------------
-// schedule: one workgroup, thread v <-> expert at visiting position v
+// schedule: one workgroup of 256 threads per projection; thread v <-> expert at visiting
+// position v for the per-expert quantities, then threads stride over the tiles
 // ---------------------------------------------------------------------------------------
-__device__ __forceinline__ long long block_excl_scan(long long v, long long* sm, long long* total) {
-  // 256 threads, Hillis-Steele in LDS
-  const int t = threadIdx.x;
-  sm[t] = v;
-  __syncthreads();
-  for (int off = 1; off < 256; off <<= 1) {
-    const long long add = t >= off ? sm[t - off] : 0;
-    __syncthreads();
-    sm[t] += add;
-    __syncthreads();
+__device__ __forceinline__ long long wave_incl_scan64(long long v, int lane) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const long long up = __shfl_up(v, off, 64);
+    if (lane >= off) v += up;
   }
-  const long long incl = sm[t];
-  *total = sm[255];
-  __syncthreads();
-  return incl - v;
+  return v;
 }
 
+struct SchedShared {
+  long long tp[kMaxExperts + 1];   // tiles before expert v
+  long long cp[kMaxExperts + 1];   // cost before expert v
+  int e[kMaxExperts], cnt[kMaxExperts], nt[kMaxExperts], kc[kMaxExperts], row0[kMaxExperts];
+  long long wsum[4][3];
+  int rows;
+};
+
 template <bool UP>
-__global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs a) {
-  __shared__ long long sm[256];
-  __shared__ int s_rows;
+__device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& sh) {
   constexpr int NCPT = Shape<UP>::NCOLS_PER_TILE;
-  const int v = threadIdx.x;
-  int e = 0, cnt = 0, nt = 0, kc = 0;
+  const int v = threadIdx.x, lane = v & 63, w = v >> 6;
+  int e = 0, cnt = 0, nt = 0, kc = 0, row0 = 0;
   if (v < a.Ne) {
-    const int g = a.order[v / a.N];
-    e = g * a.N + v % a.N;
-    cnt = a.offsets[e + 1] - a.offsets[e];
+    // visiting order: expert index major, group minor (widest group first): consecutive
+    // experts form "all-size sets", so every XCD range holds the same mix of reduction
+    // lengths instead of one range getting all the long tiles
+    const int g = a.order[v % a.Ng];
+    e = g * a.N + v / a.Ng;
+    row0 = a.offsets[e];
+    cnt = a.offsets[e + 1] - row0;
     const int ncols = UP ? a.F[g] : a.d;
     nt = (ncols + NCPT - 1) / NCPT;
     kc = (UP ? a.d : a.F[g]) / 64;
   }
-  // tile height: fewest rounds over the compute units, weighted by tile cost
-  long long tot;
-  long long kmax = 0;
-  for (int g = 0; g < a.Ng; ++g) kmax = max(kmax, (long long)((UP ? a.d : a.F[g]) / 64));
-  float best = 0.f;
-  int best_rows = 256;
-  for (int h = 256; h >= 128; h -= 64) {
-    const long long w = (long long)((cnt + h - 1) / h) * nt * kc;
-    block_excl_scan(w, sm, &tot);
-    const long long rounds = (tot + (long long)a.ncu * kmax - 1) / ((long long)a.ncu * kmax);
-    const float est = (float)rounds * ((float)(h / 64) + 0.6f);
-    if (h == 256 || est < best) { best = est; best_rows = h; }
+  sh.e[v] = e; sh.cnt[v] = cnt; sh.nt[v] = nt; sh.kc[v] = kc; sh.row0[v] = row0;
+  // tile height: fewest rounds over the compute units, weighted by the reduction length
+  long long cand[3];
+#pragma unroll
+  for (int c = 0; c < 3; ++c) {
+    const int h = 256 - 64 * c;
+    long long x = (long long)((cnt + h - 1) / h) * nt * kc;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
+    cand[c] = x;
   }
-  if (threadIdx.x == 0) s_rows = a.force_rows ? a.force_rows : best_rows;
+  if (lane == 0) { sh.wsum[w][0] = cand[0]; sh.wsum[w][1] = cand[1]; sh.wsum[w][2] = cand[2]; }
   __syncthreads();
-  const int h = s_rows;
-  const int mt = (cnt + h - 1) / h;
-  const int units = (cnt + 63) / 64;
-  long long ttot, ctot;
-  const long long tp = block_excl_scan((long long)mt * nt, sm, &ttot);
-  const long long cp = block_excl_scan((long long)units * nt * kc, sm, &ctot);
-  if (v < a.Ne) {
-    const int row0 = a.offsets[e];
-    for (int ni = 0; ni < nt; ++ni)
-      for (int mi = 0; mi < mt; ++mi) {
-        const long long idx = tp + (long long)ni * mt + mi;
-        TileRec r;
-        r.e = e;
-        r.row_start = row0 + mi * h;
-        r.rows = min(h, cnt - mi * h);
-        r.n0 = ni * NCPT;
-        a.recs[idx] = r;
-        const int before = min(mi * (h / 64), units);
-        a.cpfx[idx] = cp + ((long long)ni * units + before) * kc;
-      }
+  if (v == 0) {
+    long long kmax = 1;
+    for (int g = 0; g < a.Ng; ++g) kmax = max(kmax, (long long)((UP ? a.d : a.F[g]) / 64));
+    float best = 0.f;
+    int best_rows = 256;
+    for (int c = 0; c < 3; ++c) {
+      const long long tot = sh.wsum[0][c] + sh.wsum[1][c] + sh.wsum[2][c] + sh.wsum[3][c];
+      const long long rounds = (tot + (long long)a.ncu * kmax - 1) / ((long long)a.ncu * kmax);
+      const float est = (float)rounds * ((float)(4 - c) + 0.6f);
+      if (c == 0 || est < best) { best = est; best_rows = 256 - 64 * c; }
+    }
+    sh.rows = a.force_rows ? a.force_rows : best_rows;
   }
-  __threadfence();
   __syncthreads();
-  if (threadIdx.x <= kXcds) {
-    const int x = threadIdx.x;
-    int lo = 0, hi = (int)ttot;                 // first tile whose preceding cost >= target
-    const long long target = (ctot * x + kXcds - 1) / kXcds;
-    if (x == kXcds) lo = (int)ttot;
-    else {
+  const int h = sh.rows;
+  // exclusive prefix sums of tiles and cost over the experts
+  const long long my_t = (long long)((cnt + h - 1) / h) * nt;
+  const long long my_c = (long long)((cnt + 63) / 64) * nt * kc;
+  const long long it = wave_incl_scan64(my_t, lane), ic = wave_incl_scan64(my_c, lane);
+  if (lane == 63) { sh.wsum[w][0] = it; sh.wsum[w][1] = ic; }
+  __syncthreads();
+  long long bt = 0, bc = 0;
+  for (int ww = 0; ww < w; ++ww) { bt += sh.wsum[ww][0]; bc += sh.wsum[ww][1]; }
+  sh.tp[v] = bt + it - my_t;
+  sh.cp[v] = bc + ic - my_c;
+  if (v == 255) { sh.tp[256] = bt + it; sh.cp[256] = bc + ic; }
+  __syncthreads();
+  const int total = (int)sh.tp[256];
+  const long long ctot = sh.cp[256];
+  // expert (visiting position) of tile t: last v with tp[v] <= t
+  auto expert_of = [&](int t) {
+    int lo = 0, hi = 255;
+    while (lo < hi) {
+      const int mid = (lo + hi + 1) >> 1;
+      if (sh.tp[mid] <= t) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+  };
+  for (int t = v; t < total; t += 256) {
+    const int ve = expert_of(t);
+    const int c = sh.cnt[ve], mt = (c + h - 1) / h;
+    const int rel = t - (int)sh.tp[ve], ni = rel / mt, mi = rel % mt;
+    TileRec r;
+    r.e = sh.e[ve];
+    r.row_start = sh.row0[ve] + mi * h;
+    r.rows = min(h, c - mi * h);
+    r.n0 = ni * NCPT;
+    a.recs[t] = r;
+  }
+  // XCD x starts at the first tile whose preceding cost is >= x/8 of the total.  Inside an
+  // expert tiles run column tile major, row tile minor, and the cost before tile (ni, mi) is
+  // (ni*units + min(mi*h/64, units)) * kc, so the tile is found arithmetically once the expert
+  // is known.
+  if (v <= kXcds) {
+    int tile = total;
+    if (v < kXcds) {
+      const long long target = (ctot * v + kXcds - 1) / kXcds;
+      int lo = 0, hi = 255;                  // last expert with cp[ve] <= target
       while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (a.cpfx[mid] >= target) hi = mid; else lo = mid + 1;
+        const int mid = (lo + hi + 1) >> 1;
+        if (sh.cp[mid] <= target) lo = mid; else hi = mid - 1;
+      }
+      const int ve = lo;
+      const int c = sh.cnt[ve], kcv = sh.kc[ve];
+      const int rem = (int)(target - sh.cp[ve]);
+      if (rem <= 0 || c == 0 || kcv == 0) {
+        tile = (int)sh.tp[ve];               // (cp[ve] == target: the expert's first tile)
+        if (rem > 0) tile = (int)sh.tp[ve + 1];
+      } else {
+        const int mt = (c + h - 1) / h, units = (c + 63) / 64, hu = h / 64;
+        const int q = (rem + kcv - 1) / kcv;            // row units that must precede the tile
+        int ni = q / units;
+        const int r = q - ni * units;
+        int mi = 0;
+        if (r > 0) {
+          mi = (r + hu - 1) / hu;
+          if (mi >= mt) { mi = 0; ++ni; }
+        }
+        tile = (int)sh.tp[ve] + ni * mt + mi;
+        if (tile > (int)sh.tp[ve + 1]) tile = (int)sh.tp[ve + 1];
       }
     }
-    a.hdr->xcd_begin[x] = lo;
+    a.hdr->xcd_begin[v] = tile;
   }
-  if (threadIdx.x == 0) { a.hdr->tile_rows = h; a.hdr->total = (int)ttot; }
+  // the first ncu/8 tiles of a range are taken statically, one per workgroup
+  if (v < kXcds) a.hdr->counters[v] = a.ncu / kXcds;
+  if (v == 0) { a.hdr->tile_rows = h; a.hdr->total = total; }
+}
+
+// workgroup 0 schedules the up projection, workgroup 1 the down projection (mask bits 0 / 1)
+__global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs up, const TileArgs dn, int mask) {
+  __shared__ SchedShared sh;
+  const int which = (mask == 3) ? (int)blockIdx.x : (mask == 2 ? 1 : 0);
+  if (which == 0) build_schedule<true>(up, sh);
+  else build_schedule<false>(dn, sh);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -308,17 +370,26 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     async_copy16(src_b[j] + stage * BK, b_part(slot) + j * NWAVES * 1024 + ld_off);
   };
 
-  // prologue: request A(0), B(0), B(1); wait for A(0), B(0); read the first fragments
+  // prologue: request B(0), A(0), B(1), A(1), B(2) (those that exist), wait for the first
+  // two, read the first fragments
   PROBE_T(1);
   __syncthreads();                  // the previous tile's epilogue has left the LDS
 #pragma unroll
-  for (int j = 0; j < A_LOADS; ++j) issue_a(0, j);
-#pragma unroll
   for (int j = 0; j < B_LOADS; ++j) issue_b(0, 0, j);
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) issue_a(0, j);
   if (KT > 1) {
 #pragma unroll
     for (int j = 0; j < B_LOADS; ++j) issue_b(1, 1, j);
-    wait_vmcnt<B_LOADS>();
+#pragma unroll
+    for (int j = 0; j < A_LOADS; ++j) issue_a(1, j);
+    if (KT > 2) {
+#pragma unroll
+      for (int j = 0; j < B_LOADS; ++j) issue_b(2, 2, j);
+      wait_vmcnt<2 * B_LOADS + A_LOADS>();
+    } else {
+      wait_vmcnt<B_LOADS + A_LOADS>();
+    }
   } else {
     wait_vmcnt<0>();
   }
@@ -357,31 +428,38 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     }
   };
 
-  // Stage kt: token part kt&1, weight slot `slot`.  While it runs, the token part of stage
-  // kt+1 (its buffer was freed by the barrier that ended stage kt-1) and the weight part of
-  // stage kt+2 (slot of stage kt-1) are requested, tokens first, so that "all but the newest
-  // B_LOADS requests have landed" certifies stage kt+1 at the end.
+  // Stage kt: token part kt&1, weight slot `slot` = kt%3.  The one barrier of the stage comes
+  // after its third k-step, when every wave holds the fragments of the fourth in registers:
+  // from then on nobody reads the stage's LDS parts again, so the token part of stage kt+2 and
+  // the weight part of stage kt+3 are requested into them during the fourth k-step (tokens
+  // first, so that "all but the newest B_LOADS requests have landed" certifies stage kt+1 at
+  // the next barrier), and the first fragments of stage kt+1 are read under the fourth
+  // k-step's MFMAs instead of after a barrier.
   int slot = 0;
   auto stage = [&](int kt, auto LA, auto LB, auto LAST) {
+    // la: stage kt+2 exists (so A(kt+2) is requested and B(kt+2) may be in flight at the
+    // barrier); lb: stage kt+3 exists; last: no stage kt+1
     constexpr bool la = decltype(LA)::value, lb = decltype(LB)::value, last = decltype(LAST)::value;
     const unsigned char* pa = a_part(kt);
     const unsigned char* pb = b_part(slot);
     const int slot1 = slot == kStagesB - 1 ? 0 : slot + 1;     // stage kt+1
-    const int slot2 = slot == 0 ? kStagesB - 1 : slot - 1;     // stage kt+2 (= freed slot of kt-1)
     using c0 = std::integral_constant<int, 0>;
-    using cA = std::integral_constant<int, la ? A_LOADS : 0>;
-    using cB = std::integral_constant<int, lb ? B_LOADS : 0>;
-    kstep(f0, f1, std::true_type{}, pa, pb, 1, cA{}, [&](int j) { issue_a(kt + 1, j); });
-    kstep(f1, f0, std::true_type{}, pa, pb, 2, cB{}, [&](int j) { issue_b(kt + 2, slot2, j); });
+    using cAB = std::integral_constant<int, (la ? A_LOADS : 0) + (lb ? B_LOADS : 0)>;
+    kstep(f0, f1, std::true_type{}, pa, pb, 1, c0{}, [&](int) {});
+    kstep(f1, f0, std::true_type{}, pa, pb, 2, c0{}, [&](int) {});
     kstep(f0, f1, std::true_type{}, pa, pb, 3, c0{}, [&](int) {});
-    kstep(f1, f0, std::false_type{}, pa, pb, 0, c0{}, [&](int) {});
     if constexpr (!last) {
-      if constexpr (lb) wait_vmcnt<B_LOADS>(); else wait_vmcnt<0>();
+      // my reads of this stage are complete; my requests for stage kt+1 have landed
+      if constexpr (la) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(B_LOADS) : "memory");
+      else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
       __builtin_amdgcn_s_barrier();
       MOHGE_PIN();
-#pragma unroll
-      for (int r = 0; r < NR; ++r) f0[r] = read_frag(a_part(kt + 1), b_part(slot1), 0, r);
-      MOHGE_PIN();
+      kstep(f1, f0, std::true_type{}, a_part(kt + 1), b_part(slot1), 0, cAB{}, [&](int j) {
+        if (la && j < A_LOADS) issue_a(kt + 2, j);
+        else issue_b(kt + 3, slot, j - (la ? A_LOADS : 0));
+      });
+    } else {
+      kstep(f1, f0, std::false_type{}, pa, pb, 0, c0{}, [&](int) {});
     }
     slot = slot1;
   };
@@ -390,8 +468,9 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     using T = std::true_type;
     using Fa = std::false_type;
     int kt = 0;
-    for (; kt + 2 < KT; ++kt) stage(kt, T{}, T{}, Fa{});
-    if (kt + 1 < KT) { stage(kt, T{}, Fa{}, Fa{}); ++kt; }
+    for (; kt + 3 < KT; ++kt) stage(kt, T{}, T{}, Fa{});
+    if (kt + 2 < KT) { stage(kt, T{}, Fa{}, Fa{}); ++kt; }
+    if (kt + 1 < KT) { stage(kt, Fa{}, Fa{}, Fa{}); ++kt; }
     stage(kt, Fa{}, Fa{}, T{});
   }
   PROBE_T(3);
@@ -453,24 +532,49 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
 #endif
 }
 
+// Persistent tile kernel: workgroup b serves XCD b % 8.  Its first tile is fixed (range start
+// + b / 8); further tiles are handed out by an atomic counter per range, so a workgroup that
+// drew cheap tiles simply takes more of them.  The counter is read one tile ahead (the
+// atomic's latency hides behind the tile) and the result is passed to the other waves
+// through one LDS word between the tiles.  Which workgroup computes a tile has no influence
+// on the tile's result, so the output stays bit-identical from run to run.
 template <bool UP>
 __global__ void __launch_bounds__(64 * kWGM * kWGN) ffn_tile_kernel(const TileArgs a) {
   extern __shared__ __align__(1024) unsigned char lds[];
+  // LDS word for the hand-over: beyond the epilogue patches, inside a stage buffer that is
+  // dead between a tile's last barrier and the first barrier of the next tile
+  constexpr int kBcastOffset = 40960;
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds, nslot = gridDim.x / kXcds;
-  const int tbeg = a.hdr->xcd_begin[xcd], tend = a.hdr->xcd_begin[xcd + 1];
-  for (int t = tbeg + slot; t < tend; t += nslot) {
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  int tbeg = a.hdr->xcd_begin[xcd], tend = a.hdr->xcd_begin[xcd + 1];
+  const int total = a.hdr->total;
+  if (tbeg < 0) tbeg = 0;
+  if (tend > total) tend = total;
+  int t = tbeg + slot;
+  while (t < tend) {
+    int t_next = 0;
+    if (threadIdx.x == 0) t_next = tbeg + atomicAdd(&a.hdr->counters[xcd], 1);
     TileRec rec = a.recs[t];
     rec.e = __builtin_amdgcn_readfirstlane(rec.e);
     rec.row_start = __builtin_amdgcn_readfirstlane(rec.row_start);
     rec.rows = __builtin_amdgcn_readfirstlane(rec.rows);
     rec.n0 = __builtin_amdgcn_readfirstlane(rec.n0);
-    const int nact = (rec.rows + 63) / 64;
-    if (nact == 4) run_tile<UP, 4>(a, rec, lds, lane, w);
-    else if (nact == 3) run_tile<UP, 3>(a, rec, lds, lane, w);
-    else if (nact == 2) run_tile<UP, 2>(a, rec, lds, lane, w);
-    else run_tile<UP, 1>(a, rec, lds, lane, w);
+    // a record that does not describe rows of this call would mean a corrupted schedule:
+    // skip it rather than touch memory through it
+    const bool ok = !(rec.e < 0 || rec.e >= a.Ne || rec.rows < 1 || rec.rows > kBM ||
+                      rec.row_start < 0 || rec.row_start + rec.rows > a.P || rec.n0 < 0);
+    if (ok) {
+      const int nact = (rec.rows + 63) / 64;
+      if (nact == 4) run_tile<UP, 4>(a, rec, lds, lane, w);
+      else if (nact == 3) run_tile<UP, 3>(a, rec, lds, lane, w);
+      else if (nact == 2) run_tile<UP, 2>(a, rec, lds, lane, w);
+      else run_tile<UP, 1>(a, rec, lds, lane, w);
+    }
+    __syncthreads();       // every wave is past its epilogue (and past reading the old word)
+    if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(lds + kBcastOffset) = t_next;
+    __syncthreads();
+    t = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
   }
 }
 
@@ -479,7 +583,7 @@ __global__ void __launch_bounds__(64 * kWGM * kWGN) ffn_tile_kernel(const TileAr
 // ---------------------------------------------------------------------------------------
 static int g_force_rows[2] = {0, 0};
 #ifdef MOHGE_PROBE
-static long long* g_dbg = nullptr;
+long long* g_dbg = nullptr;
 extern "C" void mohge_probe_buffer(void* p) { g_dbg = static_cast<long long*>(p); }
 #endif
 
@@ -503,7 +607,7 @@ size_t tiled_sched_bytes(const LayerDesc& L) {
   size_t b = 0;
   for (int up = 0; up < 2; ++up) {
     const size_t n = (size_t)max_tiles(L, up);
-    b += 256 + (n * sizeof(TileRec) + 255) / 256 * 256 + (n * sizeof(long long) + 255) / 256 * 256;
+    b += 256 + (n * sizeof(TileRec) + 255) / 256 * 256;
   }
   return b;
 }
@@ -522,7 +626,7 @@ static int num_cus() {
 }
 
 template <bool UP>
-static hipError_t launch_stage(TileArgs a, hipStream_t s) {
+static hipError_t launch_stage(const TileArgs& a, hipStream_t s) {
   constexpr size_t smem = (size_t)(kStagesA * kBM + kStagesB * kBN) * kBK * 2;
   auto kern = ffn_tile_kernel<UP>;
   static bool attr_done = false;
@@ -532,7 +636,6 @@ static hipError_t launch_stage(TileArgs a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL((ffn_schedule_kernel<UP>), dim3(1), dim3(256), 0, s, a);
   hipLaunchKernelGGL(kern, dim3(a.ncu), dim3(64 * kWGM * kWGN), smem, s, a);
   return hipGetLastError();
 }
@@ -548,7 +651,7 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
   up.offsets = offsets;
   up.C = H;
   up.lda = L.d; up.ldc = L.Fmax;
-  up.Ke = L.Ke; up.Ng = L.Ng; up.N = L.N; up.Ne = L.Ne; up.d = L.d;
+  up.Ke = L.Ke; up.Ng = L.Ng; up.N = L.N; up.Ne = L.Ne; up.d = L.d; up.P = L.P;
   up.ncu = num_cus();
   // visit groups by decreasing width: the down projection's longest reductions come first
   int order[kMaxGroups];
@@ -577,14 +680,15 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
     p += 256;
     t.recs = reinterpret_cast<TileRec*>(p);
     p += (n * sizeof(TileRec) + 255) / 256 * 256;
-    t.cpfx = reinterpret_cast<long long*>(p);
-    p += (n * sizeof(long long) + 255) / 256 * 256;
     t.force_rows = g_force_rows[st];
 #ifdef MOHGE_PROBE
     t.dbg = g_dbg;
 #endif
   }
-  hipError_t e = hipSuccess;
+  // both schedules depend only on `offsets`: one launch builds whichever are needed
+  hipLaunchKernelGGL(ffn_schedule_kernel, dim3(stages == 3 ? 2 : 1), dim3(256), 0, s, up, dn, stages);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   if (stages & 1) e = launch_stage<true>(up, s);
   if (e != hipSuccess) return e;
   if (stages & 2) e = launch_stage<false>(dn, s);

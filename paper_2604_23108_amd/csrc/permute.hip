@@ -7,7 +7,9 @@
 // segment again 64 pairs at a time and ranks equal experts inside the 64 with ballots
 // (one ballot per bit of the expert id), so the order inside a bucket is the pair order.
 // Integer LDS atomics only feed counts, so nothing depends on execution order.
-// Up to 2048 pairs the three steps run in one single-workgroup kernel.
+// Up to 2048 pairs the three steps run in one single-workgroup kernel;
+// while segments x experts <= 8192 the scan is folded into the scatter kernel (two launches
+// instead of three).
 #include "common.h"
 
 namespace mohge {
@@ -15,6 +17,7 @@ namespace mohge {
 constexpr int kSegPairs = 512;                 // pairs per wave segment
 constexpr int kWavesPerBlock = 4;
 constexpr int kBlockPairs = kSegPairs * kWavesPerBlock;
+constexpr int kFusedMaxCells = 8192;            // segments x experts that the fused scatter stages in LDS
 
 struct PermArgs {
   const int32_t* eidx;
@@ -63,8 +66,11 @@ __device__ __forceinline__ void wave_scatter(const PermArgs& a, int seg, int lan
     int r = 0;
     if (active) {
       r = base[e] + __popcll(m & lt);
-      a.perm[r] = p;
-      a.inv_perm[p] = r;
+      // (a position outside [0, P) can only come from corrupted bases: never write there)
+      if (r >= 0 && r < a.P) {
+        a.perm[r] = p;
+        a.inv_perm[p] = r;
+      }
     }
     __syncthreads();
     // the highest lane of each set of equal experts advances the bucket cursor
@@ -119,12 +125,57 @@ __global__ void __launch_bounds__(1024) permute_scan_kernel(const PermArgs a) {
   }
 }
 
+// FUSED: the segment histograms are still raw counts; every workgroup sums them itself
+// (column totals -> offsets, counts of earlier segments -> its own bases) instead of reading
+// the output of a separate scan kernel.  Used while the number of segments is small.
+template <bool FUSED>
 __global__ void __launch_bounds__(256) permute_scatter_kernel(const PermArgs a) {
   __shared__ int base[kWavesPerBlock][kMaxExperts];
+  __shared__ int wtot[4];
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int seg = blockIdx.x * kWavesPerBlock + w;
-  const int segc = seg < a.nseg ? seg : a.nseg - 1;
-  for (int e = lane; e < a.Ne; e += 64) base[w][e] = a.seg_hist[(size_t)segc * a.Ne + e] + a.offsets[e];
+  if constexpr (FUSED) {
+    // stage the whole [segment][expert] count matrix in LDS with independent, coalesced
+    // loads (one memory round trip), then walk it per expert
+    __shared__ int hist[kFusedMaxCells];
+    const int cells = a.nseg * a.Ne;
+    for (int i = threadIdx.x; i < cells; i += blockDim.x) hist[i] = a.seg_hist[i];
+    __syncthreads();
+    const int e = threadIdx.x;                      // one expert per thread (Ne <= 256)
+    const int seg0 = blockIdx.x * kWavesPerBlock;
+    int run = 0, pre[kWavesPerBlock] = {0, 0, 0, 0};
+    if (e < a.Ne) {
+      for (int s = 0; s < a.nseg; ++s) {
+#pragma unroll
+        for (int k = 0; k < kWavesPerBlock; ++k)
+          if (s == seg0 + k) pre[k] = run;
+        run += hist[s * a.Ne + e];
+      }
+    }
+    // exclusive scan of the totals over the experts
+    int incl = run;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int up = __shfl_up(incl, off, 64);
+      if (lane >= off) incl += up;
+    }
+    if (lane == 63) wtot[w] = incl;
+    __syncthreads();
+    int off_e = incl - run;
+    for (int ww = 0; ww < w; ++ww) off_e += wtot[ww];
+    if (e < a.Ne) {
+#pragma unroll
+      for (int k = 0; k < kWavesPerBlock; ++k) base[k][e] = off_e + pre[k];
+      if (blockIdx.x == 0) {
+        a.counts[e] = run;
+        a.offsets[e] = off_e;
+        if (e == a.Ne - 1) a.offsets[a.Ne] = off_e + run;
+      }
+    }
+  } else {
+    const int segc = seg < a.nseg ? seg : a.nseg - 1;
+    for (int e = lane; e < a.Ne; e += 64) base[w][e] = a.seg_hist[(size_t)segc * a.Ne + e] + a.offsets[e];
+  }
   __syncthreads();
   // every wave runs the same number of rounds (pairs past P are inactive)
   PermArgs b = a;
@@ -193,8 +244,12 @@ hipError_t launch_permute(const LayerDesc& L, int dtype, const int32_t* expert_i
   } else {
     const int nblk = (a.nseg + kWavesPerBlock - 1) / kWavesPerBlock;
     hipLaunchKernelGGL(permute_hist_kernel, dim3(nblk), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, s, a);
-    hipLaunchKernelGGL(permute_scatter_kernel, dim3(nblk), dim3(256), 0, s, a);
+    if (a.nseg * a.Ne <= kFusedMaxCells) {
+      hipLaunchKernelGGL(permute_scatter_kernel<true>, dim3(nblk), dim3(256), 0, s, a);
+    } else {
+      hipLaunchKernelGGL(permute_scan_kernel, dim3(1), dim3(1024), 0, s, a);
+      hipLaunchKernelGGL(permute_scatter_kernel<false>, dim3(nblk), dim3(256), 0, s, a);
+    }
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -14,6 +14,8 @@
 // counting, softmax inside kept groups, scaling by the group score, expert top-k by
 // rank counting, a ballot + popcount to assign ascending output slots, and a
 // cross-lane sum for the gate normalisation.
+#include <type_traits>
+
 #include "common.h"
 
 namespace mohge {
@@ -36,7 +38,17 @@ struct RouteArgs {
   int Nepad;     // Ne rounded up to 64
   int kslice;    // hidden elements per wave
   int region0;   // bytes of the first LDS region (partial totals / per-wave rows)
+#ifdef MOHGE_PROBE
+  long long* dbg;
+#endif
 };
+
+#ifdef MOHGE_PROBE
+extern long long* g_dbg;
+#define RPROBE(i) ts[i] = __builtin_amdgcn_s_memtime()
+#else
+#define RPROBE(i)
+#endif
 
 template <bool BF16>
 __device__ __forceinline__ void load8(const void* base, size_t elem_off, float (&v)[8]) {
@@ -68,9 +80,13 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = lane & 15, q = lane >> 4;
   const int t0 = blockIdx.x * BT;
-  double* part = reinterpret_cast<double*>(smem);                 // [BT][NC]
+  double* part = reinterpret_cast<double*>(smem);                 // [NW][BT][NC]
   float* lg = reinterpret_cast<float*>(smem + a.region0);         // [BT][NOpad]
 
+#ifdef MOHGE_PROBE
+  long long ts[6];
+#endif
+  RPROBE(0);
   // ---- phase 1: logits ----------------------------------------------------
   size_t xrow[TM];
 #pragma unroll
@@ -97,54 +113,95 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
         for (int i = 0; i < 4; ++i) tot[tm][tn][i] = 0.0;
       }
     const int kbeg = w * a.kslice, kend = kbeg + a.kslice;
-    int step = 0;
-    for (int k = kbeg; k < kend; k += 32, ++step) {
-      float xa[TM][8], wb[TN][8];
+    // The token rows are read exactly once from HBM in small pieces (16 rows x 64 bytes per
+    // wave-wide load), so the loop is bound by memory latency unless many loads are in
+    // flight: all token loads of a chunk of up to XS 32-element steps are requested up
+    // front and kept packed in registers; the router rows (L2 resident) are requested one
+    // step ahead.  The fp32 accumulators are folded into the fp64 totals after every pair of
+    // steps (64 elements).
+    constexpr int XS = BF16 ? 16 : 4;
+    typedef typename std::conditional<BF16, uint4, float4>::type xraw_t;
+    constexpr int XR = BF16 ? 1 : 2;                 // raw registers-of-16-bytes per step
+    for (int kc = kbeg; kc < kend; kc += 32 * XS) {
+      xraw_t xraw[TM][XS][XR];
 #pragma unroll
-      for (int tm = 0; tm < TM; ++tm) load8<BF16>(a.x, xrow[tm] + k + 8 * q, xa[tm]);
+      for (int st = 0; st < XS; ++st)
+        if (kc + 32 * st < kend) {
 #pragma unroll
-      for (int tn = 0; tn < TN; ++tn) load8<false>(wrow[tn], (size_t)(k + 8 * q), wb[tn]);
+          for (int tm = 0; tm < TM; ++tm) {
+            const xraw_t* p = reinterpret_cast<const xraw_t*>(
+                static_cast<const char*>(a.x) + (xrow[tm] + kc + 32 * st + 8 * q) * (BF16 ? 2 : 4));
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-          for (int tn = 0; tn < TN; ++tn)
-            acc[tm][tn] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[tm][j], wb[tn][j], acc[tm][tn], 0, 0, 0);
-      if ((step & 1) || k + 32 >= kend) {
-#pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-          for (int tn = 0; tn < TN; ++tn) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) tot[tm][tn][i] += (double)acc[tm][tn][i];
-            acc[tm][tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int u = 0; u < XR; ++u) xraw[tm][st][u] = p[u];
           }
-      }
-    }
-    // Accumulator element i of lane (r, q) is token 4q+i, router row r of the 16x16
-    // tile.  The waves add their fp64 totals into LDS one after the other (fixed order).
-    for (int ww = 0; ww < NW; ++ww) {
-      if (w == ww) {
+        }
+      float wb[2][TN][8];
 #pragma unroll
-        for (int tm = 0; tm < TM; ++tm)
+      for (int tn = 0; tn < TN; ++tn) load8<false>(wrow[tn], (size_t)(kc + 8 * q), wb[0][tn]);
 #pragma unroll
-          for (int tn = 0; tn < TN; ++tn)
+      for (int st = 0; st < XS; ++st) {
+        const int k = kc + 32 * st;
+        if (k < kend) {
+          if (st + 1 < XS && k + 32 < kend) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              double* dst = &part[(size_t)(16 * tm + 4 * q + i) * NC + 16 * tn + r];
-              *dst = (ww == 0) ? tot[tm][tn][i] : *dst + tot[tm][tn][i];
+            for (int tn = 0; tn < TN; ++tn) load8<false>(wrow[tn], (size_t)(k + 32 + 8 * q), wb[(st + 1) & 1][tn]);
+          }
+          float xa[TM][8];
+#pragma unroll
+          for (int tm = 0; tm < TM; ++tm) {
+            if constexpr (BF16) {
+              const uint4 u = xraw[tm][st][0];
+              xa[tm][0] = __uint_as_float(u.x << 16); xa[tm][1] = __uint_as_float(u.x & 0xffff0000u);
+              xa[tm][2] = __uint_as_float(u.y << 16); xa[tm][3] = __uint_as_float(u.y & 0xffff0000u);
+              xa[tm][4] = __uint_as_float(u.z << 16); xa[tm][5] = __uint_as_float(u.z & 0xffff0000u);
+              xa[tm][6] = __uint_as_float(u.w << 16); xa[tm][7] = __uint_as_float(u.w & 0xffff0000u);
+            } else {
+              const float4 lo = xraw[tm][st][0], hi = xraw[tm][st][XR - 1];
+              xa[tm][0] = lo.x; xa[tm][1] = lo.y; xa[tm][2] = lo.z; xa[tm][3] = lo.w;
+              xa[tm][4] = hi.x; xa[tm][5] = hi.y; xa[tm][6] = hi.z; xa[tm][7] = hi.w;
             }
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+              for (int tn = 0; tn < TN; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[tm][j], wb[st & 1][tn][j], acc[tm][tn], 0, 0, 0);
+          if ((st & 1) || k + 32 >= kend) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+              for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) tot[tm][tn][i] += (double)acc[tm][tn][i];
+                acc[tm][tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+              }
+          }
+        }
       }
-      __syncthreads();
     }
+    RPROBE(1);
+    // Accumulator element i of lane (r, q) is token 4q+i, router row r of the 16x16 tile.
+    // Every wave stores its fp64 totals in its own slice; then they are added in wave order.
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          part[((size_t)w * BT + 16 * tm + 4 * q + i) * NC + 16 * tn + r] = tot[tm][tn][i];
+    __syncthreads();
     for (int idx = threadIdx.x; idx < BT * NC; idx += blockDim.x) {
       const int tl = idx / NC, ol = idx % NC;
-      if (nc + ol < a.NO) lg[tl * a.NOpad + nc + ol] = (float)part[idx];
+      double sum = 0.0;
+      for (int ww = 0; ww < NW; ++ww) sum += part[(size_t)ww * BT * NC + idx];
+      if (nc + ol < a.NO) lg[tl * a.NOpad + nc + ol] = (float)sum;
     }
     __syncthreads();
   }
 
+  RPROBE(2);
   // ---- phase 2: one wavefront per token, lane <-> expert ---------------------
   float* zrow = reinterpret_cast<float*>(smem) + (size_t)w * 4 * a.Nepad;  // biased expert logits
   float* e1row = zrow + a.Nepad;                                            // ES'
@@ -177,8 +234,11 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
       }
     }
 
+    // zrow / e1row / e2row / krow are private to this wave: LDS operations of one wave
+    // complete in order, so only the compiler has to be kept from reordering them
     for (int e = lane; e < a.Ne; e += 64) zrow[e] = lrow[a.Ng + e] + (a.bias ? a.bias[e] : 0.f);
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 
     for (int e = lane; e < a.Ne; e += 64) {
       const int g = e / a.N;
@@ -197,7 +257,8 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
       e2row[e] = e2;
       krow[e] = in ? ((a.mode == MOHGE_SELECT_GLOBAL) ? e2 : zrow[e]) : NEG_INF;
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 
     unsigned long long smask[4] = {0ull, 0ull, 0ull, 0ull};
     float dsum = 0.f;
@@ -249,20 +310,42 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
         base += __popcll(smask[j]);
       }
     }
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }
+#ifdef MOHGE_PROBE
+  RPROBE(3);
+  if (a.dbg && threadIdx.x == 0 && blockIdx.x < 256) {
+    long long* d = a.dbg + (size_t)blockIdx.x * 8;
+    for (int i = 0; i < 3; ++i) d[i] += ts[i + 1] - ts[i];
+    d[4] += 1;
+  }
+#endif
+}
+
+template <bool BF16, int TM, int TN>
+static hipError_t launch_one(const RouteArgs& a, dim3 grid, dim3 block, size_t smem, hipStream_t s) {
+  auto kern = route_kernel<BF16, TM, TN>;
+  static bool attr_done = false;      // more than 64 KB of dynamic LDS needs the opt-in
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, grid, block, smem, s, a);
+  return hipGetLastError();
 }
 
 template <bool BF16, int TM>
 static hipError_t launch_tn(const RouteArgs& a, int TN, dim3 grid, dim3 block, size_t smem,
                             hipStream_t s) {
   switch (TN) {
-    case 1: hipLaunchKernelGGL((route_kernel<BF16, TM, 1>), grid, block, smem, s, a); break;
-    case 2: hipLaunchKernelGGL((route_kernel<BF16, TM, 2>), grid, block, smem, s, a); break;
-    case 3: hipLaunchKernelGGL((route_kernel<BF16, TM, 3>), grid, block, smem, s, a); break;
-    default: hipLaunchKernelGGL((route_kernel<BF16, TM, 5>), grid, block, smem, s, a); break;
+    case 1: return launch_one<BF16, TM, 1>(a, grid, block, smem, s);
+    case 2: return launch_one<BF16, TM, 2>(a, grid, block, smem, s);
+    case 3: return launch_one<BF16, TM, 3>(a, grid, block, smem, s);
+    default: return launch_one<BF16, TM, 5>(a, grid, block, smem, s);
   }
-  return hipGetLastError();
 }
 
 hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const float* w_group,
@@ -274,6 +357,9 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
   a.gidx = group_idx; a.eidx = expert_idx; a.gates = gates; a.gs = gs_out; a.es1 = es1_out;
   a.T = L.T; a.d = L.d; a.Ng = L.Ng; a.N = L.N; a.Ne = L.Ne; a.Kg = L.Kg; a.Ke = L.Ke;
   a.mode = L.select_mode;
+#ifdef MOHGE_PROBE
+  a.dbg = g_dbg;
+#endif
   a.NO = L.Ng + L.Ne;
   a.NOpad = ((a.NO + 15) / 16) * 16 + 4;
   a.Nepad = ((L.Ne + 63) / 64) * 64;
@@ -281,14 +367,14 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
   a.kslice = L.d / NW;
   const int tiles = (a.NO + 15) / 16;
   const int TN = tiles <= 1 ? 1 : tiles == 2 ? 2 : tiles == 3 ? 3 : 5;
-  int TM = (L.T >= 16384) ? 2 : 1;
+  int TM = (L.T >= 16384 && TN <= 2) ? 2 : 1;   // wider combinations would spill registers
   size_t smem = 0;
   for (;; TM = 1) {
-    const size_t part_bytes = (size_t)16 * TM * 16 * TN * sizeof(double);
+    const size_t part_bytes = (size_t)NW * 16 * TM * 16 * TN * sizeof(double);
     const size_t rows_bytes = (size_t)NW * 4 * a.Nepad * sizeof(float);
     a.region0 = (int)(((part_bytes > rows_bytes ? part_bytes : rows_bytes) + 15) / 16 * 16);
     smem = (size_t)a.region0 + (size_t)16 * TM * a.NOpad * sizeof(float);
-    if (smem <= 64 * 1024 || TM == 1) break;
+    if (smem <= 96 * 1024 || TM == 1) break;
   }
   const int BT = 16 * TM;
   dim3 grid((L.T + BT - 1) / BT), block(64 * NW);

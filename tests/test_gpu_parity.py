@@ -193,6 +193,39 @@ def test_x_perm_materialisation_and_prepermuted_ffn_input():
     assert torch.equal(y_perm2[:w.n_pairs], L.y_perm[:w.n_pairs])
 
 
+def test_route_and_permute_many_pairs_three_kernel_path():
+    # more than 256 wave segments (P > 131072): the permutation takes its separate scan kernel
+    import paper_2604_23108_amd as M
+    from gpu_harness import to_dev
+    w = Workload("many", T=41000, d=64, n_groups=4, experts_per_group=8, d_ff=(64, 64, 64, 64),
+                 k_groups=2, k_experts=4, seed=55, skew_beta=1.0)
+    inp = generate(w)
+    inp.w_group *= np.float32(20)
+    inp.w_expert *= np.float32(20)
+    cfg = M.Config.from_workload(w)
+    x = to_dev(inp.x, True)
+    wg, we = torch.from_numpy(inp.w_group).cuda(), torch.from_numpy(inp.w_expert).cuda()
+    bias = torch.from_numpy(inp.expert_logit_bias).cuda()
+    i32 = dict(dtype=torch.int32, device="cuda")
+    gidx = torch.empty((w.T, w.k_groups), **i32)
+    eidx = torch.empty((w.T, w.k_experts), **i32)
+    gates = torch.empty((w.T, w.k_experts), dtype=torch.float32, device="cuda")
+    M.mohge_route(cfg, x, wg, we, bias, gidx, eidx, gates)
+    counts = torch.empty(w.n_experts, **i32)
+    offsets = torch.empty(w.n_experts + 1, **i32)
+    perm = torch.empty(w.n_pairs, **i32)
+    inv = torch.empty(w.n_pairs, **i32)
+    ws = torch.empty(M.mohge_workspace_size(cfg, M.CALL_PERMUTE), dtype=torch.uint8, device="cuda")
+    M.mohge_permute(cfg, eidx, counts, offsets, perm, inv, None, None, ws)
+    torch.cuda.synchronize()
+    out = dict(group_idx=gidx.cpu().numpy(), expert_idx=eidx.cpu().numpy(), gates=gates.cpu().numpy(),
+               counts=counts.cpu().numpy(), offsets=offsets.cpu().numpy(), perm=perm.cpu().numpy(),
+               inv_perm=inv.cpu().numpy())
+    ref = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias)
+    check_routing(w, out, ref, "many pairs")
+    check_permutation(w, out)
+
+
 def test_runs_are_bit_identical():
     w = MID.replace(T=1111)
     inp = generate(w)
