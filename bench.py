@@ -20,10 +20,15 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 PEAK_MFMA_BF16 = 2.5e15     # FLOP/s, dense bf16, MI355X
 PEAK_HBM = 8.0e12           # B/s
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (profiles/), scaled by the same counters on a copy kernel of known size; None until
-# measured for that workload.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch of the dominant kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE, KiB per dispatch; summaries under profiles/), each scaled by what the same
+# counter reads for a plain 256 MiB device copy in the same run: that copy reads 131089 KiB
+# of FETCH_SIZE (factor 2.0) and 262144 KiB of WRITE_SIZE (factor 1.0).  None for workloads
+# that have not been profiled.
+MEASURED_TRAFFIC = {
+    "mid_prefill": (191121 * 2.0 + 33020 * 1.0) * 1024,   # ffn_tile_kernel<up>
+    "decode": (633446 * 2.0 + 397 * 1.0) * 1024,          # ffn_skinny_kernel<up>
+}
 
 
 def event_time(fn, iters, torch):
@@ -132,12 +137,12 @@ def main():
     decode = w.T <= 32
     if decode:
         ach = bytes_up / (call_ms["ffn_up"] * 1e-3)
-        roof = {"kernel": "ffn_skinny_kernel<up> (mohge_expert_ffn_up)", "bound": "hbm",
+        roof = {"kernel": "ffn_skinny_kernel<up> (one mohge_expert_ffn_up call)", "bound": "hbm",
                 "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": ach / PEAK_HBM,
                 "traffic": MEASURED_TRAFFIC.get(args.workload)}
     else:
         ach = flops_up / (call_ms["ffn_up"] * 1e-3)
-        roof = {"kernel": "ffn_tile_kernel<up> (mohge_expert_ffn_up)", "bound": "mfma",
+        roof = {"kernel": "ffn_tile_kernel<up> + its schedule kernel (one mohge_expert_ffn_up call)", "bound": "mfma",
                 "achieved": ach / 1e12, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
                 "frac": ach / PEAK_MFMA_BF16, "traffic": MEASURED_TRAFFIC.get(args.workload)}
     t_ffn = (call_ms["ffn_up"] + call_ms["ffn_down"]) * 1e-3
