@@ -16,14 +16,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "mohge_oracle.c")
+_SRC_BWD = os.path.join(_HERE, "mohge_oracle_bwd.c")
 _LIB = os.path.join(_HERE, "libmohge_oracle.so")
 
 
 def build(force: bool = True) -> str:
     """Compile the oracle with gcc (OpenMP over independent tokens / pairs)."""
-    if force or not os.path.exists(_LIB):
+    stale = not os.path.exists(_LIB) or any(
+        os.path.getmtime(f) > os.path.getmtime(_LIB) for f in (_SRC, _SRC_BWD))
+    if force or stale:
         cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-shared",
-               "-fPIC", "-o", _LIB, _SRC, "-lm"]
+               "-fPIC", "-o", _LIB, _SRC, _SRC_BWD, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -46,7 +49,8 @@ def _load():
         _lib = C.CDLL(_LIB)
         _lib.oracle_num_threads.restype = C.c_int
         for name in ("oracle_route", "oracle_permute", "oracle_expert_ffn", "oracle_combine",
-                     "oracle_aux_loss"):
+                     "oracle_aux_loss", "oracle_combine_bwd", "oracle_expert_ffn_bwd",
+                     "oracle_route_bwd"):
             getattr(_lib, name).restype = C.c_int
     return _lib
 
@@ -196,3 +200,104 @@ def layer(w, inp, tokens=None):
                          [t.f32 for t in inp.w_down], pair_token, pair_expert)
     y = combine(w, y_pairs, r["gates"][tok])
     return dict(route=r, permute=perm, tokens=tok, y_pairs=y_pairs, y=y)
+
+
+# ---------------------------------------------------------------------------------------
+# Backward pass (chain rule over the forward definitions; see mohge_oracle_bwd.c)
+# ---------------------------------------------------------------------------------------
+
+def combine_bwd(w, y_pairs, gates, dy):
+    """dgates[q, slot] and dy_pairs[q*K_e+slot] for the n_tok rows given."""
+    lib = _load()
+    c = _cfg(w)
+    gates = np.ascontiguousarray(gates, dtype=np.float64)
+    y_pairs = np.ascontiguousarray(y_pairs, dtype=np.float64)
+    dy = _f32(dy)
+    n_tok = gates.shape[0]
+    assert y_pairs.shape == (n_tok * w.k_experts, w.d) and dy.shape == (n_tok, w.d)
+    dgates = np.empty((n_tok, w.k_experts), np.float64)
+    dy_pairs = np.empty((n_tok * w.k_experts, w.d), np.float64)
+    _check(lib.oracle_combine_bwd(C.byref(c), C.c_int64(n_tok), _p(y_pairs), _p(gates), _p(dy),
+                                  _p(dgates), _p(dy_pairs)), "combine_bwd")
+    return dgates, dy_pairs
+
+
+def expert_ffn_bwd(w, x, w_gate, w_up, w_down, pair_token, pair_expert, dy_pairs,
+                   want_weight_grads: bool = True):
+    """Returns dict(dx_pairs [n,d], dw_gate, dw_up, dw_down (lists per group, or None))."""
+    lib = _load()
+    c = _cfg(w)
+    x = _f32(x)
+    pg, kg = _ptr_array(w_gate)
+    pu, ku = _ptr_array(w_up)
+    pd, kd = _ptr_array(w_down)
+    for g in range(w.n_groups):
+        assert kg[g].shape == (w.experts_per_group, w.d_ff[g], w.d)
+        assert ku[g].shape == (w.experts_per_group, w.d_ff[g], w.d)
+        assert kd[g].shape == (w.experts_per_group, w.d, w.d_ff[g])
+    pair_token = np.ascontiguousarray(pair_token, dtype=np.int32)
+    pair_expert = np.ascontiguousarray(pair_expert, dtype=np.int32)
+    dy_pairs = np.ascontiguousarray(dy_pairs, dtype=np.float64)
+    n = pair_token.shape[0]
+    assert pair_expert.shape == (n,) and dy_pairs.shape == (n, w.d)
+    assert n == 0 or (0 <= pair_token.min() and pair_token.max() < x.shape[0])
+    assert n == 0 or (0 <= pair_expert.min() and pair_expert.max() < w.n_experts)
+    dx_pairs = np.zeros((n, w.d), np.float64)
+    out = dict(dx_pairs=dx_pairs, dw_gate=None, dw_up=None, dw_down=None)
+    tabs = [None, None, None]
+    if want_weight_grads:
+        out["dw_gate"] = [np.zeros(a.shape, np.float64) for a in kg]
+        out["dw_up"] = [np.zeros(a.shape, np.float64) for a in ku]
+        out["dw_down"] = [np.zeros(a.shape, np.float64) for a in kd]
+        tabs = [(C.c_void_p * w.n_groups)(*[a.ctypes.data for a in out[k]])
+                for k in ("dw_gate", "dw_up", "dw_down")]
+    _check(lib.oracle_expert_ffn_bwd(C.byref(c), _p(x), pg, pu, pd, C.c_int64(n), _p(pair_token),
+                                     _p(pair_expert), _p(dy_pairs), _p(dx_pairs), tabs[0],
+                                     tabs[1], tabs[2]), "expert_ffn_bwd")
+    return out
+
+
+def route_bwd(w, x, w_group, w_expert, bias, group_idx, expert_idx, dgates, f_G, f_E,
+              alpha_g=None, alpha_e=None):
+    """Router backward including both auxiliary losses.  Returns dict(dx, dw_group, dw_expert, dz)."""
+    lib = _load()
+    c = _cfg(w, 1, alpha_g, alpha_e)
+    x, w_group, w_expert = _f32(x), _f32(w_group), _f32(w_expert)
+    bias = None if bias is None else _f32(bias)
+    group_idx = np.ascontiguousarray(group_idx, dtype=np.int32)
+    expert_idx = np.ascontiguousarray(expert_idx, dtype=np.int32)
+    dgates = np.ascontiguousarray(dgates, dtype=np.float64)
+    f_G = np.ascontiguousarray(f_G, dtype=np.float64)
+    f_E = np.ascontiguousarray(f_E, dtype=np.float64)
+    assert x.shape == (w.T, w.d) and dgates.shape == (w.T, w.k_experts)
+    assert group_idx.shape == (w.T, w.k_groups) and expert_idx.shape == (w.T, w.k_experts)
+    assert f_G.shape == (w.n_groups,) and f_E.shape == (w.n_experts,)
+    out = dict(dx=np.empty((w.T, w.d), np.float64), dw_group=np.empty((w.n_groups, w.d), np.float64),
+               dw_expert=np.empty((w.n_experts, w.d), np.float64),
+               dz=np.empty((w.T, w.n_groups + w.n_experts), np.float64))
+    _check(lib.oracle_route_bwd(C.byref(c), _p(x), _p(w_group), _p(w_expert), _p(bias),
+                                _p(group_idx), _p(expert_idx), _p(dgates), _p(f_G), _p(f_E),
+                                _p(out["dx"]), _p(out["dw_group"]), _p(out["dw_expert"]),
+                                _p(out["dz"])), "route_bwd")
+    return out
+
+
+def layer_bwd(w, inp, dy, fwd=None, alpha_g=None, alpha_e=None):
+    """Gradient of  sum(dy*y) + L_G + L_E  for the whole layer (all tokens).
+
+    Returns dict(dx, dw_group, dw_expert, dw_gate, dw_up, dw_down, dgates, dy_pairs, dx_pairs).
+    """
+    fwd = layer(w, inp) if fwd is None else fwd
+    r = fwd["route"]
+    aux = aux_loss(w, r["gs"], r["es1"], r["group_idx"], r["expert_idx"], 1, alpha_g, alpha_e)
+    dgates, dy_pairs = combine_bwd(w, fwd["y_pairs"], r["gates"], dy)
+    pair_token = np.repeat(np.arange(w.T, dtype=np.int32), w.k_experts)
+    pair_expert = r["expert_idx"].reshape(-1)
+    f = expert_ffn_bwd(w, inp.x.f32, [t.f32 for t in inp.w_gate], [t.f32 for t in inp.w_up],
+                       [t.f32 for t in inp.w_down], pair_token, pair_expert, dy_pairs)
+    rb = route_bwd(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias,
+                   r["group_idx"], r["expert_idx"], dgates, aux["f_G"], aux["f_E"], alpha_g, alpha_e)
+    dx = rb["dx"] + f["dx_pairs"].reshape(w.T, w.k_experts, w.d).sum(axis=1)
+    return dict(dx=dx, dw_group=rb["dw_group"], dw_expert=rb["dw_expert"], dw_gate=f["dw_gate"],
+                dw_up=f["dw_up"], dw_down=f["dw_down"], dgates=dgates, dy_pairs=dy_pairs,
+                dx_pairs=f["dx_pairs"], dz=rb["dz"], dx_route=rb["dx"], aux=aux)
