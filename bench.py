@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="mid_prefill")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--backward", action="store_true",
+                    help="training step: forward (keeping activations, with the auxiliary losses) + backward")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -89,11 +91,19 @@ def main():
 
     w = WORKLOADS[args.workload]
     inp = generate(w)
-    dl = DeviceLayer(w, inp, training=False)
+    dl = DeviceLayer(w, inp, training=args.backward)
     L, cfg, x = dl.layer, dl.cfg, dl.x
+    if args.backward:
+        from gpu_harness import to_dev
+        if inp.dy is None:
+            sys.exit("bench.py: --backward needs a workload that draws dy (e.g. --workload training)")
+        dy = to_dev(inp.dy, True)
 
     def step():
         L.forward(x)
+        if args.backward:
+            L.transpose_weights()      # once per weight update; counted in every step here
+            L.backward(x, dy)
 
     for _ in range(args.warmup):
         step()
@@ -113,6 +123,18 @@ def main():
         "ffn_down": lambda: M.mohge_expert_ffn_down(cfg, L.ws_ffn, L.offsets, L.w2, L.y_perm),
         "combine": lambda: M.mohge_combine(cfg, L.y_perm, L.inv_perm, L.gates, L.y),
     }
+    if args.backward:
+        calls.update({
+            "ffn_train_fwd": lambda: M.mohge_expert_ffn_train(cfg, x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, L.saved),
+            "aux_loss": lambda: M.mohge_aux_loss(cfg, L.gs, L.es1, L.group_idx, L.expert_idx, L.losses, L.stats, L.ws_aux),
+            "transpose_weights": L.transpose_weights,
+            "combine_bwd": lambda: M.mohge_combine_bwd(cfg, dy, L.y_perm, L.inv_perm, L.gates, L.dgates, L.dy_perm),
+            "ffn_bwd": lambda: M.mohge_expert_ffn_bwd(cfg, x, L.perm, L.offsets, L.w13t, L.w2t, L.saved, L.dy_perm,
+                                                      L.dx_perm, L.dw13, L.dw2, L.ws_ffn_bwd),
+            "route_bwd": lambda: M.mohge_route_bwd(cfg, x, L.w_group, L.w_expert, L.gs, L.es1, L.group_idx,
+                                                   L.expert_idx, L.gates, L.dgates, L.stats, L.dx_perm, L.inv_perm,
+                                                   L.dx, L.dw_group, L.dw_expert, L.dz, L.ws_route_bwd),
+        })
     call_ms = {k: event_time(f, it, torch) for k, f in calls.items()}
 
     if args.copy_calibration:
@@ -157,6 +179,13 @@ def main():
         "combine_gbs": bytes_combine / (call_ms["combine"] * 1e-3) / 1e9,
         "count_min": int(counts.min()), "count_max": int(counts.max()),
     }
+    if args.backward:
+        # the five backward products: dH and dW_down cost what the down projection costs,
+        # dX and dW13 what the up projection costs
+        flops_bwd = 2.0 * (flops_up + flops_down)
+        parts["ffn_bwd_tflops"] = flops_bwd / (call_ms["ffn_bwd"] * 1e-3) / 1e12
+        parts["ffn_bwd_frac_mfma"] = flops_bwd / (call_ms["ffn_bwd"] * 1e-3) / PEAK_MFMA_BF16
+        parts["step"] = "forward (activations kept) + aux losses + weight transposes + backward"
     out = {
         "metric": "MoHGE layer tokens/sec + expert-FFN % bf16 MFMA peak (decode: % HBM BW)",
         "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,

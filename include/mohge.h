@@ -1,7 +1,7 @@
 /*
  * mohge.h — C boundary of the MI355X (gfx950) implementation of one MoHGE layer
  * (Mixture of Heterogeneous Grouped Experts): forward pass on one GPU's share of
- * the experts, plus the two auxiliary losses of the training variant.
+ * the experts, the two auxiliary losses of the training variant, and the backward pass.
  *
  * Notation follows the paper (section 3):
  *   T    tokens in the call,            d    hidden size,
@@ -49,7 +49,11 @@ enum {
 
 enum { MOHGE_SELECT_GLOBAL = 0, MOHGE_SELECT_PER_GROUP = 1 };
 enum { MOHGE_F32 = 0, MOHGE_BF16 = 1 };
-enum { MOHGE_CALL_PERMUTE = 0, MOHGE_CALL_EXPERT_FFN = 1, MOHGE_CALL_AUX_LOSS = 2 };
+enum {
+  MOHGE_CALL_PERMUTE = 0, MOHGE_CALL_EXPERT_FFN = 1, MOHGE_CALL_AUX_LOSS = 2,
+  MOHGE_CALL_FFN_SAVED = 3,       /* `saved` of mohge_expert_ffn_train                      */
+  MOHGE_CALL_EXPERT_FFN_BWD = 4, MOHGE_CALL_ROUTE_BWD = 5
+};
 
 typedef struct mohge_config {
   int32_t T;                  /* tokens                                              */
@@ -166,6 +170,94 @@ int mohge_combine(const mohge_config* cfg, const void* y_perm, const int32_t* in
 int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
                    const int32_t* group_idx, const int32_t* expert_idx, float* losses,
                    float* stats, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * ---- Training: backward pass of the layer (dtype MOHGE_BF16 only; MOHGE_EINVAL otherwise) ----
+ *
+ * The paper trains the layer with  L_task + L_G + L_E  (sections 3.3, 3.4.2) and prints no
+ * backward formulas; these calls apply the chain rule to the forward definitions of section
+ * 3.2 and of the two losses.  The routing decisions and the routing frequencies f are
+ * constants.  Given dy = dL_task/dy, one backward pass is
+ *     mohge_combine_bwd -> mohge_expert_ffn_bwd -> mohge_route_bwd
+ * after a forward pass that used mohge_expert_ffn_train in place of mohge_expert_ffn and kept
+ * gs, es1, gates, the indices and the permutation.  Gradients of bf16 tensors are bf16 (one
+ * rounding of an fp32 accumulator); router gradients are fp32.
+ */
+
+/*
+ * mohge_expert_ffn with the same results, which additionally keeps, in `saved` (DEVICE,
+ * mohge_workspace_size(cfg, MOHGE_CALL_FFN_SAVED) bytes, layout the library's), the hidden
+ * activations h and the pre-activations a = W_gate x, b = W_up x (bf16) of every routed row.
+ * Uses the matrix-core tile path for every T.
+ */
+int mohge_expert_ffn_train(const mohge_config* cfg, const void* x, const int32_t* perm,
+                           const int32_t* offsets, const void* const* w13, const void* const* w2,
+                           void* y_perm, void* saved, size_t saved_bytes, void* stream);
+
+/*
+ * Transposed copies of the expert weights, which the input-gradient products read (both
+ * operands of a matrix-core tile are contiguous along the reduction dimension):
+ *   w13t[g] DEVICE [N, d, 2*F_g] = per expert (W13)^T,  w2t[g] DEVICE [N, F_g, d] = (W_down)^T.
+ * All four tables are HOST arrays [N_g] of DEVICE pointers.  Needed once per weight update.
+ */
+int mohge_transpose_weights(const mohge_config* cfg, const void* const* w13, const void* const* w2,
+                            void* const* w13t, void* const* w2t, void* stream);
+
+/*
+ * Backward of mohge_combine:
+ *   dgates[t,slot] = <dy[t,:], y_perm[inv_perm[t*K_e+slot],:]>   (fp32, fixed summation order)
+ *   dy_perm[inv_perm[t*K_e+slot],:] = gates[t,slot] * dy[t,:]
+ * In:  dy DEVICE [T,d], y_perm DEVICE [P,d] (the forward's), inv_perm DEVICE [P], gates DEVICE [T,K_e].
+ * Out: dgates DEVICE [T,K_e] f32, dy_perm DEVICE [P,d].
+ */
+int mohge_combine_bwd(const mohge_config* cfg, const void* dy, const void* y_perm,
+                      const int32_t* inv_perm, const float* gates, float* dgates, void* dy_perm,
+                      void* stream);
+
+/*
+ * Backward of the expert networks.  For every routed row r of expert e, with s = sigmoid(a):
+ *   dh = W_down^T dy_perm[r],  da = dh*b*s*(1 + a*(1-s)),  db = dh*a*s,
+ *   dx_perm[r] = W_gate^T da + W_up^T db,
+ *   dw2[e] = sum_r dy_perm[r] h_r^T,  dw13[e] = sum_r [da; db] x_r^T   (zero for an expert without rows).
+ * In:  x, perm, offsets as for mohge_expert_ffn; w13t, w2t as written by
+ *      mohge_transpose_weights; saved as written by mohge_expert_ffn_train for the same
+ *      x / perm / offsets / weights; dy_perm DEVICE [P,d].
+ * Out: dx_perm DEVICE [P,d]; dw13 HOST array [N_g] of DEVICE pointers, dw13[g] [N, 2*F_g, d]
+ *      (gate rows, then up rows, as w13); dw2[g] DEVICE [N, d, F_g].  Overwritten, not accumulated.
+ * workspace DEVICE, at least mohge_workspace_size(cfg, MOHGE_CALL_EXPERT_FFN_BWD) bytes.
+ * a, b, h, dh and [da|db] pass through bf16 once each; products accumulate in fp32.
+ */
+int mohge_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int32_t* perm,
+                         const int32_t* offsets, const void* const* w13t, const void* const* w2t,
+                         const void* saved, const void* dy_perm, void* dx_perm, void* const* dw13,
+                         void* const* dw2, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Backward of mohge_route plus the router gradients of L_G and L_E, and the assembly of dx.
+ * Per token, with u_g = alpha_g (F_g/max F) f^G_g / T, v_e = alpha_e f^E_e / T,
+ * S = sum_g GS_g, sigma_g = sum_i ES'_{g,i}, D = sum_kept ES'':
+ *   dES''_e = (dgate_e - sum_kept dgate*gate) / D                        kept experts, else 0
+ *   dES'_e  = dES''_e GS_g + v_e/(sigma_g+eps) - sum_i v_i ES'_i/(sigma_g+eps)^2     kept groups
+ *   dGS_g   = sum_i dES''_{g,i} ES'_{g,i} + (u_g - sum_j u_j GS_j/S)/S               all groups
+ *   dzE_e = ES'_e (dES'_e - sum_i dES'_i ES'_i),  dzG_g = dGS_g GS_g (1-GS_g)
+ *   dw_group = dzG^T x,  dw_expert = dzE^T x,
+ *   dx[t] = sum_slot dx_perm[inv_perm[t*K_e+slot]] + dzG_t w_group + dzE_t w_expert.
+ * In:  x DEVICE [T,d]; w_group, w_expert; gs, es1, group_idx, expert_idx, gates as written by
+ *      mohge_route; dgates DEVICE [T,K_e]; stats DEVICE as written by mohge_aux_loss (f^G and
+ *      f^E are read), or NULL to leave the auxiliary losses out; dx_perm DEVICE [P,d] and
+ *      inv_perm DEVICE [P], or both NULL to get the router's part of dx alone.
+ * Out: dx DEVICE [T,d] (bf16); dw_group DEVICE [N_g,d] f32; dw_expert DEVICE [N_e,d] f32;
+ *      dz_out DEVICE [T, N_g+N_e] f32 (dzG then dzE per token; dzE is also the gradient of the
+ *      expert logit bias per token) or NULL.
+ * workspace DEVICE, at least mohge_workspace_size(cfg, MOHGE_CALL_ROUTE_BWD) bytes.
+ * Sums over tokens use a fixed order (deterministic).
+ */
+int mohge_route_bwd(const mohge_config* cfg, const void* x, const float* w_group,
+                    const float* w_expert, const float* gs, const float* es1,
+                    const int32_t* group_idx, const int32_t* expert_idx, const float* gates,
+                    const float* dgates, const float* stats, const void* dx_perm,
+                    const int32_t* inv_perm, void* dx, float* dw_group, float* dw_expert,
+                    float* dz_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of DEVICE workspace that call `which_call` (MOHGE_CALL_*) needs for `cfg`;
  * 0 for an invalid configuration or call id. */

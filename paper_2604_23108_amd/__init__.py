@@ -1,6 +1,7 @@
-"""MI355X (gfx950) implementation of one MoHGE layer's forward pass behind a C ABI.
+"""MI355X (gfx950) implementation of one MoHGE layer (forward, auxiliary losses, backward)
+behind a C ABI.
 
-`binding` marshals torch tensors into the five calls of `include/mohge.h`; every step
+`binding` marshals torch tensors into the calls of `include/mohge.h`; every step
 of the layer runs in the HIP kernels of `csrc/`.  There is no CPU or PyTorch fallback:
 if `libmohge.so` has not been built, loading fails.
 """
@@ -8,5 +9,6 @@ from .binding import (  # noqa: F401
     MohgeError, Config, lib, lib_path, mohge_route, mohge_permute, mohge_expert_ffn, mohge_expert_ffn_up, mohge_expert_ffn_down,
     mohge_combine, mohge_aux_loss, mohge_workspace_size, mohge_tune, mohge_last_error, pack_w13,
     MoHGELayer, CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS, SELECT_GLOBAL, SELECT_PER_GROUP,
-    F32, BF16,
+    F32, BF16, CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, mohge_expert_ffn_train,
+    mohge_transpose_weights, mohge_combine_bwd, mohge_expert_ffn_bwd, mohge_route_bwd,
 )

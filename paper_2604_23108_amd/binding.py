@@ -18,10 +18,12 @@ _LIB_PATH = os.path.join(_HERE, "libmohge.so")
 SELECT_GLOBAL, SELECT_PER_GROUP = 0, 1
 F32, BF16 = 0, 1
 CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
+CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD = 3, 4, 5
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
-           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_tune", "mohge_workspace_size",
-           "mohge_last_error"]
+           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_tune",
+           "mohge_expert_ffn_train", "mohge_transpose_weights", "mohge_combine_bwd",
+           "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_workspace_size", "mohge_last_error"]
 
 
 class MohgeError(RuntimeError):
@@ -51,7 +53,7 @@ def lib():
             raise MohgeError(f"{_LIB_PATH} is missing: build it with "
                              "`python -m paper_2604_23108_amd.build` (there is no fallback path)")
         l = C.CDLL(_LIB_PATH)
-        for n in EXPORTS[:8]:
+        for n in EXPORTS[:-2]:
             getattr(l, n).restype = C.c_int
         l.mohge_workspace_size.restype = C.c_size_t
         l.mohge_last_error.restype = C.c_char_p
@@ -185,6 +187,49 @@ def mohge_aux_loss(cfg, gs, es1, group_idx, expert_idx, losses, stats, workspace
                                 _stream()), "mohge_aux_loss")
 
 
+def _nbytes(t: torch.Tensor):
+    return C.c_size_t(t.numel() * t.element_size())
+
+
+def mohge_expert_ffn_train(cfg, x, perm, offsets, w13, w2, y_perm, saved):
+    for t in list(w13) + list(w2):
+        _ptr(t)
+    _check(lib().mohge_expert_ffn_train(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13),
+                                        _ptr_table(w2), _ptr(y_perm), _ptr(saved), _nbytes(saved),
+                                        _stream()), "mohge_expert_ffn_train")
+
+
+def mohge_transpose_weights(cfg, w13, w2, w13t, w2t):
+    for t in list(w13) + list(w2) + list(w13t) + list(w2t):
+        _ptr(t)
+    _check(lib().mohge_transpose_weights(cfg.ref(), _ptr_table(w13), _ptr_table(w2), _ptr_table(w13t),
+                                         _ptr_table(w2t), _stream()), "mohge_transpose_weights")
+
+
+def mohge_combine_bwd(cfg, dy, y_perm, inv_perm, gates, dgates, dy_perm):
+    _check(lib().mohge_combine_bwd(cfg.ref(), _ptr(dy), _ptr(y_perm), _ptr(inv_perm), _ptr(gates),
+                                   _ptr(dgates), _ptr(dy_perm), _stream()), "mohge_combine_bwd")
+
+
+def mohge_expert_ffn_bwd(cfg, x, perm, offsets, w13t, w2t, saved, dy_perm, dx_perm, dw13, dw2,
+                         workspace):
+    for t in list(w13t) + list(w2t) + list(dw13) + list(dw2):
+        _ptr(t)
+    _check(lib().mohge_expert_ffn_bwd(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13t),
+                                      _ptr_table(w2t), _ptr(saved), _ptr(dy_perm), _ptr(dx_perm),
+                                      _ptr_table(dw13), _ptr_table(dw2), _ptr(workspace),
+                                      _nbytes(workspace), _stream()), "mohge_expert_ffn_bwd")
+
+
+def mohge_route_bwd(cfg, x, w_group, w_expert, gs, es1, group_idx, expert_idx, gates, dgates, stats,
+                    dx_perm, inv_perm, dx, dw_group, dw_expert, dz_out, workspace):
+    _check(lib().mohge_route_bwd(cfg.ref(), _ptr(x), _ptr(w_group), _ptr(w_expert), _ptr(gs), _ptr(es1),
+                                 _ptr(group_idx), _ptr(expert_idx), _ptr(gates), _ptr(dgates),
+                                 _ptr(stats), _ptr(dx_perm), _ptr(inv_perm), _ptr(dx), _ptr(dw_group),
+                                 _ptr(dw_expert), _ptr(dz_out), _ptr(workspace), _nbytes(workspace),
+                                 _stream()), "mohge_route_bwd")
+
+
 def pack_w13(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor:
     """Layout helper: [N,F,d] gate and up matrices -> the [N,2F,d] block the library reads
     (gate rows first).  Pure data movement."""
@@ -225,6 +270,24 @@ class MoHGELayer:
         self.losses = torch.empty(2, **f32) if training else None
         self.stats = torch.empty(2 * Ng + 2 * Ne, **f32) if training else None
         self.ws_aux = torch.empty(max(16, mohge_workspace_size(cfg, CALL_AUX_LOSS)), **u8) if training else None
+        # backward pass (bf16 layers): everything it writes is allocated here, once
+        self.has_backward = training and cfg.dtype == BF16
+        if self.has_backward:
+            bf = dict(dtype=torch.bfloat16, device=device)
+            self.saved = torch.empty(max(16, mohge_workspace_size(cfg, CALL_FFN_SAVED)), **u8)
+            self.ws_ffn_bwd = torch.empty(max(16, mohge_workspace_size(cfg, CALL_EXPERT_FFN_BWD)), **u8)
+            self.ws_route_bwd = torch.empty(max(16, mohge_workspace_size(cfg, CALL_ROUTE_BWD)), **u8)
+            self.w13t = [torch.empty((w.shape[0], w.shape[2], w.shape[1]), **bf) for w in self.w13]
+            self.w2t = [torch.empty((w.shape[0], w.shape[2], w.shape[1]), **bf) for w in self.w2]
+            self.dw13 = [torch.empty_like(w) for w in self.w13]
+            self.dw2 = [torch.empty_like(w) for w in self.w2]
+            self.dgates = torch.empty((T, cfg.k_experts), **f32)
+            self.dy_perm = torch.empty((max(P, 1), cfg.d), **bf)
+            self.dx_perm = torch.empty((max(P, 1), cfg.d), **bf)
+            self.dx = torch.empty((T, cfg.d), **bf)
+            self.dw_group = torch.empty((Ng, cfg.d), **f32)
+            self.dw_expert = torch.empty((Ne, cfg.d), **f32)
+            self.dz = torch.empty((T, Ng + Ne), **f32)
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         c = self.cfg
@@ -232,9 +295,32 @@ class MoHGELayer:
                     self.gates, self.gs, self.es1)
         mohge_permute(c, self.expert_idx, self.counts, self.offsets, self.perm, self.inv_perm,
                       None, None, self.ws_permute)
-        mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws_ffn)
+        if self.has_backward:
+            mohge_expert_ffn_train(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm,
+                                   self.saved)
+        else:
+            mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws_ffn)
         mohge_combine(c, self.y_perm, self.inv_perm, self.gates, self.y)
         if self.training:
             mohge_aux_loss(c, self.gs, self.es1, self.group_idx, self.expert_idx, self.losses,
                            self.stats, self.ws_aux)
         return self.y
+
+    def transpose_weights(self):
+        """Refreshes the transposed weight copies the backward pass reads (once per weight update)."""
+        mohge_transpose_weights(self.cfg, self.w13, self.w2, self.w13t, self.w2t)
+
+    def backward(self, x: torch.Tensor, dy: torch.Tensor) -> torch.Tensor:
+        """Gradients of  sum(dy*y) + L_G + L_E  after `forward(x)`; returns dx, leaves the weight
+        gradients in dw13 / dw2 / dw_group / dw_expert."""
+        if not self.has_backward:
+            raise MohgeError("backward needs a bf16 layer created with training=True")
+        c = self.cfg
+        mohge_combine_bwd(c, dy, self.y_perm, self.inv_perm, self.gates, self.dgates, self.dy_perm)
+        mohge_expert_ffn_bwd(c, x, self.perm, self.offsets, self.w13t, self.w2t, self.saved,
+                             self.dy_perm, self.dx_perm, self.dw13, self.dw2, self.ws_ffn_bwd)
+        mohge_route_bwd(c, x, self.w_group, self.w_expert, self.gs, self.es1, self.group_idx,
+                        self.expert_idx, self.gates, self.dgates, self.stats, self.dx_perm,
+                        self.inv_perm, self.dx, self.dw_group, self.dw_expert, self.dz,
+                        self.ws_route_bwd)
+        return self.dx

@@ -95,6 +95,9 @@ size_t mohge_workspace_size(const mohge_config* cfg, int which_call) {
     case MOHGE_CALL_PERMUTE: return permute_workspace_bytes(L);
     case MOHGE_CALL_EXPERT_FFN: return ffn_workspace_bytes(L, cfg->dtype);
     case MOHGE_CALL_AUX_LOSS: return aux_workspace_bytes(L);
+    case MOHGE_CALL_FFN_SAVED: return ffn_saved_bytes(L);
+    case MOHGE_CALL_EXPERT_FFN_BWD: return ffn_bwd_workspace_bytes(L);
+    case MOHGE_CALL_ROUTE_BWD: return route_bwd_workspace_bytes(L);
     default: set_error("unknown call id %d", which_call); return 0;
   }
 }
@@ -223,6 +226,126 @@ int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
   return hip_rc(launch_aux_loss(L, *cfg, gs, es1, group_idx, expert_idx, losses, stats, workspace,
                                 (hipStream_t)stream),
                 "mohge_aux_loss");
+}
+
+// ---- training -------------------------------------------------------------------------
+
+static int need_bf16(const mohge_config* cfg, const char* what) {
+  if (cfg->dtype != MOHGE_BF16) {
+    set_error("%s is implemented for dtype MOHGE_BF16 only", what);
+    return MOHGE_EINVAL;
+  }
+  return MOHGE_OK;
+}
+
+#define PTR_TABLE(dst, src, name)                                              \
+  do {                                                                         \
+    if (!(src)) { set_error(name " pointer table is NULL"); return MOHGE_ENULL; } \
+    for (int g_ = 0; g_ < L.Ng; ++g_) { NEED((src)[g_]); (dst)[g_] = (src)[g_]; }  \
+  } while (0)
+
+int mohge_expert_ffn_train(const mohge_config* cfg, const void* x, const int32_t* perm,
+                           const int32_t* offsets, const void* const* w13, const void* const* w2,
+                           void* y_perm, void* saved, size_t saved_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if ((rc = need_bf16(cfg, "mohge_expert_ffn_train"))) return rc;
+  NEED(x); OPT(perm); NEED(offsets); NEED(y_perm); NEED(saved);
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
+  PTR_TABLE(W.w13, w13, "w13");
+  PTR_TABLE(W.w2, w2, "w2");
+  if (saved_bytes < ffn_saved_bytes(L)) {
+    set_error("expert_ffn_train: saved has %zu bytes, %zu needed", saved_bytes, ffn_saved_bytes(L));
+    return MOHGE_EWORKSPACE;
+  }
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_expert_ffn_train(L, x, perm, offsets, W, y_perm, saved, (hipStream_t)stream),
+                "mohge_expert_ffn_train");
+}
+
+int mohge_transpose_weights(const mohge_config* cfg, const void* const* w13, const void* const* w2,
+                            void* const* w13t, void* const* w2t, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if ((rc = need_bf16(cfg, "mohge_transpose_weights"))) return rc;
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
+  PTR_TABLE(W.w13, w13, "w13");
+  PTR_TABLE(W.w2, w2, "w2");
+  void* t13[kMaxGroups];
+  void* t2[kMaxGroups];
+  PTR_TABLE(t13, w13t, "w13t");
+  PTR_TABLE(t2, w2t, "w2t");
+  return hip_rc(launch_transpose_weights(L, W, t13, t2, (hipStream_t)stream), "mohge_transpose_weights");
+}
+
+int mohge_combine_bwd(const mohge_config* cfg, const void* dy, const void* y_perm,
+                      const int32_t* inv_perm, const float* gates, float* dgates, void* dy_perm,
+                      void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if ((rc = need_bf16(cfg, "mohge_combine_bwd"))) return rc;
+  NEED(dy); NEED(y_perm); NEED(inv_perm); NEED(gates); NEED(dgates); NEED(dy_perm);
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_combine_bwd(L, dy, y_perm, inv_perm, gates, dgates, dy_perm, (hipStream_t)stream),
+                "mohge_combine_bwd");
+}
+
+int mohge_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int32_t* perm,
+                         const int32_t* offsets, const void* const* w13t, const void* const* w2t,
+                         const void* saved, const void* dy_perm, void* dx_perm, void* const* dw13,
+                         void* const* dw2, void* workspace, size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if ((rc = need_bf16(cfg, "mohge_expert_ffn_bwd"))) return rc;
+  NEED(x); OPT(perm); NEED(offsets); NEED(saved); NEED(dy_perm); NEED(dx_perm); NEED(workspace);
+  const void* t13[kMaxGroups];
+  const void* t2[kMaxGroups];
+  void* g13[kMaxGroups];
+  void* g2[kMaxGroups];
+  PTR_TABLE(t13, w13t, "w13t");
+  PTR_TABLE(t2, w2t, "w2t");
+  PTR_TABLE(g13, dw13, "dw13");
+  PTR_TABLE(g2, dw2, "dw2");
+  if (workspace_bytes < ffn_bwd_workspace_bytes(L)) {
+    set_error("expert_ffn_bwd workspace: %zu bytes given, %zu needed", workspace_bytes,
+              ffn_bwd_workspace_bytes(L));
+    return MOHGE_EWORKSPACE;
+  }
+  return hip_rc(launch_expert_ffn_bwd(L, x, perm, offsets, t13, t2, saved, dy_perm, dx_perm, g13, g2,
+                                      workspace, (hipStream_t)stream),
+                "mohge_expert_ffn_bwd");
+}
+
+int mohge_route_bwd(const mohge_config* cfg, const void* x, const float* w_group,
+                    const float* w_expert, const float* gs, const float* es1,
+                    const int32_t* group_idx, const int32_t* expert_idx, const float* gates,
+                    const float* dgates, const float* stats, const void* dx_perm,
+                    const int32_t* inv_perm, void* dx, float* dw_group, float* dw_expert,
+                    float* dz_out, void* workspace, size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if ((rc = need_bf16(cfg, "mohge_route_bwd"))) return rc;
+  NEED(x); NEED(w_group); NEED(w_expert); NEED(gs); NEED(es1); NEED(group_idx); NEED(expert_idx);
+  NEED(gates); NEED(dgates); OPT(stats); OPT(dx_perm); OPT(inv_perm); NEED(dx); NEED(dw_group);
+  NEED(dw_expert); OPT(dz_out); NEED(workspace);
+  if (dx_perm && !inv_perm) { set_error("dx_perm given but inv_perm is NULL"); return MOHGE_ENULL; }
+  if (L.T < 1) { set_error("route_bwd needs T >= 1"); return MOHGE_EINVAL; }
+  if (workspace_bytes < route_bwd_workspace_bytes(L)) {
+    set_error("route_bwd workspace: %zu bytes given, %zu needed", workspace_bytes,
+              route_bwd_workspace_bytes(L));
+    return MOHGE_EWORKSPACE;
+  }
+  return hip_rc(launch_route_bwd(L, *cfg, x, w_group, w_expert, gs, es1, group_idx, expert_idx, gates,
+                                 dgates, stats, dx_perm, inv_perm, dx, dw_group, dw_expert, dz_out,
+                                 workspace, (hipStream_t)stream),
+                "mohge_route_bwd");
 }
 
 }  // extern "C"

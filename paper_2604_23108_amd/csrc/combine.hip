@@ -72,3 +72,58 @@ hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
 }
 
 }  // namespace mohge
+
+// ---------------------------------------------------------------------------------------
+// backward of the gated combine (bf16):  y_t = sum_slot gate[t,slot] * y_perm[r(t,slot)]
+//   dgates[t,slot] = <dy_t, y_perm[r]>,   dy_perm[r] = gate[t,slot] * dy_t
+// One wave per token; lanes stride the row in 16-byte chunks; the dot product is folded with a
+// butterfly, so the result does not depend on scheduling.
+// ---------------------------------------------------------------------------------------
+namespace mohge {
+
+__global__ void __launch_bounds__(256) combine_bwd_kernel(const uint4* __restrict__ dy,
+                                                          const uint4* __restrict__ y_perm,
+                                                          const int32_t* __restrict__ inv_perm,
+                                                          const float* __restrict__ gates,
+                                                          float* __restrict__ dgates,
+                                                          uint4* __restrict__ dy_perm, int T, int Ke,
+                                                          int vec_per_row) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  for (int slot = 0; slot < Ke; ++slot) {
+    const float g = gates[(size_t)t * Ke + slot];
+    const int r = inv_perm[(size_t)t * Ke + slot];
+    float dot = 0.f;
+    for (int v = lane; v < vec_per_row; v += 64) {
+      const uint4 a = dy[(size_t)t * vec_per_row + v];
+      const uint4 b = y_perm[(size_t)r * vec_per_row + v];
+      const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+      uint32_t ow[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float a0 = __uint_as_float(aw[i] << 16), a1 = __uint_as_float(aw[i] & 0xffff0000u);
+        const float b0 = __uint_as_float(bw[i] << 16), b1 = __uint_as_float(bw[i] & 0xffff0000u);
+        dot = fmaf(a0, b0, dot);
+        dot = fmaf(a1, b1, dot);
+        ow[i] = pack_bf16x2(g * a0, g * a1);
+      }
+      dy_perm[(size_t)r * vec_per_row + v] = make_uint4(ow[0], ow[1], ow[2], ow[3]);
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) dot += __shfl_xor(dot, off, 64);
+    if (lane == 0) dgates[(size_t)t * Ke + slot] = dot;
+  }
+}
+
+hipError_t launch_combine_bwd(const LayerDesc& L, const void* dy, const void* y_perm,
+                              const int32_t* inv_perm, const float* gates, float* dgates,
+                              void* dy_perm, hipStream_t s) {
+  const int vec_per_row = L.d * 2 / 16;
+  hipLaunchKernelGGL(combine_bwd_kernel, dim3((unsigned)((L.T + 3) / 4)), dim3(256), 0, s,
+                     static_cast<const uint4*>(dy), static_cast<const uint4*>(y_perm), inv_perm, gates,
+                     dgates, static_cast<uint4*>(dy_perm), L.T, L.Ke, vec_per_row);
+  return hipGetLastError();
+}
+
+}  // namespace mohge

@@ -67,6 +67,29 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
                              hipStream_t s, int stages);   // stages: bit 0 = up, bit 1 = down
 hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
                           const int32_t* inv_perm, const float* gates, void* y, hipStream_t s);
+// training: forward that keeps what the backward pass needs, and the backward launchers (bf16)
+size_t ffn_saved_bytes(const LayerDesc& L);
+hipError_t launch_expert_ffn_train(const LayerDesc& L, const void* x, const int32_t* perm,
+                                   const int32_t* offsets, const GroupPtrs& W, void* y_perm,
+                                   void* saved, hipStream_t s);
+hipError_t launch_transpose_weights(const LayerDesc& L, const GroupPtrs& W, void* const* w13t,
+                                    void* const* w2t, hipStream_t s);
+hipError_t launch_combine_bwd(const LayerDesc& L, const void* dy, const void* y_perm,
+                              const int32_t* inv_perm, const float* gates, float* dgates,
+                              void* dy_perm, hipStream_t s);
+size_t ffn_bwd_workspace_bytes(const LayerDesc& L);
+hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_t* perm,
+                                 const int32_t* offsets, const void* const* w13t,
+                                 const void* const* w2t, const void* saved, const void* dy_perm,
+                                 void* dx_perm, void* const* dw13, void* const* dw2, void* ws,
+                                 hipStream_t s);
+size_t route_bwd_workspace_bytes(const LayerDesc& L);
+hipError_t launch_route_bwd(const LayerDesc& L, const mohge_config& cfg, const void* x,
+                            const float* w_group, const float* w_expert, const float* gs,
+                            const float* es1, const int32_t* group_idx, const int32_t* expert_idx,
+                            const float* gates, const float* dgates, const float* stats,
+                            const void* dx_perm, const int32_t* inv_perm, void* dx, float* dw_group,
+                            float* dw_expert, float* dz_out, void* ws, hipStream_t s);
 int tune_tiled(int knob, int value);
 size_t tiled_sched_bytes(const LayerDesc& L);
 size_t aux_workspace_bytes(const LayerDesc& L);

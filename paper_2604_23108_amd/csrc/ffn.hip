@@ -6,7 +6,7 @@ namespace mohge {
 
 hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* perm,
                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                            hipStream_t s, int stages);
+                            hipStream_t s, int stages, void* pre);
 hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
                              hipStream_t s, int stages);
@@ -110,7 +110,33 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
   // With at most 32 tokens no expert can receive more than 32 rows: one pass of the
   // weight-streaming kernel covers it.  Otherwise the tiled matrix-core kernel.
   if (use_skinny(L)) return launch_ffn_skinny(L, x, perm, offsets, W, y_perm, ws, s, stages);
-  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages);
+  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr);
+}
+
+// Training forward (bf16): what the backward pass needs is kept in `saved`:
+//   [tile schedules][h: P x Fmax][pre-activations a|b: P x 2*Fmax]
+static size_t saved_pre_offset(const LayerDesc& L) {
+  const size_t b = tiled_sched_bytes(L) + (size_t)(L.P > 0 ? L.P : 1) * L.Fmax * 2;
+  return (b + 255) / 256 * 256;
+}
+
+size_t ffn_saved_bytes(const LayerDesc& L) {
+  return saved_pre_offset(L) + ((size_t)(L.P > 0 ? L.P : 1) * 2 * L.Fmax * 2 + 255) / 256 * 256;
+}
+
+const void* saved_h(const LayerDesc& L, const void* saved) {
+  return static_cast<const unsigned char*>(saved) + tiled_sched_bytes(L);
+}
+
+const void* saved_pre(const LayerDesc& L, const void* saved) {
+  return static_cast<const unsigned char*>(saved) + saved_pre_offset(L);
+}
+
+hipError_t launch_expert_ffn_train(const LayerDesc& L, const void* x, const int32_t* perm,
+                                   const int32_t* offsets, const GroupPtrs& W, void* y_perm,
+                                   void* saved, hipStream_t s) {
+  void* pre = static_cast<unsigned char*>(saved) + saved_pre_offset(L);
+  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, saved, s, 3, pre);
 }
 
 }  // namespace mohge

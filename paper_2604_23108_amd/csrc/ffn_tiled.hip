@@ -39,6 +39,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "tiled.h"
 
 namespace mohge {
 
@@ -48,46 +49,13 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kStagesA = 2, kStagesB = 3;   // 32 KB parts: 2 token + 3 weight = all 160 KB of LDS
 constexpr int kWGM = 2, kWGN = 4;
-constexpr int kXcds = 8;
 
-struct TileRec {
-  int e;          // expert
-  int row_start;  // first sorted position of the tile
-  int rows;       // valid token rows (1..256)
-  int n0;         // first output column (up: hidden unit, down: feature of d)
-};
+// gate and up rows share a tile in the two up-projection modes
+constexpr bool is_up(int mode) { return mode == kUp || mode == kUpSave; }
 
-struct SchedHeader {
-  int tile_rows;             // chosen tile height
-  int total;                 // number of tiles
-  int xcd_begin[kXcds + 1];  // tile ranges per XCD
-  int counters[kXcds];       // next tile of each range not yet handed out
-  int pad[13];
-};
-static_assert(sizeof(SchedHeader) <= 256, "header area");
-
-struct TileArgs {
-  const uint16_t* A;          // up: x [T,d] (gathered through perm) or [P,d]; down: H [P,lda]
-  const int32_t* perm;        // up only, may be NULL
-  const int32_t* offsets;     // [Ne+1]
-  const uint16_t* W[kMaxGroups];   // up: w13[g] [N,2F,d]; down: w2[g] [N,d,F]
-  uint16_t* C;                // up: H [P,ldc]; down: y_perm [P,ldc]
-  int lda, ldc;
-  int Ke, Ng, N, Ne, d, P;
-  int F[kMaxGroups];
-  int order[kMaxGroups];      // groups in visiting order (longest reduction first)
-  SchedHeader* hdr;
-  TileRec* recs;
-  int ncu;                    // compute units = persistent workgroups
-  int force_rows;             // 0 = choose, else 64/128/192/256
-#ifdef MOHGE_PROBE
-  long long* dbg;             // [workgroup][8]: cycle sums per phase, tile count
-#endif
-};
-
-template <bool UP>
+template <int MODE>
 struct Shape {
-  static constexpr int NCOLS_PER_TILE = UP ? kBN / 2 : kBN;
+  static constexpr int NCOLS_PER_TILE = is_up(MODE) ? kBN / 2 : kBN;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -111,9 +79,27 @@ struct SchedShared {
   int rows;
 };
 
-template <bool UP>
+// Per-expert quantities of a mode: rows (`cnt`, starting at `row0`), output columns, and
+// reduction length in 64-deep stages.
+template <int MODE>
+__device__ __forceinline__ void expert_dims(const TileArgs& a, int e, int g, int& row0, int& cnt,
+                                            int& ncols, int& kc) {
+  if constexpr (MODE == kWgrad) {
+    row0 = 0;
+    cnt = a.Mrows[g];
+    ncols = a.Ncols[g];
+    kc = (a.poff[e + 1] - a.poff[e]) / 64;
+  } else {
+    row0 = a.offsets[e];
+    cnt = a.offsets[e + 1] - row0;
+    ncols = (is_up(MODE) || MODE == kDgradH) ? a.F[g] : a.d;
+    kc = ((is_up(MODE) || MODE == kDgradH) ? a.d : a.F[g]) / 64;
+  }
+}
+
+template <int MODE>
 __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& sh) {
-  constexpr int NCPT = Shape<UP>::NCOLS_PER_TILE;
+  constexpr int NCPT = Shape<MODE>::NCOLS_PER_TILE;
   const int v = threadIdx.x, lane = v & 63, w = v >> 6;
   int e = 0, cnt = 0, nt = 0, kc = 0, row0 = 0;
   if (v < a.Ne) {
@@ -122,11 +108,9 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
     // lengths instead of one range getting all the long tiles
     const int g = a.order[v % a.Ng];
     e = g * a.N + v / a.Ng;
-    row0 = a.offsets[e];
-    cnt = a.offsets[e + 1] - row0;
-    const int ncols = UP ? a.F[g] : a.d;
+    int ncols;
+    expert_dims<MODE>(a, e, g, row0, cnt, ncols, kc);
     nt = (ncols + NCPT - 1) / NCPT;
-    kc = (UP ? a.d : a.F[g]) / 64;
   }
   sh.e[v] = e; sh.cnt[v] = cnt; sh.nt[v] = nt; sh.kc[v] = kc; sh.row0[v] = row0;
   // tile height: fewest rounds over the compute units, weighted by the reduction length
@@ -143,7 +127,8 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   __syncthreads();
   if (v == 0) {
     long long kmax = 1;
-    for (int g = 0; g < a.Ng; ++g) kmax = max(kmax, (long long)((UP ? a.d : a.F[g]) / 64));
+    for (int g = 0; g < a.Ng; ++g)
+      kmax = max(kmax, (long long)(((is_up(MODE) || MODE == kDgradH) ? a.d : a.F[g]) / 64));
     float best = 0.f;
     int best_rows = 256;
     for (int c = 0; c < 3; ++c) {
@@ -234,8 +219,15 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
 __global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs up, const TileArgs dn, int mask) {
   __shared__ SchedShared sh;
   const int which = (mask == 3) ? (int)blockIdx.x : (mask == 2 ? 1 : 0);
-  if (which == 0) build_schedule<true>(up, sh);
-  else build_schedule<false>(dn, sh);
+  if (which == 0) build_schedule<kUp>(up, sh);
+  else build_schedule<kDown>(dn, sh);
+}
+
+// schedule of one backward (or saving) launch
+template <int MODE>
+__global__ void __launch_bounds__(256) tile_schedule_kernel(const TileArgs a) {
+  __shared__ SchedShared sh;
+  build_schedule<MODE>(a, sh);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -254,6 +246,33 @@ __device__ __forceinline__ void async_copy16(const void* gptr, void* lds_uniform
 
 #define MOHGE_PIN() __builtin_amdgcn_sched_barrier(0)
 
+// SwiGLU backward for 8 packed bf16 values: with s = sigmoid(a),
+//   dA = dh * b * s * (1 + a*(1-s)),  dB = dh * a * s.
+__device__ __forceinline__ void swiglu_bwd8(const uint4 dh, const uint4 av, const uint4 bv, uint4& da,
+                                            uint4& db) {
+  const uint32_t hw[4] = {dh.x, dh.y, dh.z, dh.w};
+  const uint32_t aw[4] = {av.x, av.y, av.z, av.w};
+  const uint32_t bw[4] = {bv.x, bv.y, bv.z, bv.w};
+  uint32_t oa[4], ob[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    float ra[2], rb[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const float g = __uint_as_float(h ? (hw[i] & 0xffff0000u) : (hw[i] << 16));
+      const float x = __uint_as_float(h ? (aw[i] & 0xffff0000u) : (aw[i] << 16));
+      const float u = __uint_as_float(h ? (bw[i] & 0xffff0000u) : (bw[i] << 16));
+      const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-x));
+      ra[h] = g * u * sg * (1.f + x * (1.f - sg));
+      rb[h] = g * x * sg;
+    }
+    oa[i] = pack_bf16x2(ra[0], ra[1]);
+    ob[i] = pack_bf16x2(rb[0], rb[1]);
+  }
+  da = make_uint4(oa[0], oa[1], oa[2], oa[3]);
+  db = make_uint4(ob[0], ob[1], ob[2], ob[3]);
+}
+
 // One tile with NACT active 32-row token fragments per wave (tile rows <= 64*NACT).
 #ifdef MOHGE_PROBE
 #define PROBE_T(i) ts[i] = __builtin_amdgcn_s_memtime()
@@ -261,9 +280,10 @@ __device__ __forceinline__ void async_copy16(const void* gptr, void* lds_uniform
 #define PROBE_T(i)
 #endif
 
-template <bool UP, int NACT>
+template <int MODE, int NACT>
 __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, unsigned char* lds,
                                          int lane, int w) {
+  constexpr bool UP = is_up(MODE);
 #ifdef MOHGE_PROBE
   long long ts[6];
 #endif
@@ -288,7 +308,14 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   auto b_part = [&](int slot) { return lds + (kStagesA + slot) * PART; };
 
   const int g = rec.e / a.N, e_i = rec.e % a.N, F = a.F[g];
-  const int K = UP ? a.d : F;
+  // kWgrad: the expert's zero-padded token window [win, win + K) of the transposed operands
+  int win = 0, K;
+  if constexpr (MODE == kWgrad) {
+    win = a.poff[rec.e];
+    K = a.poff[rec.e + 1] - win;
+  } else {
+    K = (UP || MODE == kDgradH) ? a.d : F;
+  }
   const int wm = w / WGN, wn = w % WGN;
 
   // ---- global source pointers of this thread's 16-byte chunks -------------------------
@@ -306,7 +333,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     if constexpr (UP) src_row = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
     else src_row = pos;
     const int chunk = lpos ^ ((row >> SH) & (CH - 1));
-    src_a[j] = a.A + src_row * a.lda + chunk * 8;
+    src_a[j] = a.A + src_row * a.lda + win + chunk * 8;
   }
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j) {
@@ -319,12 +346,21 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
       int f = rec.n0 + (row - half * (BN / 2));
       if (f > F - 1) f = F - 1;
       wrow = (long long)e_i * 2 * F + (long long)half * F + f;
+    } else if constexpr (MODE == kDgradH) {
+      int f = rec.n0 + row;                       // W_down^T of the expert: [F, d]
+      if (f > F - 1) f = F - 1;
+      wrow = (long long)e_i * F + f;
+    } else if constexpr (MODE == kWgrad) {
+      int n = rec.n0 + row;
+      if (n > a.Ncols[g] - 1) n = a.Ncols[g] - 1;
+      wrow = n;
     } else {
       int n = rec.n0 + row;
       if (n > a.d - 1) n = a.d - 1;
       wrow = (long long)e_i * a.d + n;
     }
-    src_b[j] = a.W[g] + wrow * K + chunk * 8;
+    if constexpr (MODE == kWgrad) src_b[j] = a.B2 + wrow * a.ldb + win + chunk * 8;
+    else src_b[j] = a.W[g] + wrow * K + chunk * 8;
   }
   const int ld_off = w * 1024;      // + j * NWAVES * 1024: wave-uniform destination inside a part
 
@@ -490,34 +526,61 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     static_assert(32 * CPR % 64 == 0, "whole wave-wide copies");
     unsigned char* my = lds + w * EPI_BYTES;
     const int tok_l = lane & 31, fsub = (lane >> 5) * 4;
-    const int ncols = UP ? F : a.d;
+    const int ncols = (UP || MODE == kDgradH) ? F : (MODE == kWgrad ? a.Ncols[g] : a.d);
     const int col0 = rec.n0 + wn * OC;
+    // kUpSave makes three passes over the patch: h, then the pre-activations a and b
+    constexpr int NPASS = MODE == kUpSave ? 3 : 1;
 #pragma unroll
     for (int ti = 0; ti < NACT; ++ti) {
 #pragma unroll
-      for (int fi = 0; fi < NFo; ++fi)
+      for (int pass = 0; pass < NPASS; ++pass) {
 #pragma unroll
-        for (int blk = 0; blk < 4; ++blk) {
-          float v[4];
+        for (int fi = 0; fi < NFo; ++fi)
 #pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            if constexpr (UP) v[b] = swiglu(acc[fi][ti][blk * 4 + b], acc[fi + NF / 2][ti][blk * 4 + b]);
-            else v[b] = acc[fi][ti][blk * 4 + b];
+          for (int blk = 0; blk < 4; ++blk) {
+            float v[4];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+              if constexpr (UP) {
+                const float ga = acc[fi][ti][blk * 4 + b], ub = acc[fi + NF / 2][ti][blk * 4 + b];
+                v[b] = pass == 0 ? swiglu(ga, ub) : (pass == 1 ? ga : ub);
+              } else {
+                v[b] = acc[fi][ti][blk * 4 + b];
+              }
+            }
+            uint2 o;
+            o.x = pack_bf16x2(v[0], v[1]);
+            o.y = pack_bf16x2(v[2], v[3]);
+            *reinterpret_cast<uint2*>(my + tok_l * RS + (fi * 32 + blk * 8 + fsub) * 2) = o;
           }
-          uint2 o;
-          o.x = pack_bf16x2(v[0], v[1]);
-          o.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2*>(my + tok_l * RS + (fi * 32 + blk * 8 + fsub) * 2) = o;
-        }
 #pragma unroll
-      for (int it = 0; it < 32 * CPR / 64; ++it) {
-        const int idx = it * 64 + lane;
-        const int row = idx / CPR, c = idx % CPR;
-        const uint4 v = *reinterpret_cast<const uint4*>(my + row * RS + c * 16);
-        const int trow = (ti * WGM + wm) * 32 + row;
-        const int col = col0 + c * 8;
-        if (trow < rec.rows && col < ncols)
-          *reinterpret_cast<uint4*>(a.C + (long long)(rec.row_start + trow) * a.ldc + col) = v;
+        for (int it = 0; it < 32 * CPR / 64; ++it) {
+          const int idx = it * 64 + lane;
+          const int row = idx / CPR, c = idx % CPR;
+          const uint4 v = *reinterpret_cast<const uint4*>(my + row * RS + c * 16);
+          const int trow = (ti * WGM + wm) * 32 + row;
+          const int col = col0 + c * 8;
+          if (trow < rec.rows && col < ncols) {
+            if constexpr (MODE == kWgrad) {
+              uint16_t* dst = a.Wout[g] + ((long long)e_i * a.Mrows[g] + rec.row_start + trow) * ncols + col;
+              *reinterpret_cast<uint4*>(dst) = v;
+            } else if constexpr (MODE == kDgradH) {
+              // v holds dh; the stored a, b turn it into the gradients of the pre-activations
+              const long long at = (long long)(rec.row_start + trow) * a.ldpre + col;
+              const uint4 av = *reinterpret_cast<const uint4*>(a.pre + at);
+              const uint4 bv = *reinterpret_cast<const uint4*>(a.pre + at + F);
+              uint4 da, db;
+              swiglu_bwd8(v, av, bv, da, db);
+              *reinterpret_cast<uint4*>(a.C2 + at) = da;
+              *reinterpret_cast<uint4*>(a.C2 + at + F) = db;
+            } else if (pass == 0) {
+              *reinterpret_cast<uint4*>(a.C + (long long)(rec.row_start + trow) * a.ldc + col) = v;
+            } else {
+              const long long at = (long long)(rec.row_start + trow) * a.ldpre + (pass == 2 ? F : 0) + col;
+              *reinterpret_cast<uint4*>(a.pre + at) = v;
+            }
+          }
+        }
       }
     }
   }
@@ -538,7 +601,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
 // atomic's latency hides behind the tile) and the result is passed to the other waves
 // through one LDS word between the tiles.  Which workgroup computes a tile has no influence
 // on the tile's result, so the output stays bit-identical from run to run.
-template <bool UP>
+template <int MODE>
 __global__ void __launch_bounds__(64 * kWGM * kWGN) ffn_tile_kernel(const TileArgs a) {
   extern __shared__ __align__(1024) unsigned char lds[];
   // LDS word for the hand-over: beyond the epilogue patches, inside a stage buffer that is
@@ -562,14 +625,24 @@ __global__ void __launch_bounds__(64 * kWGM * kWGN) ffn_tile_kernel(const TileAr
     rec.n0 = __builtin_amdgcn_readfirstlane(rec.n0);
     // a record that does not describe rows of this call would mean a corrupted schedule:
     // skip it rather than touch memory through it
-    const bool ok = !(rec.e < 0 || rec.e >= a.Ne || rec.rows < 1 || rec.rows > kBM ||
-                      rec.row_start < 0 || rec.row_start + rec.rows > a.P || rec.n0 < 0);
+    bool ok = !(rec.e < 0 || rec.e >= a.Ne || rec.rows < 1 || rec.rows > kBM ||
+                rec.row_start < 0 || rec.n0 < 0);
+    if (ok) {
+      if constexpr (MODE == kWgrad) {
+        const int win = a.poff[rec.e], len = a.poff[rec.e + 1] - win;
+        ok = rec.row_start + rec.rows <= a.Mrows[rec.e / a.N] && rec.n0 < a.Ncols[rec.e / a.N] &&
+             win >= 0 && len >= 64 && (len & 63) == 0 && (win & 63) == 0 && win + len <= a.lda &&
+             win + len <= a.ldb;
+      } else {
+        ok = rec.row_start + rec.rows <= a.P;
+      }
+    }
     if (ok) {
       const int nact = (rec.rows + 63) / 64;
-      if (nact == 4) run_tile<UP, 4>(a, rec, lds, lane, w);
-      else if (nact == 3) run_tile<UP, 3>(a, rec, lds, lane, w);
-      else if (nact == 2) run_tile<UP, 2>(a, rec, lds, lane, w);
-      else run_tile<UP, 1>(a, rec, lds, lane, w);
+      if (nact == 4) run_tile<MODE, 4>(a, rec, lds, lane, w);
+      else if (nact == 3) run_tile<MODE, 3>(a, rec, lds, lane, w);
+      else if (nact == 2) run_tile<MODE, 2>(a, rec, lds, lane, w);
+      else run_tile<MODE, 1>(a, rec, lds, lane, w);
     }
     __syncthreads();       // every wave is past its epilogue (and past reading the old word)
     if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(lds + kBcastOffset) = t_next;
@@ -612,7 +685,15 @@ size_t tiled_sched_bytes(const LayerDesc& L) {
   return b;
 }
 
-static int num_cus() {
+long long tile_capacity(const LayerDesc& L, int mode) {
+  if (mode == kUp || mode == kUpSave) return max_tiles(L, true);
+  if (mode == kDown) return max_tiles(L, false);
+  if (mode == kDgradH) return ((long long)L.P / 64 + L.Ne) * ((L.Fmax + kBN - 1) / kBN);
+  const int m = L.d > 2 * L.Fmax ? L.d : 2 * L.Fmax, n = L.d > L.Fmax ? L.d : L.Fmax;
+  return (long long)L.Ne * ((m + 63) / 64) * ((n + kBN - 1) / kBN);
+}
+
+int tile_num_cus() {
   static int n = 0;
   if (!n) {
     int dev = 0;
@@ -625,10 +706,10 @@ static int num_cus() {
   return n;
 }
 
-template <bool UP>
+template <int MODE>
 static hipError_t launch_stage(const TileArgs& a, hipStream_t s) {
   constexpr size_t smem = (size_t)(kStagesA * kBM + kStagesB * kBN) * kBK * 2;
-  auto kern = ffn_tile_kernel<UP>;
+  auto kern = ffn_tile_kernel<MODE>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -640,19 +721,41 @@ static hipError_t launch_stage(const TileArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <int MODE>
+static hipError_t sched_and_run(const TileArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL((tile_schedule_kernel<MODE>), dim3(1), dim3(256), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_stage<MODE>(a, s);
+}
+
+hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s) {
+  switch (mode) {
+    case kDown: return sched_and_run<kDown>(a, s);
+    case kUpSave: return sched_and_run<kUpSave>(a, s);
+    case kDgradH: return sched_and_run<kDgradH>(a, s);
+    case kWgrad: return sched_and_run<kWgrad>(a, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// `pre` != NULL (training): the up projection also stores the pre-activations a, b as rows of
+// [P, 2*Fmax] for the backward pass.
 hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* perm,
                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                            hipStream_t s, int stages) {
+                            hipStream_t s, int stages, void* pre) {
   unsigned char* base = static_cast<unsigned char*>(ws);
   uint16_t* H = reinterpret_cast<uint16_t*>(base + tiled_sched_bytes(L));
-  TileArgs up;
+  TileArgs up{};
+  up.pre = static_cast<uint16_t*>(pre);
+  up.ldpre = 2 * L.Fmax;
   up.A = static_cast<const uint16_t*>(x);
   up.perm = perm;
   up.offsets = offsets;
   up.C = H;
   up.lda = L.d; up.ldc = L.Fmax;
   up.Ke = L.Ke; up.Ng = L.Ng; up.N = L.N; up.Ne = L.Ne; up.d = L.d; up.P = L.P;
-  up.ncu = num_cus();
+  up.ncu = tile_num_cus();
   // visit groups by decreasing width: the down projection's longest reductions come first
   int order[kMaxGroups];
   for (int g = 0; g < kMaxGroups; ++g) order[g] = g;
@@ -689,9 +792,9 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
   hipLaunchKernelGGL(ffn_schedule_kernel, dim3(stages == 3 ? 2 : 1), dim3(256), 0, s, up, dn, stages);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (stages & 1) e = launch_stage<true>(up, s);
+  if (stages & 1) e = pre ? launch_stage<kUpSave>(up, s) : launch_stage<kUp>(up, s);
   if (e != hipSuccess) return e;
-  if (stages & 2) e = launch_stage<false>(dn, s);
+  if (stages & 2) e = launch_stage<kDown>(dn, s);
   return e;
 }
 

@@ -1,0 +1,73 @@
+// Argument block and schedule records of the ragged grouped GEMM tile kernel (bf16 matrix
+// cores), shared by the forward launcher and the backward launcher.
+#pragma once
+#include "common.h"
+
+namespace mohge {
+
+constexpr int kXcds = 8;
+
+// What a launch of the tile kernel computes.  All of them are C = A . B^T with both operands
+// contiguous along the reduction dimension and C's rows following A's.
+enum TileMode {
+  kUp = 0,       // H = SiLU(X Wg^T) * (X Wu^T): rows = routed tokens, reduction over d
+  kDown = 1,     // Y = A W^T: rows = routed tokens, reduction over F[g] (forward down projection,
+                 //   and the input gradient dX = [dA|dB] . W13 with F[g] := 2 F_g, W := W13^T)
+  kUpSave = 2,   // kUp that also stores the pre-activations a, b for the backward pass
+  kDgradH = 3,   // dH = dY W_down, then (dA, dB) from the stored a, b: reduction over d
+  kWgrad = 4     // dW_e = A_e . B_e^T over the tokens of expert e (transposed activations)
+};
+
+struct TileRec {
+  int e;          // expert
+  int row_start;  // first row of the tile: sorted position (token modes) / row of dW_e (kWgrad)
+  int rows;       // valid rows (1..256)
+  int n0;         // first output column
+};
+
+struct SchedHeader {
+  int tile_rows;             // chosen tile height
+  int total;                 // number of tiles
+  int xcd_begin[kXcds + 1];  // tile ranges per XCD
+  int counters[kXcds];       // next tile of each range not yet handed out
+  int pad[13];
+};
+static_assert(sizeof(SchedHeader) <= 256, "header area");
+
+struct TileArgs {
+  const uint16_t* A;          // token modes: [rows, lda] (kUp*: x, gathered through perm if given)
+                              // kWgrad: transposed activations [features, lda], expert windows at poff
+  const int32_t* perm;        // kUp* only, may be NULL
+  const int32_t* offsets;     // [Ne+1] routed rows per expert (exclusive prefix sum)
+  const uint16_t* W[kMaxGroups];   // weight operand per group (token modes)
+  uint16_t* C;                // token modes: output [P, ldc]
+  int lda, ldc;
+  int Ke, Ng, N, Ne, d, P;
+  int F[kMaxGroups];          // kUp*, kDgradH: output width F_g; kDown: reduction length
+  int order[kMaxGroups];      // groups in visiting order (longest reduction first)
+  SchedHeader* hdr;
+  TileRec* recs;
+  int ncu;                    // compute units = persistent workgroups
+  int force_rows;             // 0 = choose, else 64/128/192/256
+  // --- backward extensions -------------------------------------------------------------
+  uint16_t* pre;              // kUpSave: out, kDgradH: in; [P, ldpre], row = a[0..F_g) b[0..F_g)
+  uint16_t* C2;               // kDgradH: out [P, ldpre], row = dA[0..F_g) dB[0..F_g)
+  int ldpre;
+  const uint16_t* B2;         // kWgrad: second transposed operand [features, ldb]
+  int ldb;
+  const int32_t* poff;        // kWgrad: [Ne+1] start of every expert's zero-padded token window
+                              //   (multiples of 64; the window length is the reduction length)
+  uint16_t* Wout[kMaxGroups]; // kWgrad: dW per group, [N, Mrows[g], Ncols[g]]
+  int Mrows[kMaxGroups], Ncols[kMaxGroups];
+#ifdef MOHGE_PROBE
+  long long* dbg;             // [workgroup][8]: cycle sums per phase, tile count
+#endif
+};
+
+// One schedule launch + one tile-kernel launch for `mode` (backward modes and kUpSave).
+hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s);
+// Largest number of tiles a schedule of `mode` can hold for layer L (sizes the record area).
+long long tile_capacity(const LayerDesc& L, int mode);
+int tile_num_cus();
+
+}  // namespace mohge

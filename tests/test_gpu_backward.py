@@ -1,0 +1,241 @@
+"""GPU parity of the backward pass (combine, expert networks, router with both auxiliary
+losses) against the fp64 oracle, through the C ABI.
+
+Tolerances: tensors the GPU stores in bf16 and everything computed from them (dgates come
+from the bf16 y_perm) are held to 2e-2 * max|reference| per tensor; the router chain fed with
+the same fp32 dgates on both sides is held to 1e-4 * max|reference|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2604_23108_amd as M
+from gpu_harness import DeviceLayer, from_dev, to_dev
+from synth import SELECT_GLOBAL, SELECT_PER_GROUP, WORKLOADS, generate
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL, F32_TOL = 2e-2, 1e-4
+
+
+def _close(got, ref, tol, what):
+    ref = np.asarray(ref, np.float64)
+    got = np.asarray(got, np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    scale = np.abs(ref).max()
+    err = np.abs(got - ref).max() if ref.size else 0.0
+    assert np.isfinite(got).all(), what
+    assert err <= tol * scale + 1e-30, f"{what}: max err {err:.3e}, allowed {tol * scale:.3e}"
+
+
+def _run_backward(w, inp):
+    """Forward + backward on the GPU; returns the device layer and host copies."""
+    print(f"[backward] workload {w.name} T={w.T} d={w.d} d_ff={w.d_ff} mode={w.select_mode}", flush=True)
+    dl = DeviceLayer(w, inp, training=True)
+    L = dl.layer
+    fwd = dl.run()
+    dy = to_dev(inp.dy, True)
+    L.transpose_weights()
+    L.backward(dl.x, dy)
+    torch.cuda.synchronize()
+    return dl, fwd, dy
+
+
+def _upload_routing(L, r, aux):
+    """Overwrites the layer's forward routing results with the oracle's (fp32 roundings), so
+    that a router-backward comparison starts from identical inputs."""
+    L.gs.copy_(torch.from_numpy(r["gs"].astype(np.float32)))
+    L.es1.copy_(torch.from_numpy(r["es1"].astype(np.float32)))
+    L.gates.copy_(torch.from_numpy(r["gates"].astype(np.float32)))
+    L.group_idx.copy_(torch.from_numpy(r["group_idx"]))
+    L.expert_idx.copy_(torch.from_numpy(r["expert_idx"]))
+    stats = np.concatenate([aux["f_G"], aux["p_G"], aux["f_E"], aux["p_E"]]).astype(np.float32)
+    L.stats.copy_(torch.from_numpy(stats))
+
+
+def _w13_split(t, F):
+    a = from_dev(t)
+    return a[:, :F, :], a[:, F:, :]
+
+
+def _medium(select_mode, seed, T=600, skew=0.0, d_ff=(128, 192, 320), N=4):
+    return WORKLOADS["training"].replace(name="bwd_medium", T=T, d=256, n_groups=3, experts_per_group=N,
+                                         d_ff=d_ff, k_groups=2, k_experts=4, select_mode=select_mode,
+                                         seed=seed, skew_beta=skew)
+
+
+@pytest.mark.parametrize("mode,seed,T,skew", [(SELECT_PER_GROUP, 31, 600, 0.0),
+                                              (SELECT_GLOBAL, 32, 333, 0.0),
+                                              (SELECT_PER_GROUP, 33, 70, 3.0)])
+def test_backward_matches_oracle(mode, seed, T, skew):
+    w = _medium(mode, seed, T, skew)
+    inp = generate(w)
+    dl, fwd, dy = _run_backward(w, inp)
+    L = dl.layer
+    ref_fwd = oracle.layer(w, inp)
+    r = ref_fwd["route"]
+    ok = r["margin"] > 1e-6
+    assert (fwd["expert_idx"][ok] == r["expert_idx"][ok]).all()
+    if not ok.all():
+        pytest.skip("a routing decision inside the exclusion margin changes the permutation")
+    ref = oracle.layer_bwd(w, inp, inp.dy.f32, ref_fwd)
+    perm = fwd["perm"]
+    P = w.n_pairs
+    # combine backward
+    _close(L.dgates.cpu().numpy(), ref["dgates"], BF16_TOL, "dgates")
+    _close(from_dev(L.dy_perm)[:P], ref["dy_pairs"][perm], BF16_TOL, "dy_perm")
+    # expert networks
+    _close(from_dev(L.dx_perm)[:P], ref["dx_pairs"][perm], BF16_TOL, "dx_perm")
+    for g in range(w.n_groups):
+        dg, du = _w13_split(L.dw13[g], w.d_ff[g])
+        _close(dg, ref["dw_gate"][g], BF16_TOL, f"dw_gate[{g}]")
+        _close(du, ref["dw_up"][g], BF16_TOL, f"dw_up[{g}]")
+        _close(from_dev(L.dw2[g]), ref["dw_down"][g], BF16_TOL, f"dw_down[{g}]")
+    # an expert without tokens has exactly zero gradients
+    counts = np.bincount(r["expert_idx"].reshape(-1), minlength=w.n_experts)
+    for e in np.nonzero(counts == 0)[0]:
+        g, i = divmod(int(e), w.experts_per_group)
+        assert (from_dev(L.dw13[g])[i] == 0).all() and (from_dev(L.dw2[g])[i] == 0).all()
+    if skew > 0:
+        assert (counts == 0).any(), "this case is meant to contain an expert without tokens"
+    # router and the assembled input gradient
+    _close(L.dw_group.cpu().numpy(), ref["dw_group"], BF16_TOL, "dw_group")
+    _close(L.dw_expert.cpu().numpy(), ref["dw_expert"], BF16_TOL, "dw_expert")
+    _close(from_dev(L.dx), ref["dx"], BF16_TOL, "dx")
+
+
+def test_route_backward_fp32_chain_and_aux_terms():
+    # the router chain alone, same fp32 dgates on both sides; large loss coefficients so that
+    # a wrong auxiliary term cannot hide below the tolerance
+    w = _medium(SELECT_GLOBAL, 34, T=500).replace(alpha_g=0.7, alpha_e=0.9)
+    inp = generate(w)
+    inp.w_group = (inp.w_group * 20).astype(np.float32)
+    inp.w_expert = (inp.w_expert * 20).astype(np.float32)
+    dl, fwd, dy = _run_backward(w, inp)
+    L, c = dl.layer, dl.cfg
+    r = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert)
+    aux = oracle.aux_loss(w, r["gs"], r["es1"], r["group_idx"], r["expert_idx"])
+    # both sides start from the same forward values: the oracle's, rounded to fp32
+    _upload_routing(L, r, aux)
+    rng = np.random.default_rng(7)
+    for case, dg in (("random dgates", rng.standard_normal((w.T, w.k_experts)).astype(np.float32)),
+                     ("aux only", np.zeros((w.T, w.k_experts), np.float32))):
+        print(f"[route_bwd] {case}", flush=True)
+        dgd = torch.from_numpy(dg).cuda()
+        M.mohge_route_bwd(c, dl.x, L.w_group, L.w_expert, L.gs, L.es1, L.group_idx, L.expert_idx,
+                          L.gates, dgd, L.stats, None, None, L.dx, L.dw_group, L.dw_expert, L.dz,
+                          L.ws_route_bwd)
+        torch.cuda.synchronize()
+        ref = oracle.route_bwd(w, inp.x.f32, inp.w_group, inp.w_expert, None, r["group_idx"],
+                               r["expert_idx"], dg, aux["f_G"], aux["f_E"])
+        assert np.abs(ref["dz"]).max() > 1e-6
+        _close(L.dz.cpu().numpy(), ref["dz"], F32_TOL, case + " dz")
+        _close(L.dw_group.cpu().numpy(), ref["dw_group"], F32_TOL, case + " dw_group")
+        _close(L.dw_expert.cpu().numpy(), ref["dw_expert"], F32_TOL, case + " dw_expert")
+        _close(from_dev(L.dx), ref["dx"], BF16_TOL, case + " dx (router part)")
+    # stats == NULL leaves the auxiliary losses out: zero dgates then give zero gradients
+    M.mohge_route_bwd(c, dl.x, L.w_group, L.w_expert, L.gs, L.es1, L.group_idx, L.expert_idx,
+                      L.gates, dgd, None, None, None, L.dx, L.dw_group, L.dw_expert, L.dz,
+                      L.ws_route_bwd)
+    torch.cuda.synchronize()
+    assert (L.dz == 0).all() and (L.dw_expert == 0).all() and (L.dx == 0).all()
+
+
+def test_transposed_weights_and_saved_activations():
+    w = _medium(SELECT_PER_GROUP, 35, T=200)
+    inp = generate(w)
+    dl, fwd, dy = _run_backward(w, inp)
+    L = dl.layer
+    for g in range(w.n_groups):
+        assert torch.equal(L.w13t[g], L.w13[g].transpose(1, 2).contiguous())
+        assert torch.equal(L.w2t[g], L.w2[g].transpose(1, 2).contiguous())
+    # the training forward gives the same y as the inference forward, bit for bit
+    dl2 = DeviceLayer(w, inp, training=False)
+    out2 = dl2.run()
+    assert np.array_equal(out2["y"], fwd["y"])
+    # determinism of the backward pass
+    keep = [L.dx.clone(), L.dw_group.clone()] + [t.clone() for t in L.dw13 + L.dw2]
+    L.backward(dl.x, dy)
+    torch.cuda.synchronize()
+    for a, b in zip(keep, [L.dx, L.dw_group] + L.dw13 + L.dw2):
+        assert torch.equal(a, b)
+
+
+def test_backward_rejects_fp32_layers():
+    w = WORKLOADS["tiny_f32"]
+    cfg = M.Config.from_workload(w)
+    t = torch.zeros(64, device="cuda")
+    with pytest.raises(M.MohgeError, match="MOHGE_BF16"):
+        M.mohge_combine_bwd(cfg, t, t, t, t, t, t)
+
+
+def test_backward_full_size_training_config_sampled():
+    w = WORKLOADS["training"]
+    inp = generate(w)
+    dl, fwd, dy = _run_backward(w, inp)
+    L, c = dl.layer, dl.cfg
+    r = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert)
+    ok = r["margin"] > 1e-6
+    assert (fwd["expert_idx"][ok] == r["expert_idx"][ok]).all()
+    assert ok.mean() > 0.999
+    same = (fwd["expert_idx"] == r["expert_idx"]).all(axis=1)
+    rng = np.random.default_rng(11)
+    Ke, d = w.k_experts, w.d
+    wg = [t.f32 for t in inp.w_gate]
+    wu = [t.f32 for t in inp.w_up]
+    wd = [t.f32 for t in inp.w_down]
+
+    # (1) sampled tokens: dgates, dy_perm, dx_perm and dx of those tokens
+    tok = np.sort(rng.choice(np.nonzero(same)[0], size=24, replace=False)).astype(np.int32)
+    f = oracle.layer(w, inp, tokens=tok)
+    dgates_ref, dy_pairs_ref = oracle.combine_bwd(w, f["y_pairs"], r["gates"][tok], inp.dy.f32[tok])
+    pair_token = np.repeat(tok, Ke)
+    pair_expert = r["expert_idx"][tok].reshape(-1)
+    fb = oracle.expert_ffn_bwd(w, inp.x.f32, wg, wu, wd, pair_token, pair_expert, dy_pairs_ref,
+                               want_weight_grads=False)
+    rows = fwd["inv_perm"].reshape(w.T, Ke)[tok].reshape(-1)
+    rows_t = torch.from_numpy(rows.astype(np.int64)).cuda()
+    _close(L.dgates.cpu().numpy()[tok], dgates_ref, BF16_TOL, "dgates (sampled tokens)")
+    _close(from_dev(L.dy_perm[rows_t]), dy_pairs_ref, BF16_TOL, "dy_perm (sampled)")
+    _close(from_dev(L.dx_perm[rows_t]), fb["dx_pairs"], BF16_TOL, "dx_perm (sampled)")
+
+    # (2) the router chain at full size on the device's own dgates, then dx of the sampled tokens
+    dg_dev = L.dgates.cpu().numpy()
+    aux = oracle.aux_loss(w, r["gs"], r["es1"], r["group_idx"], r["expert_idx"])
+    rb = oracle.route_bwd(w, inp.x.f32, inp.w_group, inp.w_expert, None, r["group_idx"],
+                          r["expert_idx"], dg_dev, aux["f_G"], aux["f_E"])
+    dx_ref = rb["dx"][tok] + fb["dx_pairs"].reshape(len(tok), Ke, d).sum(axis=1)
+    _close(from_dev(L.dx)[tok], dx_ref, BF16_TOL, "dx (sampled tokens)")
+    dz_dev = L.dz.cpu().numpy()
+    _close(dz_dev[same], rb["dz"][same], 1e-3, "dz (tokens with identical decisions)")
+    # same call again from the oracle's forward values: every token comparable, fp32 bar
+    _upload_routing(L, r, aux)
+    M.mohge_route_bwd(c, dl.x, L.w_group, L.w_expert, L.gs, L.es1, L.group_idx, L.expert_idx,
+                      L.gates, L.dgates, L.stats, None, None, L.dx, L.dw_group, L.dw_expert, L.dz,
+                      L.ws_route_bwd)
+    torch.cuda.synchronize()
+    _close(L.dz.cpu().numpy(), rb["dz"], F32_TOL, "dz (full size)")
+    _close(L.dw_group.cpu().numpy(), rb["dw_group"], F32_TOL, "dw_group (full size)")
+    _close(L.dw_expert.cpu().numpy(), rb["dw_expert"], F32_TOL, "dw_expert (full size)")
+
+    # (3) weight gradients of sampled (expert, hidden unit) sets: a hidden unit's gradient rows
+    # depend on no other unit, so the oracle runs on the expert cut down to those units
+    N = w.experts_per_group
+    for e in (1, 13, 22):
+        g, i = divmod(e, N)
+        F = w.d_ff[g]
+        J = np.sort(rng.choice(F, size=16, replace=False))
+        pairs = np.nonzero(r["expert_idx"].reshape(-1) == e)[0]
+        if not same[pairs // Ke].all():
+            continue
+        ptok = (pairs // Ke).astype(np.int32)
+        gate = r["gates"].reshape(-1)[pairs]
+        dyp = gate[:, None] * inp.dy.f32[ptok].astype(np.float64)
+        w1 = w.replace(n_groups=1, experts_per_group=1, d_ff=(len(J),), k_groups=1, k_experts=1)
+        sub = oracle.expert_ffn_bwd(w1, inp.x.f32, [wg[g][i:i + 1, J, :]], [wu[g][i:i + 1, J, :]],
+                                    [wd[g][i:i + 1][:, :, J]], ptok, np.zeros(len(pairs), np.int32), dyp)
+        Jt = torch.from_numpy(J).cuda()
+        _close(from_dev(L.dw13[g][i][Jt]), sub["dw_gate"][0][0], BF16_TOL, f"dw_gate expert {e}")
+        _close(from_dev(L.dw13[g][i][Jt + F]), sub["dw_up"][0][0], BF16_TOL, f"dw_up expert {e}")
+        _close(from_dev(L.dw2[g][i][:, Jt]), sub["dw_down"][0][0], BF16_TOL, f"dw_down expert {e}")
