@@ -77,6 +77,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--backward", action="store_true",
                     help="training step: forward (keeping activations, with the auxiliary losses) + backward")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the step as one HIP graph instead of plain launches (measured: no faster, "
+                         "the step is not bound by host launch overhead)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -105,6 +108,10 @@ def main():
             L.transpose_weights()      # once per weight update; counted in every step here
             L.backward(x, dy)
 
+    if args.graph:
+        # the timed step is one replay of a HIP graph that holds exactly the launches of step()
+        L.capture(x, dy if args.backward else None)
+        step = L.replay
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -191,7 +198,7 @@ def main():
         "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if w.dtype == "bf16" else "f32",
-        "data": "synthetic",
+        "data": "synthetic", "launch": "hip graph replay of the step" if args.graph else "eager",
         "config": {"workload": w.name, "T": w.T, "d": w.d, "groups_x_experts": f"{w.n_groups}x{w.experts_per_group}",
                    "d_ff": list(w.d_ff), "k_groups": w.k_groups, "k_experts": w.k_experts,
                    "select_mode": "per_group" if w.select_mode == 1 else "global", "seed": w.seed},

@@ -306,6 +306,31 @@ class MoHGELayer:
                            self.stats, self.ws_aux)
         return self.y
 
+    def capture(self, x: torch.Tensor, dy: Optional[torch.Tensor] = None):
+        """Records one step (forward, or forward + weight transposes + backward when `dy` is
+        given) into a HIP graph; `replay()` then launches the whole step with one call.  The step
+        allocates nothing and never synchronises with the host, so the recorded launches are
+        exactly the eager ones; `x` / `dy` are read from the same buffers on every replay."""
+        def step():
+            self.forward(x)
+            if dy is not None:
+                self.transpose_weights()
+                self.backward(x, dy)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()                      # first launches set kernel attributes: keep them out of the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        self._graph = graph
+        return graph
+
+    def replay(self):
+        self._graph.replay()
+
     def transpose_weights(self):
         """Refreshes the transposed weight copies the backward pass reads (once per weight update)."""
         mohge_transpose_weights(self.cfg, self.w13, self.w2, self.w13t, self.w2t)

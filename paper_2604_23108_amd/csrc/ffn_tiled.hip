@@ -134,7 +134,9 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
     for (int c = 0; c < 3; ++c) {
       const long long tot = sh.wsum[0][c] + sh.wsum[1][c] + sh.wsum[2][c] + sh.wsum[3][c];
       const long long rounds = (tot + (long long)a.ncu * kmax - 1) / ((long long)a.ncu * kmax);
-      const float est = (float)rounds * ((float)(4 - c) + 0.6f);
+      // measured: a stage of a tile costs about 1850 + 100 * (rows / 64) clocks (operand traffic
+      // and LDS work do not shrink with the tile height), so rounds count more than height
+      const float est = (float)rounds * ((float)(4 - c) + 18.5f);
       if (c == 0 || est < best) { best = est; best_rows = 256 - 64 * c; }
     }
     sh.rows = a.force_rows ? a.force_rows : best_rows;

@@ -253,3 +253,27 @@ def test_full_size_large_prefill_skewed_sampled():
     out, _ = full_check(w, tokens=toks)
     c = out["counts"]
     assert c.sum() == w.n_pairs and c.max() / max(1, c.min()) > 10
+
+
+def test_graph_replay_matches_eager():
+    # a captured step replayed several times, with eager work and synchronisations in between,
+    # must reproduce the eager result bit for bit on every replay
+    w = WORKLOADS["mid_prefill"].replace(T=1500, d=512, d_ff=(128, 256, 384))
+    inp = generate(w)
+    DeviceLayer = _dev()
+    dl = DeviceLayer(w, inp, training=False)
+    L = dl.layer
+    print(f"[graph] workload {w.name} T={w.T}", flush=True)
+    y_eager = L.forward(dl.x).clone()
+    idx_eager = L.expert_idx.clone()
+    torch.cuda.synchronize()
+    L.capture(dl.x)
+    other = DeviceLayer(w.replace(seed=77), generate(w.replace(seed=77)), training=False)
+    for i in range(4):
+        L.y.zero_(); L.expert_idx.zero_(); L.y_perm.zero_()
+        L.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(L.y, y_eager), f"replay {i}"
+        assert torch.equal(L.expert_idx, idx_eager)
+        other.layer.forward(other.x)            # unrelated eager work between the replays
+        torch.cuda.synchronize()
