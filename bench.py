@@ -94,7 +94,7 @@ def main():
 
     w = WORKLOADS[args.workload]
     inp = generate(w)
-    dl = DeviceLayer(w, inp, training=args.backward)
+    dl = DeviceLayer(w, inp, training=args.backward, backward=args.backward)
     L, cfg, x = dl.layer, dl.cfg, dl.x
     if args.backward:
         from gpu_harness import to_dev

@@ -245,7 +245,7 @@ class MoHGELayer:
 
     def __init__(self, cfg: Config, w_group, w_expert, w13: List[torch.Tensor],
                  w2: List[torch.Tensor], expert_logit_bias=None, training: bool = False,
-                 device="cuda"):
+                 backward: bool = False, device="cuda"):
         self.cfg = cfg
         self.w_group, self.w_expert, self.w13, self.w2 = w_group, w_expert, list(w13), list(w2)
         self.bias = expert_logit_bias
@@ -271,7 +271,9 @@ class MoHGELayer:
         self.stats = torch.empty(2 * Ng + 2 * Ne, **f32) if training else None
         self.ws_aux = torch.empty(max(16, mohge_workspace_size(cfg, CALL_AUX_LOSS)), **u8) if training else None
         # backward pass (bf16 layers): everything it writes is allocated here, once
-        self.has_backward = training and cfg.dtype == BF16
+        if backward and not (training and cfg.dtype == BF16):
+            raise MohgeError("backward needs a bf16 layer created with training=True")
+        self.has_backward = backward
         if self.has_backward:
             bf = dict(dtype=torch.bfloat16, device=device)
             self.saved = torch.empty(max(16, mohge_workspace_size(cfg, CALL_FFN_SAVED)), **u8)
@@ -339,7 +341,7 @@ class MoHGELayer:
         """Gradients of  sum(dy*y) + L_G + L_E  after `forward(x)`; returns dx, leaves the weight
         gradients in dw13 / dw2 / dw_group / dw_expert."""
         if not self.has_backward:
-            raise MohgeError("backward needs a bf16 layer created with training=True")
+            raise MohgeError("backward needs a layer created with training=True, backward=True")
         c = self.cfg
         mohge_combine_bwd(c, dy, self.y_perm, self.inv_perm, self.gates, self.dgates, self.dy_perm)
         mohge_expert_ffn_bwd(c, x, self.perm, self.offsets, self.w13t, self.w2t, self.saved,

@@ -20,7 +20,7 @@ def from_dev(t: torch.Tensor) -> np.ndarray:
 
 
 class DeviceLayer:
-    def __init__(self, w, inp, training=None, **cfg_kw):
+    def __init__(self, w, inp, training=None, backward=False, **cfg_kw):
         bf = w.dtype == "bf16"
         self.w, self.bf = w, bf
         self.cfg = M.Config.from_workload(w, **cfg_kw)
@@ -31,7 +31,8 @@ class DeviceLayer:
         self.w13 = [M.pack_w13(to_dev(g, bf), to_dev(u, bf)) for g, u in zip(inp.w_gate, inp.w_up)]
         self.w2 = [to_dev(t, bf) for t in inp.w_down]
         self.layer = M.MoHGELayer(self.cfg, self.w_group, self.w_expert, self.w13, self.w2, self.bias,
-                                  training=w.training if training is None else training)
+                                  training=(w.training if training is None else training) or backward,
+                                  backward=backward)
 
     def run(self):
         L = self.layer

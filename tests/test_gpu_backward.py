@@ -32,7 +32,7 @@ def _close(got, ref, tol, what):
 def _run_backward(w, inp):
     """Forward + backward on the GPU; returns the device layer and host copies."""
     print(f"[backward] workload {w.name} T={w.T} d={w.d} d_ff={w.d_ff} mode={w.select_mode}", flush=True)
-    dl = DeviceLayer(w, inp, training=True)
+    dl = DeviceLayer(w, inp, backward=True)
     L = dl.layer
     fwd = dl.run()
     dy = to_dev(inp.dy, True)

@@ -121,6 +121,16 @@ def test_paper_shape_global_selection_eight_widths():
     full_check(w, tokens=np.arange(0, 900, 3), scale_router=8.0)
 
 
+def test_largest_supported_expert_grid():
+    # N_g = 16 groups of 16 experts (N_e = 256, the documented maximum), 16 distinct widths,
+    # 16 experts per token, both selection modes
+    widths = tuple(64 * (1 + (5 * g) % 16) for g in range(16))
+    for mode in (SELECT_GLOBAL, SELECT_PER_GROUP):
+        w = Workload("max_grid", T=700, d=128, n_groups=16, experts_per_group=16, d_ff=widths,
+                     k_groups=4, k_experts=16, select_mode=mode, seed=41 + mode, training=True)
+        full_check(w, tokens=np.arange(0, 700, 5), scale_router=12.0)
+
+
 # ---- decode-shaped: the weight-streaming path --------------------------------------------
 @pytest.mark.parametrize("T", [1, 7, 32])
 def test_decode_shaped_small(T):
