@@ -236,6 +236,32 @@ def test_route_and_permute_many_pairs_three_kernel_path():
     check_permutation(w, out)
 
 
+@pytest.mark.parametrize("T,Ng,N", [(25, 3, 4), (512, 3, 8), (513, 16, 16), (17500, 16, 16), (32768, 3, 8),
+                                    (32769, 3, 8), (41000, 8, 8)])
+def test_permute_every_launch_path(T, Ng, N):
+    # K_e = 4: P = 100 and 2048 (one workgroup), 2052 ... 131076 (histogram launch + scatter
+    # launch with the scan folded in, while segments x experts <= 8192: 24 experts up to the
+    # largest P here, 256 experts only for the small ones), else histogram, scan, scatter;
+    # expert ids drawn directly, skewed
+    import paper_2604_23108_amd as M
+    w = Workload("perm", T=T, d=64, n_groups=Ng, experts_per_group=N, d_ff=(64,) * Ng, k_groups=2,
+                 k_experts=4, seed=0)
+    rng = np.random.default_rng(T)
+    pmf = 1.0 / (1.0 + np.arange(w.n_experts)) ** 1.1
+    eidx_h = rng.choice(w.n_experts, size=(T, 4), p=pmf / pmf.sum()).astype(np.int32)
+    print(f"[permute] P={w.n_pairs} Ne={w.n_experts}", flush=True)
+    cfg = M.Config.from_workload(w)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    eidx = torch.from_numpy(eidx_h).cuda()
+    counts, offsets = torch.empty(w.n_experts, **i32), torch.empty(w.n_experts + 1, **i32)
+    perm, inv = torch.full((w.n_pairs,), -1, **i32), torch.full((w.n_pairs,), -1, **i32)
+    ws = torch.empty(M.mohge_workspace_size(cfg, M.CALL_PERMUTE), dtype=torch.uint8, device="cuda")
+    M.mohge_permute(cfg, eidx, counts, offsets, perm, inv, None, None, ws)
+    torch.cuda.synchronize()
+    check_permutation(w, dict(expert_idx=eidx_h, counts=counts.cpu().numpy(), offsets=offsets.cpu().numpy(),
+                              perm=perm.cpu().numpy(), inv_perm=inv.cpu().numpy()))
+
+
 def test_runs_are_bit_identical():
     w = MID.replace(T=1111)
     inp = generate(w)
