@@ -5,7 +5,7 @@
 // group / expert.  Stage 1: every workgroup owns a contiguous range of tokens, a wave
 // takes one token at a time with lane <-> group / expert and keeps fp64 running sums in
 // registers; waves are added in a fixed order.  Stage 2: one workgroup adds the
-// per-workgroup partial sums in index order and evaluates the losses.  No atomics, so
+// per-workgroup partial sums (one wave per column, fixed order) and evaluates the losses.  No atomics, so
 // the result is bit-identical from run to run.
 #include "common.h"
 
@@ -69,10 +69,15 @@ __global__ void __launch_bounds__(256) aux_partial_kernel(const AuxArgs a) {
 __global__ void __launch_bounds__(256) aux_final_kernel(const AuxArgs a) {
   __shared__ double tot[2 * (kMaxGroups + kMaxExperts)];
   const int ncol = a.Ng + a.Ne;
-  for (int c = threadIdx.x; c < 2 * ncol; c += blockDim.x) {
+  // one wave per column at a time: lanes take the workgroups' partial sums in strides of 64
+  // (index order within a lane), then a butterfly adds the 64 lane sums: a fixed order
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  for (int c = w; c < 2 * ncol; c += 4) {
     double s = 0.0;
-    for (int b = 0; b < a.nblk; ++b) s += a.part[(size_t)b * 2 * ncol + c];
-    tot[c] = s;
+    for (int b = lane; b < a.nblk; b += 64) s += a.part[(size_t)b * 2 * ncol + c];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) tot[c] = s;
   }
   __syncthreads();
   const double invT = 1.0 / (double)a.T;
@@ -99,9 +104,10 @@ __global__ void __launch_bounds__(256) aux_final_kernel(const AuxArgs a) {
   }
 }
 
+// 16 tokens per workgroup (4 per wave, each a chain of dependent loads), at most 1024 workgroups
 static int aux_blocks(const LayerDesc& L) {
-  int b = (L.T + 63) / 64;
-  return b < 1 ? 1 : (b > 512 ? 512 : b);
+  int b = (L.T + 15) / 16;
+  return b < 1 ? 1 : (b > 1024 ? 1024 : b);
 }
 
 size_t aux_workspace_bytes(const LayerDesc& L) {
