@@ -152,6 +152,24 @@ int mohge_combine(const mohge_config* cfg, const void* y_perm, const int32_t* in
                   const float* gates, void* y, void* stream);
 
 /*
+ * Shared experts.  The paper's architecture table lists N_s = 2 shared experts next to the
+ * routed ones and its method text never mentions them; the reading taken here is the usual
+ * one: experts every token goes through with weight 1, added to the routed output,
+ *   y[t,:] = sum_{s<N_s} E^shared_s(x[t,:]) + sum_{kept e} gate * E_e(x[t,:]).
+ * They are run with the calls above on a second configuration (n_groups = k_groups = 1,
+ * experts_per_group = k_experts = N_s, d_ff = their width): mohge_shared_routing fills the
+ * constant routing of that configuration once (expert_idx[t,s] = s, gates = 1, and the
+ * permutation in which sorted position s*T + t is pair t*N_s + s), mohge_expert_ffn and
+ * mohge_combine then give the shared term, and mohge_combine_add adds it to the gated sum:
+ *   y[t,:] = y_add[t,:] + sum_slot gates[t,slot] * y_perm[inv_perm[t*K_e+slot], :]
+ * (y_add DEVICE [T,d] (dtype); y_add == y is allowed).
+ */
+int mohge_shared_routing(const mohge_config* cfg, int32_t* expert_idx, float* gates, int32_t* counts,
+                         int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* stream);
+int mohge_combine_add(const mohge_config* cfg, const void* y_perm, const int32_t* inv_perm,
+                      const float* gates, const void* y_add, void* y, void* stream);
+
+/*
  * Group-Wise Auxiliary Loss L_G (section 3.3) and Intra-Group Experts Auxiliary
  * Loss L_E (section 3.4.2) over the T tokens of the call:
  *   f^G_g = (N_g/K_g) * [1/T] * #{t : g kept},  p^G_g = (1/T) sum_t GS_{g,t}/sum_j GS_{j,t}

@@ -185,6 +185,18 @@ def aux_loss(w, gs, es1, group_idx, expert_idx, aux_freq_norm: int = 1, alpha_g=
                 p_E=stats[2 * Ng + Ne:].copy())
 
 
+def shared_experts(w, x, w_gate_s, w_up_s, w_down_s, tokens=None):
+    """Always-on experts (architecture table of the appendix; the reading is that every token
+    goes through all N_s of them with weight 1): returns sum_s E_s(x_t) [len(tokens), d].
+    w_gate_s / w_up_s are [N_s, F_s, d], w_down_s is [N_s, d, F_s]."""
+    n_s, f_s = w_down_s.shape[0], w_down_s.shape[2]
+    tok = np.arange(x.shape[0], dtype=np.int32) if tokens is None else np.asarray(tokens, np.int32)
+    ws = w.replace(T=x.shape[0], d=x.shape[1], n_groups=1, experts_per_group=n_s, d_ff=(f_s,), k_groups=1, k_experts=n_s)
+    y_pairs = expert_ffn(ws, x, [w_gate_s], [w_up_s], [w_down_s], np.repeat(tok, n_s),
+                         np.tile(np.arange(n_s, dtype=np.int32), len(tok)))
+    return combine(ws, y_pairs, np.ones((len(tok), n_s)))
+
+
 def layer(w, inp, tokens=None):
     """Forward pass of the layer for all tokens, or for the listed token ids.
 

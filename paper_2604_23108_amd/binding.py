@@ -23,7 +23,8 @@ CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD = 3, 4, 5
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
            "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_tune",
            "mohge_expert_ffn_train", "mohge_transpose_weights", "mohge_combine_bwd",
-           "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_workspace_size", "mohge_last_error"]
+           "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_shared_routing", "mohge_combine_add",
+           "mohge_workspace_size", "mohge_last_error"]
 
 
 class MohgeError(RuntimeError):
@@ -180,6 +181,17 @@ def mohge_combine(cfg, y_perm, inv_perm, gates, y):
                                _stream()), "mohge_combine")
 
 
+def mohge_combine_add(cfg, y_perm, inv_perm, gates, y_add, y):
+    _check(lib().mohge_combine_add(cfg.ref(), _ptr(y_perm), _ptr(inv_perm), _ptr(gates), _ptr(y_add),
+                                   _ptr(y), _stream()), "mohge_combine_add")
+
+
+def mohge_shared_routing(cfg, expert_idx, gates, counts, offsets, perm, inv_perm):
+    _check(lib().mohge_shared_routing(cfg.ref(), _ptr(expert_idx), _ptr(gates), _ptr(counts),
+                                      _ptr(offsets), _ptr(perm), _ptr(inv_perm), _stream()),
+           "mohge_shared_routing")
+
+
 def mohge_aux_loss(cfg, gs, es1, group_idx, expert_idx, losses, stats, workspace):
     _check(lib().mohge_aux_loss(cfg.ref(), _ptr(gs), _ptr(es1), _ptr(group_idx), _ptr(expert_idx),
                                 _ptr(losses), _ptr(stats), _ptr(workspace),
@@ -236,6 +248,35 @@ def pack_w13(w_gate: torch.Tensor, w_up: torch.Tensor) -> torch.Tensor:
     return torch.cat([w_gate, w_up], dim=1).contiguous()
 
 
+class SharedExperts:
+    """N_s always-on experts of one width: buffers and the constant routing, made once."""
+
+    def __init__(self, T: int, d: int, w13: torch.Tensor, w2: torch.Tensor, dtype: int = BF16,
+                 device="cuda"):
+        n_s, f_s = w2.shape[0], w2.shape[2]
+        self.cfg = Config(T=T, d=d, n_groups=1, experts_per_group=n_s, d_ff=(f_s,), k_groups=1,
+                          k_experts=n_s, select_mode=SELECT_PER_GROUP, dtype=dtype)
+        self.w13, self.w2 = [w13], [w2]
+        P = T * n_s
+        i32 = dict(dtype=torch.int32, device=device)
+        self.expert_idx = torch.empty((T, n_s), **i32)
+        self.gates = torch.empty((T, n_s), dtype=torch.float32, device=device)
+        self.counts, self.offsets = torch.empty(n_s, **i32), torch.empty(n_s + 1, **i32)
+        self.perm, self.inv_perm = torch.empty(max(P, 1), **i32), torch.empty(max(P, 1), **i32)
+        self.y_perm = torch.empty((max(P, 1), d), dtype=self.cfg.torch_dtype, device=device)
+        self.y = torch.empty((T, d), dtype=self.cfg.torch_dtype, device=device)
+        self.ws = torch.empty(max(16, mohge_workspace_size(self.cfg, CALL_EXPERT_FFN)), dtype=torch.uint8,
+                              device=device)
+        mohge_shared_routing(self.cfg, self.expert_idx, self.gates, self.counts, self.offsets, self.perm,
+                             self.inv_perm)
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        c = self.cfg
+        mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws)
+        mohge_combine(c, self.y_perm, self.inv_perm, self.gates, self.y)
+        return self.y
+
+
 class MoHGELayer:
     """Holds the device buffers of one layer call and runs the five C calls in order.
 
@@ -245,11 +286,12 @@ class MoHGELayer:
 
     def __init__(self, cfg: Config, w_group, w_expert, w13: List[torch.Tensor],
                  w2: List[torch.Tensor], expert_logit_bias=None, training: bool = False,
-                 backward: bool = False, device="cuda"):
+                 backward: bool = False, shared: Optional["SharedExperts"] = None, device="cuda"):
         self.cfg = cfg
         self.w_group, self.w_expert, self.w13, self.w2 = w_group, w_expert, list(w13), list(w2)
         self.bias = expert_logit_bias
         self.training = training
+        self.shared = shared
         T, P, Ne, Ng = cfg.T, cfg.n_pairs, cfg.n_experts, cfg.n_groups
         i32 = dict(dtype=torch.int32, device=device)
         f32 = dict(dtype=torch.float32, device=device)
@@ -271,6 +313,8 @@ class MoHGELayer:
         self.stats = torch.empty(2 * Ng + 2 * Ne, **f32) if training else None
         self.ws_aux = torch.empty(max(16, mohge_workspace_size(cfg, CALL_AUX_LOSS)), **u8) if training else None
         # backward pass (bf16 layers): everything it writes is allocated here, once
+        if backward and shared is not None:
+            raise MohgeError("the backward pass of shared experts is not implemented")
         if backward and not (training and cfg.dtype == BF16):
             raise MohgeError("backward needs a bf16 layer created with training=True")
         self.has_backward = backward
@@ -302,7 +346,10 @@ class MoHGELayer:
                                    self.saved)
         else:
             mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws_ffn)
-        mohge_combine(c, self.y_perm, self.inv_perm, self.gates, self.y)
+        if self.shared is not None:
+            mohge_combine_add(c, self.y_perm, self.inv_perm, self.gates, self.shared.forward(x), self.y)
+        else:
+            mohge_combine(c, self.y_perm, self.inv_perm, self.gates, self.y)
         if self.training:
             mohge_aux_loss(c, self.gs, self.es1, self.group_idx, self.expert_idx, self.losses,
                            self.stats, self.ws_aux)

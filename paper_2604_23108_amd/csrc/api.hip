@@ -205,8 +205,34 @@ int mohge_combine(const mohge_config* cfg, const void* y_perm, const int32_t* in
   if (rc) return rc;
   NEED(y_perm); NEED(inv_perm); NEED(gates); NEED(y);
   if (L.T == 0) return MOHGE_OK;
-  return hip_rc(launch_combine(L, cfg->dtype, y_perm, inv_perm, gates, y, (hipStream_t)stream),
+  return hip_rc(launch_combine(L, cfg->dtype, y_perm, inv_perm, gates, nullptr, y, (hipStream_t)stream),
                 "mohge_combine");
+}
+
+int mohge_combine_add(const mohge_config* cfg, const void* y_perm, const int32_t* inv_perm,
+                      const float* gates, const void* y_add, void* y, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(y_perm); NEED(inv_perm); NEED(gates); NEED(y_add); NEED(y);
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_combine(L, cfg->dtype, y_perm, inv_perm, gates, y_add, y, (hipStream_t)stream),
+                "mohge_combine_add");
+}
+
+int mohge_shared_routing(const mohge_config* cfg, int32_t* expert_idx, float* gates, int32_t* counts,
+                         int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if (L.Ng != 1 || L.Kg != 1 || L.Ke != L.N) {
+    set_error("shared routing needs n_groups = k_groups = 1 and k_experts = experts_per_group");
+    return MOHGE_EINVAL;
+  }
+  NEED(expert_idx); NEED(gates); NEED(counts); NEED(offsets); NEED(perm); NEED(inv_perm);
+  return hip_rc(launch_shared_routing(L, expert_idx, gates, counts, offsets, perm, inv_perm,
+                                      (hipStream_t)stream),
+                "mohge_shared_routing");
 }
 
 int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,

@@ -10,13 +10,25 @@ template <bool BF16>
 __global__ void __launch_bounds__(256) combine_kernel(const uint4* __restrict__ y_perm,
                                                       const int32_t* __restrict__ inv_perm,
                                                       const float* __restrict__ gates,
-                                                      uint4* __restrict__ y, int T, int Ke,
+                                                      const uint4* y_add, uint4* y, int T, int Ke,
                                                       int vec_per_row) {
   const long long total = (long long)T * vec_per_row;
   for (long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
        idx += (long long)gridDim.x * blockDim.x) {
     const int t = (int)(idx / vec_per_row), v = (int)(idx % vec_per_row);
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (y_add) {          // the term added to the gated sum (may be y itself: read before written)
+      const uint4 u = y_add[idx];
+      if constexpr (BF16) {
+        acc[0] = __uint_as_float(u.x << 16); acc[1] = __uint_as_float(u.x & 0xffff0000u);
+        acc[2] = __uint_as_float(u.y << 16); acc[3] = __uint_as_float(u.y & 0xffff0000u);
+        acc[4] = __uint_as_float(u.z << 16); acc[5] = __uint_as_float(u.z & 0xffff0000u);
+        acc[6] = __uint_as_float(u.w << 16); acc[7] = __uint_as_float(u.w & 0xffff0000u);
+      } else {
+        acc[0] = __uint_as_float(u.x); acc[1] = __uint_as_float(u.y);
+        acc[2] = __uint_as_float(u.z); acc[3] = __uint_as_float(u.w);
+      }
+    }
     for (int slot = 0; slot < Ke; ++slot) {
       const float g = gates[(size_t)t * Ke + slot];
       const int r = inv_perm[(size_t)t * Ke + slot];
@@ -54,7 +66,8 @@ __global__ void __launch_bounds__(256) combine_kernel(const uint4* __restrict__ 
 }
 
 hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
-                          const int32_t* inv_perm, const float* gates, void* y, hipStream_t s) {
+                          const int32_t* inv_perm, const float* gates, const void* y_add, void* y,
+                          hipStream_t s) {
   const bool bf = dtype == MOHGE_BF16;
   const int vec_per_row = L.d * (bf ? 2 : 4) / 16;
   const long long total = (long long)L.T * vec_per_row;
@@ -62,12 +75,44 @@ hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
   if (blocks > 256 * 64) blocks = 256 * 64;
   if (bf)
     hipLaunchKernelGGL((combine_kernel<true>), dim3((unsigned)blocks), dim3(256), 0, s,
-                       static_cast<const uint4*>(y_perm), inv_perm, gates, static_cast<uint4*>(y),
-                       L.T, L.Ke, vec_per_row);
+                       static_cast<const uint4*>(y_perm), inv_perm, gates,
+                       static_cast<const uint4*>(y_add), static_cast<uint4*>(y), L.T, L.Ke, vec_per_row);
   else
     hipLaunchKernelGGL((combine_kernel<false>), dim3((unsigned)blocks), dim3(256), 0, s,
-                       static_cast<const uint4*>(y_perm), inv_perm, gates, static_cast<uint4*>(y),
-                       L.T, L.Ke, vec_per_row);
+                       static_cast<const uint4*>(y_perm), inv_perm, gates,
+                       static_cast<const uint4*>(y_add), static_cast<uint4*>(y), L.T, L.Ke, vec_per_row);
+  return hipGetLastError();
+}
+
+// Routing of always-on ("shared") experts: every token goes to every one of the N experts of
+// the single group with gate 1.  Sorted position r = s*T + t <-> pair p = t*N + s.
+__global__ void __launch_bounds__(256) shared_routing_kernel(int T, int N, int32_t* expert_idx,
+                                                             float* gates, int32_t* counts,
+                                                             int32_t* offsets, int32_t* perm,
+                                                             int32_t* inv_perm) {
+  const long long P = (long long)T * N;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < P; i += (long long)gridDim.x * 256) {
+    const int t_of_p = (int)(i / N), s_of_p = (int)(i % N);     // i as pair id
+    expert_idx[i] = s_of_p;
+    gates[i] = 1.f;
+    inv_perm[i] = s_of_p * T + t_of_p;
+    const int s_of_r = (int)(i / T), t_of_r = (int)(i % T);     // i as sorted position
+    perm[i] = t_of_r * N + s_of_r;
+  }
+  if (blockIdx.x == 0 && threadIdx.x <= (unsigned)N) {
+    offsets[threadIdx.x] = threadIdx.x * T;
+    if (threadIdx.x < (unsigned)N) counts[threadIdx.x] = T;
+  }
+}
+
+hipError_t launch_shared_routing(const LayerDesc& L, int32_t* expert_idx, float* gates,
+                                 int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                                 hipStream_t s) {
+  long long blocks = ((long long)L.P + 255) / 256;
+  if (blocks < 1) blocks = 1;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(shared_routing_kernel, dim3((unsigned)blocks), dim3(256), 0, s, L.T, L.N, expert_idx,
+                     gates, counts, offsets, perm, inv_perm);
   return hipGetLastError();
 }
 

@@ -66,7 +66,11 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
                              hipStream_t s, int stages);   // stages: bit 0 = up, bit 1 = down
 hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
-                          const int32_t* inv_perm, const float* gates, void* y, hipStream_t s);
+                          const int32_t* inv_perm, const float* gates, const void* y_add, void* y,
+                          hipStream_t s);
+hipError_t launch_shared_routing(const LayerDesc& L, int32_t* expert_idx, float* gates,
+                                 int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                                 hipStream_t s);
 // training: forward that keeps what the backward pass needs, and the backward launchers (bf16)
 size_t ffn_saved_bytes(const LayerDesc& L);
 hipError_t launch_expert_ffn_train(const LayerDesc& L, const void* x, const int32_t* perm,

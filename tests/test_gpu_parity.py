@@ -262,6 +262,49 @@ def test_permute_every_launch_path(T, Ng, N):
                               perm=perm.cpu().numpy(), inv_perm=inv.cpu().numpy()))
 
 
+def test_shared_experts_added_to_the_routed_output():
+    import paper_2604_23108_amd as M
+    from gpu_harness import to_dev
+    w = WORKLOADS["paper_1b"].replace(T=800, d=256)
+    inp = generate(w)
+    inp.w_group *= np.float32(8)
+    inp.w_expert *= np.float32(8)
+    rng = np.random.default_rng(9)
+    n_s, f_s = 2, 192
+    from synth import bf16_bits_to_f32, f32_to_bf16_bits
+    rb = lambda a: bf16_bits_to_f32(f32_to_bf16_bits(a))
+    g_s = rb(rng.standard_normal((n_s, f_s, w.d)).astype(np.float32) * 0.02)
+    u_s = rb(rng.standard_normal((n_s, f_s, w.d)).astype(np.float32) * 0.02)
+    d_s = rb(rng.standard_normal((n_s, w.d, f_s)).astype(np.float32) * 0.02)
+    dev = lambda a: torch.from_numpy(a).cuda().to(torch.bfloat16)       # exact: values are bf16 already
+    print(f"[shared] T={w.T} d={w.d} N_s={n_s} F_s={f_s}", flush=True)
+    shared = M.SharedExperts(w.T, w.d, M.pack_w13(dev(g_s), dev(u_s)), dev(d_s))
+    cfg = M.Config.from_workload(w)
+    w13 = [M.pack_w13(to_dev(g, True), to_dev(u, True)) for g, u in zip(inp.w_gate, inp.w_up)]
+    w2 = [to_dev(t, True) for t in inp.w_down]
+    L = M.MoHGELayer(cfg, torch.from_numpy(inp.w_group).cuda(), torch.from_numpy(inp.w_expert).cuda(), w13, w2,
+                     shared=shared)
+    y = L.forward(to_dev(inp.x, True)).float().cpu().numpy()
+    torch.cuda.synchronize()
+    # constant routing of the shared configuration
+    assert (shared.expert_idx.cpu().numpy() == np.arange(n_s)[None, :]).all()
+    p = oracle.permute(w.replace(n_groups=1, experts_per_group=n_s, k_groups=1, k_experts=n_s, d_ff=(f_s,)),
+                       shared.expert_idx.cpu().numpy())
+    assert (shared.perm.cpu().numpy() == p["perm"]).all() and (shared.inv_perm.cpu().numpy() == p["inv_perm"]).all()
+    assert (shared.offsets.cpu().numpy() == p["offsets"]).all() and (shared.counts.cpu().numpy() == p["counts"]).all()
+    tok = np.arange(0, w.T, 4)
+    ref = oracle.layer(w, inp, tokens=tok)
+    keep = ref["route"]["margin"][tok] >= MARGIN
+    assert (L.expert_idx.cpu().numpy()[tok][keep] == ref["route"]["expert_idx"][tok][keep]).all()
+    y_sh = oracle.shared_experts(w, inp.x.f32, g_s, u_s, d_s, tokens=tok)
+    want = ref["y"] + y_sh
+    assert np.abs(y_sh).max() > 0.2 * np.abs(ref["y"]).max()           # the shared term is not negligible
+    err = np.abs(y[tok][keep] - want[keep]).max()
+    assert err <= 2e-2 * np.abs(want).max(), f"error {err}"
+    sh_err = np.abs(shared.y.float().cpu().numpy()[tok] - y_sh).max()
+    assert sh_err <= 2e-2 * np.abs(y_sh).max()
+
+
 def test_runs_are_bit_identical():
     w = MID.replace(T=1111)
     inp = generate(w)

@@ -387,3 +387,21 @@ def test_skewed_workload_counts_range_over_ten_x():
     counts = np.bincount(r["expert_idx"].reshape(-1), minlength=w.n_experts)
     assert counts.sum() == w.n_pairs
     assert counts.max() / max(1, counts.min()) > 10
+
+
+def test_shared_experts_are_a_sum_of_dense_swiglu_blocks():
+    # the always-on experts of the architecture table: every token, weight 1
+    rng = np.random.default_rng(3)
+    T, d, n_s, f_s = 7, 16, 2, 24
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    g, u = (rng.standard_normal((n_s, f_s, d)).astype(np.float32) * 0.3 for _ in range(2))
+    dn = rng.standard_normal((n_s, d, f_s)).astype(np.float32) * 0.3
+    w = WORKLOADS["tiny_f32"]
+    got = oracle.shared_experts(w, x, g, u, dn)
+    want = np.zeros((T, d))
+    X = x.astype(np.float64)
+    for s_ in range(n_s):
+        a, b = X @ g[s_].astype(np.float64).T, X @ u[s_].astype(np.float64).T
+        want += (a / (1 + np.exp(-a)) * b) @ dn[s_].astype(np.float64).T
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(oracle.shared_experts(w, x, g, u, dn, tokens=[5, 1]), want[[5, 1]], rtol=1e-12)
