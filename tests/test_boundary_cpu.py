@@ -72,3 +72,30 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(4)
     with pytest.raises(M.MohgeError, match="GPU"):
         M.mohge_combine(cfg, t, t, t, t)
+
+
+def test_training_entry_points_check_their_arguments():
+    cfg = M.Config(T=8192, d=2048, n_groups=3, experts_per_group=8, d_ff=(512, 1024, 1536), k_groups=2, k_experts=4)
+    P, Fmax, d = 8192 * 4, 1536, 2048
+    # saved = schedules + h [P, Fmax] + pre-activations [P, 2 Fmax]
+    saved = M.mohge_workspace_size(cfg, M.CALL_FFN_SAVED)
+    assert 3 * P * Fmax * 2 <= saved <= 3 * P * Fmax * 2 + (1 << 20)
+    # backward workspace holds [dA|dB] and four transposed activation buffers in padded windows
+    bwd = M.mohge_workspace_size(cfg, M.CALL_EXPERT_FFN_BWD)
+    Pp = P + 64 * 24
+    need = P * 2 * Fmax * 2 + (2 * d + 3 * Fmax) * Pp * 2
+    assert need <= bwd <= need + (1 << 20)
+    assert M.mohge_workspace_size(cfg, M.CALL_ROUTE_BWD) >= 8192 * 27 * 4
+    lib = M.lib()
+    assert lib.mohge_combine_bwd(cfg.ref(), None, None, None, None, None, None, None) == -2
+    assert "NULL" in M.mohge_last_error()
+    assert lib.mohge_expert_ffn_bwd(cfg.ref(), *([None] * 13)) == -2
+    assert lib.mohge_route_bwd(cfg.ref(), *([None] * 19)) == -2
+    assert lib.mohge_expert_ffn_train(cfg.ref(), *([None] * 9)) == -2
+    # fp32 layers have no backward pass
+    f32 = M.Config(T=64, d=128, n_groups=3, experts_per_group=4, d_ff=(64, 128, 256), k_groups=2, k_experts=2, dtype=M.F32)
+    assert lib.mohge_combine_bwd(f32.ref(), None, None, None, None, None, None, None) == -1
+    assert "MOHGE_BF16" in M.mohge_last_error()
+    # shared routing only for the one-group, all-experts configuration
+    assert lib.mohge_shared_routing(cfg.ref(), None, None, None, None, None, None, None) == -1
+    assert "shared routing" in M.mohge_last_error()
