@@ -170,8 +170,9 @@ def test_backward_rejects_fp32_layers():
         M.mohge_combine_bwd(cfg, t, t, t, t, t, t)
 
 
-def test_backward_full_size_training_config_sampled():
-    w = WORKLOADS["training"]
+def _check_backward_sampled(w, n_tok, experts, n_units=16):
+    """Full-size run, oracle on samples: gradients of sampled tokens, the router chain at full
+    size, and the weight gradients of sampled hidden units of the listed experts."""
     inp = generate(w)
     dl, fwd, dy = _run_backward(w, inp)
     L, c = dl.layer, dl.cfg
@@ -187,7 +188,7 @@ def test_backward_full_size_training_config_sampled():
     wd = [t.f32 for t in inp.w_down]
 
     # (1) sampled tokens: dgates, dy_perm, dx_perm and dx of those tokens
-    tok = np.sort(rng.choice(np.nonzero(same)[0], size=24, replace=False)).astype(np.int32)
+    tok = np.sort(rng.choice(np.nonzero(same)[0], size=n_tok, replace=False)).astype(np.int32)
     f = oracle.layer(w, inp, tokens=tok)
     dgates_ref, dy_pairs_ref = oracle.combine_bwd(w, f["y_pairs"], r["gates"][tok], inp.dy.f32[tok])
     pair_token = np.repeat(tok, Ke)
@@ -222,10 +223,10 @@ def test_backward_full_size_training_config_sampled():
     # (3) weight gradients of sampled (expert, hidden unit) sets: a hidden unit's gradient rows
     # depend on no other unit, so the oracle runs on the expert cut down to those units
     N = w.experts_per_group
-    for e in (1, 13, 22):
+    for e in experts:
         g, i = divmod(e, N)
         F = w.d_ff[g]
-        J = np.sort(rng.choice(F, size=16, replace=False))
+        J = np.sort(rng.choice(F, size=n_units, replace=False))
         pairs = np.nonzero(r["expert_idx"].reshape(-1) == e)[0]
         if not same[pairs // Ke].all():
             continue
@@ -239,3 +240,15 @@ def test_backward_full_size_training_config_sampled():
         _close(from_dev(L.dw13[g][i][Jt]), sub["dw_gate"][0][0], BF16_TOL, f"dw_gate expert {e}")
         _close(from_dev(L.dw13[g][i][Jt + F]), sub["dw_up"][0][0], BF16_TOL, f"dw_up expert {e}")
         _close(from_dev(L.dw2[g][i][:, Jt]), sub["dw_down"][0][0], BF16_TOL, f"dw_down expert {e}")
+
+
+def test_backward_full_size_training_config_sampled():
+    _check_backward_sampled(WORKLOADS["training"], 24, (1, 13, 22))
+
+
+def test_backward_element_offsets_beyond_2_31():
+    # P*d, P*2*max F and the transposed buffers all exceed 2^31 elements
+    w = WORKLOADS["training"].replace(name="big_offsets_bwd", T=135168, d=4096, n_groups=2,
+                                      experts_per_group=2, d_ff=(256, 4096), k_groups=2, k_experts=4, seed=62)
+    assert w.n_pairs * w.d > 2 ** 31
+    _check_backward_sampled(w, 10, (3,), n_units=2)

@@ -334,6 +334,19 @@ def test_full_size_large_prefill_skewed_sampled():
     assert c.sum() == w.n_pairs and c.max() / max(1, c.min()) > 10
 
 
+def test_element_offsets_beyond_2_31():
+    # P*d and P*max F both exceed 2^31 elements (P = 540672 rows of 4096): every row offset must
+    # be computed in 64 bits.  Two groups of two experts, every token goes to all four.
+    w = Workload("big_offsets", T=135168, d=4096, n_groups=2, experts_per_group=2, d_ff=(256, 4096),
+                 k_groups=2, k_experts=4, seed=61)
+    assert w.n_pairs * w.d > 2 ** 31 and w.n_pairs * max(w.d_ff) > 2 ** 31
+    rng = np.random.default_rng(7)
+    toks = np.sort(np.concatenate([rng.choice(w.T, size=12, replace=False), [0, w.T - 1]]))
+    print(f"[big offsets] T={w.T} P={w.n_pairs} d={w.d}", flush=True)
+    out, _ = full_check(w, tokens=toks)
+    assert (out["counts"] == w.T).all()
+
+
 def test_graph_replay_matches_eager():
     # a captured step replayed several times, with eager work and synchronisations in between,
     # must reproduce the eager result bit for bit on every replay
