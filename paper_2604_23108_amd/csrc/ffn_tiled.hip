@@ -298,8 +298,8 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   constexpr int KK = BK / 16;                                        // MFMA k-steps per stage
   constexpr int B_LOADS = BN * CH / NT;
   // wave-wide load j of the token part fills tile rows [64j, 64j+64): only NACT of them matter
-  constexpr int A_LOADS = NACT;
-  static_assert(BM * CH / NT == 4 && B_LOADS == 4, "load bookkeeping below assumes 4 + 4");
+  constexpr int A_LOADS = NACT * (64 / (NWAVES * RPL));
+  static_assert(64 % (NWAVES * RPL) == 0 && B_LOADS * NWAVES * RPL == BN, "whole wave-wide loads");
   constexpr int PART = BM * ROWB;                 // 32 KB: one token part or one weight part
   constexpr int NM = NACT * NF;     // MFMAs per k-step
   constexpr int NR = NACT + NF;     // fragment reads per k-step
