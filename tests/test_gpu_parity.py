@@ -74,6 +74,9 @@ def full_check(w, tokens=None, scale_router=1.0):
     check_permutation(w, out)
     toks = np.arange(w.T) if tokens is None else tokens
     check_output(w, inp, out, ref, keep, toks)
+    # properties that hold at any size
+    assert np.isfinite(out["y"]).all() and np.abs(out["gates"].sum(axis=1) - 1.0).max() <= 2e-6
+    assert out["counts"].sum() == w.n_pairs and (out["gates"] > 0).all()
     # scores and auxiliary losses
     np.testing.assert_allclose(out["gs"], ref["gs"], atol=1e-6)
     # ES' = exp(z - max) / sum in fp32: the difference z - max carries an absolute error of about
@@ -121,6 +124,30 @@ def test_mid_bf16_skewed_counts():
 def test_paper_shape_global_selection_eight_widths():
     w = WORKLOADS["paper_1b"].replace(T=900, d=256)
     full_check(w, tokens=np.arange(0, 900, 3), scale_router=8.0)
+
+
+def test_random_configurations():
+    # 24 seeded random layer shapes: group count, experts per group, widths (multiples of 64),
+    # hidden size, K_g, K_e, selection mode, token count (ragged tails, tiles of every height,
+    # the single-workgroup permutation and the tiled one, the weight-streaming path for T <= 32)
+    rng = np.random.default_rng(2024)
+    for case in range(24):
+        Ng = int(rng.integers(1, 7))
+        N = int(rng.integers(1, 9))
+        Kg = int(rng.integers(1, Ng + 1))
+        mode = int(rng.integers(0, 2))
+        if mode == SELECT_PER_GROUP:
+            Ke = Kg * int(rng.integers(1, N + 1))
+        else:
+            Ke = int(rng.integers(1, Kg * N + 1))
+        d = 64 * int(rng.integers(1, 5))
+        widths = tuple(64 * int(v) for v in rng.integers(1, 7, Ng))
+        T = int(rng.choice([1, 5, 31, 33, 64, 200, 517, 1100]))
+        w = Workload(f"random{case}", T=T, d=d, n_groups=Ng, experts_per_group=N, d_ff=widths,
+                     k_groups=Kg, k_experts=Ke, select_mode=mode, seed=1000 + case, training=True,
+                     skew_beta=float(rng.choice([0.0, 1.5])))
+        print(f"[random] case {case}: T={T} d={d} {Ng}x{N} d_ff={widths} Kg={Kg} Ke={Ke} mode={mode}", flush=True)
+        full_check(w, scale_router=10.0)
 
 
 def test_largest_supported_expert_grid():
