@@ -108,7 +108,6 @@ def main():
     def step():
         L.forward(x)
         if args.backward:
-            L.transpose_weights()      # once per weight update; counted in every step here
             L.backward(x, dy)
 
     if args.graph:
@@ -137,9 +136,8 @@ def main():
         calls.update({
             "ffn_train_fwd": lambda: M.mohge_expert_ffn_train(cfg, x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, L.saved),
             "aux_loss": lambda: M.mohge_aux_loss(cfg, L.gs, L.es1, L.group_idx, L.expert_idx, L.losses, L.stats, L.ws_aux),
-            "transpose_weights": L.transpose_weights,
             "combine_bwd": lambda: M.mohge_combine_bwd(cfg, dy, L.y_perm, L.inv_perm, L.gates, L.dgates, L.dy_perm),
-            "ffn_bwd": lambda: M.mohge_expert_ffn_bwd(cfg, x, L.perm, L.offsets, L.w13t, L.w2t, L.saved, L.dy_perm,
+            "ffn_bwd": lambda: M.mohge_expert_ffn_bwd(cfg, x, L.perm, L.offsets, L.w13, L.w2, L.saved, L.dy_perm,
                                                       L.dx_perm, L.dw13, L.dw2, L.ws_ffn_bwd),
             "route_bwd": lambda: M.mohge_route_bwd(cfg, x, L.w_group, L.w_expert, L.gs, L.es1, L.group_idx,
                                                    L.expert_idx, L.gates, L.dgates, L.stats, L.dx_perm, L.inv_perm,
@@ -195,7 +193,7 @@ def main():
         flops_bwd = 2.0 * (flops_up + flops_down)
         parts["ffn_bwd_tflops"] = flops_bwd / (call_ms["ffn_bwd"] * 1e-3) / 1e12
         parts["ffn_bwd_frac_mfma"] = flops_bwd / (call_ms["ffn_bwd"] * 1e-3) / PEAK_MFMA_BF16
-        parts["step"] = "forward (activations kept) + aux losses + weight transposes + backward"
+        parts["step"] = "forward (activations kept) + aux losses + backward"
     out = {
         "metric": "MoHGE layer tokens/sec + expert-FFN % bf16 MFMA peak (decode: % HBM BW)",
         "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,

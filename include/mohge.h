@@ -213,15 +213,6 @@ int mohge_expert_ffn_train(const mohge_config* cfg, const void* x, const int32_t
                            void* y_perm, void* saved, size_t saved_bytes, void* stream);
 
 /*
- * Transposed copies of the expert weights, which the input-gradient products read (both
- * operands of a matrix-core tile are contiguous along the reduction dimension):
- *   w13t[g] DEVICE [N, d, 2*F_g] = per expert (W13)^T,  w2t[g] DEVICE [N, F_g, d] = (W_down)^T.
- * All four tables are HOST arrays [N_g] of DEVICE pointers.  Needed once per weight update.
- */
-int mohge_transpose_weights(const mohge_config* cfg, const void* const* w13, const void* const* w2,
-                            void* const* w13t, void* const* w2t, void* stream);
-
-/*
  * Backward of mohge_combine:
  *   dgates[t,slot] = <dy[t,:], y_perm[inv_perm[t*K_e+slot],:]>   (fp32, fixed summation order)
  *   dy_perm[inv_perm[t*K_e+slot],:] = gates[t,slot] * dy[t,:]
@@ -237,16 +228,16 @@ int mohge_combine_bwd(const mohge_config* cfg, const void* dy, const void* y_per
  *   dh = W_down^T dy_perm[r],  da = dh*b*s*(1 + a*(1-s)),  db = dh*a*s,
  *   dx_perm[r] = W_gate^T da + W_up^T db,
  *   dw2[e] = sum_r dy_perm[r] h_r^T,  dw13[e] = sum_r [da; db] x_r^T   (zero for an expert without rows).
- * In:  x, perm, offsets as for mohge_expert_ffn; w13t, w2t as written by
- *      mohge_transpose_weights; saved as written by mohge_expert_ffn_train for the same
- *      x / perm / offsets / weights; dy_perm DEVICE [P,d].
+ * In:  x, perm, offsets, w13, w2 as for mohge_expert_ffn (the weights are read in
+ *      that layout, no transposed copies are needed); saved as written by
+ *      mohge_expert_ffn_train for the same x / perm / offsets / weights; dy_perm DEVICE [P,d].
  * Out: dx_perm DEVICE [P,d]; dw13 HOST array [N_g] of DEVICE pointers, dw13[g] [N, 2*F_g, d]
  *      (gate rows, then up rows, as w13); dw2[g] DEVICE [N, d, F_g].  Overwritten, not accumulated.
  * workspace DEVICE, at least mohge_workspace_size(cfg, MOHGE_CALL_EXPERT_FFN_BWD) bytes.
  * a, b, h, dh and [da|db] pass through bf16 once each; products accumulate in fp32.
  */
 int mohge_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int32_t* perm,
-                         const int32_t* offsets, const void* const* w13t, const void* const* w2t,
+                         const int32_t* offsets, const void* const* w13, const void* const* w2,
                          const void* saved, const void* dy_perm, void* dx_perm, void* const* dw13,
                          void* const* dw2, void* workspace, size_t workspace_bytes, void* stream);
 

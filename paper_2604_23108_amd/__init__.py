@@ -10,6 +10,6 @@ from .binding import (  # noqa: F401
     mohge_combine, mohge_aux_loss, mohge_workspace_size, mohge_tune, mohge_last_error, pack_w13,
     MoHGELayer, CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS, SELECT_GLOBAL, SELECT_PER_GROUP,
     F32, BF16, CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, mohge_expert_ffn_train,
-    mohge_transpose_weights, mohge_combine_bwd, mohge_expert_ffn_bwd, mohge_route_bwd,
+    mohge_combine_bwd, mohge_expert_ffn_bwd, mohge_route_bwd,
     mohge_shared_routing, mohge_combine_add, SharedExperts,
 )

@@ -22,7 +22,7 @@ CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD = 3, 4, 5
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
            "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_tune",
-           "mohge_expert_ffn_train", "mohge_transpose_weights", "mohge_combine_bwd",
+           "mohge_expert_ffn_train", "mohge_combine_bwd",
            "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_shared_routing", "mohge_combine_add",
            "mohge_workspace_size", "mohge_last_error"]
 
@@ -211,24 +211,17 @@ def mohge_expert_ffn_train(cfg, x, perm, offsets, w13, w2, y_perm, saved):
                                         _stream()), "mohge_expert_ffn_train")
 
 
-def mohge_transpose_weights(cfg, w13, w2, w13t, w2t):
-    for t in list(w13) + list(w2) + list(w13t) + list(w2t):
-        _ptr(t)
-    _check(lib().mohge_transpose_weights(cfg.ref(), _ptr_table(w13), _ptr_table(w2), _ptr_table(w13t),
-                                         _ptr_table(w2t), _stream()), "mohge_transpose_weights")
-
-
 def mohge_combine_bwd(cfg, dy, y_perm, inv_perm, gates, dgates, dy_perm):
     _check(lib().mohge_combine_bwd(cfg.ref(), _ptr(dy), _ptr(y_perm), _ptr(inv_perm), _ptr(gates),
                                    _ptr(dgates), _ptr(dy_perm), _stream()), "mohge_combine_bwd")
 
 
-def mohge_expert_ffn_bwd(cfg, x, perm, offsets, w13t, w2t, saved, dy_perm, dx_perm, dw13, dw2,
+def mohge_expert_ffn_bwd(cfg, x, perm, offsets, w13, w2, saved, dy_perm, dx_perm, dw13, dw2,
                          workspace):
-    for t in list(w13t) + list(w2t) + list(dw13) + list(dw2):
+    for t in list(w13) + list(w2) + list(dw13) + list(dw2):
         _ptr(t)
-    _check(lib().mohge_expert_ffn_bwd(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13t),
-                                      _ptr_table(w2t), _ptr(saved), _ptr(dy_perm), _ptr(dx_perm),
+    _check(lib().mohge_expert_ffn_bwd(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13),
+                                      _ptr_table(w2), _ptr(saved), _ptr(dy_perm), _ptr(dx_perm),
                                       _ptr_table(dw13), _ptr_table(dw2), _ptr(workspace),
                                       _nbytes(workspace), _stream()), "mohge_expert_ffn_bwd")
 
@@ -323,8 +316,6 @@ class MoHGELayer:
             self.saved = torch.empty(max(16, mohge_workspace_size(cfg, CALL_FFN_SAVED)), **u8)
             self.ws_ffn_bwd = torch.empty(max(16, mohge_workspace_size(cfg, CALL_EXPERT_FFN_BWD)), **u8)
             self.ws_route_bwd = torch.empty(max(16, mohge_workspace_size(cfg, CALL_ROUTE_BWD)), **u8)
-            self.w13t = [torch.empty((w.shape[0], w.shape[2], w.shape[1]), **bf) for w in self.w13]
-            self.w2t = [torch.empty((w.shape[0], w.shape[2], w.shape[1]), **bf) for w in self.w2]
             self.dw13 = [torch.empty_like(w) for w in self.w13]
             self.dw2 = [torch.empty_like(w) for w in self.w2]
             self.dgates = torch.empty((T, cfg.k_experts), **f32)
@@ -356,14 +347,13 @@ class MoHGELayer:
         return self.y
 
     def capture(self, x: torch.Tensor, dy: Optional[torch.Tensor] = None):
-        """Records one step (forward, or forward + weight transposes + backward when `dy` is
+        """Records one step (forward, or forward + backward when `dy` is
         given) into a HIP graph; `replay()` then launches the whole step with one call.  The step
         allocates nothing and never synchronises with the host, so the recorded launches are
         exactly the eager ones; `x` / `dy` are read from the same buffers on every replay."""
         def step():
             self.forward(x)
             if dy is not None:
-                self.transpose_weights()
                 self.backward(x, dy)
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
@@ -380,10 +370,6 @@ class MoHGELayer:
     def replay(self):
         self._graph.replay()
 
-    def transpose_weights(self):
-        """Refreshes the transposed weight copies the backward pass reads (once per weight update)."""
-        mohge_transpose_weights(self.cfg, self.w13, self.w2, self.w13t, self.w2t)
-
     def backward(self, x: torch.Tensor, dy: torch.Tensor) -> torch.Tensor:
         """Gradients of  sum(dy*y) + L_G + L_E  after `forward(x)`; returns dx, leaves the weight
         gradients in dw13 / dw2 / dw_group / dw_expert."""
@@ -391,7 +377,7 @@ class MoHGELayer:
             raise MohgeError("backward needs a layer created with training=True, backward=True")
         c = self.cfg
         mohge_combine_bwd(c, dy, self.y_perm, self.inv_perm, self.gates, self.dgates, self.dy_perm)
-        mohge_expert_ffn_bwd(c, x, self.perm, self.offsets, self.w13t, self.w2t, self.saved,
+        mohge_expert_ffn_bwd(c, x, self.perm, self.offsets, self.w13, self.w2, self.saved,
                              self.dy_perm, self.dx_perm, self.dw13, self.dw2, self.ws_ffn_bwd)
         mohge_route_bwd(c, x, self.w_group, self.w_expert, self.gs, self.es1, self.group_idx,
                         self.expert_idx, self.gates, self.dgates, self.stats, self.dx_perm,

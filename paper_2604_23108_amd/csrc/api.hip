@@ -291,23 +291,6 @@ int mohge_expert_ffn_train(const mohge_config* cfg, const void* x, const int32_t
                 "mohge_expert_ffn_train");
 }
 
-int mohge_transpose_weights(const mohge_config* cfg, const void* const* w13, const void* const* w2,
-                            void* const* w13t, void* const* w2t, void* stream) {
-  LayerDesc L;
-  int rc = check_config(cfg, &L);
-  if (rc) return rc;
-  if ((rc = need_bf16(cfg, "mohge_transpose_weights"))) return rc;
-  GroupPtrs W;
-  memset(&W, 0, sizeof(W));
-  PTR_TABLE(W.w13, w13, "w13");
-  PTR_TABLE(W.w2, w2, "w2");
-  void* t13[kMaxGroups];
-  void* t2[kMaxGroups];
-  PTR_TABLE(t13, w13t, "w13t");
-  PTR_TABLE(t2, w2t, "w2t");
-  return hip_rc(launch_transpose_weights(L, W, t13, t2, (hipStream_t)stream), "mohge_transpose_weights");
-}
-
 int mohge_combine_bwd(const mohge_config* cfg, const void* dy, const void* y_perm,
                       const int32_t* inv_perm, const float* gates, float* dgates, void* dy_perm,
                       void* stream) {
@@ -322,7 +305,7 @@ int mohge_combine_bwd(const mohge_config* cfg, const void* dy, const void* y_per
 }
 
 int mohge_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int32_t* perm,
-                         const int32_t* offsets, const void* const* w13t, const void* const* w2t,
+                         const int32_t* offsets, const void* const* w13, const void* const* w2,
                          const void* saved, const void* dy_perm, void* dx_perm, void* const* dw13,
                          void* const* dw2, void* workspace, size_t workspace_bytes, void* stream) {
   LayerDesc L;
@@ -330,12 +313,12 @@ int mohge_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int32_t* 
   if (rc) return rc;
   if ((rc = need_bf16(cfg, "mohge_expert_ffn_bwd"))) return rc;
   NEED(x); OPT(perm); NEED(offsets); NEED(saved); NEED(dy_perm); NEED(dx_perm); NEED(workspace);
-  const void* t13[kMaxGroups];
-  const void* t2[kMaxGroups];
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
   void* g13[kMaxGroups];
   void* g2[kMaxGroups];
-  PTR_TABLE(t13, w13t, "w13t");
-  PTR_TABLE(t2, w2t, "w2t");
+  PTR_TABLE(W.w13, w13, "w13");
+  PTR_TABLE(W.w2, w2, "w2");
   PTR_TABLE(g13, dw13, "dw13");
   PTR_TABLE(g2, dw2, "dw2");
   if (workspace_bytes < ffn_bwd_workspace_bytes(L)) {
@@ -343,7 +326,7 @@ int mohge_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int32_t* 
               ffn_bwd_workspace_bytes(L));
     return MOHGE_EWORKSPACE;
   }
-  return hip_rc(launch_expert_ffn_bwd(L, x, perm, offsets, t13, t2, saved, dy_perm, dx_perm, g13, g2,
+  return hip_rc(launch_expert_ffn_bwd(L, x, perm, offsets, W, saved, dy_perm, dx_perm, g13, g2,
                                       workspace, (hipStream_t)stream),
                 "mohge_expert_ffn_bwd");
 }

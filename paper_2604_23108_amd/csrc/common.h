@@ -76,17 +76,14 @@ size_t ffn_saved_bytes(const LayerDesc& L);
 hipError_t launch_expert_ffn_train(const LayerDesc& L, const void* x, const int32_t* perm,
                                    const int32_t* offsets, const GroupPtrs& W, void* y_perm,
                                    void* saved, hipStream_t s);
-hipError_t launch_transpose_weights(const LayerDesc& L, const GroupPtrs& W, void* const* w13t,
-                                    void* const* w2t, hipStream_t s);
 hipError_t launch_combine_bwd(const LayerDesc& L, const void* dy, const void* y_perm,
                               const int32_t* inv_perm, const float* gates, float* dgates,
                               void* dy_perm, hipStream_t s);
 size_t ffn_bwd_workspace_bytes(const LayerDesc& L);
 hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_t* perm,
-                                 const int32_t* offsets, const void* const* w13t,
-                                 const void* const* w2t, const void* saved, const void* dy_perm,
-                                 void* dx_perm, void* const* dw13, void* const* dw2, void* ws,
-                                 hipStream_t s);
+                                 const int32_t* offsets, const GroupPtrs& W, const void* saved,
+                                 const void* dy_perm, void* dx_perm, void* const* dw13,
+                                 void* const* dw2, void* ws, hipStream_t s);
 size_t route_bwd_workspace_bytes(const LayerDesc& L);
 hipError_t launch_route_bwd(const LayerDesc& L, const mohge_config& cfg, const void* x,
                             const float* w_group, const float* w_expert, const float* gs,

@@ -36,6 +36,19 @@
 // The MFMA takes the weight fragment as first operand: a lane then holds 4 consecutive
 // output features of one token; the epilogue packs them to bf16 (hardware conversion),
 // transposes through a wave-private LDS patch and stores whole row segments.
+//
+// Backward products (modes of the same kernel).  Their second operand, and for the weight
+// gradients both operands, are stored with the reduction index as the row: dH = dY W_down
+// reduces over the rows of W_down[e] ([d, F]), dX = [dA|dB] W13 over the rows of W13[e]
+// ([2F, d]), dW_e = A_e^T B_e over the routed rows of expert e.  Such an operand is staged as
+// 64 reduction rows x 256 features (512-byte row segments, again through global_load_lds,
+// chunks swizzled by the row), and its MFMA fragments are read with ds_read_b64_tr_b16, which
+// hands every lane four consecutive reduction indices of one feature.  No operand is
+// transposed in memory.  The ragged reduction of the weight gradients needs no padding
+// either: rows past the expert's last token are fetched from a row of zeros.  The
+// transposing read moves fewer bytes per clock than the 128-bit read (measured about 0.75x),
+// which costs these modes 15-20 % against a hypothetical pre-transposed operand; writing and
+// re-reading the transposed copies cost more than that.
 #include <type_traits>
 
 #include "common.h"
@@ -52,6 +65,11 @@ constexpr int kWGM = 2, kWGN = 4;
 
 // gate and up rows share a tile in the two up-projection modes
 constexpr bool is_up(int mode) { return mode == kUp || mode == kUpSave; }
+// operand stored reduction-index major (features contiguous): read through the transposing LDS read
+constexpr bool tr_a(int mode) { return mode == kWgrad; }
+constexpr bool tr_b(int mode) { return mode == kWgrad || mode == kDgradH || mode == kDgradX; }
+// reduction over d, F_g output columns
+constexpr bool red_d(int mode) { return is_up(mode) || mode == kDgradH; }
 
 template <int MODE>
 struct Shape {
@@ -88,12 +106,13 @@ __device__ __forceinline__ void expert_dims(const TileArgs& a, int e, int g, int
     row0 = 0;
     cnt = a.Mrows[g];
     ncols = a.Ncols[g];
-    kc = (a.poff[e + 1] - a.poff[e]) / 64;
+    kc = (a.offsets[e + 1] - a.offsets[e] + 63) / 64;
+    if (kc < 1) kc = 1;          // an expert without tokens still gets its zero gradient written
   } else {
     row0 = a.offsets[e];
     cnt = a.offsets[e + 1] - row0;
-    ncols = (is_up(MODE) || MODE == kDgradH) ? a.F[g] : a.d;
-    kc = ((is_up(MODE) || MODE == kDgradH) ? a.d : a.F[g]) / 64;
+    ncols = red_d(MODE) ? a.F[g] : a.d;
+    kc = (red_d(MODE) ? a.d : a.F[g]) / 64;
   }
 }
 
@@ -128,7 +147,7 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   if (v == 0) {
     long long kmax = 1;
     for (int g = 0; g < a.Ng; ++g)
-      kmax = max(kmax, (long long)(((is_up(MODE) || MODE == kDgradH) ? a.d : a.F[g]) / 64));
+      kmax = max(kmax, (long long)((red_d(MODE) ? a.d : a.F[g]) / 64));
     float best = 0.f;
     int best_rows = 256;
     for (int c = 0; c < 3; ++c) {
@@ -286,6 +305,9 @@ template <int MODE, int NACT>
 __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, unsigned char* lds,
                                          int lane, int w) {
   constexpr bool UP = is_up(MODE);
+  constexpr bool TRA = tr_a(MODE), TRB = tr_b(MODE);   // operand read by transposing LDS reads
+  constexpr bool WG = MODE == kWgrad;
+  constexpr bool DH = MODE == kDgradH;
 #ifdef MOHGE_PROBE
   long long ts[6];
 #endif
@@ -298,7 +320,8 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   constexpr int KK = BK / 16;                                        // MFMA k-steps per stage
   constexpr int B_LOADS = BN * CH / NT;
   // wave-wide load j of the token part fills tile rows [64j, 64j+64): only NACT of them matter
-  constexpr int A_LOADS = NACT * (64 / (NWAVES * RPL));
+  // (token-major operands: a part is 64 tokens x 256 features, all of it is loaded)
+  constexpr int A_LOADS = TRA ? BM * CH / NT : NACT * (64 / (NWAVES * RPL));
   static_assert(64 % (NWAVES * RPL) == 0 && B_LOADS * NWAVES * RPL == BN, "whole wave-wide loads");
   constexpr int PART = BM * ROWB;                 // 32 KB: one token part or one weight part
   constexpr int NM = NACT * NF;     // MFMAs per k-step
@@ -310,13 +333,15 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   auto b_part = [&](int slot) { return lds + (kStagesA + slot) * PART; };
 
   const int g = rec.e / a.N, e_i = rec.e % a.N, F = a.F[g];
-  // kWgrad: the expert's zero-padded token window [win, win + K) of the transposed operands
-  int win = 0, K;
-  if constexpr (MODE == kWgrad) {
-    win = a.poff[rec.e];
-    K = a.poff[rec.e + 1] - win;
+  int K;
+  int tok0 = 0, ntok = 0;       // kWgrad: the expert's routed rows [tok0, tok0 + ntok)
+  if constexpr (WG) {
+    tok0 = a.offsets[rec.e];
+    ntok = a.offsets[rec.e + 1] - tok0;
+    K = (ntok + BK - 1) / BK * BK;
+    if (K < BK) K = BK;
   } else {
-    K = (UP || MODE == kDgradH) ? a.d : F;
+    K = red_d(MODE) ? a.d : F;
   }
   const int wm = w / WGN, wn = w % WGN;
 
@@ -324,10 +349,43 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   // wave-wide load j fills tile rows (j*NWAVES + w)*RPL .. +RPL-1; lane l fills row l/CH,
   // physical chunk l%CH, which holds logical chunk (l%CH) ^ ((row >> SH) & (CH-1)).
   const int lrow = lane / CH, lpos = lane % CH;
-  const uint16_t* src_a[A_LOADS];
-  const uint16_t* src_b[B_LOADS];
+  const uint16_t* src_a[TRA ? 1 : A_LOADS];
+  const uint16_t* src_b[TRB ? 1 : B_LOADS];
+  // Operands stored reduction-index major (rows = reduction index, features contiguous): a part
+  // holds 64 reduction rows x 256 features, 512 bytes a row.  Wave-wide load j fills rows
+  // 2*(j*NWAVES + w) and the next one; lane l fills physical chunk l%32 of row t = that + l/32,
+  // which holds logical chunk (l%32) ^ (4*(t&3)): the four rows a transposing read touches at
+  // once then sit in different banks.
+  static_assert(!(TRA || TRB) || (NWAVES % 2 == 0 && B_LOADS == BM * CH / NT), "part layout");
+  const int trow0 = 2 * w + (lane >> 5);          // row of load 0; load j: + 2*NWAVES*j
+  const int tr_lc = (lane & 31) ^ (4 * (trow0 & 3));
+  const uint16_t* zsrc = nullptr;
+  unsigned tr_ldb = 0;                            // row pitch of the B operand in elements
+  if constexpr (TRA) {
+    int ma = rec.row_start + tr_lc * 8;
+    // feature chunks past the matrix edge: any chunk inside the row (never stored)
+    if (ma > a.Mrows[g] - 8) ma = a.Mrows[g] - 8;
+    src_a[0] = a.A + (long long)(tok0 + trow0) * a.lda + ma;      // load 0 of stage 0
+  }
+  if constexpr (TRB) {
+    int nb = rec.n0 + tr_lc * 8;
+    if constexpr (WG) {
+      if (nb > a.Ncols[g] - 8) nb = a.Ncols[g] - 8;
+      zsrc = a.zero_row + (lane & 31) * 8;
+      tr_ldb = a.ldb;
+      src_b[0] = a.B2 + (long long)(tok0 + trow0) * a.ldb + nb;
+    } else if constexpr (DH) {
+      if (nb > F - 8) nb = F - 8;                 // W_down[e]: [d, F]
+      tr_ldb = F;
+      src_b[0] = a.W[g] + ((long long)e_i * a.d + trow0) * F + nb;
+    } else {
+      if (nb > a.d - 8) nb = a.d - 8;             // W13[e]: [2F, d]; F holds 2 F_g here
+      tr_ldb = a.d;
+      src_b[0] = a.W[g] + ((long long)e_i * F + trow0) * a.d + nb;
+    }
+  }
 #pragma unroll
-  for (int j = 0; j < A_LOADS; ++j) {
+  for (int j = 0; j < (TRA ? 0 : A_LOADS); ++j) {
     const int row = (j * NWAVES + w) * RPL + lrow;
     const int rr = row < rec.rows ? row : rec.rows - 1;     // rows past the end: any valid row
     const int pos = rec.row_start + rr;
@@ -335,10 +393,10 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     if constexpr (UP) src_row = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
     else src_row = pos;
     const int chunk = lpos ^ ((row >> SH) & (CH - 1));
-    src_a[j] = a.A + src_row * a.lda + win + chunk * 8;
+    src_a[j] = a.A + src_row * a.lda + chunk * 8;
   }
 #pragma unroll
-  for (int j = 0; j < B_LOADS; ++j) {
+  for (int j = 0; j < (TRB ? 0 : B_LOADS); ++j) {
     const int row = (j * NWAVES + w) * RPL + lrow;
     const int chunk = lpos ^ ((row >> SH) & (CH - 1));
     long long wrow;
@@ -348,34 +406,37 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
       int f = rec.n0 + (row - half * (BN / 2));
       if (f > F - 1) f = F - 1;
       wrow = (long long)e_i * 2 * F + (long long)half * F + f;
-    } else if constexpr (MODE == kDgradH) {
-      int f = rec.n0 + row;                       // W_down^T of the expert: [F, d]
-      if (f > F - 1) f = F - 1;
-      wrow = (long long)e_i * F + f;
-    } else if constexpr (MODE == kWgrad) {
-      int n = rec.n0 + row;
-      if (n > a.Ncols[g] - 1) n = a.Ncols[g] - 1;
-      wrow = n;
     } else {
       int n = rec.n0 + row;
       if (n > a.d - 1) n = a.d - 1;
       wrow = (long long)e_i * a.d + n;
     }
-    if constexpr (MODE == kWgrad) src_b[j] = a.B2 + wrow * a.ldb + win + chunk * 8;
-    else src_b[j] = a.W[g] + wrow * K + chunk * 8;
+    src_b[j] = a.W[g] + wrow * K + chunk * 8;
   }
   const int ld_off = w * 1024;      // + j * NWAVES * 1024: wave-uniform destination inside a part
 
   // ---- LDS offsets of the MFMA operand fragments ---------------------------------------
   // fragment row = base + lane%32, logical chunk = 2*kk + lane/32
+  // Token-major parts: the transposing read works on groups of 16 lanes.  Lane 4*a + b of a
+  // group passes the address of 4 features (8 bytes) of token k0 + a at feature m0 + 4*b and
+  // gets back tokens k0..k0+3 of feature m0 + (its index in the group).  Group q of the wave
+  // covers features 16*(q&1).. of the fragment and tokens 8*(q>>1).. of the k-step, so two
+  // reads (k0, k0 + 4) give a lane its 8 consecutive reduction indices of one fragment row.
   const int frow = lane & 31, fh = lane >> 5;
-  int foff[KK];
+  const int tq = lane >> 4, ta = (lane & 15) >> 2, tb = lane & 3;
+  int foff[KK], foff_t[KK];       // plain parts / reduction-major parts (only one is live
+                                  // unless the two operands differ)
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk)
+  for (int kk = 0; kk < KK; ++kk) {
+    foff_t[kk] = (16 * kk + 8 * (tq >> 1) + ta) * 512 + (2 * (tq & 1) + (tb >> 1)) * 16 + (tb & 1) * 8;
     foff[kk] = frow * ROWB + (((2 * kk + fh) ^ ((frow >> SH) & (CH - 1))) << 4);
+  }
+  // first feature of a fragment -> its 16-byte chunk, swizzled like the loads wrote it
+  auto tr_base = [&](int feat) { return (((feat >> 3) ^ (4 * ta)) << 4); };
   int fbase[NR];     // token fragments first (interleaved over the wave rows), then weights
 #pragma unroll
-  for (int ti = 0; ti < NACT; ++ti) fbase[ti] = ((ti * WGM + wm) * 32) * ROWB;
+  for (int ti = 0; ti < NACT; ++ti)
+    fbase[ti] = TRA ? tr_base((ti * WGM + wm) * 32) : ((ti * WGM + wm) * 32) * ROWB;
 #pragma unroll
   for (int fi = 0; fi < NF; ++fi) {
     int row;
@@ -385,7 +446,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     } else {
       row = wn * WTN + fi * 32;
     }
-    fbase[NACT + fi] = row * ROWB;
+    fbase[NACT + fi] = TRB ? tr_base(row) : row * ROWB;
   }
 
   f32x16 acc[NF][NACT];
@@ -399,13 +460,41 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   const int KT = K / BK;
   // fragment r of k-step kk of the stage whose parts are pa (tokens) / pb (weights)
   auto read_frag = [&](const unsigned char* pa, const unsigned char* pb, int kk, int r) {
-    return *reinterpret_cast<const bf16x8*>((r < NACT ? pa : pb) + fbase[r] + foff[kk]);
+    const bool tr = r < NACT ? TRA : TRB;
+    const unsigned char* p = (r < NACT ? pa : pb) + fbase[r] + (tr ? foff_t[kk] : foff[kk]);
+    if (tr) {
+      typedef short s16x4 __attribute__((ext_vector_type(4)));
+      typedef short s16x8 __attribute__((ext_vector_type(8)));
+      typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * 512));
+      const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, v);
+    } else {
+      return *reinterpret_cast<const bf16x8*>(p);
+    }
+  };
+  // reduction-major operands: load j of a stage starts 2*NWAVES*j rows further down; in
+  // kWgrad the rows are routed tokens, and those at or past the expert's count read the zero
+  // row instead
+  auto tr_src = [&](const uint16_t* base, unsigned ld, int stage, int j) {
+    const int t = stage * BK + 2 * NWAVES * j;      // row of this load, less trow0
+    // wave-uniform 32 x 32 -> 64 bit product: stays in scalar registers
+    const uint16_t* p = base + (unsigned long long)(unsigned)t * ld;
+    if constexpr (WG) return t + trow0 < ntok ? p : zsrc;
+    else return p;
   };
   auto issue_a = [&](int stage, int j) {
-    async_copy16(src_a[j] + stage * BK, a_part(stage) + j * NWAVES * 1024 + ld_off);
+    const uint16_t* src;
+    if constexpr (TRA) src = tr_src(src_a[0], a.lda, stage, j);
+    else src = src_a[j] + stage * BK;
+    async_copy16(src, a_part(stage) + j * NWAVES * 1024 + ld_off);
   };
   auto issue_b = [&](int stage, int slot, int j) {
-    async_copy16(src_b[j] + stage * BK, b_part(slot) + j * NWAVES * 1024 + ld_off);
+    const uint16_t* src;
+    if constexpr (TRB) src = tr_src(src_b[0], tr_ldb, stage, j);
+    else src = src_b[j] + stage * BK;
+    async_copy16(src, b_part(slot) + j * NWAVES * 1024 + ld_off);
   };
 
   // prologue: request B(0), A(0), B(1), A(1), B(2) (those that exist), wait for the first
@@ -528,7 +617,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     static_assert(32 * CPR % 64 == 0, "whole wave-wide copies");
     unsigned char* my = lds + w * EPI_BYTES;
     const int tok_l = lane & 31, fsub = (lane >> 5) * 4;
-    const int ncols = (UP || MODE == kDgradH) ? F : (MODE == kWgrad ? a.Ncols[g] : a.d);
+    const int ncols = red_d(MODE) ? F : (WG ? a.Ncols[g] : a.d);
     const int col0 = rec.n0 + wn * OC;
     // kUpSave makes three passes over the patch: h, then the pre-activations a and b
     constexpr int NPASS = MODE == kUpSave ? 3 : 1;
@@ -563,10 +652,10 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
           const int trow = (ti * WGM + wm) * 32 + row;
           const int col = col0 + c * 8;
           if (trow < rec.rows && col < ncols) {
-            if constexpr (MODE == kWgrad) {
+            if constexpr (WG) {
               uint16_t* dst = a.Wout[g] + ((long long)e_i * a.Mrows[g] + rec.row_start + trow) * ncols + col;
               *reinterpret_cast<uint4*>(dst) = v;
-            } else if constexpr (MODE == kDgradH) {
+            } else if constexpr (DH) {
               // v holds dh; the stored a, b turn it into the gradients of the pre-activations
               const long long at = (long long)(rec.row_start + trow) * a.ldpre + col;
               const uint4 av = *reinterpret_cast<const uint4*>(a.pre + at);
@@ -631,10 +720,9 @@ __global__ void __launch_bounds__(64 * kWGM * kWGN) ffn_tile_kernel(const TileAr
                 rec.row_start < 0 || rec.n0 < 0);
     if (ok) {
       if constexpr (MODE == kWgrad) {
-        const int win = a.poff[rec.e], len = a.poff[rec.e + 1] - win;
         ok = rec.row_start + rec.rows <= a.Mrows[rec.e / a.N] && rec.n0 < a.Ncols[rec.e / a.N] &&
-             win >= 0 && len >= 64 && (len & 63) == 0 && (win & 63) == 0 && win + len <= a.lda &&
-             win + len <= a.ldb;
+             a.zero_row != nullptr && a.offsets[rec.e] >= 0 && a.offsets[rec.e + 1] <= a.P &&
+             a.offsets[rec.e] <= a.offsets[rec.e + 1];
       } else {
         ok = rec.row_start + rec.rows <= a.P;
       }
@@ -689,7 +777,7 @@ size_t tiled_sched_bytes(const LayerDesc& L) {
 
 long long tile_capacity(const LayerDesc& L, int mode) {
   if (mode == kUp || mode == kUpSave) return max_tiles(L, true);
-  if (mode == kDown) return max_tiles(L, false);
+  if (mode == kDown || mode == kDgradX) return max_tiles(L, false);
   if (mode == kDgradH) return ((long long)L.P / 64 + L.Ne) * ((L.Fmax + kBN - 1) / kBN);
   const int m = L.d > 2 * L.Fmax ? L.d : 2 * L.Fmax, n = L.d > L.Fmax ? L.d : L.Fmax;
   return (long long)L.Ne * ((m + 63) / 64) * ((n + kBN - 1) / kBN);
@@ -733,9 +821,9 @@ static hipError_t sched_and_run(const TileArgs& a, hipStream_t s) {
 
 hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s) {
   switch (mode) {
-    case kDown: return sched_and_run<kDown>(a, s);
     case kUpSave: return sched_and_run<kUpSave>(a, s);
     case kDgradH: return sched_and_run<kDgradH>(a, s);
+    case kDgradX: return sched_and_run<kDgradX>(a, s);
     case kWgrad: return sched_and_run<kWgrad>(a, s);
     default: return hipErrorInvalidValue;
   }

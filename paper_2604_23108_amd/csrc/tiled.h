@@ -7,20 +7,24 @@ namespace mohge {
 
 constexpr int kXcds = 8;
 
-// What a launch of the tile kernel computes.  All of them are C = A . B^T with both operands
-// contiguous along the reduction dimension and C's rows following A's.
+// What a launch of the tile kernel computes: C = A . B with fp32 accumulation.  An operand is
+// either contiguous along the reduction dimension ("plain": its LDS rows feed the matrix cores
+// through 128-bit reads) or stored reduction-index major, i.e. with its features contiguous
+// ("reduction-major": the fragments come out of LDS through the transposing 64-bit read).
 enum TileMode {
   kUp = 0,       // H = SiLU(X Wg^T) * (X Wu^T): rows = routed tokens, reduction over d
-  kDown = 1,     // Y = A W^T: rows = routed tokens, reduction over F[g] (forward down projection,
-                 //   and the input gradient dX = [dA|dB] . W13 with F[g] := 2 F_g, W := W13^T)
+  kDown = 1,     // Y = A W^T: rows = routed tokens, reduction over F[g]
   kUpSave = 2,   // kUp that also stores the pre-activations a, b for the backward pass
-  kDgradH = 3,   // dH = dY W_down, then (dA, dB) from the stored a, b: reduction over d
-  kWgrad = 4     // dW_e = A_e . B_e^T over the tokens of expert e (transposed activations)
+  kDgradH = 3,   // dH = dY W_down, then (dA, dB) from the stored a, b: reduction over d, B = W_down
+                 //   as stored ([N, d, F]: reduction-major)
+  kDgradX = 4,   // dX = [dA|dB] W13: reduction over F[g] := 2 F_g, B = W13 as stored ([N, 2F, d])
+  kWgrad = 5     // dW_e = A_e^T B_e over the routed rows of expert e: both operands token-major
+                 //   ([P, features]), i.e. reduction-major
 };
 
 struct TileRec {
   int e;          // expert
-  int row_start;  // first row of the tile: sorted position (token modes) / row of dW_e (kWgrad)
+  int row_start;  // first row of the tile: sorted position / row of dW_e (kWgrad)
   int rows;       // valid rows (1..256)
   int n0;         // first output column
 };
@@ -36,10 +40,10 @@ static_assert(sizeof(SchedHeader) <= 256, "header area");
 
 struct TileArgs {
   const uint16_t* A;          // token modes: [rows, lda] (kUp*: x, gathered through perm if given)
-                              // kWgrad: transposed activations [features, lda], expert windows at poff
+                              // kWgrad: [P, lda] in sorted order, its columns are the rows of dW
   const int32_t* perm;        // kUp* only, may be NULL
   const int32_t* offsets;     // [Ne+1] routed rows per expert (exclusive prefix sum)
-  const uint16_t* W[kMaxGroups];   // weight operand per group (token modes)
+  const uint16_t* W[kMaxGroups];   // weight operand per group (all modes but kWgrad)
   uint16_t* C;                // token modes: output [P, ldc]
   int lda, ldc;
   int Ke, Ng, N, Ne, d, P;
@@ -53,10 +57,10 @@ struct TileArgs {
   uint16_t* pre;              // kUpSave: out, kDgradH: in; [P, ldpre], row = a[0..F_g) b[0..F_g)
   uint16_t* C2;               // kDgradH: out [P, ldpre], row = dA[0..F_g) dB[0..F_g)
   int ldpre;
-  const uint16_t* B2;         // kWgrad: second transposed operand [features, ldb]
+  const uint16_t* B2;         // kWgrad: [P, ldb] in sorted order, its columns are the columns of dW
   int ldb;
-  const int32_t* poff;        // kWgrad: [Ne+1] start of every expert's zero-padded token window
-                              //   (multiples of 64; the window length is the reduction length)
+  const uint16_t* zero_row;   // kWgrad: 512 bytes of zeros (stands in for the rows past an
+                              //   expert's last token in its final 64-token stage)
   uint16_t* Wout[kMaxGroups]; // kWgrad: dW per group, [N, Mrows[g], Ncols[g]]
   int Mrows[kMaxGroups], Ncols[kMaxGroups];
 #ifdef MOHGE_PROBE

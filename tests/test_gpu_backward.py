@@ -36,7 +36,6 @@ def _run_backward(w, inp):
     L = dl.layer
     fwd = dl.run()
     dy = to_dev(inp.dy, True)
-    L.transpose_weights()
     L.backward(dl.x, dy)
     torch.cuda.synchronize()
     return dl, fwd, dy
@@ -188,14 +187,11 @@ def test_route_backward_fp32_chain_and_aux_terms():
     assert (L.dz == 0).all() and (L.dw_expert == 0).all() and (L.dx == 0).all()
 
 
-def test_transposed_weights_and_saved_activations():
+def test_training_forward_and_backward_determinism():
     w = _medium(SELECT_PER_GROUP, 35, T=200)
     inp = generate(w)
     dl, fwd, dy = _run_backward(w, inp)
     L = dl.layer
-    for g in range(w.n_groups):
-        assert torch.equal(L.w13t[g], L.w13[g].transpose(1, 2).contiguous())
-        assert torch.equal(L.w2t[g], L.w2[g].transpose(1, 2).contiguous())
     # the training forward gives the same y as the inference forward, bit for bit
     dl2 = DeviceLayer(w, inp, training=False)
     out2 = dl2.run()
@@ -205,6 +201,23 @@ def test_transposed_weights_and_saved_activations():
     L.backward(dl.x, dy)
     torch.cuda.synchronize()
     for a, b in zip(keep, [L.dx, L.dw_group] + L.dw13 + L.dw2):
+        assert torch.equal(a, b)
+
+
+def test_expert_backward_with_rows_already_in_sorted_order():
+    """perm == NULL: x holds one row per (token, slot) pair in sorted order; same gradients."""
+    w = _medium(SELECT_GLOBAL, 36, T=333)
+    inp = generate(w)
+    dl, fwd, dy = _run_backward(w, inp)
+    L = dl.layer
+    keep = [t.clone() for t in L.dw13 + L.dw2] + [L.dx_perm.clone()]
+    xs = dl.x[(L.perm[:dl.cfg.n_pairs] // dl.cfg.k_experts).long()].contiguous()
+    for t in L.dw13 + L.dw2 + [L.dx_perm]:
+        t.fill_(float("nan"))
+    M.mohge_expert_ffn_bwd(dl.cfg, xs, None, L.offsets, L.w13, L.w2, L.saved, L.dy_perm, L.dx_perm,
+                           L.dw13, L.dw2, L.ws_ffn_bwd)
+    torch.cuda.synchronize()
+    for a, b in zip(keep, L.dw13 + L.dw2 + [L.dx_perm]):
         assert torch.equal(a, b)
 
 
@@ -293,7 +306,7 @@ def test_backward_full_size_training_config_sampled():
 
 
 def test_backward_element_offsets_beyond_2_31():
-    # P*d, P*2*max F and the transposed buffers all exceed 2^31 elements
+    # P*d and P*2*max F exceed 2^31 elements
     w = WORKLOADS["training"].replace(name="big_offsets_bwd", T=135168, d=4096, n_groups=2,
                                       experts_per_group=2, d_ff=(256, 4096), k_groups=2, k_experts=4, seed=62)
     assert w.n_pairs * w.d > 2 ** 31
