@@ -5,8 +5,8 @@
 // group / expert.  Stage 1: every workgroup owns a contiguous range of tokens, a wave
 // takes one token at a time with lane <-> group / expert and keeps fp64 running sums in
 // registers; waves are added in a fixed order.  Stage 2: one workgroup adds the
-// per-workgroup partial sums (one wave per column, fixed order) and evaluates the losses.  No atomics, so
-// the result is bit-identical from run to run.
+// per-workgroup partial sums (rows of partial sums read side by side, fixed order) and
+// evaluates the losses.  No atomics, so the result is bit-identical from run to run.
 #include "common.h"
 
 namespace mohge {
@@ -66,18 +66,30 @@ __global__ void __launch_bounds__(256) aux_partial_kernel(const AuxArgs a) {
     a.part[(size_t)blockIdx.x * 2 * ncol + c] = ((red[0][c] + red[1][c]) + red[2][c]) + red[3][c];
 }
 
-__global__ void __launch_bounds__(256) aux_final_kernel(const AuxArgs a) {
+__global__ void __launch_bounds__(1024) aux_final_kernel(const AuxArgs a) {
   __shared__ double tot[2 * (kMaxGroups + kMaxExperts)];
-  const int ncol = a.Ng + a.Ne;
-  // one wave per column at a time: lanes take the workgroups' partial sums in strides of 64
-  // (index order within a lane), then a butterfly adds the 64 lane sums: a fixed order
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  for (int c = w; c < 2 * ncol; c += 4) {
+  __shared__ double red[1024];
+  const int ncol = a.Ng + a.Ne, C = 2 * ncol;
+  // thread t adds column t % C over the partial-sum rows r, r + R, r + 2R, ... (r = t / C, R =
+  // row groups that fit the workgroup): neighbouring threads read neighbouring columns of one
+  // row.  Then the R sums of a column are added in index order: a fixed order throughout.
+  const int R = 1024 / C > 0 ? 1024 / C : 1;
+  const int col = threadIdx.x % C, r = threadIdx.x / C;
+  if (r < R) {
+    double s0 = 0.0, s1 = 0.0;
+    int b = r;
+    for (; b + R < a.nblk; b += 2 * R) {
+      s0 += a.part[(size_t)b * C + col];
+      s1 += a.part[(size_t)(b + R) * C + col];
+    }
+    if (b < a.nblk) s0 += a.part[(size_t)b * C + col];
+    red[r * C + col] = s0 + s1;
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < C; c += blockDim.x) {
     double s = 0.0;
-    for (int b = lane; b < a.nblk; b += 64) s += a.part[(size_t)b * 2 * ncol + c];
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off, 64);
-    if (lane == 0) tot[c] = s;
+    for (int i = 0; i < R; ++i) s += red[i * C + c];
+    tot[c] = s;
   }
   __syncthreads();
   const double invT = 1.0 / (double)a.T;
@@ -126,7 +138,7 @@ hipError_t launch_aux_loss(const LayerDesc& L, const mohge_config& cfg, const fl
   a.alpha_g = cfg.alpha_g; a.alpha_e = cfg.alpha_e; a.eps = cfg.eps; a.freq_norm = cfg.aux_freq_norm;
   for (int g = 0; g < kMaxGroups; ++g) a.ratio[g] = g < L.Ng ? (float)L.F[g] / (float)L.Fmax : 0.f;
   hipLaunchKernelGGL(aux_partial_kernel, dim3(a.nblk), dim3(256), 0, s, a);
-  hipLaunchKernelGGL(aux_final_kernel, dim3(1), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(aux_final_kernel, dim3(1), dim3(1024), 0, s, a);
   return hipGetLastError();
 }
 

@@ -94,61 +94,48 @@ hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_
     return a;
   };
 
-  // x in sorted order (and the row of zeros); at least one workgroup so the zeros get written
+  TileArgs dh = with_sched(t, 0), dxa = with_sched(t, 1), w2a = with_sched(t, 2), w13a = with_sched(t, 3);
+  // dH = dY W_down, fused with the SwiGLU derivative: [dA|dB] rows
+  dh.A = static_cast<const uint16_t*>(dy_perm);
+  dh.lda = L.d;
+  dh.pre = const_cast<uint16_t*>(static_cast<const uint16_t*>(saved_pre(L, saved)));
+  dh.C2 = dab;
+  // dX = [dA|dB] W13: reduction length 2 F_g
+  dxa.A = dab;
+  dxa.lda = 2 * L.Fmax;
+  dxa.C = static_cast<uint16_t*>(dx_perm);
+  dxa.ldc = L.d;
+  // dW_down[e] = dY_e^T H_e : rows d, columns F_g
+  w2a.A = static_cast<const uint16_t*>(dy_perm); w2a.lda = L.d;
+  w2a.B2 = static_cast<const uint16_t*>(saved_h(L, saved)); w2a.ldb = L.Fmax;
+  // dW13[e] = [dA|dB]_e^T X_e : rows 2 F_g (gate rows, then up rows), columns d
+  w13a.A = dab; w13a.lda = 2 * L.Fmax; w13a.ldb = L.d;
+  w13a.B2 = perm ? xs : static_cast<const uint16_t*>(x);
+  w2a.zero_row = w13a.zero_row = zero_row;
+  w2a.force_rows = w13a.force_rows = 256;
+  for (int g = 0; g < L.Ng; ++g) {
+    dh.F[g] = L.F[g]; dh.W[g] = static_cast<const uint16_t*>(W.w2[g]);
+    dxa.F[g] = 2 * L.F[g]; dxa.W[g] = static_cast<const uint16_t*>(W.w13[g]);
+    w2a.F[g] = L.F[g]; w2a.Mrows[g] = L.d; w2a.Ncols[g] = L.F[g];
+    w2a.Wout[g] = static_cast<uint16_t*>(dw2[g]);
+    w13a.F[g] = L.F[g]; w13a.Mrows[g] = 2 * L.F[g]; w13a.Ncols[g] = L.d;
+    w13a.Wout[g] = static_cast<uint16_t*>(dw13[g]);
+  }
+
+  // all four tile schedules (they depend on `offsets` only), then x in sorted order (and the
+  // row of zeros; at least one workgroup so the zeros get written), then the products
+  hipError_t e = launch_bwd_schedules(dh, dxa, w2a, w13a, s);
+  if (e != hipSuccess) return e;
   const unsigned gather_blocks = L.P > 0 && perm ? (unsigned)((L.P + 3) / 4) : 1u;
   hipLaunchKernelGGL(gather_sorted_rows_kernel, dim3(gather_blocks), dim3(256), 0, s,
                      static_cast<const uint4*>(x), perm, reinterpret_cast<uint4*>(xs), L.P, L.Ke,
                      L.d / 8, reinterpret_cast<uint4*>(zero_row));
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e != hipSuccess) return e;
-
-  // dH = dY W_down, fused with the SwiGLU derivative: [dA|dB] rows
-  {
-    TileArgs a = with_sched(t, 0);
-    a.A = static_cast<const uint16_t*>(dy_perm);
-    a.lda = L.d;
-    a.pre = const_cast<uint16_t*>(static_cast<const uint16_t*>(saved_pre(L, saved)));
-    a.C2 = dab;
-    for (int g = 0; g < L.Ng; ++g) { a.F[g] = L.F[g]; a.W[g] = static_cast<const uint16_t*>(W.w2[g]); }
-    e = launch_tile_gemm(kDgradH, a, s);
-    if (e != hipSuccess) return e;
-  }
-  // dX = [dA|dB] W13: reduction length 2 F_g
-  {
-    TileArgs a = with_sched(t, 1);
-    a.A = dab;
-    a.lda = 2 * L.Fmax;
-    a.C = static_cast<uint16_t*>(dx_perm);
-    a.ldc = L.d;
-    for (int g = 0; g < L.Ng; ++g) { a.F[g] = 2 * L.F[g]; a.W[g] = static_cast<const uint16_t*>(W.w13[g]); }
-    e = launch_tile_gemm(kDgradX, a, s);
-    if (e != hipSuccess) return e;
-  }
-  // dW_down[e] = dY_e^T H_e : rows d, columns F_g
-  {
-    TileArgs a = with_sched(t, 2);
-    a.A = static_cast<const uint16_t*>(dy_perm); a.lda = L.d;
-    a.B2 = static_cast<const uint16_t*>(saved_h(L, saved)); a.ldb = L.Fmax;
-    a.zero_row = zero_row; a.force_rows = 256;
-    for (int g = 0; g < L.Ng; ++g) {
-      a.F[g] = L.F[g]; a.Mrows[g] = L.d; a.Ncols[g] = L.F[g];
-      a.Wout[g] = static_cast<uint16_t*>(dw2[g]);
-    }
-    e = launch_tile_gemm(kWgrad, a, s);
-    if (e != hipSuccess) return e;
-  }
-  // dW13[e] = [dA|dB]_e^T X_e : rows 2 F_g (gate rows, then up rows), columns d
-  {
-    TileArgs a = with_sched(t, 3);
-    a.A = dab; a.lda = 2 * L.Fmax; a.ldb = L.d;
-    a.B2 = perm ? xs : static_cast<const uint16_t*>(x);
-    a.zero_row = zero_row; a.force_rows = 256;
-    for (int g = 0; g < L.Ng; ++g) {
-      a.F[g] = L.F[g]; a.Mrows[g] = 2 * L.F[g]; a.Ncols[g] = L.d;
-      a.Wout[g] = static_cast<uint16_t*>(dw13[g]);
-    }
-    e = launch_tile_gemm(kWgrad, a, s);
-  }
+  if ((e = launch_tiles(kDgradH, dh, s)) != hipSuccess) return e;
+  if ((e = launch_tiles(kDgradX, dxa, s)) != hipSuccess) return e;
+  if ((e = launch_tiles(kWgrad, w2a, s)) != hipSuccess) return e;
+  e = launch_tiles(kWgrad, w13a, s);
   return e;
 }
 

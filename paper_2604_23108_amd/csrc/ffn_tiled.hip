@@ -244,7 +244,17 @@ __global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs up, co
   else build_schedule<kDown>(dn, sh);
 }
 
-// schedule of one backward (or saving) launch
+// the four schedules of the expert backward pass in one launch: workgroup i <-> launch i
+__global__ void __launch_bounds__(256) bwd_schedule_kernel(const TileArgs dh, const TileArgs dx,
+                                                           const TileArgs w2, const TileArgs w13) {
+  __shared__ SchedShared sh;
+  if (blockIdx.x == 0) build_schedule<kDgradH>(dh, sh);
+  else if (blockIdx.x == 1) build_schedule<kDgradX>(dx, sh);
+  else if (blockIdx.x == 2) build_schedule<kWgrad>(w2, sh);
+  else build_schedule<kWgrad>(w13, sh);
+}
+
+// schedule of one launch
 template <int MODE>
 __global__ void __launch_bounds__(256) tile_schedule_kernel(const TileArgs a) {
   __shared__ SchedShared sh;
@@ -817,6 +827,21 @@ static hipError_t sched_and_run(const TileArgs& a, hipStream_t s) {
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return launch_stage<MODE>(a, s);
+}
+
+hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const TileArgs& w2,
+                                const TileArgs& w13, hipStream_t s) {
+  hipLaunchKernelGGL(bwd_schedule_kernel, dim3(4), dim3(256), 0, s, dh, dx, w2, w13);
+  return hipGetLastError();
+}
+
+hipError_t launch_tiles(int mode, const TileArgs& a, hipStream_t s) {
+  switch (mode) {
+    case kDgradH: return launch_stage<kDgradH>(a, s);
+    case kDgradX: return launch_stage<kDgradX>(a, s);
+    case kWgrad: return launch_stage<kWgrad>(a, s);
+    default: return hipErrorInvalidValue;
+  }
 }
 
 hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s) {

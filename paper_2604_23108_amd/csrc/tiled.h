@@ -70,6 +70,10 @@ struct TileArgs {
 
 // One schedule launch + one tile-kernel launch for `mode` (backward modes and kUpSave).
 hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s);
+// The expert backward pass: all four schedules in one launch, then the tile launches alone.
+hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const TileArgs& w2,
+                                const TileArgs& w13, hipStream_t s);
+hipError_t launch_tiles(int mode, const TileArgs& a, hipStream_t s);
 // Largest number of tiles a schedule of `mode` can hold for layer L (sizes the record area).
 long long tile_capacity(const LayerDesc& L, int mode);
 int tile_num_cus();
