@@ -135,50 +135,100 @@ __global__ void __launch_bounds__(256) route_bwd_token_kernel(const RouteBwdArgs
   }
 }
 
-// partial sums of dW[z, c] = sum_t dz[t, z] x[t, c]: grid (d/64, S); a wave takes every 4th
-// token of the split, lane <-> column; 32 rows z at a time are kept in registers
-constexpr int kZC = 32;
+// partial sums of dW[z, c] = sum_t dz[t, z] x[t, c] on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32: C[32x32] += A[32x2] B[2x32]): grid (ceil(d/1024), S), a wave owns 256
+// columns and a pass of 32 rows z, and takes the tokens of its split two at a time.  Lane
+// (j = lane%32, k = lane/32) loads dz[t+k, z0+j] (the A operand as it is) and the 8 columns
+// c0 + 8j .. +7 of x[t+k] (one 16-byte load); MFMA m takes element m of every lane's eight, so
+// its 32 B-columns are the tile columns {8j + m}.  A lane ends up with 8 consecutive columns of
+// 16 rows.  Loads run one group of 4 steps ahead of the arithmetic; nothing crosses waves.
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+constexpr int kZC = 32, kTU = 4;
 
 __global__ void __launch_bounds__(256) route_bwd_wgrad_kernel(const RouteBwdArgs a) {
-  __shared__ float red[4][kZC][64];
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int c = blockIdx.x * 64 + lane;
+  const int j = lane & 31, k = lane >> 5;
+  const int c0 = (blockIdx.x * 4 + w) * 256;
+  if (c0 >= a.d) return;                       // wave-uniform; the kernel has no barriers
+  const int c = c0 + 8 * j;
+  const bool col_ok = c < a.d;
+  const int cc = col_ok ? c : 0;
   const int t0 = blockIdx.y * a.tok_per_split;
   const int t1 = min(a.T, t0 + a.tok_per_split);
   for (int z0 = 0; z0 < a.Z; z0 += kZC) {
-    float acc[kZC];
+    const int zl = z0 + j;
+    // step at token t: this lane's token is t + k (dz = 0 past the split or past Z)
+    auto load = [&](int t, uint4& xv, float& dzv) {
+      const int tok = t + k, tt = min(tok, a.T - 1);
+      xv = *reinterpret_cast<const uint4*>(a.x + (size_t)tt * a.d + cc);
+      const float v = a.dz[(size_t)tt * a.Z + min(zl, a.Z - 1)];
+      dzv = (tok < t1 && zl < a.Z) ? v : 0.f;
+    };
+    f32x16_t acc[8];
 #pragma unroll
-    for (int i = 0; i < kZC; ++i) acc[i] = 0.f;
-    for (int t = t0 + w; t < t1; t += 4) {
-      const float xv = bf16_to_f32(a.x[(size_t)t * a.d + c]);
-      const float* row = a.dz + (size_t)t * a.Z;
+    for (int m = 0; m < 8; ++m)
 #pragma unroll
-      for (int i = 0; i < kZC; ++i) {
-        const int z = min(z0 + i, a.Z - 1);       // rows past Z repeat the last one, never stored
-        acc[i] = fmaf(row[z], xv, acc[i]);
+      for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
+    uint4 xc[kTU];
+    float dc[kTU];
+#pragma unroll
+    for (int i = 0; i < kTU; ++i) load(t0 + 2 * i, xc[i], dc[i]);
+    for (int t = t0; t < t1; t += 2 * kTU) {
+      uint4 xn[kTU];
+      float dn[kTU];
+#pragma unroll
+      for (int i = 0; i < kTU; ++i) load(t + 2 * kTU + 2 * i, xn[i], dn[i]);
+#pragma unroll
+      for (int i = 0; i < kTU; ++i) {
+        const uint32_t u[4] = {xc[i].x, xc[i].y, xc[i].z, xc[i].w};
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+          const float xf = __uint_as_float((m & 1) ? (u[m >> 1] & 0xffff0000u) : (u[m >> 1] << 16));
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(dc[i], xf, acc[m], 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < kTU; ++i) { xc[i] = xn[i]; dc[i] = dn[i]; }
+    }
+    // accumulator r of a lane: row 8*(r/4) + 4*k + r%4 of the pass, B-column j
+    if (col_ok) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int z = z0 + 8 * (r / 4) + 4 * k + (r % 4);
+        if (z < a.Z) {
+          float4* dst = reinterpret_cast<float4*>(a.part + ((size_t)blockIdx.y * a.Z + z) * a.d + c);
+          dst[0] = make_float4(acc[0][r], acc[1][r], acc[2][r], acc[3][r]);
+          dst[1] = make_float4(acc[4][r], acc[5][r], acc[6][r], acc[7][r]);
+        }
       }
     }
-#pragma unroll
-    for (int i = 0; i < kZC; ++i) red[w][i][lane] = acc[i];
-    __syncthreads();
-    for (int i = w; i < kZC; i += 4) {
-      const int z = z0 + i;
-      if (z < a.Z)
-        a.part[((size_t)blockIdx.y * a.Z + z) * a.d + c] =
-            ((red[0][i][lane] + red[1][i][lane]) + red[2][i][lane]) + red[3][i][lane];
-    }
-    __syncthreads();
   }
 }
 
+// dW = sum of the S partial slices, in a fixed order: thread (q, j) of a workgroup adds slices
+// j, j + 8, ... of four neighbouring elements, then the 8 sums are added in index order.
 __global__ void __launch_bounds__(256) route_bwd_wsum_kernel(const RouteBwdArgs a) {
-  const size_t n = (size_t)a.Z * a.d;
-  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) {
-    float s = 0.f;
-    for (int k = 0; k < a.S; ++k) s += a.part[(size_t)k * n + i];
-    const size_t z = i / a.d, c = i % a.d;
-    if (z < (size_t)a.Ng) a.dw_group[z * a.d + c] = s;
-    else a.dw_expert[(z - a.Ng) * a.d + c] = s;
+  __shared__ float4 red[8][32];
+  const size_t n4 = (size_t)a.Z * a.d / 4;                 // d is a multiple of 4
+  const int q = threadIdx.x & 31, j = threadIdx.x >> 5;
+  const size_t i4 = (size_t)blockIdx.x * 32 + q;
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (i4 < n4) {
+    const float4* p = reinterpret_cast<const float4*>(a.part) + i4;
+    for (int k = j; k < a.S; k += 8) {
+      const float4 v = p[(size_t)k * n4];
+      s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    }
+  }
+  red[j][q] = s;
+  __syncthreads();
+  if (j == 0 && i4 < n4) {
+    float4 t = red[0][q];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) { t.x += red[k][q].x; t.y += red[k][q].y; t.z += red[k][q].z; t.w += red[k][q].w; }
+    const size_t i = i4 * 4, z = i / a.d, c = i % a.d;
+    float* dst = z < (size_t)a.Ng ? a.dw_group + z * a.d + c : a.dw_expert + (z - a.Ng) * a.d + c;
+    *reinterpret_cast<float4*>(dst) = t;
   }
 }
 
@@ -230,9 +280,14 @@ __global__ void __launch_bounds__(256) route_bwd_dx_kernel(const RouteBwdArgs a)
   }
 }
 
+// token splits of the weight-gradient reduction: about 64 tokens each, at most 256 splits and at
+// most 64 MB of partial sums
 static int wgrad_splits(const LayerDesc& L) {
-  int s = (L.T + 255) / 256;
-  return s < 1 ? 1 : (s > 64 ? 64 : s);
+  long long s = (L.T + 63) / 64;
+  const long long cap = (64ll << 20) / ((long long)(L.Ng + L.Ne) * L.d * 4);
+  if (s > cap) s = cap;
+  if (s > 256) s = 256;
+  return s < 1 ? 1 : (int)s;
 }
 
 static size_t up256(size_t b) { return (b + 255) / 256 * 256; }
@@ -266,8 +321,8 @@ hipError_t launch_route_bwd(const LayerDesc& L, const mohge_config& cfg, const v
   a.dz = dz_out ? dz_out : reinterpret_cast<float*>(base);
   a.part = reinterpret_cast<float*>(base + dz_bytes);
   hipLaunchKernelGGL(route_bwd_token_kernel, dim3((unsigned)((L.T + 3) / 4)), dim3(256), 0, s, a);
-  hipLaunchKernelGGL(route_bwd_wgrad_kernel, dim3((unsigned)(L.d / 64), (unsigned)a.S), dim3(256), 0, s, a);
-  hipLaunchKernelGGL(route_bwd_wsum_kernel, dim3(256), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(route_bwd_wgrad_kernel, dim3((unsigned)((L.d + 1023) / 1024), (unsigned)a.S), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(route_bwd_wsum_kernel, dim3((unsigned)(((size_t)a.Z * L.d / 4 + 31) / 32)), dim3(256), 0, s, a);
   hipLaunchKernelGGL(route_bwd_dx_kernel, dim3((unsigned)((L.T + 7) / 8), (unsigned)((L.d + 2047) / 2048)),
                      dim3(256), 0, s, a);
   return hipGetLastError();

@@ -150,6 +150,23 @@ def test_backward_random_configurations():
     assert done >= 10
 
 
+def test_backward_many_experts_wide_model():
+    """More than 32 router rows (two passes of the router weight-gradient kernel), a model width
+    that is not a multiple of its 512-column blocks, several token splits."""
+    w = WORKLOADS["training"].replace(name="bwd_many", T=900, d=576, n_groups=4, experts_per_group=12,
+                                      d_ff=(64, 128, 64, 192), k_groups=3, k_experts=6,
+                                      select_mode=SELECT_PER_GROUP, seed=77)
+    inp = generate(w)
+    inp.w_group = (inp.w_group * 10).astype(np.float32)
+    inp.w_expert = (inp.w_expert * 10).astype(np.float32)
+    dl, fwd, dy = _run_backward(w, inp)
+    ref_fwd = oracle.layer(w, inp)
+    keep = ref_fwd["route"]["margin"] > 1e-6
+    assert keep.all(), "pick another seed: a routing decision falls inside the exclusion margin"
+    assert (fwd["expert_idx"] == ref_fwd["route"]["expert_idx"]).all()
+    _compare_all_gradients(w, inp, dl, fwd, ref_fwd)
+
+
 def test_route_backward_fp32_chain_and_aux_terms():
     # the router chain alone, same fp32 dgates on both sides; large loss coefficients so that
     # a wrong auxiliary term cannot hide below the tolerance
