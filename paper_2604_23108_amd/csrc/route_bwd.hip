@@ -235,8 +235,7 @@ __global__ void __launch_bounds__(256) route_bwd_wsum_kernel(const RouteBwdArgs 
 // dx: grid (ceil(T/8), ceil(d/2048)); a thread owns 8 columns of 8 tokens
 __global__ void __launch_bounds__(256) route_bwd_dx_kernel(const RouteBwdArgs a) {
   constexpr int TB = 8;
-  const int c = (blockIdx.y * 256 + threadIdx.x) * 8;
-  if (c >= a.d) return;
+  const int c = (blockIdx.y * 256 + threadIdx.x) * 8;      // c >= d: helps staging dz only
   const int t0 = blockIdx.x * TB;
   float acc[TB][8];
 #pragma unroll
@@ -244,30 +243,51 @@ __global__ void __launch_bounds__(256) route_bwd_dx_kernel(const RouteBwdArgs a)
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[k][i] = 0.f;
     const int t = t0 + k;
-    if (t < a.T && a.dx_perm) {
-      for (int slot = 0; slot < a.Ke; ++slot) {
-        const int r = a.inv_perm[(size_t)t * a.Ke + slot];
-        const uint4 u = *reinterpret_cast<const uint4*>(a.dx_perm + (size_t)r * a.d + c);
-        acc[k][0] += __uint_as_float(u.x << 16); acc[k][1] += __uint_as_float(u.x & 0xffff0000u);
-        acc[k][2] += __uint_as_float(u.y << 16); acc[k][3] += __uint_as_float(u.y & 0xffff0000u);
-        acc[k][4] += __uint_as_float(u.z << 16); acc[k][5] += __uint_as_float(u.z & 0xffff0000u);
-        acc[k][6] += __uint_as_float(u.w << 16); acc[k][7] += __uint_as_float(u.w & 0xffff0000u);
+    if (t < a.T && a.dx_perm && c < a.d) {
+      // four slots at a time: the row loads are issued together, then added in slot order
+      for (int s0 = 0; s0 < a.Ke; s0 += 4) {
+        uint4 u[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int r = a.inv_perm[(size_t)t * a.Ke + min(s0 + i, a.Ke - 1)];
+          u[i] = *reinterpret_cast<const uint4*>(a.dx_perm + (size_t)r * a.d + c);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          if (s0 + i < a.Ke) {
+            acc[k][0] += __uint_as_float(u[i].x << 16); acc[k][1] += __uint_as_float(u[i].x & 0xffff0000u);
+            acc[k][2] += __uint_as_float(u[i].y << 16); acc[k][3] += __uint_as_float(u[i].y & 0xffff0000u);
+            acc[k][4] += __uint_as_float(u[i].z << 16); acc[k][5] += __uint_as_float(u[i].z & 0xffff0000u);
+            acc[k][6] += __uint_as_float(u[i].w << 16); acc[k][7] += __uint_as_float(u[i].w & 0xffff0000u);
+          }
+        }
       }
     }
   }
-  for (int z = 0; z < a.Z; ++z) {
-    const float* wr = z < a.Ng ? a.w_group + (size_t)z * a.d + c : a.w_expert + (size_t)(z - a.Ng) * a.d + c;
-    const float4 w0 = *reinterpret_cast<const float4*>(wr), w1 = *reinterpret_cast<const float4*>(wr + 4);
+  // dz of the workgroup's 8 tokens: one contiguous block of dz[T, Z], staged in LDS and read
+  // back as broadcasts
+  __shared__ float dzs[TB * (kMaxGroups + kMaxExperts)];
+  {
+    const int n = TB * a.Z;
+    const size_t base = (size_t)t0 * a.Z, lim = (size_t)a.T * a.Z;
+    for (int i = threadIdx.x; i < n; i += 256) dzs[i] = base + i < lim ? a.dz[base + i] : 0.f;
+  }
+  __syncthreads();
+  if (c < a.d) {
+    for (int z = 0; z < a.Z; ++z) {
+      const float* wr = z < a.Ng ? a.w_group + (size_t)z * a.d + c : a.w_expert + (size_t)(z - a.Ng) * a.d + c;
+      const float4 w0 = *reinterpret_cast<const float4*>(wr), w1 = *reinterpret_cast<const float4*>(wr + 4);
 #pragma unroll
-    for (int k = 0; k < TB; ++k) {
-      const int t = min(t0 + k, a.T - 1);
-      const float dzv = a.dz[(size_t)t * a.Z + z];
-      acc[k][0] = fmaf(dzv, w0.x, acc[k][0]); acc[k][1] = fmaf(dzv, w0.y, acc[k][1]);
-      acc[k][2] = fmaf(dzv, w0.z, acc[k][2]); acc[k][3] = fmaf(dzv, w0.w, acc[k][3]);
-      acc[k][4] = fmaf(dzv, w1.x, acc[k][4]); acc[k][5] = fmaf(dzv, w1.y, acc[k][5]);
-      acc[k][6] = fmaf(dzv, w1.z, acc[k][6]); acc[k][7] = fmaf(dzv, w1.w, acc[k][7]);
+      for (int k = 0; k < TB; ++k) {
+        const float dzv = dzs[k * a.Z + z];
+        acc[k][0] = fmaf(dzv, w0.x, acc[k][0]); acc[k][1] = fmaf(dzv, w0.y, acc[k][1]);
+        acc[k][2] = fmaf(dzv, w0.z, acc[k][2]); acc[k][3] = fmaf(dzv, w0.w, acc[k][3]);
+        acc[k][4] = fmaf(dzv, w1.x, acc[k][4]); acc[k][5] = fmaf(dzv, w1.y, acc[k][5]);
+        acc[k][6] = fmaf(dzv, w1.z, acc[k][6]); acc[k][7] = fmaf(dzv, w1.w, acc[k][7]);
+      }
     }
   }
+  if (c >= a.d) return;
 #pragma unroll
   for (int k = 0; k < TB; ++k) {
     const int t = t0 + k;
