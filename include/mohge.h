@@ -205,7 +205,8 @@ int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
 /*
  * mohge_expert_ffn with the same results, which additionally keeps, in `saved` (DEVICE,
  * mohge_workspace_size(cfg, MOHGE_CALL_FFN_SAVED) bytes, layout the library's), the hidden
- * activations h and the pre-activations a = W_gate x, b = W_up x (bf16) of every routed row.
+ * activations h and, with a = W_gate x, b = W_up x, the two factors b*SiLU'(a) and SiLU(a) that turn
+ * dh into (da, db) (all bf16) of every routed row.
  * Uses the matrix-core tile path for every T.
  */
 int mohge_expert_ffn_train(const mohge_config* cfg, const void* x, const int32_t* perm,
@@ -234,7 +235,7 @@ int mohge_combine_bwd(const mohge_config* cfg, const void* dy, const void* y_per
  * Out: dx_perm DEVICE [P,d]; dw13 HOST array [N_g] of DEVICE pointers, dw13[g] [N, 2*F_g, d]
  *      (gate rows, then up rows, as w13); dw2[g] DEVICE [N, d, F_g].  Overwritten, not accumulated.
  * workspace DEVICE, at least mohge_workspace_size(cfg, MOHGE_CALL_EXPERT_FFN_BWD) bytes.
- * a, b, h, dh and [da|db] pass through bf16 once each; products accumulate in fp32.
+ * h, the two stored factors, dh and [da|db] pass through bf16 once each; products accumulate in fp32.
  */
 int mohge_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int32_t* perm,
                          const int32_t* offsets, const void* const* w13, const void* const* w2,

@@ -36,6 +36,8 @@ def build(verbose: bool = False) -> str:
     global LIB, OBJDIR
     if os.environ.get("MOHGE_PROBE"):      # instrumented build for timing probes, separate file
         FLAGS.append("-DMOHGE_PROBE")
+        if os.environ.get("MOHGE_EXP"):
+            FLAGS.append("-D" + os.environ["MOHGE_EXP"])
         LIB = os.path.join(HERE, "libmohge_probe.so")
         OBJDIR = os.path.join(HERE, "_build_probe")
     os.makedirs(OBJDIR, exist_ok=True)

@@ -114,7 +114,7 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
 }
 
 // Training forward (bf16): what the backward pass needs is kept in `saved`:
-//   [tile schedules][h: P x Fmax][pre-activations a|b: P x 2*Fmax]
+//   [tile schedules][h: P x Fmax][backward factors b SiLU'(a) | SiLU(a): P x 2*Fmax]
 static size_t saved_pre_offset(const LayerDesc& L) {
   const size_t b = tiled_sched_bytes(L) + (size_t)(L.P > 0 ? L.P : 1) * L.Fmax * 2;
   return (b + 255) / 256 * 256;

@@ -25,6 +25,10 @@ namespace mohge {
 
 const void* saved_h(const LayerDesc& L, const void* saved);
 const void* saved_pre(const LayerDesc& L, const void* saved);
+#ifdef MOHGE_PROBE
+extern long long* g_dbg;     // cycle counters of the instrumented build
+extern int g_dbg_which;      // which of the four launches fills them
+#endif
 
 // rows of x in sorted order: xs[p] = x[perm[p] / Ke]; one wave per row (perm == NULL: x already
 // is in sorted order, nothing is copied).  Workgroup 0 also
@@ -122,6 +126,12 @@ hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_
     w13a.Wout[g] = static_cast<uint16_t*>(dw13[g]);
   }
 
+#ifdef MOHGE_PROBE
+  {
+    TileArgs* sel[4] = {&dh, &dxa, &w2a, &w13a};
+    if (g_dbg_which >= 0 && g_dbg_which < 4) sel[g_dbg_which]->dbg = g_dbg;
+  }
+#endif
   // all four tile schedules (they depend on `offsets` only), then x in sorted order (and the
   // row of zeros; at least one workgroup so the zeros get written), then the products
   hipError_t e = launch_bwd_schedules(dh, dxa, w2a, w13a, s);

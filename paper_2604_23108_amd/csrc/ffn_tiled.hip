@@ -74,6 +74,11 @@ constexpr bool red_d(int mode) { return is_up(mode) || mode == kDgradH; }
 template <int MODE>
 struct Shape {
   static constexpr int NCOLS_PER_TILE = is_up(MODE) ? kBN / 2 : kBN;
+  // wave grid of the workgroup: 2 x 4 waves with 128 x 64 wave tiles (2 x 2 waves with
+  // 128 x 128 wave tiles read a third fewer fragments per MFMA but measured slower in every
+  // mode, the weight gradients with their transposing reads included)
+  static constexpr int WGM = kWGM, WGN = kWGN;
+  static constexpr int THREADS = 64 * WGM * WGN;
 };
 
 // ---------------------------------------------------------------------------------------
@@ -277,13 +282,14 @@ __device__ __forceinline__ void async_copy16(const void* gptr, void* lds_uniform
 
 #define MOHGE_PIN() __builtin_amdgcn_sched_barrier(0)
 
-// SwiGLU backward for 8 packed bf16 values: with s = sigmoid(a),
-//   dA = dh * b * s * (1 + a*(1-s)),  dB = dh * a * s.
-__device__ __forceinline__ void swiglu_bwd8(const uint4 dh, const uint4 av, const uint4 bv, uint4& da,
+// SwiGLU backward for 8 packed bf16 values.  The training forward stored, per hidden unit,
+//   p = b * SiLU'(a) = b * s * (1 + a*(1-s))   and   q = SiLU(a) = a * s,   s = sigmoid(a),
+// so that  dA = dh * p,  dB = dh * q.
+__device__ __forceinline__ void swiglu_bwd8(const uint4 dh, const uint4 pv, const uint4 qv, uint4& da,
                                             uint4& db) {
   const uint32_t hw[4] = {dh.x, dh.y, dh.z, dh.w};
-  const uint32_t aw[4] = {av.x, av.y, av.z, av.w};
-  const uint32_t bw[4] = {bv.x, bv.y, bv.z, bv.w};
+  const uint32_t pw[4] = {pv.x, pv.y, pv.z, pv.w};
+  const uint32_t qw[4] = {qv.x, qv.y, qv.z, qv.w};
   uint32_t oa[4], ob[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
@@ -291,11 +297,8 @@ __device__ __forceinline__ void swiglu_bwd8(const uint4 dh, const uint4 av, cons
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       const float g = __uint_as_float(h ? (hw[i] & 0xffff0000u) : (hw[i] << 16));
-      const float x = __uint_as_float(h ? (aw[i] & 0xffff0000u) : (aw[i] << 16));
-      const float u = __uint_as_float(h ? (bw[i] & 0xffff0000u) : (bw[i] << 16));
-      const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-x));
-      ra[h] = g * u * sg * (1.f + x * (1.f - sg));
-      rb[h] = g * x * sg;
+      ra[h] = g * __uint_as_float(h ? (pw[i] & 0xffff0000u) : (pw[i] << 16));
+      rb[h] = g * __uint_as_float(h ? (qw[i] & 0xffff0000u) : (qw[i] << 16));
     }
     oa[i] = pack_bf16x2(ra[0], ra[1]);
     ob[i] = pack_bf16x2(rb[0], rb[1]);
@@ -323,7 +326,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
 #endif
   PROBE_T(0);
   constexpr int BM = kBM, BN = kBN, BK = kBK;
-  constexpr int WGM = kWGM, WGN = kWGN, NWAVES = WGM * WGN, NT = 64 * NWAVES;
+  constexpr int WGM = Shape<MODE>::WGM, WGN = Shape<MODE>::WGN, NWAVES = WGM * WGN, NT = 64 * NWAVES;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MF = WTM / 32, NF = WTN / 32;
   constexpr int CH = BK / 8, ROWB = BK * 2, RPL = 64 / CH, SH = 1;   // 8 chunks, 128-byte rows
@@ -555,7 +558,10 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
       for (int q = 0; q < PER; ++q) {
         const int x = i * PER + q;
         if (RN && x < NR) {
-          nxt[x] = read_frag(pa, pb, kk_next, x);
+          // in order of first use by the next k-step's MFMAs: weight fragment 0, the token
+          // fragments, then the other weight fragments
+          const int fr = x == 0 ? NACT : (x <= NACT ? x - 1 : x);
+          nxt[fr] = read_frag(pa, pb, kk_next, fr);
           MOHGE_PIN();
         } else if (x < NX) {
           issue_one(x - (RN ? NR : 0));
@@ -629,33 +635,66 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
     const int tok_l = lane & 31, fsub = (lane >> 5) * 4;
     const int ncols = red_d(MODE) ? F : (WG ? a.Ncols[g] : a.d);
     const int col0 = rec.n0 + wn * OC;
-    // kUpSave makes three passes over the patch: h, then the pre-activations a and b
+    // kUpSave makes three passes over the patch: h, then the backward factors p and q
     constexpr int NPASS = MODE == kUpSave ? 3 : 1;
+    constexpr int NIT = 32 * CPR / 64;     // row-segment copies per lane and fragment
+    // kDgradH: the stored factor chunks a lane will meet in the copy loop are requested before
+    // the transposition through LDS (rows / columns past the tile edge: any valid chunk)
+    auto load_pre = [&](int ti, uint4 (&pa)[NIT], uint4 (&pb)[NIT]) {
+#pragma unroll
+      for (int it = 0; it < NIT; ++it) {
+        const int idx = it * 64 + lane;
+        int trow = (ti * WGM + wm) * 32 + idx / CPR, col = col0 + (idx % CPR) * 8;
+        if (trow > rec.rows - 1) trow = rec.rows - 1;
+        if (col > ncols - 8) col = ncols - 8;
+        const long long at = (long long)(rec.row_start + trow) * a.ldpre + col;
+        pa[it] = *reinterpret_cast<const uint4*>(a.pre + at);
+        pb[it] = *reinterpret_cast<const uint4*>(a.pre + at + F);
+      }
+    };
 #pragma unroll
     for (int ti = 0; ti < NACT; ++ti) {
+      uint4 pre_a[DH ? NIT : 1], pre_b[DH ? NIT : 1];
+      if constexpr (DH) load_pre(ti, pre_a, pre_b);
+      // kUpSave: the two factors the backward pass multiplies dh with, computed along with h
+      // (one sigmoid per element) and kept packed until their pass
+      uint2 keep_p[MODE == kUpSave ? NFo * 4 : 1], keep_q[MODE == kUpSave ? NFo * 4 : 1];
 #pragma unroll
       for (int pass = 0; pass < NPASS; ++pass) {
 #pragma unroll
         for (int fi = 0; fi < NFo; ++fi)
 #pragma unroll
           for (int blk = 0; blk < 4; ++blk) {
-            float v[4];
+            uint2 o;
+            if (MODE == kUpSave && pass > 0) {
+              o = pass == 1 ? keep_p[fi * 4 + blk] : keep_q[fi * 4 + blk];
+            } else {
+              float v[4], vp[4], vq[4];
 #pragma unroll
-            for (int b = 0; b < 4; ++b) {
-              if constexpr (UP) {
-                const float ga = acc[fi][ti][blk * 4 + b], ub = acc[fi + NF / 2][ti][blk * 4 + b];
-                v[b] = pass == 0 ? swiglu(ga, ub) : (pass == 1 ? ga : ub);
-              } else {
-                v[b] = acc[fi][ti][blk * 4 + b];
+              for (int b = 0; b < 4; ++b) {
+                if constexpr (MODE == kUpSave) {
+                  const float ga = acc[fi][ti][blk * 4 + b], ub = acc[fi + NF / 2][ti][blk * 4 + b];
+                  const float sg = __builtin_amdgcn_rcpf(1.f + __expf(-ga));
+                  vq[b] = ga * sg;                                   // SiLU(a)
+                  v[b] = ga * ub * sg;                               // h, rounded as in kUp
+                  vp[b] = ub * sg * (1.f + ga * (1.f - sg));         // b * SiLU'(a)
+                } else if constexpr (UP) {
+                  v[b] = swiglu(acc[fi][ti][blk * 4 + b], acc[fi + NF / 2][ti][blk * 4 + b]);
+                } else {
+                  v[b] = acc[fi][ti][blk * 4 + b];
+                }
+              }
+              o.x = pack_bf16x2(v[0], v[1]);
+              o.y = pack_bf16x2(v[2], v[3]);
+              if constexpr (MODE == kUpSave) {
+                keep_p[fi * 4 + blk] = make_uint2(pack_bf16x2(vp[0], vp[1]), pack_bf16x2(vp[2], vp[3]));
+                keep_q[fi * 4 + blk] = make_uint2(pack_bf16x2(vq[0], vq[1]), pack_bf16x2(vq[2], vq[3]));
               }
             }
-            uint2 o;
-            o.x = pack_bf16x2(v[0], v[1]);
-            o.y = pack_bf16x2(v[2], v[3]);
             *reinterpret_cast<uint2*>(my + tok_l * RS + (fi * 32 + blk * 8 + fsub) * 2) = o;
           }
 #pragma unroll
-        for (int it = 0; it < 32 * CPR / 64; ++it) {
+        for (int it = 0; it < NIT; ++it) {
           const int idx = it * 64 + lane;
           const int row = idx / CPR, c = idx % CPR;
           const uint4 v = *reinterpret_cast<const uint4*>(my + row * RS + c * 16);
@@ -666,12 +705,10 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
               uint16_t* dst = a.Wout[g] + ((long long)e_i * a.Mrows[g] + rec.row_start + trow) * ncols + col;
               *reinterpret_cast<uint4*>(dst) = v;
             } else if constexpr (DH) {
-              // v holds dh; the stored a, b turn it into the gradients of the pre-activations
+              // v holds dh; the stored factors turn it into the gradients of the pre-activations
               const long long at = (long long)(rec.row_start + trow) * a.ldpre + col;
-              const uint4 av = *reinterpret_cast<const uint4*>(a.pre + at);
-              const uint4 bv = *reinterpret_cast<const uint4*>(a.pre + at + F);
               uint4 da, db;
-              swiglu_bwd8(v, av, bv, da, db);
+              swiglu_bwd8(v, pre_a[it], pre_b[it], da, db);
               *reinterpret_cast<uint4*>(a.C2 + at) = da;
               *reinterpret_cast<uint4*>(a.C2 + at + F) = db;
             } else if (pass == 0) {
@@ -703,7 +740,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
 // through one LDS word between the tiles.  Which workgroup computes a tile has no influence
 // on the tile's result, so the output stays bit-identical from run to run.
 template <int MODE>
-__global__ void __launch_bounds__(64 * kWGM * kWGN) ffn_tile_kernel(const TileArgs a) {
+__global__ void __launch_bounds__(Shape<MODE>::THREADS) ffn_tile_kernel(const TileArgs a) {
   extern __shared__ __align__(1024) unsigned char lds[];
   // LDS word for the hand-over: beyond the epilogue patches, inside a stage buffer that is
   // dead between a tile's last barrier and the first barrier of the next tile
@@ -757,6 +794,8 @@ __global__ void __launch_bounds__(64 * kWGM * kWGN) ffn_tile_kernel(const TileAr
 static int g_force_rows[2] = {0, 0};
 #ifdef MOHGE_PROBE
 long long* g_dbg = nullptr;
+int g_dbg_which = -1;
+extern "C" void mohge_probe_select(int which) { g_dbg_which = which; }
 extern "C" void mohge_probe_buffer(void* p) { g_dbg = static_cast<long long*>(p); }
 #endif
 
@@ -817,7 +856,7 @@ static hipError_t launch_stage(const TileArgs& a, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.ncu), dim3(64 * kWGM * kWGN), smem, s, a);
+  hipLaunchKernelGGL(kern, dim3(a.ncu), dim3(Shape<MODE>::THREADS), smem, s, a);
   return hipGetLastError();
 }
 
@@ -854,8 +893,8 @@ hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s) {
   }
 }
 
-// `pre` != NULL (training): the up projection also stores the pre-activations a, b as rows of
-// [P, 2*Fmax] for the backward pass.
+// `pre` != NULL (training): the up projection also stores the backward factors b SiLU'(a) and
+// SiLU(a) as rows of [P, 2*Fmax] for the backward pass.
 hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* perm,
                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
                             hipStream_t s, int stages, void* pre) {

@@ -14,8 +14,8 @@ constexpr int kXcds = 8;
 enum TileMode {
   kUp = 0,       // H = SiLU(X Wg^T) * (X Wu^T): rows = routed tokens, reduction over d
   kDown = 1,     // Y = A W^T: rows = routed tokens, reduction over F[g]
-  kUpSave = 2,   // kUp that also stores the pre-activations a, b for the backward pass
-  kDgradH = 3,   // dH = dY W_down, then (dA, dB) from the stored a, b: reduction over d, B = W_down
+  kUpSave = 2,   // kUp that also stores p = b SiLU'(a) and q = SiLU(a) for the backward pass
+  kDgradH = 3,   // dH = dY W_down, then (dA, dB) = dH (p, q): reduction over d, B = W_down
                  //   as stored ([N, d, F]: reduction-major)
   kDgradX = 4,   // dX = [dA|dB] W13: reduction over F[g] := 2 F_g, B = W13 as stored ([N, 2F, d])
   kWgrad = 5     // dW_e = A_e^T B_e over the routed rows of expert e: both operands token-major
@@ -54,7 +54,7 @@ struct TileArgs {
   int ncu;                    // compute units = persistent workgroups
   int force_rows;             // 0 = choose, else 64/128/192/256
   // --- backward extensions -------------------------------------------------------------
-  uint16_t* pre;              // kUpSave: out, kDgradH: in; [P, ldpre], row = a[0..F_g) b[0..F_g)
+  uint16_t* pre;              // kUpSave: out, kDgradH: in; [P, ldpre], row = p[0..F_g) q[0..F_g)
   uint16_t* C2;               // kDgradH: out [P, ldpre], row = dA[0..F_g) dB[0..F_g)
   int ldpre;
   const uint16_t* B2;         // kWgrad: [P, ldb] in sorted order, its columns are the columns of dW
