@@ -275,7 +275,9 @@ size_t mohge_workspace_size(const mohge_config* cfg, int which_call);
 
 /* Tuning hook for benchmarks: knob 0 / 1 forces the token-tile height (64, 128, 192 or
  * 256 rows; 0 = chosen per call from the routed counts) of the up / down projection of the
- * bf16 prefill path.  Results do not depend on it.  Process-wide, not thread-safe. */
+ * bf16 prefill path; knob 2 = 0 runs the up and the down projection of mohge_expert_ffn /
+ * mohge_expert_ffn_train as two launches instead of one fused launch (1, the default).
+ * Results do not depend on any of them.  Process-wide, not thread-safe. */
 int mohge_tune(int knob, int value);
 
 /* Message of the last error on this thread ("" if none); valid until the next call. */

@@ -98,8 +98,10 @@ struct SchedShared {
   long long tp[kMaxExperts + 1];   // tiles before expert v
   long long cp[kMaxExperts + 1];   // cost before expert v
   int e[kMaxExperts], cnt[kMaxExperts], nt[kMaxExperts], kc[kMaxExperts], row0[kMaxExperts];
+  int fp[kMaxExperts + 1];         // row blocks before expert v
   long long wsum[4][3];
   int rows;
+  int xb[kXcds + 1];               // tile ranges per XCD (copy of the header's)
 };
 
 // Per-expert quantities of a mode: rows (`cnt`, starting at `row0`), output columns, and
@@ -121,23 +123,20 @@ __device__ __forceinline__ void expert_dims(const TileArgs& a, int e, int g, int
   }
 }
 
+// Tile height for a launch of MODE: the candidate with the lowest estimated time.  Called by all
+// 256 threads; uses sh.wsum and sh.rows.
 template <int MODE>
-__device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& sh) {
+__device__ __forceinline__ int choose_tile_rows(const TileArgs& a, SchedShared& sh) {
   constexpr int NCPT = Shape<MODE>::NCOLS_PER_TILE;
   const int v = threadIdx.x, lane = v & 63, w = v >> 6;
-  int e = 0, cnt = 0, nt = 0, kc = 0, row0 = 0;
+  int cnt = 0, nt = 0, kc = 0;
   if (v < a.Ne) {
-    // visiting order: expert index major, group minor (widest group first): consecutive
-    // experts form "all-size sets", so every XCD range holds the same mix of reduction
-    // lengths instead of one range getting all the long tiles
     const int g = a.order[v % a.Ng];
-    e = g * a.N + v / a.Ng;
-    int ncols;
+    const int e = g * a.N + v / a.Ng;
+    int ncols, row0;
     expert_dims<MODE>(a, e, g, row0, cnt, ncols, kc);
     nt = (ncols + NCPT - 1) / NCPT;
   }
-  sh.e[v] = e; sh.cnt[v] = cnt; sh.nt[v] = nt; sh.kc[v] = kc; sh.row0[v] = row0;
-  // tile height: fewest rounds over the compute units, weighted by the reduction length
   long long cand[3];
 #pragma unroll
   for (int c = 0; c < 3; ++c) {
@@ -147,6 +146,7 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
     for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off, 64);
     cand[c] = x;
   }
+  __syncthreads();
   if (lane == 0) { sh.wsum[w][0] = cand[0]; sh.wsum[w][1] = cand[1]; sh.wsum[w][2] = cand[2]; }
   __syncthreads();
   if (v == 0) {
@@ -167,17 +167,42 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   }
   __syncthreads();
   const int h = sh.rows;
-  // exclusive prefix sums of tiles and cost over the experts
+  __syncthreads();
+  return h;
+}
+
+// Tile list of a launch of MODE with tile height h.  FUSED: the list belongs to a launch that
+// runs up and down tiles together; down tiles then carry the number of up tiles they wait for.
+template <int MODE>
+__device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& sh, int h, bool fused) {
+  constexpr int NCPT = Shape<MODE>::NCOLS_PER_TILE;
+  const int v = threadIdx.x, lane = v & 63, w = v >> 6;
+  int e = 0, cnt = 0, nt = 0, kc = 0, row0 = 0;
+  if (v < a.Ne) {
+    // visiting order: expert index major, group minor (widest group first): consecutive
+    // experts form "all-size sets", so every XCD range holds the same mix of reduction
+    // lengths instead of one range getting all the long tiles
+    const int g = a.order[v % a.Ng];
+    e = g * a.N + v / a.Ng;
+    int ncols;
+    expert_dims<MODE>(a, e, g, row0, cnt, ncols, kc);
+    nt = (ncols + NCPT - 1) / NCPT;
+  }
+  sh.e[v] = e; sh.cnt[v] = cnt; sh.nt[v] = nt; sh.kc[v] = kc; sh.row0[v] = row0;
+  // exclusive prefix sums of tiles, cost and row blocks over the experts
   const long long my_t = (long long)((cnt + h - 1) / h) * nt;
   const long long my_c = (long long)((cnt + 63) / 64) * nt * kc;
+  const long long my_f = MODE == kWgrad ? 0 : (cnt + h - 1) / h;
   const long long it = wave_incl_scan64(my_t, lane), ic = wave_incl_scan64(my_c, lane);
-  if (lane == 63) { sh.wsum[w][0] = it; sh.wsum[w][1] = ic; }
+  const long long jf = wave_incl_scan64(my_f, lane);
+  if (lane == 63) { sh.wsum[w][0] = it; sh.wsum[w][1] = ic; sh.wsum[w][2] = jf; }
   __syncthreads();
-  long long bt = 0, bc = 0;
-  for (int ww = 0; ww < w; ++ww) { bt += sh.wsum[ww][0]; bc += sh.wsum[ww][1]; }
+  long long bt = 0, bc = 0, bf = 0;
+  for (int ww = 0; ww < w; ++ww) { bt += sh.wsum[ww][0]; bc += sh.wsum[ww][1]; bf += sh.wsum[ww][2]; }
   sh.tp[v] = bt + it - my_t;
   sh.cp[v] = bc + ic - my_c;
-  if (v == 255) { sh.tp[256] = bt + it; sh.cp[256] = bc + ic; }
+  sh.fp[v] = (int)(bf + jf - my_f);
+  if (v == 255) { sh.tp[256] = bt + it; sh.cp[256] = bc + ic; sh.fp[256] = (int)(bf + jf); }
   __syncthreads();
   const int total = (int)sh.tp[256];
   const long long ctot = sh.cp[256];
@@ -199,6 +224,10 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
     r.row_start = sh.row0[ve] + mi * h;
     r.rows = min(h, c - mi * h);
     r.n0 = ni * NCPT;
+    r.fam = sh.fp[ve] + mi;
+    // a down tile of the fused forward waits for the up tiles of its row block: one per 128
+    // hidden units of the expert's group (F holds the group's width in kDown)
+    r.need = (fused && MODE == kDown) ? (a.F[r.e / a.N] + kBN / 2 - 1) / (kBN / 2) : 0;
     a.recs[t] = r;
   }
   // XCD x starts at the first tile whose preceding cost is >= x/8 of the total.  Inside an
@@ -235,15 +264,49 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
       }
     }
     a.hdr->xcd_begin[v] = tile;
+    sh.xb[v] = tile;
   }
-  // the first ncu/8 tiles of a range are taken statically, one per workgroup
-  if (v < kXcds) a.hdr->counters[v] = a.ncu / kXcds;
+  __syncthreads();
+  // tail[x]: the tiles at the end of range x that belong to an expert whose tiles continue in
+  // range x+1.  The fused launch computes them first (see fused_phase).
+  if (v < kXcds) {
+    const int cut = sh.xb[v + 1];
+    int n = 0;
+    if (cut > 0 && cut < total) {
+      const int ve = expert_of(cut);                 // expert of the first tile of range x+1
+      n = cut - (int)sh.tp[ve];                      // its tiles before the cut ...
+      n = min(n, cut - sh.xb[v]);                    // ... that lie inside range x
+      if (n < 0) n = 0;
+    }
+    a.hdr->tail[v] = n;
+  }
+  // the first ncu/8 tiles of a range are taken statically, one per workgroup (fused launch:
+  // every tile is handed out by the counter, so that the tiles a waiting workgroup depends on
+  // never sit with a workgroup that has not started yet)
+  if (v < kXcds) a.hdr->counters[v] = fused ? 0 : a.ncu / kXcds;
   if (v == 0) { a.hdr->tile_rows = h; a.hdr->total = total; }
+  // fused forward: the row-block counters start at zero (the up list's workgroup clears them)
+  if (fused && is_up(MODE))
+    for (int i = v; i < sh.fp[256]; i += 256) a.fam_done[i] = 0;
 }
 
-// workgroup 0 schedules the up projection, workgroup 1 the down projection (mask bits 0 / 1)
+template <int MODE>
+__device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& sh) {
+  const int h = choose_tile_rows<MODE>(a, sh);
+  build_schedule<MODE>(a, sh, h, false);
+}
+
+// workgroup 0 schedules the up projection, workgroup 1 the down projection (mask bits 0 / 1).
+// mask 7: both lists for the fused launch, which needs one tile height for both (the up
+// projection's choice, it is the larger part) so that row blocks coincide.
 __global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs up, const TileArgs dn, int mask) {
   __shared__ SchedShared sh;
+  if (mask == 7) {
+    const int h = choose_tile_rows<kUp>(up, sh);
+    if (blockIdx.x == 0) build_schedule<kUp>(up, sh, h, true);
+    else build_schedule<kDown>(dn, sh, h, true);
+    return;
+  }
   const int which = (mask == 3) ? (int)blockIdx.x : (mask == 2 ? 1 : 0);
   if (which == 0) build_schedule<kUp>(up, sh);
   else build_schedule<kDown>(dn, sh);
@@ -281,6 +344,15 @@ __device__ __forceinline__ void async_copy16(const void* gptr, void* lds_uniform
 }
 
 #define MOHGE_PIN() __builtin_amdgcn_sched_barrier(0)
+
+// 16-byte store performed at device scope (the sc1 cache policy of a vector store): written
+// through the XCD's L2, so that once the store has completed (vmcnt) a workgroup on any XCD
+// that has not cached the line before reads the new data.
+__device__ __forceinline__ void store16_device_scope(void* p, const uint4 v) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 q = {v.x, v.y, v.z, v.w};
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(q) : "memory");
+}
 
 // SwiGLU backward for 8 packed bf16 values.  The training forward stored, per hidden unit,
 //   p = b * SiLU'(a) = b * s * (1 + a*(1-s))   and   q = SiLU(a) = a * s,   s = sigmoid(a),
@@ -712,7 +784,9 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
               *reinterpret_cast<uint4*>(a.C2 + at) = da;
               *reinterpret_cast<uint4*>(a.C2 + at + F) = db;
             } else if (pass == 0) {
-              *reinterpret_cast<uint4*>(a.C + (long long)(rec.row_start + trow) * a.ldc + col) = v;
+              uint16_t* dst = a.C + (long long)(rec.row_start + trow) * a.ldc + col;
+              if (UP && a.coherent_out) store16_device_scope(dst, v);
+              else *reinterpret_cast<uint4*>(dst) = v;
             } else {
               const long long at = (long long)(rec.row_start + trow) * a.ldpre + (pass == 2 ? F : 0) + col;
               *reinterpret_cast<uint4*>(a.pre + at) = v;
@@ -788,10 +862,118 @@ __global__ void __launch_bounds__(Shape<MODE>::THREADS) ffn_tile_kernel(const Ti
   }
 }
 
+// Fused forward: the up tiles and the down tiles of a layer call in one persistent launch.
+// Workgroup b serves XCD b % 8: first the up tiles of that XCD's range of the up list, then the
+// down tiles of its range of the down list, each range with its own hand-out counter as in
+// ffn_tile_kernel.  A down tile reads the H rows of one (expert, row block), which the up tiles
+// of that row block write: every finished up tile adds one to the row block's counter
+// (fam_done), a down tile waits until the counter has reached the number of up tiles of the
+// block.  What makes the hand-over sound on any XCD:
+//  * H is stored at device scope (coherent_out), and every wave waits for its stores (vmcnt)
+//    before the workgroup barrier that precedes the counter increment;
+//  * the consumer reads the counter at device scope and reads H only after that; no cache on
+//    its path can hold an older copy of these lines, since nothing reads H rows of a row block
+//    in this launch before the block's counter is complete, and launch boundaries invalidate
+//    the caches.
+// Waiting cannot deadlock: tiles are handed out in list order, all up tiles of an XCD come
+// before its down tiles, and an up tile never waits for anything; a down tile whose row block
+// belongs to another XCD's range waits for tiles that were handed out there before any of
+// that XCD's down tiles.  The wait is bounded all the same (kSpinLimit polls, about a second);
+// if it ever expires the tile is computed regardless and a flag is left in the down header.
+constexpr int kSpinLimit = 1 << 22;
+
+// one phase of the fused launch: PHASE 0 = up tiles (UPMODE), 1 = down tiles
+template <int UPMODE, int PHASE>
+__device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* lds, int lane, int w) {
+  constexpr int kBcastOffset = 40960;
+  const int xcd = blockIdx.x % kXcds;
+  int tbeg = a.hdr->xcd_begin[xcd], tend = a.hdr->xcd_begin[xcd + 1];
+  const int total = a.hdr->total;
+  if (tbeg < 0) tbeg = 0;
+  if (tend > total) tend = total;
+  // The counter hands out positions 0, 1, 2, ... of the range.  Up phase: the positions map to
+  // the range's tail first (tiles of an expert that continues in the next XCD's range: down
+  // tiles of both ranges wait for them), then to the rest in list order; the head of the range,
+  // which the previous range's down tiles may wait for, comes right after.  Down phase: list
+  // order, the order in which the up tiles they depend on were handed out.
+  const int n = tend - tbeg;
+  int ntail = PHASE == 0 ? a.hdr->tail[xcd] : 0;
+  ntail = ntail < 0 ? 0 : (ntail > n ? n : ntail);
+  __syncthreads();         // (second phase: everybody has read the last hand-over word)
+  if (threadIdx.x == 0)
+    *reinterpret_cast<volatile int*>(lds + kBcastOffset) = atomicAdd(&a.hdr->counters[xcd], 1);
+  __syncthreads();
+  int pos = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
+  while (pos >= 0 && pos < n) {
+    const int t = pos < ntail ? tend - ntail + pos : tbeg + (pos - ntail);
+    int t_next = 0;
+    if (threadIdx.x == 0) t_next = atomicAdd(&a.hdr->counters[xcd], 1);
+    TileRec rec = a.recs[t];
+    rec.e = __builtin_amdgcn_readfirstlane(rec.e);
+    rec.row_start = __builtin_amdgcn_readfirstlane(rec.row_start);
+    rec.rows = __builtin_amdgcn_readfirstlane(rec.rows);
+    rec.n0 = __builtin_amdgcn_readfirstlane(rec.n0);
+    rec.fam = __builtin_amdgcn_readfirstlane(rec.fam);
+    rec.need = __builtin_amdgcn_readfirstlane(rec.need);
+    const bool ok = !(rec.e < 0 || rec.e >= a.Ne || rec.rows < 1 || rec.rows > kBM || rec.row_start < 0 ||
+                      rec.n0 < 0 || rec.row_start + rec.rows > a.P || rec.fam < 0 || rec.fam > a.P);
+    if (ok) {
+      const int nact = (rec.rows + 63) / 64;
+      if constexpr (PHASE == 0) {
+        if (nact == 4) run_tile<UPMODE, 4>(a, rec, lds, lane, w);
+        else if (nact == 3) run_tile<UPMODE, 3>(a, rec, lds, lane, w);
+        else if (nact == 2) run_tile<UPMODE, 2>(a, rec, lds, lane, w);
+        else run_tile<UPMODE, 1>(a, rec, lds, lane, w);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's H stores are done
+      } else {
+        if (threadIdx.x == 0) {
+#ifdef MOHGE_PROBE
+          const long long w0 = __builtin_amdgcn_s_memtime();
+#endif
+          int polls = 0;
+          while (__hip_atomic_load(&a.fam_done[rec.fam], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < rec.need) {
+            if (++polls > kSpinLimit) { a.hdr->pad[0] = 1; break; }
+            __builtin_amdgcn_s_sleep(8);
+          }
+#ifdef MOHGE_PROBE
+          if (a.dbg) {
+            a.dbg[(size_t)blockIdx.x * 8 + 6] += __builtin_amdgcn_s_memtime() - w0;
+            a.dbg[(size_t)blockIdx.x * 8 + 7] += polls > 0;
+          }
+#endif
+        }
+        __syncthreads();
+        if (nact == 4) run_tile<kDown, 4>(a, rec, lds, lane, w);
+        else if (nact == 3) run_tile<kDown, 3>(a, rec, lds, lane, w);
+        else if (nact == 2) run_tile<kDown, 2>(a, rec, lds, lane, w);
+        else run_tile<kDown, 1>(a, rec, lds, lane, w);
+      }
+    }
+    __syncthreads();       // every wave is past its epilogue (and, up tiles, past its stores)
+    if (threadIdx.x == 0) {
+      if (PHASE == 0 && ok)
+        __hip_atomic_fetch_add(&a.fam_done[rec.fam], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *reinterpret_cast<volatile int*>(lds + kBcastOffset) = t_next;
+    }
+    __syncthreads();
+    pos = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
+  }
+}
+
+template <int UPMODE>
+__global__ void __launch_bounds__(Shape<kUp>::THREADS) ffn_fused_kernel(const TileArgs up, const TileArgs dn) {
+  extern __shared__ __align__(1024) unsigned char lds[];
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  fused_phase<UPMODE, 0>(up, lds, lane, w);
+  fused_phase<UPMODE, 1>(dn, lds, lane, w);
+}
+
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
 static int g_force_rows[2] = {0, 0};
+static int g_fused_forward = 1;      // 0: separate up and down launches
 #ifdef MOHGE_PROBE
 long long* g_dbg = nullptr;
 int g_dbg_which = -1;
@@ -800,6 +982,7 @@ extern "C" void mohge_probe_buffer(void* p) { g_dbg = static_cast<long long*>(p)
 #endif
 
 int tune_tiled(int knob, int value) {
+  if (knob == 2) { g_fused_forward = value != 0; return 0; }
   if (knob < 0 || knob > 1) return -1;
   if (value != 0 && value != 64 && value != 128 && value != 192 && value != 256) return -1;
   g_force_rows[knob] = value;
@@ -814,14 +997,20 @@ static long long max_tiles(const LayerDesc& L, bool up) {
   return mt * ((ncols + ncpt - 1) / ncpt);
 }
 
-// bytes at the start of the workspace reserved for the two schedules
+// row-block counters of the fused launch: at most one row block per 64 routed rows plus a
+// partial one per expert
+static size_t fam_bytes(const LayerDesc& L) {
+  return ((size_t)(L.P / 64 + L.Ne + 1) * sizeof(int) + 255) / 256 * 256;
+}
+
+// bytes at the start of the workspace reserved for the two schedules and the row-block counters
 size_t tiled_sched_bytes(const LayerDesc& L) {
   size_t b = 0;
   for (int up = 0; up < 2; ++up) {
     const size_t n = (size_t)max_tiles(L, up);
     b += 256 + (n * sizeof(TileRec) + 255) / 256 * 256;
   }
-  return b;
+  return b + fam_bytes(L);
 }
 
 long long tile_capacity(const LayerDesc& L, int mode) {
@@ -857,6 +1046,21 @@ static hipError_t launch_stage(const TileArgs& a, hipStream_t s) {
     attr_done = true;
   }
   hipLaunchKernelGGL(kern, dim3(a.ncu), dim3(Shape<MODE>::THREADS), smem, s, a);
+  return hipGetLastError();
+}
+
+template <int UPMODE>
+static hipError_t launch_fused(const TileArgs& up, const TileArgs& dn, hipStream_t s) {
+  constexpr size_t smem = (size_t)(kStagesA * kBM + kStagesB * kBN) * kBK * 2;
+  auto kern = ffn_fused_kernel<UPMODE>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(up.ncu), dim3(Shape<kUp>::THREADS), smem, s, up, dn);
   return hipGetLastError();
 }
 
@@ -941,6 +1145,15 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
 #ifdef MOHGE_PROBE
     t.dbg = g_dbg;
 #endif
+  }
+  up.fam_done = dn.fam_done = reinterpret_cast<int*>(p);
+  // the whole forward in one launch: up and down tiles share the persistent workgroups
+  if (stages == 3 && g_fused_forward) {
+    up.coherent_out = 1;
+    hipLaunchKernelGGL(ffn_schedule_kernel, dim3(2), dim3(256), 0, s, up, dn, 7);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    return pre ? launch_fused<kUpSave>(up, dn, s) : launch_fused<kUp>(up, dn, s);
   }
   // both schedules depend only on `offsets`: one launch builds whichever are needed
   hipLaunchKernelGGL(ffn_schedule_kernel, dim3(stages == 3 ? 2 : 1), dim3(256), 0, s, up, dn, stages);

@@ -27,6 +27,8 @@ struct TileRec {
   int row_start;  // first row of the tile: sorted position / row of dW_e (kWgrad)
   int rows;       // valid rows (1..256)
   int n0;         // first output column
+  int fam;        // token modes: index of the tile's (expert, row block) among all row blocks
+  int need;       // fused forward, down tiles: up tiles that must have finished (else 0)
 };
 
 struct SchedHeader {
@@ -34,7 +36,8 @@ struct SchedHeader {
   int total;                 // number of tiles
   int xcd_begin[kXcds + 1];  // tile ranges per XCD
   int counters[kXcds];       // next tile of each range not yet handed out
-  int pad[13];
+  int tail[kXcds];           // tiles at the end of each range whose expert continues in the next range
+  int pad[5];
 };
 static_assert(sizeof(SchedHeader) <= 256, "header area");
 
@@ -53,6 +56,10 @@ struct TileArgs {
   TileRec* recs;
   int ncu;                    // compute units = persistent workgroups
   int force_rows;             // 0 = choose, else 64/128/192/256
+  // --- fused forward (up and down tiles in one launch) ------------------------------------
+  int* fam_done;              // [row blocks] finished up tiles per row block (zeroed by the schedule)
+  int coherent_out;           // kUp*: store H at device scope, so that a down tile running on
+                              //   another XCD reads what an up tile wrote in the same launch
   // --- backward extensions -------------------------------------------------------------
   uint16_t* pre;              // kUpSave: out, kDgradH: in; [P, ldpre], row = p[0..F_g) q[0..F_g)
   uint16_t* C2;               // kDgradH: out [P, ldpre], row = dA[0..F_g) dB[0..F_g)

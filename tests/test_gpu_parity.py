@@ -408,3 +408,38 @@ def test_graph_replay_matches_eager():
         assert torch.equal(L.expert_idx, idx_eager)
         other.layer.forward(other.x)            # unrelated eager work between the replays
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("training", [False, True])
+def test_fused_forward_equals_separate_launches(training):
+    """The one-launch forward (up and down tiles share the persistent workgroups, down tiles wait
+    for the row-block counters) against the two-launch forward, bit for bit, on one layer object
+    whose input changes from call to call: a down tile that read hidden activations of an earlier
+    call (a missing wait, a stale cache line) would show."""
+    import paper_2604_23108_amd as M
+    from gpu_harness import to_dev
+    w = WORKLOADS["mid_prefill"].replace(T=2300, d=768, d_ff=(128, 448, 640), seed=91)
+    DeviceLayer = _dev()
+    dl = DeviceLayer(w, generate(w), training=training, backward=training)
+    L = dl.layer
+    try:
+        for it in range(6):
+            wi = w.replace(seed=100 + it, skew_beta=float(it % 3))
+            x = to_dev(generate(wi).x, True)
+            print(f"[fused] training={training} call {it} seed={wi.seed}", flush=True)
+            M.mohge_tune(2, 1)
+            y_fused = L.forward(x).clone()
+            saved_fused = L.saved.clone() if training else None
+            counts = L.counts.clone()
+            M.mohge_tune(2, 0)
+            y_two = L.forward(x).clone()
+            torch.cuda.synchronize()
+            assert torch.equal(L.counts, counts)
+            assert torch.equal(y_fused, y_two), f"call {it}"
+            if training:
+                # the saved hidden activations and backward factors (behind the schedule area,
+                # whose records differ between the two launch forms)
+                tail = L.saved.numel() - 3 * max(dl.cfg.n_pairs, 1) * max(w.d_ff) * 2
+                assert torch.equal(saved_fused[tail:], L.saved[tail:]), f"call {it}: saved activations"
+    finally:
+        M.mohge_tune(2, 1)
