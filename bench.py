@@ -126,7 +126,7 @@ def main():
     # per-call timing with HIP events (state from the last step is valid input for each call)
     it = max(10, args.steps)
     calls = {
-        "route": lambda: M.mohge_route(cfg, x, L.w_group, L.w_expert, L.bias, L.group_idx, L.expert_idx, L.gates, L.gs, L.es1),
+        "route": lambda: M.mohge_route(cfg, x, L.w_group, L.w_expert, L.bias, L.group_idx, L.expert_idx, L.gates, L.gs, L.es1, L.ws_route),
         "permute": lambda: M.mohge_permute(cfg, L.expert_idx, L.counts, L.offsets, L.perm, L.inv_perm, None, None, L.ws_permute),
         "ffn_up": lambda: M.mohge_expert_ffn_up(cfg, x, L.perm, L.offsets, L.w13, L.ws_ffn),
         "ffn_down": lambda: M.mohge_expert_ffn_down(cfg, L.ws_ffn, L.offsets, L.w2, L.y_perm),

@@ -52,7 +52,8 @@ enum { MOHGE_F32 = 0, MOHGE_BF16 = 1 };
 enum {
   MOHGE_CALL_PERMUTE = 0, MOHGE_CALL_EXPERT_FFN = 1, MOHGE_CALL_AUX_LOSS = 2,
   MOHGE_CALL_FFN_SAVED = 3,       /* `saved` of mohge_expert_ffn_train                      */
-  MOHGE_CALL_EXPERT_FFN_BWD = 4, MOHGE_CALL_ROUTE_BWD = 5
+  MOHGE_CALL_EXPERT_FFN_BWD = 4, MOHGE_CALL_ROUTE_BWD = 5,
+  MOHGE_CALL_ROUTE = 6            /* optional workspace of mohge_route (0 when it has no use) */
 };
 
 typedef struct mohge_config {
@@ -87,10 +88,16 @@ typedef struct mohge_config {
  *      gates DEVICE [T,K_e] aligned with expert_idx; gs_out DEVICE [T,N_g] (GS) and
  *      es1_out DEVICE [T,N_e] (ES', zero outside kept groups), each may be NULL.
  * Logits are accumulated in fp32 (fp64 across 64-wide slices of d).
+ * workspace DEVICE, optional (NULL / 0 allowed): with at least
+ * mohge_workspace_size(cfg, MOHGE_CALL_ROUTE) bytes and few tokens (decode) the reduction over d
+ * is spread over many workgroups, which leave partial sums there, instead of running on one
+ * workgroup per 16 tokens.  The logits of the two forms can differ in the last bit (the fp64
+ * partial sums are grouped differently); each form is deterministic.
  */
 int mohge_route(const mohge_config* cfg, const void* x, const float* w_group,
                 const float* w_expert, const float* expert_logit_bias, int32_t* group_idx,
-                int32_t* expert_idx, float* gates, float* gs_out, float* es1_out, void* stream);
+                int32_t* expert_idx, float* gates, float* gs_out, float* es1_out,
+                void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Token permutation: buckets the P pairs by expert in stable order (expert id, then

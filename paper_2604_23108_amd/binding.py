@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "libmohge.so")
 SELECT_GLOBAL, SELECT_PER_GROUP = 0, 1
 F32, BF16 = 0, 1
 CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
-CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD = 3, 4, 5
+CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE = 3, 4, 5, 6
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
            "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_tune",
@@ -134,10 +134,12 @@ def mohge_workspace_size(cfg: Config, which_call: int) -> int:
 
 
 def mohge_route(cfg, x, w_group, w_expert, expert_logit_bias, group_idx, expert_idx, gates,
-                gs_out=None, es1_out=None):
+                gs_out=None, es1_out=None, workspace=None):
     _check(lib().mohge_route(cfg.ref(), _ptr(x), _ptr(w_group), _ptr(w_expert),
                              _ptr(expert_logit_bias), _ptr(group_idx), _ptr(expert_idx),
-                             _ptr(gates), _ptr(gs_out), _ptr(es1_out), _stream()), "mohge_route")
+                             _ptr(gates), _ptr(gs_out), _ptr(es1_out), _ptr(workspace),
+                             _nbytes(workspace) if workspace is not None else C.c_size_t(0), _stream()),
+           "mohge_route")
 
 
 def mohge_permute(cfg, expert_idx, counts, offsets, perm, inv_perm, x, x_perm, workspace):
@@ -302,6 +304,8 @@ class MoHGELayer:
         u8 = dict(dtype=torch.uint8, device=device)
         self.ws_permute = torch.empty(max(16, mohge_workspace_size(cfg, CALL_PERMUTE)), **u8)
         self.ws_ffn = torch.empty(max(16, mohge_workspace_size(cfg, CALL_EXPERT_FFN)), **u8)
+        n_route = mohge_workspace_size(cfg, CALL_ROUTE)
+        self.ws_route = torch.empty(n_route, **u8) if n_route else None
         self.losses = torch.empty(2, **f32) if training else None
         self.stats = torch.empty(2 * Ng + 2 * Ne, **f32) if training else None
         self.ws_aux = torch.empty(max(16, mohge_workspace_size(cfg, CALL_AUX_LOSS)), **u8) if training else None
@@ -329,7 +333,7 @@ class MoHGELayer:
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         c = self.cfg
         mohge_route(c, x, self.w_group, self.w_expert, self.bias, self.group_idx, self.expert_idx,
-                    self.gates, self.gs, self.es1)
+                    self.gates, self.gs, self.es1, self.ws_route)
         mohge_permute(c, self.expert_idx, self.counts, self.offsets, self.perm, self.inv_perm,
                       None, None, self.ws_permute)
         if self.has_backward:

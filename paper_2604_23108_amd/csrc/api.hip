@@ -98,21 +98,24 @@ size_t mohge_workspace_size(const mohge_config* cfg, int which_call) {
     case MOHGE_CALL_FFN_SAVED: return ffn_saved_bytes(L);
     case MOHGE_CALL_EXPERT_FFN_BWD: return ffn_bwd_workspace_bytes(L);
     case MOHGE_CALL_ROUTE_BWD: return route_bwd_workspace_bytes(L);
+    case MOHGE_CALL_ROUTE: return route_workspace_bytes(L);
     default: set_error("unknown call id %d", which_call); return 0;
   }
 }
 
 int mohge_route(const mohge_config* cfg, const void* x, const float* w_group,
                 const float* w_expert, const float* expert_logit_bias, int32_t* group_idx,
-                int32_t* expert_idx, float* gates, float* gs_out, float* es1_out, void* stream) {
+                int32_t* expert_idx, float* gates, float* gs_out, float* es1_out,
+                void* workspace, size_t workspace_bytes, void* stream) {
   LayerDesc L;
   int rc = check_config(cfg, &L);
   if (rc) return rc;
   NEED(x); NEED(w_group); NEED(w_expert); OPT(expert_logit_bias);
-  NEED(group_idx); NEED(expert_idx); NEED(gates); OPT(gs_out); OPT(es1_out);
+  NEED(group_idx); NEED(expert_idx); NEED(gates); OPT(gs_out); OPT(es1_out); OPT(workspace);
   if (L.T == 0) return MOHGE_OK;
   return hip_rc(launch_route(L, cfg->dtype, x, w_group, w_expert, expert_logit_bias, group_idx,
-                             expert_idx, gates, gs_out, es1_out, (hipStream_t)stream),
+                             expert_idx, gates, gs_out, es1_out, workspace, workspace_bytes,
+                             (hipStream_t)stream),
                 "mohge_route");
 }
 

@@ -56,7 +56,8 @@ __device__ __forceinline__ float swiglu(float g, float u) {
 hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const float* w_group,
                         const float* w_expert, const float* bias, int32_t* group_idx,
                         int32_t* expert_idx, float* gates, float* gs_out, float* es1_out,
-                        hipStream_t s);
+                        void* ws, size_t ws_bytes, hipStream_t s);
+size_t route_workspace_bytes(const LayerDesc& L);
 size_t permute_workspace_bytes(const LayerDesc& L);
 hipError_t launch_permute(const LayerDesc& L, int dtype, const int32_t* expert_idx,
                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,

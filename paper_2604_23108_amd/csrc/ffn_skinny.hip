@@ -108,6 +108,7 @@ __global__ void __launch_bounds__(256) ffn_skinny_kernel(const SkinnyArgs a) {
             acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[f][u].v, xf[tb][u].v, acc[f][tb], 0, 0, 0);
     };
     int k0 = 0;
+    for (; k0 + 256 <= K; k0 += 256) step(k0, std::integral_constant<int, 8>{});
     for (; k0 + 128 <= K; k0 += 128) step(k0, std::integral_constant<int, 4>{});
     for (; k0 < K; k0 += 64) step(k0, std::integral_constant<int, 2>{});
 

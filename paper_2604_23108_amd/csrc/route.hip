@@ -10,6 +10,10 @@
 // hidden elements, and the per-wave totals are added in fp64 in a fixed order.  This
 // keeps the logit error near 1e-7, which bit-exact top-k agreement with an fp64
 // reference needs.
+// With few tokens (decode) one workgroup per 16 tokens leaves most of the chip idle while two
+// compute units grind through the whole reduction: then the hidden dimension is split over
+// grid.y workgroups as well, each leaves its fp64 sums in a workspace, and a second small kernel
+// adds them in a fixed order and runs phase 2.
 // Phase 2 runs one wavefront per token with lane <-> expert: group top-K_g by rank
 // counting, softmax inside kept groups, scaling by the group score, expert top-k by
 // rank counting, a ballot + popcount to assign ascending output slots, and a
@@ -38,6 +42,9 @@ struct RouteArgs {
   int Nepad;     // Ne rounded up to 64
   int kslice;    // hidden elements per wave
   int region0;   // bytes of the first LDS region (partial totals / per-wave rows)
+  int dsplit;    // > 1: the hidden dimension is also split over grid.y workgroups, which leave
+                 //   their fp64 logit sums in gpart; route_finish_kernel adds them and selects
+  double* gpart; // [dsplit][T][NO]
 #ifdef MOHGE_PROBE
   long long* dbg;
 #endif
@@ -72,136 +79,10 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-template <bool BF16, int TM, int TN>
-__global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
-  extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int BT = 16 * TM, NC = 16 * TN;
-  const int NW = blockDim.x >> 6;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int r = lane & 15, q = lane >> 4;
-  const int t0 = blockIdx.x * BT;
-  double* part = reinterpret_cast<double*>(smem);                 // [NW][BT][NC]
-  float* lg = reinterpret_cast<float*>(smem + a.region0);         // [BT][NOpad]
-
-#ifdef MOHGE_PROBE
-  long long ts[6];
-#endif
-  RPROBE(0);
-  // ---- phase 1: logits ----------------------------------------------------
-  size_t xrow[TM];
-#pragma unroll
-  for (int tm = 0; tm < TM; ++tm) {
-    int t = t0 + 16 * tm + r;
-    xrow[tm] = (size_t)(t < a.T ? t : a.T - 1) * a.d;
-  }
-  for (int nc = 0; nc < a.NO; nc += NC) {
-    const float* wrow[TN];
-#pragma unroll
-    for (int tn = 0; tn < TN; ++tn) {
-      int o = nc + 16 * tn + r;
-      if (o > a.NO - 1) o = a.NO - 1;
-      wrow[tn] = (o < a.Ng) ? a.wg + (size_t)o * a.d : a.we + (size_t)(o - a.Ng) * a.d;
-    }
-    f32x4 acc[TM][TN];
-    double tot[TM][TN][4];
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) {
-        acc[tm][tn] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) tot[tm][tn][i] = 0.0;
-      }
-    const int kbeg = w * a.kslice, kend = kbeg + a.kslice;
-    // The token rows are read exactly once from HBM in small pieces (16 rows x 64 bytes per
-    // wave-wide load), so the loop is bound by memory latency unless many loads are in
-    // flight: all token loads of a chunk of up to XS 32-element steps are requested up
-    // front and kept packed in registers; the router rows (L2 resident) are requested one
-    // step ahead.  The fp32 accumulators are folded into the fp64 totals after every pair of
-    // steps (64 elements).
-    constexpr int XS = BF16 ? 16 : 4;
-    typedef typename std::conditional<BF16, uint4, float4>::type xraw_t;
-    constexpr int XR = BF16 ? 1 : 2;                 // raw registers-of-16-bytes per step
-    for (int kc = kbeg; kc < kend; kc += 32 * XS) {
-      xraw_t xraw[TM][XS][XR];
-#pragma unroll
-      for (int st = 0; st < XS; ++st)
-        if (kc + 32 * st < kend) {
-#pragma unroll
-          for (int tm = 0; tm < TM; ++tm) {
-            const xraw_t* p = reinterpret_cast<const xraw_t*>(
-                static_cast<const char*>(a.x) + (xrow[tm] + kc + 32 * st + 8 * q) * (BF16 ? 2 : 4));
-#pragma unroll
-            for (int u = 0; u < XR; ++u) xraw[tm][st][u] = p[u];
-          }
-        }
-      float wb[2][TN][8];
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn) load8<false>(wrow[tn], (size_t)(kc + 8 * q), wb[0][tn]);
-#pragma unroll
-      for (int st = 0; st < XS; ++st) {
-        const int k = kc + 32 * st;
-        if (k < kend) {
-          if (st + 1 < XS && k + 32 < kend) {
-#pragma unroll
-            for (int tn = 0; tn < TN; ++tn) load8<false>(wrow[tn], (size_t)(k + 32 + 8 * q), wb[(st + 1) & 1][tn]);
-          }
-          float xa[TM][8];
-#pragma unroll
-          for (int tm = 0; tm < TM; ++tm) {
-            if constexpr (BF16) {
-              const uint4 u = xraw[tm][st][0];
-              xa[tm][0] = __uint_as_float(u.x << 16); xa[tm][1] = __uint_as_float(u.x & 0xffff0000u);
-              xa[tm][2] = __uint_as_float(u.y << 16); xa[tm][3] = __uint_as_float(u.y & 0xffff0000u);
-              xa[tm][4] = __uint_as_float(u.z << 16); xa[tm][5] = __uint_as_float(u.z & 0xffff0000u);
-              xa[tm][6] = __uint_as_float(u.w << 16); xa[tm][7] = __uint_as_float(u.w & 0xffff0000u);
-            } else {
-              const float4 lo = xraw[tm][st][0], hi = xraw[tm][st][XR - 1];
-              xa[tm][0] = lo.x; xa[tm][1] = lo.y; xa[tm][2] = lo.z; xa[tm][3] = lo.w;
-              xa[tm][4] = hi.x; xa[tm][5] = hi.y; xa[tm][6] = hi.z; xa[tm][7] = hi.w;
-            }
-          }
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-              for (int tn = 0; tn < TN; ++tn)
-                acc[tm][tn] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[tm][j], wb[st & 1][tn][j], acc[tm][tn], 0, 0, 0);
-          if ((st & 1) || k + 32 >= kend) {
-#pragma unroll
-            for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-              for (int tn = 0; tn < TN; ++tn) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) tot[tm][tn][i] += (double)acc[tm][tn][i];
-                acc[tm][tn] = f32x4{0.f, 0.f, 0.f, 0.f};
-              }
-          }
-        }
-      }
-    }
-    RPROBE(1);
-    // Accumulator element i of lane (r, q) is token 4q+i, router row r of the 16x16 tile.
-    // Every wave stores its fp64 totals in its own slice; then they are added in wave order.
-#pragma unroll
-    for (int tm = 0; tm < TM; ++tm)
-#pragma unroll
-      for (int tn = 0; tn < TN; ++tn)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          part[((size_t)w * BT + 16 * tm + 4 * q + i) * NC + 16 * tn + r] = tot[tm][tn][i];
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < BT * NC; idx += blockDim.x) {
-      const int tl = idx / NC, ol = idx % NC;
-      double sum = 0.0;
-      for (int ww = 0; ww < NW; ++ww) sum += part[(size_t)ww * BT * NC + idx];
-      if (nc + ol < a.NO) lg[tl * a.NOpad + nc + ol] = (float)sum;
-    }
-    __syncthreads();
-  }
-
-  RPROBE(2);
+// Phase 2 for the BT tokens from t0 whose logits are in lg ([BT][NOpad], LDS); uses the first
+// LDS region for the per-wave rows.
+__device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* smem, const float* lg,
+                                             int t0, int BT, int NW, int w, int lane) {
   // ---- phase 2: one wavefront per token, lane <-> expert ---------------------
   float* zrow = reinterpret_cast<float*>(smem) + (size_t)w * 4 * a.Nepad;  // biased expert logits
   float* e1row = zrow + a.Nepad;                                            // ES'
@@ -313,6 +194,146 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
   }
+}
+
+template <bool BF16, int TM, int TN>
+__global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int BT = 16 * TM, NC = 16 * TN;
+  const int NW = blockDim.x >> 6;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r = lane & 15, q = lane >> 4;
+  const int t0 = blockIdx.x * BT;
+  double* part = reinterpret_cast<double*>(smem);                 // [NW][BT][NC]
+  float* lg = reinterpret_cast<float*>(smem + a.region0);         // [BT][NOpad]
+
+#ifdef MOHGE_PROBE
+  long long ts[6];
+#endif
+  RPROBE(0);
+  // ---- phase 1: logits ----------------------------------------------------
+  size_t xrow[TM];
+#pragma unroll
+  for (int tm = 0; tm < TM; ++tm) {
+    int t = t0 + 16 * tm + r;
+    xrow[tm] = (size_t)(t < a.T ? t : a.T - 1) * a.d;
+  }
+  for (int nc = 0; nc < a.NO; nc += NC) {
+    const float* wrow[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      int o = nc + 16 * tn + r;
+      if (o > a.NO - 1) o = a.NO - 1;
+      wrow[tn] = (o < a.Ng) ? a.wg + (size_t)o * a.d : a.we + (size_t)(o - a.Ng) * a.d;
+    }
+    f32x4 acc[TM][TN];
+    double tot[TM][TN][4];
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) {
+        acc[tm][tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) tot[tm][tn][i] = 0.0;
+      }
+    const int kbeg = ((int)blockIdx.y * NW + w) * a.kslice, kend = kbeg + a.kslice;
+    // The token rows are read exactly once from HBM in small pieces (16 rows x 64 bytes per
+    // wave-wide load), so the loop is bound by memory latency unless many loads are in
+    // flight: all token loads of a chunk of up to XS 32-element steps are requested up
+    // front and kept packed in registers; the router rows (L2 resident) are requested one
+    // step ahead.  The fp32 accumulators are folded into the fp64 totals after every pair of
+    // steps (64 elements).
+    constexpr int XS = BF16 ? 16 : 4;
+    typedef typename std::conditional<BF16, uint4, float4>::type xraw_t;
+    constexpr int XR = BF16 ? 1 : 2;                 // raw registers-of-16-bytes per step
+    for (int kc = kbeg; kc < kend; kc += 32 * XS) {
+      xraw_t xraw[TM][XS][XR];
+#pragma unroll
+      for (int st = 0; st < XS; ++st)
+        if (kc + 32 * st < kend) {
+#pragma unroll
+          for (int tm = 0; tm < TM; ++tm) {
+            const xraw_t* p = reinterpret_cast<const xraw_t*>(
+                static_cast<const char*>(a.x) + (xrow[tm] + kc + 32 * st + 8 * q) * (BF16 ? 2 : 4));
+#pragma unroll
+            for (int u = 0; u < XR; ++u) xraw[tm][st][u] = p[u];
+          }
+        }
+      float wb[2][TN][8];
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn) load8<false>(wrow[tn], (size_t)(kc + 8 * q), wb[0][tn]);
+#pragma unroll
+      for (int st = 0; st < XS; ++st) {
+        const int k = kc + 32 * st;
+        if (k < kend) {
+          if (st + 1 < XS && k + 32 < kend) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) load8<false>(wrow[tn], (size_t)(k + 32 + 8 * q), wb[(st + 1) & 1][tn]);
+          }
+          float xa[TM][8];
+#pragma unroll
+          for (int tm = 0; tm < TM; ++tm) {
+            if constexpr (BF16) {
+              const uint4 u = xraw[tm][st][0];
+              xa[tm][0] = __uint_as_float(u.x << 16); xa[tm][1] = __uint_as_float(u.x & 0xffff0000u);
+              xa[tm][2] = __uint_as_float(u.y << 16); xa[tm][3] = __uint_as_float(u.y & 0xffff0000u);
+              xa[tm][4] = __uint_as_float(u.z << 16); xa[tm][5] = __uint_as_float(u.z & 0xffff0000u);
+              xa[tm][6] = __uint_as_float(u.w << 16); xa[tm][7] = __uint_as_float(u.w & 0xffff0000u);
+            } else {
+              const float4 lo = xraw[tm][st][0], hi = xraw[tm][st][XR - 1];
+              xa[tm][0] = lo.x; xa[tm][1] = lo.y; xa[tm][2] = lo.z; xa[tm][3] = lo.w;
+              xa[tm][4] = hi.x; xa[tm][5] = hi.y; xa[tm][6] = hi.z; xa[tm][7] = hi.w;
+            }
+          }
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+              for (int tn = 0; tn < TN; ++tn)
+                acc[tm][tn] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[tm][j], wb[st & 1][tn][j], acc[tm][tn], 0, 0, 0);
+          if ((st & 1) || k + 32 >= kend) {
+#pragma unroll
+            for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+              for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) tot[tm][tn][i] += (double)acc[tm][tn][i];
+                acc[tm][tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+              }
+          }
+        }
+      }
+    }
+    RPROBE(1);
+    // Accumulator element i of lane (r, q) is token 4q+i, router row r of the 16x16 tile.
+    // Every wave stores its fp64 totals in its own slice; then they are added in wave order.
+#pragma unroll
+    for (int tm = 0; tm < TM; ++tm)
+#pragma unroll
+      for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          part[((size_t)w * BT + 16 * tm + 4 * q + i) * NC + 16 * tn + r] = tot[tm][tn][i];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < BT * NC; idx += blockDim.x) {
+      const int tl = idx / NC, ol = idx % NC;
+      double sum = 0.0;
+      for (int ww = 0; ww < NW; ++ww) sum += part[(size_t)ww * BT * NC + idx];
+      if (nc + ol < a.NO) {
+        if (a.dsplit > 1) {
+          if (t0 + tl < a.T) a.gpart[((size_t)blockIdx.y * a.T + t0 + tl) * a.NO + nc + ol] = sum;
+        } else {
+          lg[tl * a.NOpad + nc + ol] = (float)sum;
+        }
+      }
+    }
+    __syncthreads();
+  }
+
+  RPROBE(2);
+  if (a.dsplit > 1) return;          // route_finish_kernel takes over
+  route_select(a, smem, lg, t0, BT, NW, w, lane);
 #ifdef MOHGE_PROBE
   RPROBE(3);
   if (a.dbg && threadIdx.x == 0 && blockIdx.x < 256) {
@@ -321,6 +342,26 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
     d[4] += 1;
   }
 #endif
+}
+
+// Second kernel of the split form: one workgroup per 16 tokens adds the dsplit partial logit
+// sums of its tokens in index order and runs phase 2.
+__global__ void __launch_bounds__(512) route_finish_kernel(const RouteArgs a) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int BT = 16;
+  const int NW = blockDim.x >> 6;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t0 = blockIdx.x * BT;
+  float* lg = reinterpret_cast<float*>(smem + a.region0);         // [BT][NOpad]
+  for (int idx = threadIdx.x; idx < BT * a.NO; idx += blockDim.x) {
+    const int tl = idx / a.NO, o = idx % a.NO;
+    double sum = 0.0;
+    if (t0 + tl < a.T)
+      for (int sp = 0; sp < a.dsplit; ++sp) sum += a.gpart[((size_t)sp * a.T + t0 + tl) * a.NO + o];
+    lg[tl * a.NOpad + o] = (float)sum;
+  }
+  __syncthreads();
+  route_select(a, smem, lg, t0, BT, NW, w, lane);
 }
 
 template <bool BF16, int TM, int TN>
@@ -348,10 +389,19 @@ static hipError_t launch_tn(const RouteArgs& a, int TN, dim3 grid, dim3 block, s
   }
 }
 
+// Split form: used for at most kSplitMaxT tokens; the workspace holds up to kSplitMax partial
+// sums of every logit.
+constexpr int kSplitMaxT = 256, kSplitMax = 16;
+
+size_t route_workspace_bytes(const LayerDesc& L) {
+  if (L.T > kSplitMaxT) return 0;
+  return ((size_t)kSplitMax * (L.T > 0 ? L.T : 1) * (L.Ng + L.Ne) * sizeof(double) + 255) / 256 * 256;
+}
+
 hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const float* w_group,
                         const float* w_expert, const float* bias, int32_t* group_idx,
                         int32_t* expert_idx, float* gates, float* gs_out, float* es1_out,
-                        hipStream_t s) {
+                        void* ws, size_t ws_bytes, hipStream_t s) {
   RouteArgs a;
   a.x = x; a.wg = w_group; a.we = w_expert; a.bias = bias;
   a.gidx = group_idx; a.eidx = expert_idx; a.gates = gates; a.gs = gs_out; a.es1 = es1_out;
@@ -365,6 +415,22 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
   a.Nepad = ((L.Ne + 63) / 64) * 64;
   const int NW = (L.d % 256 == 0) ? 8 : (L.d % 128 == 0) ? 4 : 2;
   a.kslice = L.d / NW;
+  // few tokens: split the reduction over more workgroups (a slice stays a whole number of
+  // 32-element steps) until there are about 128 of them
+  a.dsplit = 1;
+  a.gpart = nullptr;
+  if (ws && L.T <= kSplitMaxT && ws_bytes >= route_workspace_bytes(L)) {
+    const int blocks = (L.T + 15) / 16;
+    int ds = 1;
+    while (ds * 2 <= kSplitMax && blocks * ds * 2 <= 128 && (a.kslice / (ds * 2)) % 32 == 0 &&
+           a.kslice / (ds * 2) >= 32)
+      ds *= 2;
+    if (ds > 1) {
+      a.dsplit = ds;
+      a.kslice /= ds;
+      a.gpart = static_cast<double*>(ws);
+    }
+  }
   const int tiles = (a.NO + 15) / 16;
   const int TN = tiles <= 1 ? 1 : tiles == 2 ? 2 : tiles == 3 ? 3 : 5;
   int TM = (L.T >= 16384 && TN <= 2) ? 2 : 1;   // wider combinations would spill registers
@@ -377,12 +443,23 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
     if (smem <= 96 * 1024 || TM == 1) break;
   }
   const int BT = 16 * TM;
-  dim3 grid((L.T + BT - 1) / BT), block(64 * NW);
+  dim3 grid((L.T + BT - 1) / BT, a.dsplit), block(64 * NW);
   const bool bf = dtype == MOHGE_BF16;
-  if (TM == 2) return bf ? launch_tn<true, 2>(a, TN, grid, block, smem, s)
-                         : launch_tn<false, 2>(a, TN, grid, block, smem, s);
-  return bf ? launch_tn<true, 1>(a, TN, grid, block, smem, s)
-            : launch_tn<false, 1>(a, TN, grid, block, smem, s);
+  hipError_t e;
+  if (TM == 2) e = bf ? launch_tn<true, 2>(a, TN, grid, block, smem, s)
+                      : launch_tn<false, 2>(a, TN, grid, block, smem, s);
+  else e = bf ? launch_tn<true, 1>(a, TN, grid, block, smem, s)
+              : launch_tn<false, 1>(a, TN, grid, block, smem, s);
+  if (e != hipSuccess || a.dsplit == 1) return e;
+  static bool attr_done = false;
+  if (!attr_done) {
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(route_finish_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(route_finish_kernel, dim3((L.T + 15) / 16), block, smem, s, a);
+  return hipGetLastError();
 }
 
 }  // namespace mohge

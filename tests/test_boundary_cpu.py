@@ -55,7 +55,7 @@ def test_null_pointers_and_workspace_sizes():
     cfg = M.Config(T=4096, d=2048, n_groups=3, experts_per_group=8, d_ff=(512, 1024, 1536), k_groups=2, k_experts=4)
     assert M.lib().mohge_combine(cfg.ref(), None, None, None, None, None) == -2
     assert "NULL" in M.mohge_last_error()
-    assert M.lib().mohge_route(None, None, None, None, None, None, None, None, None, None, None) == -2
+    assert M.lib().mohge_route(None, None, None, None, None, None, None, None, None, None, None, 0, None) == -2
     P = 4096 * 4
     # hidden activations plus the tile schedules of the matrix-core path
     assert P * 1536 * 2 <= M.mohge_workspace_size(cfg, M.CALL_EXPERT_FFN) <= P * 1536 * 2 + (1 << 20)

@@ -443,3 +443,42 @@ def test_fused_forward_equals_separate_launches(training):
                 assert torch.equal(saved_fused[tail:], L.saved[tail:]), f"call {it}: saved activations"
     finally:
         M.mohge_tune(2, 1)
+
+
+@pytest.mark.parametrize("T,d,Ng,N", [(1, 4096, 4, 16), (7, 4096, 4, 16), (32, 4096, 4, 16), (200, 1024, 8, 16),
+                                      (256, 320, 3, 5), (40, 64, 2, 2)])
+def test_router_with_and_without_workspace(T, d, Ng, N):
+    """Few tokens: with its optional workspace the router spreads the reduction over many
+    workgroups (two kernels).  Both forms against the oracle, and against each other."""
+    import paper_2604_23108_amd as M
+    from gpu_harness import to_dev
+    w = Workload("route_ws", T=T, d=d, n_groups=Ng, experts_per_group=N, d_ff=tuple([64] * Ng),
+                 k_groups=min(2, Ng), k_experts=min(2, Ng) * min(2, N), seed=300 + T, training=True)
+    inp = generate(w)
+    cfg = M.Config.from_workload(w)
+    x = to_dev(inp.x, True)
+    wg, we = torch.from_numpy(inp.w_group).cuda(), torch.from_numpy(inp.w_expert).cuda()
+    bias = None if inp.expert_logit_bias is None else torch.from_numpy(inp.expert_logit_bias).cuda()
+    n_ws = M.mohge_workspace_size(cfg, M.CALL_ROUTE)
+    assert n_ws >= 16 * T * (Ng + Ng * N) * 8
+    ref = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias)
+    outs = []
+    for ws in (None, torch.empty(n_ws, dtype=torch.uint8, device="cuda")):
+        print(f"[route] T={T} d={d} workspace={'yes' if ws is not None else 'no'}", flush=True)
+        i32 = dict(dtype=torch.int32, device="cuda")
+        f32 = dict(dtype=torch.float32, device="cuda")
+        gidx = torch.full((T, w.k_groups), -1, **i32)
+        eidx = torch.full((T, w.k_experts), -1, **i32)
+        gates = torch.full((T, w.k_experts), float("nan"), **f32)
+        gs = torch.full((T, Ng), float("nan"), **f32)
+        es1 = torch.full((T, Ng * N), float("nan"), **f32)
+        M.mohge_route(cfg, x, wg, we, bias, gidx, eidx, gates, gs, es1, ws)
+        torch.cuda.synchronize()
+        out = dict(group_idx=gidx.cpu().numpy(), expert_idx=eidx.cpu().numpy(), gates=gates.cpu().numpy())
+        keep, _ = check_routing(w, out, ref, f"workspace={ws is not None}")
+        assert np.abs(gs.cpu().numpy() - ref["gs"]).max() <= 1e-6
+        assert np.allclose(es1.cpu().numpy(), ref["es1"], rtol=2e-6, atol=1e-6)
+        outs.append((out, keep))
+    (a, keep), (b, _) = outs
+    assert (a["expert_idx"][keep] == b["expert_idx"][keep]).all()
+    assert np.abs(a["gates"][keep] - b["gates"][keep]).max() <= 1e-6
