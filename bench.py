@@ -26,9 +26,10 @@ PEAK_HBM = 8.0e12           # B/s
 # of FETCH_SIZE (factor 2.0) and 262144 KiB of WRITE_SIZE (factor 1.0).  None for workloads
 # that have not been profiled.
 MEASURED_TRAFFIC = {
-    "mid_prefill": (191420 * 2.0 + 33020 * 1.0) * 1024,   # ffn_tile_kernel<up>
-    "decode": (632690 * 2.0 + 400 * 1.0) * 1024,          # ffn_skinny_kernel<up>
-    "training": (403880 * 2.0 + 65259 * 1.0) * 1024,      # ffn_tile_kernel<up>
+    "mid_prefill": (308250 * 2.0 + 98620 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
+    "decode": (628760 * 2.0 + 379 * 1.0) * 1024,          # ffn_skinny_kernel<up>
+    "training": (636820 * 2.0 + 326870 * 1.0) * 1024,     # ffn_fused_kernel<up that saves + down>
+    "large_prefill_skewed": (5145300 * 2.0 + 696360 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
 }
 
 
@@ -128,6 +129,7 @@ def main():
     calls = {
         "route": lambda: M.mohge_route(cfg, x, L.w_group, L.w_expert, L.bias, L.group_idx, L.expert_idx, L.gates, L.gs, L.es1, L.ws_route),
         "permute": lambda: M.mohge_permute(cfg, L.expert_idx, L.counts, L.offsets, L.perm, L.inv_perm, None, None, L.ws_permute),
+        "ffn": lambda: M.mohge_expert_ffn(cfg, x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, L.ws_ffn),
         "ffn_up": lambda: M.mohge_expert_ffn_up(cfg, x, L.perm, L.offsets, L.w13, L.ws_ffn),
         "ffn_down": lambda: M.mohge_expert_ffn_down(cfg, L.ws_ffn, L.offsets, L.w2, L.y_perm),
         "combine": lambda: M.mohge_combine(cfg, L.y_perm, L.inv_perm, L.gates, L.y),
@@ -171,9 +173,12 @@ def main():
                 "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": ach / PEAK_HBM,
                 "traffic": MEASURED_TRAFFIC.get(args.workload)}
     else:
-        ach = flops_up / (call_ms["ffn_up"] * 1e-3)
-        roof = {"kernel": "ffn_tile_kernel<up> + its schedule kernel (one mohge_expert_ffn_up call)", "bound": "mfma",
-                "achieved": ach / 1e12, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
+        # the step's expert networks are one launch (up and down tiles together) plus its schedule
+        key = "ffn_train_fwd" if args.backward else "ffn"
+        ach = (flops_up + flops_down) / (call_ms[key] * 1e-3)
+        roof = {"kernel": "ffn_fused_kernel + its schedule kernel (one %s call)" %
+                          ("mohge_expert_ffn_train" if args.backward else "mohge_expert_ffn"),
+                "bound": "mfma", "achieved": ach / 1e12, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
                 "frac": ach / PEAK_MFMA_BF16, "traffic": MEASURED_TRAFFIC.get(args.workload)}
     t_ffn = (call_ms["ffn_up"] + call_ms["ffn_down"]) * 1e-3
     parts = {

@@ -126,7 +126,7 @@ __device__ __forceinline__ void expert_dims(const TileArgs& a, int e, int g, int
 // Tile height for a launch of MODE: the candidate with the lowest estimated time.  Called by all
 // 256 threads; uses sh.wsum and sh.rows.
 template <int MODE>
-__device__ __forceinline__ int choose_tile_rows(const TileArgs& a, SchedShared& sh) {
+__device__ __forceinline__ int choose_tile_rows(const TileArgs& a, SchedShared& sh, bool fused = false) {
   constexpr int NCPT = Shape<MODE>::NCOLS_PER_TILE;
   const int v = threadIdx.x, lane = v & 63, w = v >> 6;
   int cnt = 0, nt = 0, kc = 0;
@@ -160,7 +160,10 @@ __device__ __forceinline__ int choose_tile_rows(const TileArgs& a, SchedShared& 
       const long long rounds = (tot + (long long)a.ncu * kmax - 1) / ((long long)a.ncu * kmax);
       // measured: a stage of a tile costs about 1850 + 100 * (rows / 64) clocks (operand traffic
       // and LDS work do not shrink with the tile height), so rounds count more than height
-      const float est = (float)rounds * ((float)(4 - c) + 18.5f);
+      // (fused launch: the down tiles fill the last round of up tiles, so the up tiles are
+      // costed by their total work rather than by whole rounds)
+      const float units = fused ? (float)tot / (float)((long long)a.ncu * kmax) : (float)rounds;
+      const float est = units * ((float)(4 - c) + 18.5f);
       if (c == 0 || est < best) { best = est; best_rows = 256 - 64 * c; }
     }
     sh.rows = a.force_rows ? a.force_rows : best_rows;
@@ -302,7 +305,7 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
 __global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs up, const TileArgs dn, int mask) {
   __shared__ SchedShared sh;
   if (mask == 7) {
-    const int h = choose_tile_rows<kUp>(up, sh);
+    const int h = choose_tile_rows<kUp>(up, sh, true);
     if (blockIdx.x == 0) build_schedule<kUp>(up, sh, h, true);
     else build_schedule<kDown>(dn, sh, h, true);
     return;
@@ -975,6 +978,10 @@ __global__ void __launch_bounds__(Shape<kUp>::THREADS) ffn_fused_kernel(const Ti
 static int g_force_rows[2] = {0, 0};
 static int g_fused_forward = 1;      // 0: separate up and down launches
 #ifdef MOHGE_PROBE
+static int g_probe_plain_stores = 0;
+extern "C" void mohge_probe_plain_stores(int v) { g_probe_plain_stores = v; }
+#endif
+#ifdef MOHGE_PROBE
 long long* g_dbg = nullptr;
 int g_dbg_which = -1;
 extern "C" void mohge_probe_select(int which) { g_dbg_which = which; }
@@ -1150,6 +1157,9 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
   // the whole forward in one launch: up and down tiles share the persistent workgroups
   if (stages == 3 && g_fused_forward) {
     up.coherent_out = 1;
+#ifdef MOHGE_PROBE
+    if (g_probe_plain_stores) up.coherent_out = 0;      // timing experiment of the instrumented build only
+#endif
     hipLaunchKernelGGL(ffn_schedule_kernel, dim3(2), dim3(256), 0, s, up, dn, 7);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
