@@ -589,6 +589,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   // two, read the first fragments
   PROBE_T(1);
   __syncthreads();                  // the previous tile's epilogue has left the LDS
+  PROBE_T(5);
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j) issue_b(0, 0, j);
 #pragma unroll
@@ -804,6 +805,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   if (a.dbg && threadIdx.x == 0) {
     long long* d = a.dbg + (size_t)blockIdx.x * 8;
     for (int i = 0; i < 4; ++i) d[i] += ts[i + 1] - ts[i];
+    d[6] += ts[5] - ts[1];          // of the prologue: waiting at the barrier
     d[4] += 1;
     d[5] += KT;
   }
