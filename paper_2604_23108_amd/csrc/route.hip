@@ -84,10 +84,11 @@ __device__ __forceinline__ float wave_sum(float v) {
 __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* smem, const float* lg,
                                              int t0, int BT, int NW, int w, int lane) {
   // ---- phase 2: one wavefront per token, lane <-> expert ---------------------
-  float* zrow = reinterpret_cast<float*>(smem) + (size_t)w * 4 * a.Nepad;  // biased expert logits
+  float* zrow = reinterpret_cast<float*>(smem) + (size_t)w * 5 * a.Nepad;  // biased expert logits
   float* e1row = zrow + a.Nepad;                                            // ES'
   float* e2row = e1row + a.Nepad;                                           // ES''
   float* krow = e2row + a.Nepad;                                            // selection key
+  float* xrow = krow + a.Nepad;                                             // exp(z - max of the group)
   const int klimit = (a.mode == MOHGE_SELECT_GLOBAL) ? a.Ke : a.Ke / a.Kg;
   const int iters = (BT + NW - 1) / NW;
   const float NEG_INF = -__builtin_inff();
@@ -121,21 +122,40 @@ __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* 
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
+    // every expert's exp(z - max of its group) once (one expf per lane and expert instead of
+    // one per lane and group member); the sums below add these in member order
     for (int e = lane; e < a.Ne; e += 64) {
       const int g = e / a.N;
-      const bool in = (gmask >> g) & 1ull;
-      float e1 = 0.f, e2 = 0.f;
-      if (in) {
+      float ex = 0.f;
+      if ((gmask >> g) & 1ull) {
         const float* zg_row = zrow + g * a.N;
         float mx = NEG_INF;
+#pragma unroll 8
         for (int i = 0; i < a.N; ++i) mx = fmaxf(mx, zg_row[i]);
+        ex = expf(zrow[e] - mx);
+      }
+      xrow[e] = ex;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+
+    for (int e = lane; e < a.Nepad; e += 64) {
+      const int g = e < a.Ne ? e / a.N : 0;
+      const bool in = e < a.Ne && ((gmask >> g) & 1ull);
+      float e1 = 0.f, e2 = 0.f;
+      if (in) {
+        const float* xg_row = xrow + g * a.N;
         float sum = 0.f;
-        for (int i = 0; i < a.N; ++i) sum += expf(zg_row[i] - mx);
-        e1 = expf(zrow[e] - mx) / sum;
+#pragma unroll 8
+        for (int i = 0; i < a.N; ++i) sum += xg_row[i];
+        e1 = xrow[e] / sum;
         e2 = e1 * (1.f / (1.f + expf(-lrow[g])));
       }
-      e1row[e] = e1;
-      e2row[e] = e2;
+      if (e < a.Ne) {
+        e1row[e] = e1;
+        e2row[e] = e2;
+      }
+      // (entries past N_e exist so that the rank loop can read the keys four at a time)
       krow[e] = in ? ((a.mode == MOHGE_SELECT_GLOBAL) ? e2 : zrow[e]) : NEG_INF;
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -155,11 +175,16 @@ __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* 
           const float key = krow[e];
           int rank = 0;
           if (a.mode == MOHGE_SELECT_GLOBAL) {
-            for (int e2i = 0; e2i < a.Ne; ++e2i) {
-              const float k2 = krow[e2i];
-              rank += (k2 > key) || (k2 == key && e2i < e);
+#pragma unroll 8
+            for (int e2i = 0; e2i < a.Nepad; e2i += 4) {
+              const float4 k4 = *reinterpret_cast<const float4*>(krow + e2i);
+              rank += (k4.x > key) || (k4.x == key && e2i < e);
+              rank += (k4.y > key) || (k4.y == key && e2i + 1 < e);
+              rank += (k4.z > key) || (k4.z == key && e2i + 2 < e);
+              rank += (k4.w > key) || (k4.w == key && e2i + 3 < e);
             }
           } else {
+#pragma unroll 8
             for (int i = 0; i < a.N; ++i) {
               const int e2i = g * a.N + i;
               const float k2 = krow[e2i];
@@ -437,7 +462,7 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
   size_t smem = 0;
   for (;; TM = 1) {
     const size_t part_bytes = (size_t)NW * 16 * TM * 16 * TN * sizeof(double);
-    const size_t rows_bytes = (size_t)NW * 4 * a.Nepad * sizeof(float);
+    const size_t rows_bytes = (size_t)NW * 5 * a.Nepad * sizeof(float);
     a.region0 = (int)(((part_bytes > rows_bytes ? part_bytes : rows_bytes) + 15) / 16 * 16);
     smem = (size_t)a.region0 + (size_t)16 * TM * a.NOpad * sizeof(float);
     if (smem <= 96 * 1024 || TM == 1) break;
