@@ -170,6 +170,10 @@ int mohge_combine(const mohge_config* cfg, const void* y_perm, const int32_t* in
  * mohge_combine then give the shared term, and mohge_combine_add adds it to the gated sum:
  *   y[t,:] = y_add[t,:] + sum_slot gates[t,slot] * y_perm[inv_perm[t*K_e+slot], :]
  * (y_add DEVICE [T,d] (dtype); y_add == y is allowed).
+ * Their backward pass needs no call of its own either: on the shared configuration,
+ * mohge_combine_bwd with the constant gates turns dy into dy_perm, mohge_expert_ffn_bwd gives
+ * dx_perm and the weight gradients, and mohge_combine_add adds the N_s rows of dx_perm of a
+ * token to the routed part of dx.
  */
 int mohge_shared_routing(const mohge_config* cfg, int32_t* expert_idx, float* gates, int32_t* counts,
                          int32_t* offsets, int32_t* perm, int32_t* inv_perm, void* stream);

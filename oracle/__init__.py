@@ -294,6 +294,20 @@ def route_bwd(w, x, w_group, w_expert, bias, group_idx, expert_idx, dgates, f_G,
     return out
 
 
+def shared_experts_bwd(w, x, dy, w_gate_s, w_up_s, w_down_s):
+    """Backward of `shared_experts` for all tokens: every token passes dy[t] (weight 1) to each of
+    the N_s experts.  Returns dict(dx [T,d], dw_gate, dw_up [N_s,F_s,d], dw_down [N_s,d,F_s])."""
+    n_s, f_s = w_down_s.shape[0], w_down_s.shape[2]
+    T = x.shape[0]
+    ws = w.replace(T=T, d=x.shape[1], n_groups=1, experts_per_group=n_s, d_ff=(f_s,), k_groups=1, k_experts=n_s)
+    pair_token = np.repeat(np.arange(T, dtype=np.int32), n_s)
+    pair_expert = np.tile(np.arange(n_s, dtype=np.int32), T)
+    dy_pairs = np.repeat(np.asarray(dy, np.float64), n_s, axis=0)
+    f = expert_ffn_bwd(ws, x, [w_gate_s], [w_up_s], [w_down_s], pair_token, pair_expert, dy_pairs)
+    return dict(dx=f["dx_pairs"].reshape(T, n_s, x.shape[1]).sum(axis=1), dw_gate=f["dw_gate"][0],
+                dw_up=f["dw_up"][0], dw_down=f["dw_down"][0])
+
+
 def layer_bwd(w, inp, dy, fwd=None, alpha_g=None, alpha_e=None):
     """Gradient of  sum(dy*y) + L_G + L_E  for the whole layer (all tokens).
 

@@ -247,7 +247,7 @@ class SharedExperts:
     """N_s always-on experts of one width: buffers and the constant routing, made once."""
 
     def __init__(self, T: int, d: int, w13: torch.Tensor, w2: torch.Tensor, dtype: int = BF16,
-                 device="cuda"):
+                 device="cuda", backward: bool = False):
         n_s, f_s = w2.shape[0], w2.shape[2]
         self.cfg = Config(T=T, d=d, n_groups=1, experts_per_group=n_s, d_ff=(f_s,), k_groups=1,
                           k_experts=n_s, select_mode=SELECT_PER_GROUP, dtype=dtype)
@@ -264,12 +264,42 @@ class SharedExperts:
                               device=device)
         mohge_shared_routing(self.cfg, self.expert_idx, self.gates, self.counts, self.offsets, self.perm,
                              self.inv_perm)
+        self.has_backward = backward
+        if backward:
+            if dtype != BF16:
+                raise MohgeError("backward needs bf16 shared experts")
+            u8 = dict(dtype=torch.uint8, device=device)
+            bf = dict(dtype=torch.bfloat16, device=device)
+            self.saved = torch.empty(max(16, mohge_workspace_size(self.cfg, CALL_FFN_SAVED)), **u8)
+            self.ws_bwd = torch.empty(max(16, mohge_workspace_size(self.cfg, CALL_EXPERT_FFN_BWD)), **u8)
+            self.dgates = torch.empty((T, n_s), dtype=torch.float32, device=device)
+            self.dy_perm = torch.empty((max(P, 1), d), **bf)
+            self.dx_perm = torch.empty((max(P, 1), d), **bf)
+            self.dw13, self.dw2 = [torch.empty_like(w13)], [torch.empty_like(w2)]
+            self.dx = torch.empty((T, d), **bf)
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         c = self.cfg
-        mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws)
+        if self.has_backward:
+            mohge_expert_ffn_train(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.saved)
+        else:
+            mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws)
         mohge_combine(c, self.y_perm, self.inv_perm, self.gates, self.y)
         return self.y
+
+    def backward(self, x: torch.Tensor, dy: torch.Tensor, dx_add: torch.Tensor) -> torch.Tensor:
+        """After `forward(x)`: weight gradients into dw13 / dw2, and dx = dx_add + the shared
+        experts' input gradient.  Every token hands dy[t] to each expert with weight 1, so the
+        layer's own calls do it: the combine backward with the constant gates, the expert
+        backward, and a gated combine of the K rows of dx_perm per token on top of dx_add."""
+        if not self.has_backward:
+            raise MohgeError("SharedExperts was created without backward=True")
+        c = self.cfg
+        mohge_combine_bwd(c, dy, self.y_perm, self.inv_perm, self.gates, self.dgates, self.dy_perm)
+        mohge_expert_ffn_bwd(c, x, self.perm, self.offsets, self.w13, self.w2, self.saved, self.dy_perm,
+                             self.dx_perm, self.dw13, self.dw2, self.ws_bwd)
+        mohge_combine_add(c, self.dx_perm, self.inv_perm, self.gates, dx_add, self.dx)
+        return self.dx
 
 
 class MoHGELayer:
@@ -310,8 +340,8 @@ class MoHGELayer:
         self.stats = torch.empty(2 * Ng + 2 * Ne, **f32) if training else None
         self.ws_aux = torch.empty(max(16, mohge_workspace_size(cfg, CALL_AUX_LOSS)), **u8) if training else None
         # backward pass (bf16 layers): everything it writes is allocated here, once
-        if backward and shared is not None:
-            raise MohgeError("the backward pass of shared experts is not implemented")
+        if backward and shared is not None and not shared.has_backward:
+            raise MohgeError("backward with shared experts needs SharedExperts(..., backward=True)")
         if backward and not (training and cfg.dtype == BF16):
             raise MohgeError("backward needs a bf16 layer created with training=True")
         self.has_backward = backward
@@ -387,4 +417,6 @@ class MoHGELayer:
                         self.expert_idx, self.gates, self.dgates, self.stats, self.dx_perm,
                         self.inv_perm, self.dx, self.dw_group, self.dw_expert, self.dz,
                         self.ws_route_bwd)
+        if self.shared is not None:
+            return self.shared.backward(x, dy, self.dx)
         return self.dx

@@ -328,3 +328,44 @@ def test_backward_element_offsets_beyond_2_31():
                                       experts_per_group=2, d_ff=(256, 4096), k_groups=2, k_experts=4, seed=62)
     assert w.n_pairs * w.d > 2 ** 31
     _check_backward_sampled(w, 10, (3,), n_units=2)
+
+
+def test_backward_with_shared_experts():
+    """A training layer with always-on experts: dx and the shared experts' weight gradients
+    against the oracle (routed part + shared part)."""
+    from synth import bf16_bits_to_f32, f32_to_bf16_bits
+    w = _medium(SELECT_PER_GROUP, 41, T=450)
+    inp = generate(w)
+    rng = np.random.default_rng(17)
+    n_s, f_s = 2, 192
+    rb = lambda a: bf16_bits_to_f32(f32_to_bf16_bits(a))
+    g_s = rb(rng.standard_normal((n_s, f_s, w.d)).astype(np.float32) * 0.05)
+    u_s = rb(rng.standard_normal((n_s, f_s, w.d)).astype(np.float32) * 0.05)
+    d_s = rb(rng.standard_normal((n_s, w.d, f_s)).astype(np.float32) * 0.05)
+    dev = lambda a: torch.from_numpy(a).cuda().to(torch.bfloat16)       # exact: values are bf16 already
+    print(f"[backward, shared] T={w.T} d={w.d} N_s={n_s} F_s={f_s}", flush=True)
+    shared = M.SharedExperts(w.T, w.d, M.pack_w13(dev(g_s), dev(u_s)), dev(d_s), backward=True)
+    cfg = M.Config.from_workload(w)
+    w13 = [M.pack_w13(to_dev(g, True), to_dev(u, True)) for g, u in zip(inp.w_gate, inp.w_up)]
+    w2 = [to_dev(t, True) for t in inp.w_down]
+    L = M.MoHGELayer(cfg, torch.from_numpy(inp.w_group).cuda(), torch.from_numpy(inp.w_expert).cuda(), w13, w2,
+                     training=True, backward=True, shared=shared)
+    x, dy = to_dev(inp.x, True), to_dev(inp.dy, True)
+    y = L.forward(x)
+    dx = L.backward(x, dy)
+    torch.cuda.synchronize()
+    ref_fwd = oracle.layer(w, inp)
+    assert (ref_fwd["route"]["margin"] > 1e-6).all(), "pick another seed"
+    assert (L.expert_idx.cpu().numpy() == ref_fwd["route"]["expert_idx"]).all()
+    y_sh = oracle.shared_experts(w, inp.x.f32, g_s, u_s, d_s)
+    _close(from_dev(y), ref_fwd["y"] + y_sh, BF16_TOL, "y with shared experts")
+    g = oracle.layer_bwd(w, inp, inp.dy.f32, ref_fwd)
+    gs = oracle.shared_experts_bwd(w, inp.x.f32, inp.dy.f32, g_s, u_s, d_s)
+    assert np.abs(gs["dx"]).max() > 0.1 * np.abs(g["dx"]).max()          # the shared part is not negligible
+    _close(from_dev(dx), g["dx"] + gs["dx"], BF16_TOL, "dx with shared experts")
+    dw13 = from_dev(shared.dw13[0])
+    _close(dw13[:, :f_s], gs["dw_gate"], BF16_TOL, "shared dw_gate")
+    _close(dw13[:, f_s:], gs["dw_up"], BF16_TOL, "shared dw_up")
+    _close(from_dev(shared.dw2[0]), gs["dw_down"], BF16_TOL, "shared dw_down")
+    # the routed experts' gradients are untouched by the shared term
+    _close(from_dev(L.dw2[0]), g["dw_down"][0], BF16_TOL, "routed dw_down[0]")

@@ -213,3 +213,28 @@ def test_single_expert_reduces_to_a_dense_swiglu_mlp():
     _close(got["dw_up"][0][0], dB.T @ X, 1e-12, "dW_up")
     _close(got["dx"], dA @ G + dB @ U, 1e-12, "dx")
     assert np.abs(got["dw_expert"]).max() < 1e-18 and np.abs(got["dgates"]).max() > 0
+
+
+def test_shared_experts_backward_matches_autograd():
+    """Always-on experts: y[t] = sum_s W_down_s (SiLU(W_gate_s x_t) * (W_up_s x_t)), written in torch
+    float64; autograd of sum(dy*y) against the oracle's composition."""
+    rng = np.random.default_rng(5)
+    T, d, n_s, f_s = 13, 10, 3, 7
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    dy = rng.standard_normal((T, d)).astype(np.float32)
+    g_s = rng.standard_normal((n_s, f_s, d)).astype(np.float32) * 0.5
+    u_s = rng.standard_normal((n_s, f_s, d)).astype(np.float32) * 0.5
+    d_s = rng.standard_normal((n_s, d, f_s)).astype(np.float32) * 0.5
+    w = WORKLOADS["tiny_f32"]
+    got = oracle.shared_experts_bwd(w, x, dy, g_s, u_s, d_s)
+    tx = torch.tensor(x, dtype=torch.float64, requires_grad=True)
+    tg, tu, td = (torch.tensor(a, dtype=torch.float64, requires_grad=True) for a in (g_s, u_s, d_s))
+    y = torch.zeros((T, d), dtype=torch.float64)
+    for s in range(n_s):
+        a, b = tx @ tg[s].T, tx @ tu[s].T
+        y = y + (torch.nn.functional.silu(a) * b) @ td[s].T
+    # the forward agrees with the oracle's forward first
+    assert np.allclose(y.detach().numpy(), oracle.shared_experts(w, x, g_s, u_s, d_s), rtol=1e-10, atol=1e-12)
+    (y * torch.tensor(dy, dtype=torch.float64)).sum().backward()
+    for name, ref in (("dx", tx.grad), ("dw_gate", tg.grad), ("dw_up", tu.grad), ("dw_down", td.grad)):
+        assert np.allclose(got[name], ref.numpy(), rtol=1e-9, atol=1e-11), name
