@@ -51,7 +51,7 @@ static size_t up256(size_t b) { return (b + 255) / 256 * 256; }
 
 struct BwdLayout {
   size_t sched[4], recs[4];   // dgrad-h, dgrad-x, wgrad-2, wgrad-13
-  size_t zero, dab, xs, total;
+  size_t zero, fam, dab, xs, total;
 };
 
 static BwdLayout bwd_layout(const LayerDesc& L) {
@@ -64,6 +64,7 @@ static BwdLayout bwd_layout(const LayerDesc& L) {
   }
   const size_t P = L.P > 0 ? L.P : 1;
   o.zero = p; p += 512;
+  o.fam = p;  p += up256((size_t)(L.P / 64 + L.Ne + 1) * sizeof(int));     // row-block counters
   o.dab = p;  p += up256(P * 2 * L.Fmax * 2);
   o.xs = p;   p += up256(P * L.d * 2);
   o.total = p;
@@ -132,6 +133,12 @@ hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_
     if (g_dbg_which >= 0 && g_dbg_which < 4) sel[g_dbg_which]->dbg = g_dbg;
   }
 #endif
+  // fused form: dX tiles wait for the row-block counters the dH tiles increment
+  const bool fused = fused_launches();
+  if (fused) {
+    dh.coherent_out = 1;
+    dh.fam_done = dxa.fam_done = reinterpret_cast<int*>(base + lay.fam);
+  }
   // all four tile schedules (they depend on `offsets` only), then x in sorted order (and the
   // row of zeros; at least one workgroup so the zeros get written), then the products
   hipError_t e = launch_bwd_schedules(dh, dxa, w2a, w13a, s);
@@ -142,6 +149,10 @@ hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_
                      L.d / 8, reinterpret_cast<uint4*>(zero_row));
   e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (fused) {
+    if ((e = launch_dgrad_pair(dh, dxa, s)) != hipSuccess) return e;
+    return launch_wgrad_pair(w2a, w13a, s);
+  }
   if ((e = launch_tiles(kDgradH, dh, s)) != hipSuccess) return e;
   if ((e = launch_tiles(kDgradX, dxa, s)) != hipSuccess) return e;
   if ((e = launch_tiles(kWgrad, w2a, s)) != hipSuccess) return e;

@@ -230,7 +230,11 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
     r.fam = sh.fp[ve] + mi;
     // a down tile of the fused forward waits for the up tiles of its row block: one per 128
     // hidden units of the expert's group (F holds the group's width in kDown)
-    r.need = (fused && MODE == kDown) ? (a.F[r.e / a.N] + kBN / 2 - 1) / (kBN / 2) : 0;
+    // (kDown: F holds the group's width, the up tiles are 128 hidden units wide; kDgradX: F holds
+    // twice the width, the dH tiles are 256 hidden units wide)
+    r.need = !fused ? 0
+             : MODE == kDown ? (a.F[r.e / a.N] + kBN / 2 - 1) / (kBN / 2)
+             : MODE == kDgradX ? (a.F[r.e / a.N] / 2 + kBN - 1) / kBN : 0;
     a.recs[t] = r;
   }
   // XCD x starts at the first tile whose preceding cost is >= x/8 of the total.  Inside an
@@ -289,7 +293,7 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   if (v < kXcds) a.hdr->counters[v] = fused ? 0 : a.ncu / kXcds;
   if (v == 0) { a.hdr->tile_rows = h; a.hdr->total = total; }
   // fused forward: the row-block counters start at zero (the up list's workgroup clears them)
-  if (fused && is_up(MODE))
+  if (fused && (is_up(MODE) || MODE == kDgradH))
     for (int i = v; i < sh.fp[256]; i += 256) a.fam_done[i] = 0;
 }
 
@@ -316,9 +320,23 @@ __global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs up, co
 }
 
 // the four schedules of the expert backward pass in one launch: workgroup i <-> launch i
+// fused: the lists are for two fused launches (dH then dX, which waits for dH's row blocks and
+// so shares its tile height; the two weight gradients one after the other)
 __global__ void __launch_bounds__(256) bwd_schedule_kernel(const TileArgs dh, const TileArgs dx,
-                                                           const TileArgs w2, const TileArgs w13) {
+                                                           const TileArgs w2, const TileArgs w13, int fused) {
   __shared__ SchedShared sh;
+  if (fused) {
+    if (blockIdx.x < 2) {
+      const int h = choose_tile_rows<kDgradH>(dh, sh, true);
+      if (blockIdx.x == 0) build_schedule<kDgradH>(dh, sh, h, true);
+      else build_schedule<kDgradX>(dx, sh, h, true);
+    } else {
+      const TileArgs& a = blockIdx.x == 2 ? w2 : w13;
+      const int h = choose_tile_rows<kWgrad>(a, sh);
+      build_schedule<kWgrad>(a, sh, h, true);
+    }
+    return;
+  }
   if (blockIdx.x == 0) build_schedule<kDgradH>(dh, sh);
   else if (blockIdx.x == 1) build_schedule<kDgradX>(dx, sh);
   else if (blockIdx.x == 2) build_schedule<kWgrad>(w2, sh);
@@ -785,8 +803,13 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
               const long long at = (long long)(rec.row_start + trow) * a.ldpre + col;
               uint4 da, db;
               swiglu_bwd8(v, pre_a[it], pre_b[it], da, db);
-              *reinterpret_cast<uint4*>(a.C2 + at) = da;
-              *reinterpret_cast<uint4*>(a.C2 + at + F) = db;
+              if (a.coherent_out) {
+                store16_device_scope(a.C2 + at, da);
+                store16_device_scope(a.C2 + at + F, db);
+              } else {
+                *reinterpret_cast<uint4*>(a.C2 + at) = da;
+                *reinterpret_cast<uint4*>(a.C2 + at + F) = db;
+              }
             } else if (pass == 0) {
               uint16_t* dst = a.C + (long long)(rec.row_start + trow) * a.ldc + col;
               if (UP && a.coherent_out) store16_device_scope(dst, v);
@@ -887,9 +910,12 @@ __global__ void __launch_bounds__(Shape<MODE>::THREADS) ffn_tile_kernel(const Ti
 // if it ever expires the tile is computed regardless and a flag is left in the down header.
 constexpr int kSpinLimit = 1 << 22;
 
-// one phase of the fused launch: PHASE 0 = up tiles (UPMODE), 1 = down tiles
-template <int UPMODE, int PHASE>
+// One phase of a fused launch: the tiles of one list in MODE.  ROLE 1: producer (every finished
+// tile adds one to its row block's counter; the range's straddling tail goes first), ROLE 2:
+// consumer (a tile waits until its row block's counter has reached rec.need), ROLE 0: neither.
+template <int MODE, int ROLE>
 __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* lds, int lane, int w) {
+  constexpr int PHASE = ROLE == 1 ? 0 : 1;
   constexpr int kBcastOffset = 40960;
   const int xcd = blockIdx.x % kXcds;
   int tbeg = a.hdr->xcd_begin[xcd], tend = a.hdr->xcd_begin[xcd + 1];
@@ -920,17 +946,20 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
     rec.n0 = __builtin_amdgcn_readfirstlane(rec.n0);
     rec.fam = __builtin_amdgcn_readfirstlane(rec.fam);
     rec.need = __builtin_amdgcn_readfirstlane(rec.need);
-    const bool ok = !(rec.e < 0 || rec.e >= a.Ne || rec.rows < 1 || rec.rows > kBM || rec.row_start < 0 ||
-                      rec.n0 < 0 || rec.row_start + rec.rows > a.P || rec.fam < 0 || rec.fam > a.P);
+    bool ok = !(rec.e < 0 || rec.e >= a.Ne || rec.rows < 1 || rec.rows > kBM || rec.row_start < 0 ||
+                rec.n0 < 0 || rec.fam < 0);
+    if (ok) {
+      if constexpr (MODE == kWgrad) {
+        ok = rec.row_start + rec.rows <= a.Mrows[rec.e / a.N] && rec.n0 < a.Ncols[rec.e / a.N] &&
+             a.zero_row != nullptr && a.offsets[rec.e] >= 0 && a.offsets[rec.e + 1] <= a.P &&
+             a.offsets[rec.e] <= a.offsets[rec.e + 1];
+      } else {
+        ok = rec.row_start + rec.rows <= a.P && rec.fam <= a.P;
+      }
+    }
     if (ok) {
       const int nact = (rec.rows + 63) / 64;
-      if constexpr (PHASE == 0) {
-        if (nact == 4) run_tile<UPMODE, 4>(a, rec, lds, lane, w);
-        else if (nact == 3) run_tile<UPMODE, 3>(a, rec, lds, lane, w);
-        else if (nact == 2) run_tile<UPMODE, 2>(a, rec, lds, lane, w);
-        else run_tile<UPMODE, 1>(a, rec, lds, lane, w);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's H stores are done
-      } else {
+      if constexpr (ROLE == 2) {
         if (threadIdx.x == 0) {
 #ifdef MOHGE_PROBE
           const long long w0 = __builtin_amdgcn_s_memtime();
@@ -948,15 +977,17 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
 #endif
         }
         __syncthreads();
-        if (nact == 4) run_tile<kDown, 4>(a, rec, lds, lane, w);
-        else if (nact == 3) run_tile<kDown, 3>(a, rec, lds, lane, w);
-        else if (nact == 2) run_tile<kDown, 2>(a, rec, lds, lane, w);
-        else run_tile<kDown, 1>(a, rec, lds, lane, w);
       }
+      if (nact == 4) run_tile<MODE, 4>(a, rec, lds, lane, w);
+      else if (nact == 3) run_tile<MODE, 3>(a, rec, lds, lane, w);
+      else if (nact == 2) run_tile<MODE, 2>(a, rec, lds, lane, w);
+      else run_tile<MODE, 1>(a, rec, lds, lane, w);
+      if constexpr (ROLE == 1)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's output stores are done
     }
     __syncthreads();       // every wave is past its epilogue (and, up tiles, past its stores)
     if (threadIdx.x == 0) {
-      if (PHASE == 0 && ok)
+      if (ROLE == 1 && ok)
         __hip_atomic_fetch_add(&a.fam_done[rec.fam], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *reinterpret_cast<volatile int*>(lds + kBcastOffset) = t_next;
     }
@@ -965,13 +996,16 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
   }
 }
 
-template <int UPMODE>
-__global__ void __launch_bounds__(Shape<kUp>::THREADS) ffn_fused_kernel(const TileArgs up, const TileArgs dn) {
+// first: the tiles of list `p` in mode M0, then those of list `q` in mode M1; DEP: the second
+// list's tiles wait for row blocks of the first
+template <int M0, int M1, bool DEP>
+__global__ void __launch_bounds__(Shape<M0>::THREADS) ffn_fused_kernel(const TileArgs p, const TileArgs q) {
+  static_assert(Shape<M0>::THREADS == Shape<M1>::THREADS, "one workgroup shape");
   extern __shared__ __align__(1024) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  fused_phase<UPMODE, 0>(up, lds, lane, w);
-  fused_phase<UPMODE, 1>(dn, lds, lane, w);
+  fused_phase<M0, DEP ? 1 : 0>(p, lds, lane, w);
+  fused_phase<M1, DEP ? 2 : 0>(q, lds, lane, w);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1058,10 +1092,10 @@ static hipError_t launch_stage(const TileArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int UPMODE>
+template <int M0, int M1, bool DEP>
 static hipError_t launch_fused(const TileArgs& up, const TileArgs& dn, hipStream_t s) {
   constexpr size_t smem = (size_t)(kStagesA * kBM + kStagesB * kBN) * kBK * 2;
-  auto kern = ffn_fused_kernel<UPMODE>;
+  auto kern = ffn_fused_kernel<M0, M1, DEP>;
   static bool attr_done = false;
   if (!attr_done) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1069,7 +1103,7 @@ static hipError_t launch_fused(const TileArgs& up, const TileArgs& dn, hipStream
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(up.ncu), dim3(Shape<kUp>::THREADS), smem, s, up, dn);
+  hipLaunchKernelGGL(kern, dim3(up.ncu), dim3(Shape<M0>::THREADS), smem, s, up, dn);
   return hipGetLastError();
 }
 
@@ -1083,8 +1117,20 @@ static hipError_t sched_and_run(const TileArgs& a, hipStream_t s) {
 
 hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const TileArgs& w2,
                                 const TileArgs& w13, hipStream_t s) {
-  hipLaunchKernelGGL(bwd_schedule_kernel, dim3(4), dim3(256), 0, s, dh, dx, w2, w13);
+  hipLaunchKernelGGL(bwd_schedule_kernel, dim3(4), dim3(256), 0, s, dh, dx, w2, w13, g_fused_forward);
   return hipGetLastError();
+}
+
+bool fused_launches() { return g_fused_forward != 0; }
+
+// dH and dX in one launch (dX tiles wait for the dH tiles of their row block)
+hipError_t launch_dgrad_pair(const TileArgs& dh, const TileArgs& dx, hipStream_t s) {
+  return launch_fused<kDgradH, kDgradX, true>(dh, dx, s);
+}
+
+// the two weight-gradient products in one launch
+hipError_t launch_wgrad_pair(const TileArgs& w2, const TileArgs& w13, hipStream_t s) {
+  return launch_fused<kWgrad, kWgrad, false>(w2, w13, s);
 }
 
 hipError_t launch_tiles(int mode, const TileArgs& a, hipStream_t s) {
@@ -1165,7 +1211,7 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
     hipLaunchKernelGGL(ffn_schedule_kernel, dim3(2), dim3(256), 0, s, up, dn, 7);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return pre ? launch_fused<kUpSave>(up, dn, s) : launch_fused<kUp>(up, dn, s);
+    return pre ? launch_fused<kUpSave, kDown, true>(up, dn, s) : launch_fused<kUp, kDown, true>(up, dn, s);
   }
   // both schedules depend only on `offsets`: one launch builds whichever are needed
   hipLaunchKernelGGL(ffn_schedule_kernel, dim3(stages == 3 ? 2 : 1), dim3(256), 0, s, up, dn, stages);

@@ -81,6 +81,11 @@ hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s);
 hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const TileArgs& w2,
                                 const TileArgs& w13, hipStream_t s);
 hipError_t launch_tiles(int mode, const TileArgs& a, hipStream_t s);
+// Fused launches (default; mohge_tune knob 2 = 0 turns them off): dH then dX in one launch, the
+// two weight gradients in one launch.  The schedules must have been built in the same form.
+bool fused_launches();
+hipError_t launch_dgrad_pair(const TileArgs& dh, const TileArgs& dx, hipStream_t s);
+hipError_t launch_wgrad_pair(const TileArgs& w2, const TileArgs& w13, hipStream_t s);
 // Largest number of tiles a schedule of `mode` can hold for layer L (sizes the record area).
 long long tile_capacity(const LayerDesc& L, int mode);
 int tile_num_cus();

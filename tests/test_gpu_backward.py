@@ -369,3 +369,32 @@ def test_backward_with_shared_experts():
     _close(from_dev(shared.dw2[0]), gs["dw_down"], BF16_TOL, "shared dw_down")
     # the routed experts' gradients are untouched by the shared term
     _close(from_dev(L.dw2[0]), g["dw_down"][0], BF16_TOL, "routed dw_down[0]")
+
+
+def test_fused_backward_launches_equal_separate_launches():
+    """The backward products as two fused launches (dH -> dX with row-block counters, the two
+    weight gradients back to back) against the four-launch form, bit for bit, with inputs that
+    change from call to call."""
+    w = _medium(SELECT_PER_GROUP, 52, T=900, d_ff=(128, 448, 640))
+    dl = DeviceLayer(w, generate(w), backward=True)
+    L = dl.layer
+    try:
+        for it in range(4):
+            wi = w.replace(seed=500 + it, skew_beta=float(it % 2) * 2.0)
+            inp = generate(wi)
+            x, dy = to_dev(inp.x, True), to_dev(inp.dy, True)
+            print(f"[fused backward] call {it} seed={wi.seed}", flush=True)
+            res = []
+            for knob in (1, 0):
+                M.mohge_tune(2, knob)
+                L.forward(x)
+                for t in L.dw13 + L.dw2 + [L.dx_perm, L.dx]:
+                    t.fill_(float("nan"))
+                L.backward(x, dy)
+                torch.cuda.synchronize()
+                res.append([t.clone() for t in L.dw13 + L.dw2 + [L.dx_perm[:dl.cfg.n_pairs], L.dx, L.dw_expert]])
+            for a, b in zip(*res):
+                assert torch.equal(a, b), f"call {it}"
+                assert torch.isfinite(a.float()).all()
+    finally:
+        M.mohge_tune(2, 1)
