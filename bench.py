@@ -28,7 +28,7 @@ PEAK_HBM = 8.0e12           # B/s
 MEASURED_TRAFFIC = {
     "mid_prefill": (308250 * 2.0 + 98620 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
     "decode": (628760 * 2.0 + 379 * 1.0) * 1024,          # ffn_skinny_kernel<up>
-    "training": (636820 * 2.0 + 326870 * 1.0) * 1024,     # ffn_fused_kernel<up that saves + down>
+    "training": (639010 * 2.0 + 326870 * 1.0) * 1024,     # ffn_fused_kernel<up that saves + down>
     "large_prefill_skewed": (5145300 * 2.0 + 696360 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
 }
 

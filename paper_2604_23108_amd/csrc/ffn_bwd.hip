@@ -17,7 +17,8 @@
 // index as the row; the tile kernel reads such operands through the transposing LDS read, so
 // the weights are used as the forward pass stores them and no activation is transposed in
 // memory.  The only helper pass gathers the rows of x into sorted order for the last product
-// (the other three activations already are in sorted order).
+// (the other three activations already are in sorted order); it shares a launch with the tile
+// schedules.
 #include "common.h"
 #include "tiled.h"
 
@@ -29,20 +30,6 @@ const void* saved_pre(const LayerDesc& L, const void* saved);
 extern long long* g_dbg;     // cycle counters of the instrumented build
 extern int g_dbg_which;      // which of the four launches fills them
 #endif
-
-// rows of x in sorted order: xs[p] = x[perm[p] / Ke]; one wave per row (perm == NULL: x already
-// is in sorted order, nothing is copied).  Workgroup 0 also
-// clears the 512-byte row of zeros the weight-gradient tiles read past an expert's last row.
-__global__ void __launch_bounds__(256) gather_sorted_rows_kernel(const uint4* __restrict__ x,
-                                                                 const int32_t* __restrict__ perm,
-                                                                 uint4* __restrict__ xs, int P, int Ke,
-                                                                 int chunks, uint4* __restrict__ zero_row) {
-  if (blockIdx.x == 0 && threadIdx.x < 32) zero_row[threadIdx.x] = make_uint4(0u, 0u, 0u, 0u);
-  const int p = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-  if (p >= P || perm == nullptr) return;
-  const long long row = perm[p] / Ke;
-  for (int c = lane; c < chunks; c += 64) xs[(long long)p * chunks + c] = x[row * chunks + c];
-}
 
 // ---------------------------------------------------------------------------------------
 // workspace layout and the launch sequence
@@ -139,15 +126,12 @@ hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_
     dh.coherent_out = 1;
     dh.fam_done = dxa.fam_done = reinterpret_cast<int*>(base + lay.fam);
   }
-  // all four tile schedules (they depend on `offsets` only), then x in sorted order (and the
-  // row of zeros; at least one workgroup so the zeros get written), then the products
-  hipError_t e = launch_bwd_schedules(dh, dxa, w2a, w13a, s);
-  if (e != hipSuccess) return e;
-  const unsigned gather_blocks = L.P > 0 && perm ? (unsigned)((L.P + 3) / 4) : 1u;
-  hipLaunchKernelGGL(gather_sorted_rows_kernel, dim3(gather_blocks), dim3(256), 0, s,
-                     static_cast<const uint4*>(x), perm, reinterpret_cast<uint4*>(xs), L.P, L.Ke,
-                     L.d / 8, reinterpret_cast<uint4*>(zero_row));
-  e = hipGetLastError();
+  // one launch: all four tile schedules (they depend on `offsets` only) and, on further
+  // workgroups, x in sorted order and the row of zeros; then the products
+  GatherArgs ga;
+  ga.x = static_cast<const uint4*>(x); ga.perm = perm; ga.xs = reinterpret_cast<uint4*>(xs);
+  ga.zero_row = reinterpret_cast<uint4*>(zero_row); ga.P = L.P; ga.Ke = L.Ke; ga.chunks = L.d / 8;
+  hipError_t e = launch_bwd_schedules(dh, dxa, w2a, w13a, ga, s);
   if (e != hipSuccess) return e;
   if (fused) {
     if ((e = launch_dgrad_pair(dh, dxa, s)) != hipSuccess) return e;

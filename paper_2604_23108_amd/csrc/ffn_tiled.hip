@@ -323,17 +323,31 @@ __global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs up, co
 // fused: the lists are for two fused launches (dH then dX, which waits for dH's row blocks and
 // so shares its tile height; the two weight gradients one after the other)
 __global__ void __launch_bounds__(256) bwd_schedule_kernel(const TileArgs dh, const TileArgs dx,
-                                                           const TileArgs w2, const TileArgs w13, int fused) {
+                                                           const TileArgs w2, const TileArgs w13, int fused,
+                                                           const GatherArgs ga) {
+  if (blockIdx.x >= 4) {
+    // rows of x in sorted order, one wave per row; the first of these workgroups also clears the
+    // row of zeros the weight-gradient tiles read past an expert's last row
+    const int b = blockIdx.x - 4;
+    if (b == 0 && threadIdx.x < 32) ga.zero_row[threadIdx.x] = make_uint4(0u, 0u, 0u, 0u);
+    const int p = b * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (p >= ga.P || ga.perm == nullptr) return;
+    const long long row = ga.perm[p] / ga.Ke;
+    for (int c = lane; c < ga.chunks; c += 64) ga.xs[(long long)p * ga.chunks + c] = ga.x[row * ga.chunks + c];
+    return;
+  }
   __shared__ SchedShared sh;
   if (fused) {
     if (blockIdx.x < 2) {
       const int h = choose_tile_rows<kDgradH>(dh, sh, true);
       if (blockIdx.x == 0) build_schedule<kDgradH>(dh, sh, h, true);
       else build_schedule<kDgradX>(dx, sh, h, true);
+    } else if (blockIdx.x == 2) {
+      const int h = choose_tile_rows<kWgrad>(w2, sh);
+      build_schedule<kWgrad>(w2, sh, h, true);
     } else {
-      const TileArgs& a = blockIdx.x == 2 ? w2 : w13;
-      const int h = choose_tile_rows<kWgrad>(a, sh);
-      build_schedule<kWgrad>(a, sh, h, true);
+      const int h = choose_tile_rows<kWgrad>(w13, sh);
+      build_schedule<kWgrad>(w13, sh, h, true);
     }
     return;
   }
@@ -1116,8 +1130,11 @@ static hipError_t sched_and_run(const TileArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const TileArgs& w2,
-                                const TileArgs& w13, hipStream_t s) {
-  hipLaunchKernelGGL(bwd_schedule_kernel, dim3(4), dim3(256), 0, s, dh, dx, w2, w13, g_fused_forward);
+                                const TileArgs& w13, const GatherArgs& ga, hipStream_t s) {
+  // at least one gather workgroup, so that the row of zeros gets written
+  const unsigned gather_blocks = ga.P > 0 && ga.perm ? (unsigned)((ga.P + 3) / 4) : 1u;
+  hipLaunchKernelGGL(bwd_schedule_kernel, dim3(4 + gather_blocks), dim3(256), 0, s, dh, dx, w2, w13,
+                     g_fused_forward, ga);
   return hipGetLastError();
 }
 

@@ -78,8 +78,17 @@ struct TileArgs {
 // One schedule launch + one tile-kernel launch for `mode` (backward modes and kUpSave).
 hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s);
 // The expert backward pass: all four schedules in one launch, then the tile launches alone.
+// The same launch also gathers the rows of x into sorted order (xs[p] = x[perm[p] / Ke], nothing
+// if perm == NULL) and clears the 512-byte row of zeros: workgroups beyond the first four.
+struct GatherArgs {
+  const uint4* x;
+  const int32_t* perm;
+  uint4* xs;
+  uint4* zero_row;
+  int P, Ke, chunks;          // chunks = 16-byte pieces of a row
+};
 hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const TileArgs& w2,
-                                const TileArgs& w13, hipStream_t s);
+                                const TileArgs& w13, const GatherArgs& ga, hipStream_t s);
 hipError_t launch_tiles(int mode, const TileArgs& a, hipStream_t s);
 // Fused launches (default; mohge_tune knob 2 = 0 turns them off): dH then dX in one launch, the
 // two weight gradients in one launch.  The schedules must have been built in the same form.
