@@ -197,6 +197,28 @@ def shared_experts(w, x, w_gate_s, w_up_s, w_down_s, tokens=None):
     return combine(ws, y_pairs, np.ones((len(tok), n_s)))
 
 
+def decode_e4m3(codes):
+    """FP8 E4M3 (the OCP 8-bit format without infinities: 1 sign, 4 exponent bits with bias 7, 3
+    mantissa bits; exponent field 0 is subnormal, S.1111.111 is NaN, largest finite value 448)
+    -> float64.  `codes` is any uint8 array."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(c & 0x80, -1.0, 1.0)
+    ex = (c >> 3) & 0xF
+    man = (c & 0x7).astype(np.float64)
+    normal = (1.0 + man / 8.0) * np.exp2((ex - 7).astype(np.float64))
+    subnormal = (man / 8.0) * 2.0 ** -6
+    val = sign * np.where(ex == 0, subnormal, normal)
+    return np.where((ex == 15) & ((c & 0x7) == 7), np.nan, val)
+
+
+def dequantize_rows(codes, scale):
+    """Weights stored as E4M3 codes with one fp32 scale per row (last axis = the row's elements):
+    value = scale[row] * decode(code), as float32 (exact: 4 significant bits times an fp32 scale
+    rounds once, like the multiplication the kernel's epilogue does on the accumulated sum would
+    not; the oracle therefore multiplies the weights, in float64, and rounds nothing)."""
+    return decode_e4m3(codes) * np.asarray(scale, np.float64)[..., None]
+
+
 def layer(w, inp, tokens=None):
     """Forward pass of the layer for all tokens, or for the listed token ids.
 

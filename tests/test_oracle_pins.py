@@ -405,3 +405,26 @@ def test_shared_experts_are_a_sum_of_dense_swiglu_blocks():
         want += (a / (1 + np.exp(-a)) * b) @ dn[s_].astype(np.float64).T
     np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(oracle.shared_experts(w, x, g, u, dn, tokens=[5, 1]), want[[5, 1]], rtol=1e-12)
+
+
+def test_e4m3_decoder_against_the_format_definition_and_a_library():
+    """FP8 E4M3 (OCP 8-bit floating point, the variant with NaN but no infinities): values the
+    format definition fixes, and all 256 codes against torch's float8_e4m3fn."""
+    import torch
+    d = oracle.decode_e4m3
+    fixed = {0x00: 0.0, 0x38: 1.0, 0x40: 2.0, 0x30: 0.5, 0x3C: 1.5, 0x08: 2.0 ** -6, 0x01: 2.0 ** -9,
+             0x07: 7 * 2.0 ** -9, 0x7E: 448.0, 0x77: 240.0, 0xB8: -1.0, 0xFE: -448.0, 0x3F: 1.875}
+    for code, val in fixed.items():
+        assert d(np.uint8(code)) == val, hex(code)
+    assert np.isnan(d(np.uint8(0x7F))) and np.isnan(d(np.uint8(0xFF)))
+    assert np.signbit(d(np.uint8(0x80))) and d(np.uint8(0x80)) == 0.0
+    codes = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy().astype(np.float64)
+    got = d(codes)
+    assert np.array_equal(np.isnan(got), np.isnan(lib))
+    ok = ~np.isnan(got)
+    assert np.array_equal(got[ok], lib[ok])
+    # monotone in the code within a sign, 4 significant bits
+    assert (np.diff(got[:0x7F]) > 0).all()
+    q = oracle.dequantize_rows(np.array([[0x38, 0x40], [0xB8, 0x30]], np.uint8), np.array([2.0, 0.5], np.float32))
+    assert np.array_equal(q, np.array([[2.0, 4.0], [-0.5, 0.25]]))
