@@ -214,6 +214,24 @@ int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
  */
 
 /*
+ * mohge_expert_ffn for decode with quantised expert weights (not in the paper: halves the bytes
+ * the memory-bound decode step streams).  w13q[g] DEVICE [N, 2*F_g, d] and w2q[g] DEVICE
+ * [N, d, F_g] hold FP8 E4M3 codes (the OCP 8-bit format: 1 sign, 4 exponent bits with bias 7,
+ * 3 mantissa bits, no infinities, S.1111.111 = NaN), one byte per element in the layout of
+ * w13 / w2; w13_scale[g] DEVICE [N, 2*F_g] f32 and w2_scale[g] DEVICE [N, d] f32 hold one scale per
+ * weight row: the weight is scale[row] * value(code).  x, H and y_perm stay bf16; the codes are
+ * converted exactly to bf16 matrix-core operands, sums are fp32, the scale multiplies the sum.
+ * Only for cfg->dtype == MOHGE_BF16 and T <= 32 (MOHGE_EINVAL otherwise).  workspace as for
+ * mohge_expert_ffn.  mohge_fp8_decode converts n codes to f32 with the same hardware conversion
+ * (DEVICE pointers), for checks and tools.
+ */
+int mohge_expert_ffn_w8(const mohge_config* cfg, const void* x, const int32_t* perm,
+                        const int32_t* offsets, const void* const* w13q, const float* const* w13_scale,
+                        const void* const* w2q, const float* const* w2_scale, void* y_perm,
+                        void* workspace, size_t workspace_bytes, void* stream);
+int mohge_fp8_decode(const void* codes, float* out, size_t n, void* stream);
+
+/*
  * mohge_expert_ffn with the same results, which additionally keeps, in `saved` (DEVICE,
  * mohge_workspace_size(cfg, MOHGE_CALL_FFN_SAVED) bytes, layout the library's), the hidden
  * activations h and, with a = W_gate x, b = W_up x, the two factors b*SiLU'(a) and SiLU(a) that turn

@@ -22,7 +22,7 @@ CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE = 3, 4, 5, 6
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
            "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_tune",
-           "mohge_expert_ffn_train", "mohge_combine_bwd",
+           "mohge_expert_ffn_train", "mohge_expert_ffn_w8", "mohge_fp8_decode", "mohge_combine_bwd",
            "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_shared_routing", "mohge_combine_add",
            "mohge_workspace_size", "mohge_last_error"]
 
@@ -161,6 +161,32 @@ def mohge_expert_ffn(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], w2: Seq
                                   _ptr_table(w2), _ptr(y_perm), _ptr(workspace),
                                   C.c_size_t(workspace.numel() * workspace.element_size()),
                                   _stream()), "mohge_expert_ffn")
+
+
+def mohge_expert_ffn_w8(cfg, x, perm, offsets, w13q, w13_scale, w2q, w2_scale, y_perm, workspace):
+    for t in list(w13q) + list(w13_scale) + list(w2q) + list(w2_scale):
+        _ptr(t)
+    _check(lib().mohge_expert_ffn_w8(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13q),
+                                     _ptr_table(w13_scale), _ptr_table(w2q), _ptr_table(w2_scale),
+                                     _ptr(y_perm), _ptr(workspace), _nbytes(workspace), _stream()),
+           "mohge_expert_ffn_w8")
+
+
+def mohge_fp8_decode(codes: torch.Tensor, out: torch.Tensor):
+    _check(lib().mohge_fp8_decode(_ptr(codes), _ptr(out), C.c_size_t(codes.numel()), _stream()),
+           "mohge_fp8_decode")
+
+
+def quantize_rows_e4m3(w: torch.Tensor):
+    """Per-row FP8 E4M3 quantisation of a weight tensor [..., rows, cols] (argument preparation,
+    done with torch): scale[row] = max|row| / 448 (1 for an all-zero row), codes = the row divided
+    by its scale, rounded to nearest even.  Returns (codes uint8 of w's shape, scales f32 of
+    w's shape without the last axis)."""
+    wf = w.float()
+    amax = wf.abs().amax(dim=-1)
+    scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
+    codes = (wf / scale.unsqueeze(-1)).to(torch.float8_e4m3fn).view(torch.uint8)
+    return codes.contiguous(), scale.contiguous()
 
 
 def mohge_expert_ffn_up(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], h):
@@ -317,6 +343,7 @@ class MoHGELayer:
         self.bias = expert_logit_bias
         self.training = training
         self.shared = shared
+        self.w8 = None          # (codes13, scales13, codes2, scales2) once use_fp8_weights() was called
         T, P, Ne, Ng = cfg.T, cfg.n_pairs, cfg.n_experts, cfg.n_groups
         i32 = dict(dtype=torch.int32, device=device)
         f32 = dict(dtype=torch.float32, device=device)
@@ -369,6 +396,8 @@ class MoHGELayer:
         if self.has_backward:
             mohge_expert_ffn_train(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm,
                                    self.saved)
+        elif self.w8 is not None:
+            mohge_expert_ffn_w8(c, x, self.perm, self.offsets, *self.w8, self.y_perm, self.ws_ffn)
         else:
             mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws_ffn)
         if self.shared is not None:
@@ -379,6 +408,14 @@ class MoHGELayer:
             mohge_aux_loss(c, self.gs, self.es1, self.group_idx, self.expert_idx, self.losses,
                            self.stats, self.ws_aux)
         return self.y
+
+    def use_fp8_weights(self):
+        """Decode only (T <= 32): quantises the expert weights per row to FP8 E4M3 once and makes
+        forward() stream those instead of the bf16 weights."""
+        if self.cfg.T > 32 or self.cfg.dtype != BF16 or self.has_backward:
+            raise MohgeError("FP8 expert weights are served by the bf16 decode path only (T <= 32)")
+        q = [quantize_rows_e4m3(w) for w in self.w13], [quantize_rows_e4m3(w) for w in self.w2]
+        self.w8 = ([c for c, _ in q[0]], [s for _, s in q[0]], [c for c, _ in q[1]], [s for _, s in q[1]])
 
     def capture(self, x: torch.Tensor, dy: Optional[torch.Tensor] = None):
         """Records one step (forward, or forward + backward when `dy` is

@@ -164,6 +164,55 @@ int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm
                 "mohge_expert_ffn");
 }
 
+static int need_bf16(const mohge_config* cfg, const char* what) {
+  if (cfg->dtype != MOHGE_BF16) {
+    set_error("%s is implemented for dtype MOHGE_BF16 only", what);
+    return MOHGE_EINVAL;
+  }
+  return MOHGE_OK;
+}
+
+int mohge_expert_ffn_w8(const mohge_config* cfg, const void* x, const int32_t* perm,
+                        const int32_t* offsets, const void* const* w13q, const float* const* w13_scale,
+                        const void* const* w2q, const float* const* w2_scale, void* y_perm,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if ((rc = need_bf16(cfg, "mohge_expert_ffn_w8"))) return rc;
+  if (!ffn_w8_supported(L)) {
+    set_error("mohge_expert_ffn_w8: FP8 weights are served by the decode path only (T <= 32), T = %d", L.T);
+    return MOHGE_EINVAL;
+  }
+  NEED(x); OPT(perm); NEED(offsets); NEED(y_perm); NEED(workspace);
+  if (!w13q || !w2q || !w13_scale || !w2_scale) { set_error("a weight / scale pointer table is NULL"); return MOHGE_ENULL; }
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
+  const float* s13[kMaxGroups];
+  const float* s2[kMaxGroups];
+  for (int g = 0; g < L.Ng; ++g) {
+    NEED(w13q[g]); NEED(w2q[g]); NEED(w13_scale[g]); NEED(w2_scale[g]);
+    W.w13[g] = w13q[g];
+    W.w2[g] = w2q[g];
+    s13[g] = w13_scale[g];
+    s2[g] = w2_scale[g];
+  }
+  if (workspace_bytes < ffn_workspace_bytes(L, cfg->dtype)) {
+    set_error("expert_ffn_w8 workspace: %zu bytes given, %zu needed", workspace_bytes,
+              ffn_workspace_bytes(L, cfg->dtype));
+    return MOHGE_EWORKSPACE;
+  }
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_expert_ffn_w8(L, x, perm, offsets, W, s13, s2, y_perm, workspace, (hipStream_t)stream),
+                "mohge_expert_ffn_w8");
+}
+
+int mohge_fp8_decode(const void* codes, float* out, size_t n, void* stream) {
+  if (n == 0) return MOHGE_OK;
+  NEED(codes); NEED(out);
+  return hip_rc(launch_fp8_decode(codes, out, (long long)n, (hipStream_t)stream), "mohge_fp8_decode");
+}
+
 int mohge_expert_ffn_up(const mohge_config* cfg, const void* x, const int32_t* perm,
                         const int32_t* offsets, const void* const* w13, void* h, size_t h_bytes,
                         void* stream) {
@@ -258,14 +307,6 @@ int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
 }
 
 // ---- training -------------------------------------------------------------------------
-
-static int need_bf16(const mohge_config* cfg, const char* what) {
-  if (cfg->dtype != MOHGE_BF16) {
-    set_error("%s is implemented for dtype MOHGE_BF16 only", what);
-    return MOHGE_EINVAL;
-  }
-  return MOHGE_OK;
-}
 
 #define PTR_TABLE(dst, src, name)                                              \
   do {                                                                         \

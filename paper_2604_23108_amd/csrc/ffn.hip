@@ -9,7 +9,7 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
                             hipStream_t s, int stages, void* pre);
 hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                             hipStream_t s, int stages);
+                             hipStream_t s, int stages, const float* const* s13, const float* const* s2);
 
 // ---- fp32: one wave per (sorted row, output element block) ----------------------------
 // A wave computes 4 outputs of one row at a time: lanes stride the reduction dimension
@@ -109,8 +109,17 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
   if (dtype == MOHGE_F32) return launch_ffn_f32(L, x, perm, offsets, W, y_perm, ws, s, stages);
   // With at most 32 tokens no expert can receive more than 32 rows: one pass of the
   // weight-streaming kernel covers it.  Otherwise the tiled matrix-core kernel.
-  if (use_skinny(L)) return launch_ffn_skinny(L, x, perm, offsets, W, y_perm, ws, s, stages);
+  if (use_skinny(L)) return launch_ffn_skinny(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr, nullptr);
   return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr);
+}
+
+// Decode with FP8 E4M3 weights (one fp32 scale per weight row): the weight-streaming kernel only
+bool ffn_w8_supported(const LayerDesc& L) { return use_skinny(L); }
+
+hipError_t launch_expert_ffn_w8(const LayerDesc& L, const void* x, const int32_t* perm,
+                                const int32_t* offsets, const GroupPtrs& Wq, const float* const* s13,
+                                const float* const* s2, void* y_perm, void* ws, hipStream_t s) {
+  return launch_ffn_skinny(L, x, perm, offsets, Wq, y_perm, ws, s, 3, s13, s2);
 }
 
 // Training forward (bf16): what the backward pass needs is kept in `saved`:

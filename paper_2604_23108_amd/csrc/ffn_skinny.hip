@@ -8,6 +8,12 @@
 // which is the operand layout, so weights go global -> registers -> matrix core with no
 // LDS traffic; token rows come through L1/L2 (lanes past the token count load nothing).
 // Experts without tokens are skipped on the device: their workgroups exit at once.
+//
+// W8 variant: the weights are stored as FP8 E4M3 codes with one fp32 scale per weight row, which
+// halves the bytes the decode step streams.  A lane loads 16 codes (16 bytes) of its row, the
+// hardware conversion turns them into two bf16 operand fragments (E4M3 values are exact in bf16)
+// and the token operand is read with the same assignment of reduction indices to operand slots;
+// the row scale multiplies the fp32 sum in the epilogue.
 #include <type_traits>
 
 #include "common.h"
@@ -21,7 +27,8 @@ struct SkinnyArgs {
   const uint16_t* A;              // up: x; down: H
   const int32_t* perm;            // up only, may be NULL
   const int32_t* offsets;
-  const uint16_t* W[kMaxGroups];
+  const uint16_t* W[kMaxGroups];  // bf16 weights, or E4M3 codes (W8)
+  const float* S[kMaxGroups];     // W8: scale per weight row, same row order as W
   uint16_t* C;
   int lda, ldc, Ke, Ng, N, d;
   int F[kMaxGroups];
@@ -145,9 +152,189 @@ __global__ void __launch_bounds__(256) ffn_skinny_kernel(const SkinnyArgs a) {
   }
 }
 
+// 16 E4M3 codes -> two operand fragments of 8 bf16 (codes 0..7 and 8..15)
+__device__ __forceinline__ void fp8x16_to_bf16(const uint4 c, Frag& lo, Frag& hi) {
+  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+  uint32_t o[8];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);   // codes 0, 1 of the word
+    const f32x2 b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);    // codes 2, 3
+    // exact in bf16: keep the upper halves of the fp32 patterns
+    o[2 * i] = (__float_as_uint(a[0]) >> 16) | (__float_as_uint(a[1]) & 0xffff0000u);
+    o[2 * i + 1] = (__float_as_uint(b[0]) >> 16) | (__float_as_uint(b[1]) & 0xffff0000u);
+  }
+  lo.u = make_uint4(o[0], o[1], o[2], o[3]);
+  hi.u = make_uint4(o[4], o[5], o[6], o[7]);
+}
+
+// FP8-weight variant of ffn_skinny_kernel: same work split; a unit of the reduction is 64
+// indices: lane (r, q) holds indices 16q .. 16q+15 of its weight row (one 16-byte load) and of
+// its token (two 16-byte loads), used as two MFMA steps (16q+0..7, then 16q+8..15).
+template <bool UP>
+__global__ void __launch_bounds__(256) ffn_skinny_w8_kernel(const SkinnyArgs a) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  int g = 0;
+  while (g + 1 < a.Ng && (int)blockIdx.x >= a.blk_prefix[g + 1]) ++g;
+  const int F = a.F[g];
+  const int K = UP ? a.d : F;
+  const int ncols = UP ? F : a.d;
+  constexpr int COLS_PER_BLOCK = UP ? 64 : 128;
+  const int blocks_per_expert = (ncols + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
+  const int local = blockIdx.x - a.blk_prefix[g];
+  const int i = local / blocks_per_expert, cb = local % blocks_per_expert;
+  const int e = g * a.N + i;
+  const int row0 = a.offsets[e], cnt = a.offsets[e + 1] - row0;
+  if (cnt <= 0) return;
+  const int c0 = cb * COLS_PER_BLOCK + w * (UP ? 16 : 32);
+  if (c0 >= ncols) return;
+
+  // the two weight-row sets of this wave (bytes: one code per element) and their row indices
+  const uint8_t* wbase = reinterpret_cast<const uint8_t*>(a.W[g]);
+  const uint8_t* wp[2];
+  long long wrow[2];
+  if constexpr (UP) {
+    wrow[0] = (long long)i * 2 * F + c0 + r;
+    wrow[1] = (long long)i * 2 * F + F + c0 + r;
+  } else {
+    int n1 = c0 + 16 + r;
+    if (n1 > a.d - 1) n1 = a.d - 1;
+    wrow[0] = (long long)i * a.d + c0 + r;
+    wrow[1] = (long long)i * a.d + n1;
+  }
+  wp[0] = wbase + wrow[0] * K + 16 * q;
+  wp[1] = wbase + wrow[1] * K + 16 * q;
+
+  for (int tb0 = 0; tb0 < cnt; tb0 += 32) {
+    const uint16_t* xp[2];
+    bool xv[2];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      const int tt = tb0 + 16 * tb + r;
+      xv[tb] = tt < cnt;
+      const int pos = row0 + (xv[tb] ? tt : 0);
+      long long src;
+      if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
+      else src = pos;
+      xp[tb] = a.A + src * a.lda + 16 * q;
+    }
+    f32x4 acc[2][2];
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+      for (int tb = 0; tb < 2; ++tb) acc[f][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto step = [&](int k0, auto UC) {
+      constexpr int U = decltype(UC)::value;
+      uint4 wq[2][U];
+      Frag xf[2][U][2];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + k0 + 64 * u);
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+          xf[tb][u][0].u = make_uint4(0u, 0u, 0u, 0u);
+          xf[tb][u][1].u = make_uint4(0u, 0u, 0u, 0u);
+          if (xv[tb]) {
+            xf[tb][u][0].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 64 * u);
+            xf[tb][u][1].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 64 * u + 8);
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+          Frag wlo, whi;
+          fp8x16_to_bf16(wq[f][u], wlo, whi);
+#pragma unroll
+          for (int tb = 0; tb < 2; ++tb) {
+            acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wlo.v, xf[tb][u][0].v, acc[f][tb], 0, 0, 0);
+            acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whi.v, xf[tb][u][1].v, acc[f][tb], 0, 0, 0);
+          }
+        }
+    };
+    int k0 = 0;
+    for (; k0 + 256 <= K; k0 += 256) step(k0, std::integral_constant<int, 4>{});
+    for (; k0 < K; k0 += 64) step(k0, std::integral_constant<int, 1>{});
+
+    // lane holds token r of each token block, weight rows 4q..4q+3 of each row set: their scales
+    float sc[2][4];
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        // row of accumulator element b: set f, row c0 (+16 for the down projection's second set) + 4q + b
+        long long row;
+        if constexpr (UP) row = (long long)i * 2 * F + (long long)f * F + c0 + 4 * q + b;
+        else {
+          int n = c0 + 16 * f + 4 * q + b;
+          if (n > a.d - 1) n = a.d - 1;
+          row = (long long)i * a.d + n;
+        }
+        sc[f][b] = a.S[g][row];
+      }
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      const int tt = tb0 + 16 * tb + r;
+      if (tt >= cnt) continue;
+      uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
+      if constexpr (UP) {
+        float v[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const float gt = acc[0][tb][b] * sc[0][b], up = acc[1][tb][b] * sc[1][b];
+          v[b] = gt / (1.f + __expf(-gt)) * up;
+        }
+        uint2 o;
+        o.x = pack_bf16x2(v[0], v[1]);
+        o.y = pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
+      } else {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+          const int col = c0 + 16 * f + 4 * q;
+          if (col < ncols) {
+            uint2 o;
+            o.x = pack_bf16x2(acc[f][tb][0] * sc[f][0], acc[f][tb][1] * sc[f][1]);
+            o.y = pack_bf16x2(acc[f][tb][2] * sc[f][2], acc[f][tb][3] * sc[f][3]);
+            *reinterpret_cast<uint2*>(crow + col) = o;
+          }
+        }
+      }
+    }
+  }
+}
+
+// codes -> fp32, for checks and tools
+__global__ void __launch_bounds__(256) fp8_decode_kernel(const uint8_t* __restrict__ q, float* __restrict__ out,
+                                                         long long n) {
+  const long long i = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i >= n) return;
+  uint32_t wv = 0;
+  for (int b = 0; b < 4; ++b)
+    if (i + b < n) wv |= (uint32_t)q[i + b] << (8 * b);
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)wv, false), hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)wv, true);
+  const float v[4] = {lo[0], lo[1], hi[0], hi[1]};
+  for (int b = 0; b < 4; ++b)
+    if (i + b < n) out[i + b] = v[b];
+}
+
+hipError_t launch_fp8_decode(const void* q, float* out, long long n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fp8_decode_kernel, dim3((unsigned)((n + 1023) / 1024)), dim3(256), 0, s,
+                     static_cast<const uint8_t*>(q), out, n);
+  return hipGetLastError();
+}
+
 hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                             hipStream_t s, int stages) {
+                             hipStream_t s, int stages, const float* const* s13, const float* const* s2) {
+  const bool w8 = s13 != nullptr;
   SkinnyArgs up;
   up.A = static_cast<const uint16_t*>(x);
   up.perm = perm;
@@ -164,6 +351,8 @@ hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* p
     up.F[g] = dn.F[g] = g < L.Ng ? L.F[g] : 0;
     up.W[g] = static_cast<const uint16_t*>(W.w13[g]);
     dn.W[g] = static_cast<const uint16_t*>(W.w2[g]);
+    up.S[g] = w8 && g < L.Ng ? s13[g] : nullptr;
+    dn.S[g] = w8 && g < L.Ng ? s2[g] : nullptr;
     up.blk_prefix[g] = nu;
     dn.blk_prefix[g] = nd;
     if (g < L.Ng) {
@@ -173,6 +362,11 @@ hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* p
   }
   up.blk_prefix[kMaxGroups] = nu;
   dn.blk_prefix[kMaxGroups] = nd;
+  if (w8) {
+    if (stages & 1) hipLaunchKernelGGL((ffn_skinny_w8_kernel<true>), dim3(nu), dim3(256), 0, s, up);
+    if (stages & 2) hipLaunchKernelGGL((ffn_skinny_w8_kernel<false>), dim3(nd), dim3(256), 0, s, dn);
+    return hipGetLastError();
+  }
   if (stages & 1) hipLaunchKernelGGL((ffn_skinny_kernel<true>), dim3(nu), dim3(256), 0, s, up);
   if (stages & 2) hipLaunchKernelGGL((ffn_skinny_kernel<false>), dim3(nd), dim3(256), 0, s, dn);
   return hipGetLastError();

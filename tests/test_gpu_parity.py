@@ -482,3 +482,69 @@ def test_router_with_and_without_workspace(T, d, Ng, N):
     (a, keep), (b, _) = outs
     assert (a["expert_idx"][keep] == b["expert_idx"][keep]).all()
     assert np.abs(a["gates"][keep] - b["gates"][keep]).max() <= 1e-6
+
+
+def test_fp8_code_conversion_matches_the_format():
+    """All 256 E4M3 codes through the hardware conversion the quantised-weight kernel uses."""
+    import paper_2604_23108_amd as M
+    codes = torch.arange(256, dtype=torch.uint8).repeat(5)[:1277].cuda()      # ragged length
+    out = torch.full((codes.numel(),), 123.0, dtype=torch.float32, device="cuda")
+    M.mohge_fp8_decode(codes, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    ref = oracle.decode_e4m3(codes.cpu().numpy())
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    ok = ~np.isnan(ref)
+    assert np.array_equal(got[ok], ref[ok])
+    assert np.array_equal(np.signbit(got[ok]), np.signbit(ref[ok]))
+
+
+@pytest.mark.parametrize("T", [1, 9, 32])
+def test_decode_with_fp8_weights(T):
+    """Decode with quantised expert weights against the oracle run on the dequantised weights
+    (scale * value(code), decoded by the oracle's own decoder)."""
+    import paper_2604_23108_amd as M
+    from gpu_harness import to_dev
+    w = WORKLOADS["decode"].replace(T=T, d=1024, d_ff=(192, 256, 384, 512), seed=600 + T)
+    inp = generate(w)
+    DeviceLayer = _dev()
+    dl = DeviceLayer(w, inp, training=False)
+    L = dl.layer
+    print(f"[fp8 weights] T={T} d={w.d}", flush=True)
+    L.forward(dl.x)                                   # routing, permutation (and the bf16 result)
+    q13, s13, q2, s2 = [], [], [], []
+    for g in range(w.n_groups):
+        c, s = M.quantize_rows_e4m3(L.w13[g]); q13.append(c); s13.append(s)
+        c, s = M.quantize_rows_e4m3(L.w2[g]); q2.append(c); s2.append(s)
+    y_perm = torch.full_like(L.y_perm, float("nan"))
+    M.mohge_expert_ffn_w8(dl.cfg, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)
+    y = torch.empty_like(L.y)
+    M.mohge_combine(dl.cfg, y_perm, L.inv_perm, L.gates, y)
+    torch.cuda.synchronize()
+    # oracle on the dequantised weights
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    wg, wu, wd = [], [], []
+    for g in range(w.n_groups):
+        F = w.d_ff[g]
+        w13 = oracle.dequantize_rows(q13[g].cpu().numpy(), s13[g].cpu().numpy())     # [N, 2F, d]
+        wg.append(f32(w13[:, :F])); wu.append(f32(w13[:, F:]))
+        wd.append(f32(oracle.dequantize_rows(q2[g].cpu().numpy(), s2[g].cpu().numpy())))
+    # (fp32 holds scale * code exactly enough: 4 significant bits times an fp32 scale)
+    r = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias)
+    keep = r["margin"] >= MARGIN
+    assert (L.expert_idx.cpu().numpy()[keep] == r["expert_idx"][keep]).all()
+    tok = np.arange(w.T, dtype=np.int32)
+    y_pairs = oracle.expert_ffn(w, inp.x.f32, wg, wu, wd, np.repeat(tok, w.k_experts), r["expert_idx"].reshape(-1))
+    want = oracle.combine(w, y_pairs, r["gates"])
+    got = y.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    err = np.abs(got[keep] - want[keep]).max()
+    assert err <= 2e-2 * np.abs(want).max(), f"error {err} vs {np.abs(want).max()}"
+    # quantisation really happened: the result differs from the bf16-weight result, by little
+    ref16 = L.y.float().cpu().numpy()
+    dq = np.abs(got - ref16).max()
+    assert 0 < dq <= 0.15 * np.abs(ref16).max()
+    # prefill sizes are refused
+    cfg_big = M.Config.from_workload(w.replace(T=64))
+    with pytest.raises(M.MohgeError, match="decode"):
+        M.mohge_expert_ffn_w8(cfg_big, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)
