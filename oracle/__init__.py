@@ -219,6 +219,38 @@ def dequantize_rows(codes, scale):
     return decode_e4m3(codes) * np.asarray(scale, np.float64)[..., None]
 
 
+def decode_e2m1(nibbles):
+    """FP4 E2M1 (the OCP microscaling element format: 1 sign, 2 exponent bits with bias 1, 1
+    mantissa bit, no infinities or NaN; exponent field 0 is subnormal) -> float64.  `nibbles` is
+    any integer array with values 0..15."""
+    c = np.asarray(nibbles).astype(np.int64)
+    sign = np.where(c & 0x8, -1.0, 1.0)
+    ex = (c >> 1) & 0x3
+    man = (c & 0x1).astype(np.float64)
+    normal = (1.0 + man / 2.0) * np.exp2((ex - 1).astype(np.float64))
+    subnormal = man / 2.0
+    return sign * np.where(ex == 0, subnormal, normal)
+
+
+def decode_e8m0(codes):
+    """E8M0 block scale of the microscaling formats: 2^(code - 127), code 255 is NaN."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.float64)
+    return np.where(c == 255, np.nan, np.exp2(c - 127.0))
+
+
+def dequantize_mxfp4(packed, scales):
+    """Weights stored in the MXFP4 microscaling format: along the last axis, blocks of 32 elements
+    share one E8M0 scale; elements are E2M1 codes packed two to a byte, the element with the even
+    index in the low four bits.  packed [..., K/2] uint8, scales [..., K/32] uint8 ->
+    [..., K] float64 = scale(block) * decode(code), exact."""
+    p = np.asarray(packed, dtype=np.uint8)
+    lo, hi = p & 0xF, p >> 4
+    codes = np.stack([lo, hi], axis=-1).reshape(*p.shape[:-1], p.shape[-1] * 2)
+    sc = np.repeat(decode_e8m0(scales), 32, axis=-1)
+    assert sc.shape == codes.shape
+    return decode_e2m1(codes) * sc
+
+
 def layer(w, inp, tokens=None):
     """Forward pass of the layer for all tokens, or for the listed token ids.
 

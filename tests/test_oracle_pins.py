@@ -428,3 +428,29 @@ def test_e4m3_decoder_against_the_format_definition_and_a_library():
     assert (np.diff(got[:0x7F]) > 0).all()
     q = oracle.dequantize_rows(np.array([[0x38, 0x40], [0xB8, 0x30]], np.uint8), np.array([2.0, 0.5], np.float32))
     assert np.array_equal(q, np.array([[2.0, 4.0], [-0.5, 0.25]]))
+
+
+def test_mxfp4_decoders_against_the_format_tables_and_a_library():
+    """MXFP4 (OCP microscaling): the eight E2M1 magnitudes the format lists, the E8M0 scale as a
+    power of two (checked against torch's float8_e8m0fnu for all codes), and a hand-packed block."""
+    import torch
+    mags = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    got = oracle.decode_e2m1(np.arange(16))
+    assert np.array_equal(got[:8], np.array(mags))
+    assert np.array_equal(got[8:], -np.array(mags)) and np.signbit(got[8])
+    codes = np.arange(256, dtype=np.uint8)
+    sc = oracle.decode_e8m0(codes)
+    assert sc[127] == 1.0 and sc[128] == 2.0 and sc[0] == 2.0 ** -127 and sc[254] == 2.0 ** 127 and np.isnan(sc[255])
+    lib = torch.from_numpy(codes.copy()).view(torch.float8_e8m0fnu).to(torch.float32).numpy().astype(np.float64)
+    assert np.array_equal(sc[:255], lib[:255]) and np.isnan(lib[255])
+    # one row of 64 elements = two blocks; element 2j in the low nibble of byte j
+    packed = np.zeros((1, 32), np.uint8)
+    packed[0, 0] = 0x72          # elements 0, 1 = codes 2 (1.0), 7 (6.0)
+    packed[0, 15] = 0xF1         # elements 30, 31 = codes 1 (0.5), 15 (-6.0)
+    packed[0, 16] = 0x0C         # elements 32, 33 = codes 12 (-2.0), 0
+    scales = np.array([[128, 125]], np.uint8)       # 2, 1/4
+    w = oracle.dequantize_mxfp4(packed, scales)
+    assert w.shape == (1, 64)
+    expect = np.zeros(64)
+    expect[0], expect[1], expect[30], expect[31], expect[32] = 2.0, 12.0, 1.0, -12.0, -0.5
+    assert np.array_equal(w[0], expect)
