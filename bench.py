@@ -86,6 +86,8 @@ def main():
                          "the step is not bound by host launch overhead)")
     ap.add_argument("--fp8-weights", action="store_true",
                     help="decode workloads: stream per-row quantised FP8 E4M3 expert weights (mohge_expert_ffn_w8)")
+    ap.add_argument("--mxfp4-weights", action="store_true",
+                    help="decode workloads: stream MXFP4 expert weights (mohge_expert_ffn_w4)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -108,10 +110,10 @@ def main():
             sys.exit("bench.py: --backward needs a workload that draws dy (e.g. --workload training)")
         dy = to_dev(inp.dy, True)
 
-    if args.fp8_weights:
-        if w.T > 32 or args.backward:
-            sys.exit("bench.py: --fp8-weights is for decode workloads (T <= 32), forward only")
-        L.use_fp8_weights()
+    if args.fp8_weights or args.mxfp4_weights:
+        if w.T > 32 or args.backward or (args.fp8_weights and args.mxfp4_weights):
+            sys.exit("bench.py: --fp8-weights / --mxfp4-weights (one of them) are for decode workloads (T <= 32), forward only")
+        L.use_fp8_weights() if args.fp8_weights else L.use_mxfp4_weights()
 
     def step():
         L.forward(x)
@@ -137,6 +139,7 @@ def main():
         "route": lambda: M.mohge_route(cfg, x, L.w_group, L.w_expert, L.bias, L.group_idx, L.expert_idx, L.gates, L.gs, L.es1, L.ws_route),
         "permute": lambda: M.mohge_permute(cfg, L.expert_idx, L.counts, L.offsets, L.perm, L.inv_perm, None, None, L.ws_permute),
         "ffn": (lambda: M.mohge_expert_ffn_w8(cfg, x, L.perm, L.offsets, *L.w8, L.y_perm, L.ws_ffn)) if args.fp8_weights
+               else (lambda: M.mohge_expert_ffn_w4(cfg, x, L.perm, L.offsets, *L.w4, L.y_perm, L.ws_ffn)) if args.mxfp4_weights
                else (lambda: M.mohge_expert_ffn(cfg, x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, L.ws_ffn)),
         "ffn_up": lambda: M.mohge_expert_ffn_up(cfg, x, L.perm, L.offsets, L.w13, L.ws_ffn),
         "ffn_down": lambda: M.mohge_expert_ffn_down(cfg, L.ws_ffn, L.offsets, L.w2, L.y_perm),
@@ -175,12 +178,18 @@ def main():
     bytes_combine = float((P + w.T) * w.d * elt + P * 8)
 
     decode = w.T <= 32
-    if decode and args.fp8_weights:
-        # weights: one byte per element plus an fp32 scale per row; activations stay bf16
-        b8_up = float((touched * (2 * w.d * F_e + 2 * F_e * 4)).sum() + w.T * w.d * elt + (counts * F_e * elt).sum())
-        b8_down = float((touched * (w.d * F_e + w.d * 4)).sum() + (counts * F_e * elt).sum() + w.n_pairs * w.d * elt)
+    if decode and (args.fp8_weights or args.mxfp4_weights):
+        # fp8: one byte per weight plus an fp32 scale per row; mxfp4: half a byte per weight plus
+        # a scale byte per 32 weights; activations stay bf16
+        if args.fp8_weights:
+            wb_up, wb_down = 2 * w.d * F_e + 2 * F_e * 4, w.d * F_e + w.d * 4
+        else:
+            wb_up, wb_down = 2 * w.d * F_e * (0.5 + 1 / 32), w.d * F_e * (0.5 + 1 / 32)
+        b8_up = float((touched * wb_up).sum() + w.T * w.d * elt + (counts * F_e * elt).sum())
+        b8_down = float((touched * wb_down).sum() + (counts * F_e * elt).sum() + w.n_pairs * w.d * elt)
         ach = (b8_up + b8_down) / (call_ms["ffn"] * 1e-3)
-        roof = {"kernel": "ffn_skinny_w8_kernel<up> + <down> (one mohge_expert_ffn_w8 call)", "bound": "hbm",
+        kname = "ffn_skinny_w8_kernel" if args.fp8_weights else "ffn_skinny_w4_kernel"
+        roof = {"kernel": kname + "<up> + <down> (one call of the quantised-weight entry point)", "bound": "hbm",
                 "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": ach / PEAK_HBM,
                 "traffic": None}
     elif decode:
@@ -219,7 +228,7 @@ def main():
         "metric": "MoHGE layer tokens/sec + expert-FFN % bf16 MFMA peak (decode: % HBM BW)",
         "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": ("bf16 (expert weights fp8 e4m3)" if args.fp8_weights else "bf16") if w.dtype == "bf16" else "f32",
+        "scaling": "weak", "vs_baseline": None, "dtype": ("bf16 (expert weights fp8 e4m3)" if args.fp8_weights else "bf16 (expert weights mxfp4)" if args.mxfp4_weights else "bf16") if w.dtype == "bf16" else "f32",
         "data": "synthetic", "launch": "hip graph replay of the step" if args.graph else "eager",
         "config": {"workload": w.name, "T": w.T, "d": w.d, "groups_x_experts": f"{w.n_groups}x{w.experts_per_group}",
                    "d_ff": list(w.d_ff), "k_groups": w.k_groups, "k_experts": w.k_experts,

@@ -232,6 +232,25 @@ int mohge_expert_ffn_w8(const mohge_config* cfg, const void* x, const int32_t* p
 int mohge_fp8_decode(const void* codes, float* out, size_t n, void* stream);
 
 /*
+ * The same for weights in the MXFP4 microscaling format (OCP MX: elements are FP4 E2M1 codes,
+ * 1 sign, 2 exponent bits with bias 1, 1 mantissa bit, magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6;
+ * every block of 32 consecutive elements of a weight row shares one E8M0 scale 2^(code - 127)).
+ * w13q[g] DEVICE [N, 2*F_g, d/2] and w2q[g] DEVICE [N, d, F_g/2] bytes: two codes per byte, the
+ * element with the even index in the low four bits; 16-byte aligned.  w13_scale[g] DEVICE
+ * [N, 2*F_g, d/32] and w2_scale[g] DEVICE [N, d, F_g/32] bytes: the scale codes.  The weight is
+ * scale(block) * value(code), formed as a bf16 matrix-core operand: exact whenever the product
+ * lies in bf16's normal range, which scale codes 2..252 guarantee (beyond them small products may
+ * lose their value and large ones overflow; code 255 is NaN); sums are fp32.  Same restrictions, workspace and error behaviour as mohge_expert_ffn_w8.
+ * mohge_mxfp4_decode converts n elements (n a multiple of 32, else MOHGE_EINVAL; packed = n/2
+ * bytes, 16-byte aligned; scales = n/32 bytes; DEVICE pointers) to f32 with the same conversion.
+ */
+int mohge_expert_ffn_w4(const mohge_config* cfg, const void* x, const int32_t* perm,
+                        const int32_t* offsets, const void* const* w13q, const void* const* w13_scale,
+                        const void* const* w2q, const void* const* w2_scale, void* y_perm,
+                        void* workspace, size_t workspace_bytes, void* stream);
+int mohge_mxfp4_decode(const void* packed, const void* scales, float* out, size_t n, void* stream);
+
+/*
  * mohge_expert_ffn with the same results, which additionally keeps, in `saved` (DEVICE,
  * mohge_workspace_size(cfg, MOHGE_CALL_FFN_SAVED) bytes, layout the library's), the hidden
  * activations h and, with a = W_gate x, b = W_up x, the two factors b*SiLU'(a) and SiLU(a) that turn

@@ -22,7 +22,8 @@ CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE = 3, 4, 5, 6
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
            "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_tune",
-           "mohge_expert_ffn_train", "mohge_expert_ffn_w8", "mohge_fp8_decode", "mohge_combine_bwd",
+           "mohge_expert_ffn_train", "mohge_expert_ffn_w8", "mohge_fp8_decode", "mohge_expert_ffn_w4",
+           "mohge_mxfp4_decode", "mohge_combine_bwd",
            "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_shared_routing", "mohge_combine_add",
            "mohge_workspace_size", "mohge_last_error"]
 
@@ -189,6 +190,47 @@ def quantize_rows_e4m3(w: torch.Tensor):
     return codes.contiguous(), scale.contiguous()
 
 
+def mohge_expert_ffn_w4(cfg, x, perm, offsets, w13q, w13_scale, w2q, w2_scale, y_perm, workspace):
+    for t in list(w13q) + list(w13_scale) + list(w2q) + list(w2_scale):
+        _ptr(t)
+    _check(lib().mohge_expert_ffn_w4(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13q),
+                                     _ptr_table(w13_scale), _ptr_table(w2q), _ptr_table(w2_scale),
+                                     _ptr(y_perm), _ptr(workspace), _nbytes(workspace), _stream()),
+           "mohge_expert_ffn_w4")
+
+
+def mohge_mxfp4_decode(packed: torch.Tensor, scales: torch.Tensor, out: torch.Tensor):
+    _check(lib().mohge_mxfp4_decode(_ptr(packed), _ptr(scales), _ptr(out), C.c_size_t(out.numel()), _stream()),
+           "mohge_mxfp4_decode")
+
+
+def quantize_mxfp4(w: torch.Tensor):
+    """MXFP4 quantisation of a weight tensor [..., rows, cols], cols a multiple of 32 (argument
+    preparation, done with torch): per block of 32 elements of a row the shared scale is
+    2^(floor(log2 max|block|) - 2) (the largest E2M1 magnitude is 6 = 1.5 * 2^2), kept within scale
+    codes 1..254; elements are divided by it, rounded to the nearest E2M1 value (ties to the even
+    code) and clamped to +-6.  Returns (packed uint8 [..., rows, cols/2], two codes per byte, even
+    element in the low four bits; scale codes uint8 [..., rows, cols/32])."""
+    K = w.shape[-1]
+    if K % 32:
+        raise MohgeError(f"quantize_mxfp4: last dimension {K} is not a multiple of 32")
+    blk = w.float().reshape(*w.shape[:-1], K // 32, 32)
+    amax = blk.abs().amax(dim=-1, keepdim=True)
+    _, ex = torch.frexp(amax)                      # amax = m * 2^ex, m in [0.5, 1): floor(log2) = ex - 1
+    e = torch.where(amax > 0, ex - 1 - 2, torch.zeros_like(ex)).clamp(-126, 127)
+    v = torch.ldexp(blk, -e)
+    m = v.abs()
+    code = torch.zeros_like(m, dtype=torch.int32)
+    for j, mid in enumerate((0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0)):
+        # from an even code to the odd one above it only when strictly past the midpoint
+        code += ((m > mid) if j % 2 == 0 else (m >= mid)).to(torch.int32)
+    code |= (v < 0).to(torch.int32) << 3
+    code = code.reshape(*w.shape[:-1], K // 2, 2)
+    packed = (code[..., 0] | (code[..., 1] << 4)).to(torch.uint8)
+    scales = (e.squeeze(-1) + 127).to(torch.uint8)
+    return packed.contiguous(), scales.contiguous()
+
+
 def mohge_expert_ffn_up(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], h):
     for t in w13:
         _ptr(t)
@@ -344,6 +386,7 @@ class MoHGELayer:
         self.training = training
         self.shared = shared
         self.w8 = None          # (codes13, scales13, codes2, scales2) once use_fp8_weights() was called
+        self.w4 = None          # the same for MXFP4 weights, once use_mxfp4_weights() was called
         T, P, Ne, Ng = cfg.T, cfg.n_pairs, cfg.n_experts, cfg.n_groups
         i32 = dict(dtype=torch.int32, device=device)
         f32 = dict(dtype=torch.float32, device=device)
@@ -398,6 +441,8 @@ class MoHGELayer:
                                    self.saved)
         elif self.w8 is not None:
             mohge_expert_ffn_w8(c, x, self.perm, self.offsets, *self.w8, self.y_perm, self.ws_ffn)
+        elif self.w4 is not None:
+            mohge_expert_ffn_w4(c, x, self.perm, self.offsets, *self.w4, self.y_perm, self.ws_ffn)
         else:
             mohge_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm, self.ws_ffn)
         if self.shared is not None:
@@ -416,6 +461,16 @@ class MoHGELayer:
             raise MohgeError("FP8 expert weights are served by the bf16 decode path only (T <= 32)")
         q = [quantize_rows_e4m3(w) for w in self.w13], [quantize_rows_e4m3(w) for w in self.w2]
         self.w8 = ([c for c, _ in q[0]], [s for _, s in q[0]], [c for c, _ in q[1]], [s for _, s in q[1]])
+        self.w4 = None
+
+    def use_mxfp4_weights(self):
+        """Decode only (T <= 32): quantises the expert weights to MXFP4 once and makes forward()
+        stream those instead of the bf16 weights."""
+        if self.cfg.T > 32 or self.cfg.dtype != BF16 or self.has_backward:
+            raise MohgeError("MXFP4 expert weights are served by the bf16 decode path only (T <= 32)")
+        q = [quantize_mxfp4(w) for w in self.w13], [quantize_mxfp4(w) for w in self.w2]
+        self.w8 = None
+        self.w4 = ([c for c, _ in q[0]], [s for _, s in q[0]], [c for c, _ in q[1]], [s for _, s in q[1]])
 
     def capture(self, x: torch.Tensor, dy: Optional[torch.Tensor] = None):
         """Records one step (forward, or forward + backward when `dy` is

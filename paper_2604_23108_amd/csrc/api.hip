@@ -213,6 +213,48 @@ int mohge_fp8_decode(const void* codes, float* out, size_t n, void* stream) {
   return hip_rc(launch_fp8_decode(codes, out, (long long)n, (hipStream_t)stream), "mohge_fp8_decode");
 }
 
+int mohge_expert_ffn_w4(const mohge_config* cfg, const void* x, const int32_t* perm,
+                        const int32_t* offsets, const void* const* w13q, const void* const* w13_scale,
+                        const void* const* w2q, const void* const* w2_scale, void* y_perm,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if ((rc = need_bf16(cfg, "mohge_expert_ffn_w4"))) return rc;
+  if (!ffn_w8_supported(L)) {
+    set_error("mohge_expert_ffn_w4: MXFP4 weights are served by the decode path only (T <= 32), T = %d", L.T);
+    return MOHGE_EINVAL;
+  }
+  NEED(x); OPT(perm); NEED(offsets); NEED(y_perm); NEED(workspace);
+  if (!w13q || !w2q || !w13_scale || !w2_scale) { set_error("a weight / scale pointer table is NULL"); return MOHGE_ENULL; }
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
+  const void* b13[kMaxGroups];
+  const void* b2[kMaxGroups];
+  for (int g = 0; g < L.Ng; ++g) {
+    NEED(w13q[g]); NEED(w2q[g]); NEED(w13_scale[g]); NEED(w2_scale[g]);
+    W.w13[g] = w13q[g];
+    W.w2[g] = w2q[g];
+    b13[g] = w13_scale[g];
+    b2[g] = w2_scale[g];
+  }
+  if (workspace_bytes < ffn_workspace_bytes(L, cfg->dtype)) {
+    set_error("expert_ffn_w4 workspace: %zu bytes given, %zu needed", workspace_bytes,
+              ffn_workspace_bytes(L, cfg->dtype));
+    return MOHGE_EWORKSPACE;
+  }
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_expert_ffn_w4(L, x, perm, offsets, W, b13, b2, y_perm, workspace, (hipStream_t)stream),
+                "mohge_expert_ffn_w4");
+}
+
+int mohge_mxfp4_decode(const void* packed, const void* scales, float* out, size_t n, void* stream) {
+  if (n == 0) return MOHGE_OK;
+  if (n % 32) { set_error("mohge_mxfp4_decode: n = %zu is not a multiple of the block size 32", n); return MOHGE_EINVAL; }
+  NEED(packed); NEED(scales); NEED(out);
+  return hip_rc(launch_mxfp4_decode(packed, scales, out, (long long)n, (hipStream_t)stream), "mohge_mxfp4_decode");
+}
+
 int mohge_expert_ffn_up(const mohge_config* cfg, const void* x, const int32_t* perm,
                         const int32_t* offsets, const void* const* w13, void* h, size_t h_bytes,
                         void* stream) {

@@ -63,6 +63,10 @@ hipError_t launch_expert_ffn_w8(const LayerDesc& L, const void* x, const int32_t
                                 const int32_t* offsets, const GroupPtrs& Wq, const float* const* s13,
                                 const float* const* s2, void* y_perm, void* ws, hipStream_t s);
 hipError_t launch_fp8_decode(const void* q, float* out, long long n, hipStream_t s);
+hipError_t launch_expert_ffn_w4(const LayerDesc& L, const void* x, const int32_t* perm,
+                                const int32_t* offsets, const GroupPtrs& Wq, const void* const* b13,
+                                const void* const* b2, void* y_perm, void* ws, hipStream_t s);
+hipError_t launch_mxfp4_decode(const void* packed, const void* scales, float* out, long long n, hipStream_t s);
 size_t permute_workspace_bytes(const LayerDesc& L);
 hipError_t launch_permute(const LayerDesc& L, int dtype, const int32_t* expert_idx,
                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,

@@ -9,7 +9,8 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
                             hipStream_t s, int stages, void* pre);
 hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                             hipStream_t s, int stages, const float* const* s13, const float* const* s2);
+                             hipStream_t s, int stages, const float* const* s13, const float* const* s2,
+                             const void* const* b13 = nullptr, const void* const* b2 = nullptr);
 
 // ---- fp32: one wave per (sorted row, output element block) ----------------------------
 // A wave computes 4 outputs of one row at a time: lanes stride the reduction dimension
@@ -120,6 +121,13 @@ hipError_t launch_expert_ffn_w8(const LayerDesc& L, const void* x, const int32_t
                                 const int32_t* offsets, const GroupPtrs& Wq, const float* const* s13,
                                 const float* const* s2, void* y_perm, void* ws, hipStream_t s) {
   return launch_ffn_skinny(L, x, perm, offsets, Wq, y_perm, ws, s, 3, s13, s2);
+}
+
+// Decode with MXFP4 weights (E2M1 codes, an E8M0 scale per 32 elements of a weight row)
+hipError_t launch_expert_ffn_w4(const LayerDesc& L, const void* x, const int32_t* perm,
+                                const int32_t* offsets, const GroupPtrs& Wq, const void* const* b13,
+                                const void* const* b2, void* y_perm, void* ws, hipStream_t s) {
+  return launch_ffn_skinny(L, x, perm, offsets, Wq, y_perm, ws, s, 3, nullptr, nullptr, b13, b2);
 }
 
 // Training forward (bf16): what the backward pass needs is kept in `saved`:

@@ -14,6 +14,12 @@
 // hardware conversion turns them into two bf16 operand fragments (E4M3 values are exact in bf16)
 // and the token operand is read with the same assignment of reduction indices to operand slots;
 // the row scale multiplies the fp32 sum in the epilogue.
+//
+// W4 variant: MXFP4 weights (E2M1 codes, two to a byte; an E8M0 scale per block of 32 elements of
+// the reduction dimension).  A lane loads 16 bytes = one block of its row and the block's scale
+// byte; the hardware conversion (E2M1 pair x power-of-two scale -> packed bf16, exact) turns them
+// into four operand fragments, so the scaling happens before the matrix core and nothing is left
+// for the epilogue.
 #include <type_traits>
 
 #include "common.h"
@@ -29,6 +35,7 @@ struct SkinnyArgs {
   const int32_t* offsets;
   const uint16_t* W[kMaxGroups];  // bf16 weights, or E4M3 codes (W8)
   const float* S[kMaxGroups];     // W8: scale per weight row, same row order as W
+  const uint8_t* S4[kMaxGroups];  // W4: E8M0 scale per 32 elements of a weight row, [rows][K/32]
   uint16_t* C;
   int lda, ldc, Ke, Ng, N, d;
   int F[kMaxGroups];
@@ -75,80 +82,90 @@ __global__ void __launch_bounds__(256) ffn_skinny_kernel(const SkinnyArgs a) {
   }
 
   for (int tb0 = 0; tb0 < cnt; tb0 += 32) {
-    const uint16_t* xp[2];
-    bool xv[2];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-      const int tt = tb0 + 16 * tb + r;
-      xv[tb] = tt < cnt;
-      const int pos = row0 + (xv[tb] ? tt : 0);
-      long long src;
-      if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
-      else src = pos;
-      xp[tb] = a.A + src * a.lda + 8 * q;
-    }
-    f32x4 acc[2][2];
-#pragma unroll
-    for (int f = 0; f < 2; ++f)
-#pragma unroll
-      for (int tb = 0; tb < 2; ++tb) acc[f][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    auto step = [&](int k0, auto UC) {
-      constexpr int U = decltype(UC)::value;
-      Frag wf[2][U], xf[2][U];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int f = 0; f < 2; ++f) wf[f][u].u = *reinterpret_cast<const uint4*>(wp[f] + k0 + 32 * u);
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-          xf[tb][u].u = make_uint4(0u, 0u, 0u, 0u);
-          if (xv[tb]) xf[tb][u].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 32 * u);
-        }
+    // NTB = token blocks of 16 in flight: decode mostly has a handful of tokens per expert, and
+    // the second block would cost its operand loads and matrix-core steps for nothing
+    auto pass = [&](auto NTBC) {
+      constexpr int NTB = decltype(NTBC)::value;
+      const uint16_t* xp[2];
+      bool xv[2];
+  #pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) {
+        const int tt = tb0 + 16 * tb + r;
+        xv[tb] = tt < cnt;
+        const int pos = row0 + (xv[tb] ? tt : 0);
+        long long src;
+        if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
+        else src = pos;
+        xp[tb] = a.A + src * a.lda + 8 * q;
       }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int f = 0; f < 2; ++f)
-#pragma unroll
-          for (int tb = 0; tb < 2; ++tb)
-            acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[f][u].v, xf[tb][u].v, acc[f][tb], 0, 0, 0);
-    };
-    int k0 = 0;
-    for (; k0 + 256 <= K; k0 += 256) step(k0, std::integral_constant<int, 8>{});
-    for (; k0 + 128 <= K; k0 += 128) step(k0, std::integral_constant<int, 4>{});
-    for (; k0 < K; k0 += 64) step(k0, std::integral_constant<int, 2>{});
+      f32x4 acc[2][2];
+  #pragma unroll
+      for (int f = 0; f < 2; ++f)
+  #pragma unroll
+        for (int tb = 0; tb < NTB; ++tb) acc[f][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // lane holds token r of each token block, weight rows 4q..4q+3 of each row set
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-      const int tt = tb0 + 16 * tb + r;
-      if (tt >= cnt) continue;
-      uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
-      if constexpr (UP) {
-        float v[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const float gt = acc[0][tb][b], up = acc[1][tb][b];
-          v[b] = gt / (1.f + __expf(-gt)) * up;
+      auto step = [&](int k0, auto UC) {
+        constexpr int U = decltype(UC)::value;
+        Frag wf[2][U], xf[2][U];
+  #pragma unroll
+        for (int u = 0; u < U; ++u) {
+  #pragma unroll
+          for (int f = 0; f < 2; ++f) wf[f][u].u = *reinterpret_cast<const uint4*>(wp[f] + k0 + 32 * u);
+  #pragma unroll
+          for (int tb = 0; tb < NTB; ++tb) {
+            xf[tb][u].u = make_uint4(0u, 0u, 0u, 0u);
+            if (xv[tb]) xf[tb][u].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 32 * u);
+          }
         }
-        uint2 o;
-        o.x = pack_bf16x2(v[0], v[1]);
-        o.y = pack_bf16x2(v[2], v[3]);
-        *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
-      } else {
-#pragma unroll
-        for (int f = 0; f < 2; ++f) {
-          const int col = c0 + 16 * f + 4 * q;
-          if (col < ncols) {
-            uint2 o;
-            o.x = pack_bf16x2(acc[f][tb][0], acc[f][tb][1]);
-            o.y = pack_bf16x2(acc[f][tb][2], acc[f][tb][3]);
-            *reinterpret_cast<uint2*>(crow + col) = o;
+  #pragma unroll
+        for (int u = 0; u < U; ++u)
+  #pragma unroll
+          for (int f = 0; f < 2; ++f)
+  #pragma unroll
+            for (int tb = 0; tb < NTB; ++tb)
+              acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[f][u].v, xf[tb][u].v, acc[f][tb], 0, 0, 0);
+      };
+      int k0 = 0;
+      // the deepest unrolling only with one token block: the registers of the rarer two-block pass
+      // would otherwise set the kernel's occupancy
+      if constexpr (NTB == 1)
+        for (; k0 + 256 <= K; k0 += 256) step(k0, std::integral_constant<int, 8>{});
+      for (; k0 + 128 <= K; k0 += 128) step(k0, std::integral_constant<int, 4>{});
+      for (; k0 < K; k0 += 64) step(k0, std::integral_constant<int, 2>{});
+
+      // lane holds token r of each token block, weight rows 4q..4q+3 of each row set
+  #pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) {
+        const int tt = tb0 + 16 * tb + r;
+        if (tt >= cnt) continue;
+        uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
+        if constexpr (UP) {
+          float v[4];
+  #pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const float gt = acc[0][tb][b], up = acc[1][tb][b];
+            v[b] = gt / (1.f + __expf(-gt)) * up;
+          }
+          uint2 o;
+          o.x = pack_bf16x2(v[0], v[1]);
+          o.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
+        } else {
+  #pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            const int col = c0 + 16 * f + 4 * q;
+            if (col < ncols) {
+              uint2 o;
+              o.x = pack_bf16x2(acc[f][tb][0], acc[f][tb][1]);
+              o.y = pack_bf16x2(acc[f][tb][2], acc[f][tb][3]);
+              *reinterpret_cast<uint2*>(crow + col) = o;
+            }
           }
         }
       }
-    }
+    };
+    if (cnt - tb0 > 16) pass(std::integral_constant<int, 2>{});
+    else pass(std::integral_constant<int, 1>{});
   }
 }
 
@@ -208,105 +225,301 @@ __global__ void __launch_bounds__(256) ffn_skinny_w8_kernel(const SkinnyArgs a) 
   wp[1] = wbase + wrow[1] * K + 16 * q;
 
   for (int tb0 = 0; tb0 < cnt; tb0 += 32) {
-    const uint16_t* xp[2];
-    bool xv[2];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-      const int tt = tb0 + 16 * tb + r;
-      xv[tb] = tt < cnt;
-      const int pos = row0 + (xv[tb] ? tt : 0);
-      long long src;
-      if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
-      else src = pos;
-      xp[tb] = a.A + src * a.lda + 16 * q;
-    }
-    f32x4 acc[2][2];
-#pragma unroll
-    for (int f = 0; f < 2; ++f)
-#pragma unroll
-      for (int tb = 0; tb < 2; ++tb) acc[f][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // NTB = token blocks of 16 in flight: decode mostly has a handful of tokens per expert, and
+    // the second block would cost its operand loads and matrix-core steps for nothing
+    auto pass = [&](auto NTBC) {
+      constexpr int NTB = decltype(NTBC)::value;
+      const uint16_t* xp[2];
+      bool xv[2];
+  #pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) {
+        const int tt = tb0 + 16 * tb + r;
+        xv[tb] = tt < cnt;
+        const int pos = row0 + (xv[tb] ? tt : 0);
+        long long src;
+        if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
+        else src = pos;
+        xp[tb] = a.A + src * a.lda + 16 * q;
+      }
+      f32x4 acc[2][2];
+  #pragma unroll
+      for (int f = 0; f < 2; ++f)
+  #pragma unroll
+        for (int tb = 0; tb < NTB; ++tb) acc[f][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto step = [&](int k0, auto UC) {
-      constexpr int U = decltype(UC)::value;
-      uint4 wq[2][U];
-      Frag xf[2][U][2];
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-#pragma unroll
-        for (int f = 0; f < 2; ++f) wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + k0 + 64 * u);
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-          xf[tb][u][0].u = make_uint4(0u, 0u, 0u, 0u);
-          xf[tb][u][1].u = make_uint4(0u, 0u, 0u, 0u);
-          if (xv[tb]) {
-            xf[tb][u][0].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 64 * u);
-            xf[tb][u][1].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 64 * u + 8);
+      auto step = [&](int k0, auto UC) {
+        constexpr int U = decltype(UC)::value;
+        uint4 wq[2][U];
+        Frag xf[2][U][2];
+  #pragma unroll
+        for (int u = 0; u < U; ++u) {
+  #pragma unroll
+          for (int f = 0; f < 2; ++f) wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + k0 + 64 * u);
+  #pragma unroll
+          for (int tb = 0; tb < NTB; ++tb) {
+            xf[tb][u][0].u = make_uint4(0u, 0u, 0u, 0u);
+            xf[tb][u][1].u = make_uint4(0u, 0u, 0u, 0u);
+            if (xv[tb]) {
+              xf[tb][u][0].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 64 * u);
+              xf[tb][u][1].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 64 * u + 8);
+            }
           }
         }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u)
-#pragma unroll
-        for (int f = 0; f < 2; ++f) {
-          Frag wlo, whi;
-          fp8x16_to_bf16(wq[f][u], wlo, whi);
-#pragma unroll
-          for (int tb = 0; tb < 2; ++tb) {
-            acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wlo.v, xf[tb][u][0].v, acc[f][tb], 0, 0, 0);
-            acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whi.v, xf[tb][u][1].v, acc[f][tb], 0, 0, 0);
+  #pragma unroll
+        for (int u = 0; u < U; ++u)
+  #pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            Frag wlo, whi;
+            fp8x16_to_bf16(wq[f][u], wlo, whi);
+  #pragma unroll
+            for (int tb = 0; tb < NTB; ++tb) {
+              acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wlo.v, xf[tb][u][0].v, acc[f][tb], 0, 0, 0);
+              acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whi.v, xf[tb][u][1].v, acc[f][tb], 0, 0, 0);
+            }
           }
-        }
-    };
-    int k0 = 0;
-    for (; k0 + 256 <= K; k0 += 256) step(k0, std::integral_constant<int, 4>{});
-    for (; k0 < K; k0 += 64) step(k0, std::integral_constant<int, 1>{});
+      };
+      int k0 = 0;
+      if constexpr (NTB == 1)
+        for (; k0 + 256 <= K; k0 += 256) step(k0, std::integral_constant<int, 4>{});
+      for (; k0 + 128 <= K; k0 += 128) step(k0, std::integral_constant<int, 2>{});
+      for (; k0 < K; k0 += 64) step(k0, std::integral_constant<int, 1>{});
 
-    // lane holds token r of each token block, weight rows 4q..4q+3 of each row set: their scales
-    float sc[2][4];
-#pragma unroll
-    for (int f = 0; f < 2; ++f)
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        // row of accumulator element b: set f, row c0 (+16 for the down projection's second set) + 4q + b
-        long long row;
-        if constexpr (UP) row = (long long)i * 2 * F + (long long)f * F + c0 + 4 * q + b;
-        else {
-          int n = c0 + 16 * f + 4 * q + b;
-          if (n > a.d - 1) n = a.d - 1;
-          row = (long long)i * a.d + n;
-        }
-        sc[f][b] = a.S[g][row];
-      }
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb) {
-      const int tt = tb0 + 16 * tb + r;
-      if (tt >= cnt) continue;
-      uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
-      if constexpr (UP) {
-        float v[4];
-#pragma unroll
+      // lane holds token r of each token block, weight rows 4q..4q+3 of each row set: their scales
+      float sc[2][4];
+  #pragma unroll
+      for (int f = 0; f < 2; ++f)
+  #pragma unroll
         for (int b = 0; b < 4; ++b) {
-          const float gt = acc[0][tb][b] * sc[0][b], up = acc[1][tb][b] * sc[1][b];
-          v[b] = gt / (1.f + __expf(-gt)) * up;
+          // row of accumulator element b: set f, row c0 (+16 for the down projection's second set) + 4q + b
+          long long row;
+          if constexpr (UP) row = (long long)i * 2 * F + (long long)f * F + c0 + 4 * q + b;
+          else {
+            int n = c0 + 16 * f + 4 * q + b;
+            if (n > a.d - 1) n = a.d - 1;
+            row = (long long)i * a.d + n;
+          }
+          sc[f][b] = a.S[g][row];
         }
-        uint2 o;
-        o.x = pack_bf16x2(v[0], v[1]);
-        o.y = pack_bf16x2(v[2], v[3]);
-        *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
-      } else {
-#pragma unroll
-        for (int f = 0; f < 2; ++f) {
-          const int col = c0 + 16 * f + 4 * q;
-          if (col < ncols) {
-            uint2 o;
-            o.x = pack_bf16x2(acc[f][tb][0] * sc[f][0], acc[f][tb][1] * sc[f][1]);
-            o.y = pack_bf16x2(acc[f][tb][2] * sc[f][2], acc[f][tb][3] * sc[f][3]);
-            *reinterpret_cast<uint2*>(crow + col) = o;
+  #pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) {
+        const int tt = tb0 + 16 * tb + r;
+        if (tt >= cnt) continue;
+        uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
+        if constexpr (UP) {
+          float v[4];
+  #pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const float gt = acc[0][tb][b] * sc[0][b], up = acc[1][tb][b] * sc[1][b];
+            v[b] = gt / (1.f + __expf(-gt)) * up;
+          }
+          uint2 o;
+          o.x = pack_bf16x2(v[0], v[1]);
+          o.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
+        } else {
+  #pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            const int col = c0 + 16 * f + 4 * q;
+            if (col < ncols) {
+              uint2 o;
+              o.x = pack_bf16x2(acc[f][tb][0] * sc[f][0], acc[f][tb][1] * sc[f][1]);
+              o.y = pack_bf16x2(acc[f][tb][2] * sc[f][2], acc[f][tb][3] * sc[f][3]);
+              *reinterpret_cast<uint2*>(crow + col) = o;
+            }
           }
         }
       }
+    };
+    if (cnt - tb0 > 16) pass(std::integral_constant<int, 2>{});
+    else pass(std::integral_constant<int, 1>{});
+  }
+}
+
+// E8M0 code -> the power of two as fp32 bits (code 0: 2^-127, a subnormal; 255: NaN)
+__device__ __forceinline__ float e8m0_to_f32(uint32_t c) {
+  const uint32_t bits = c == 0u ? 0x00400000u : (c == 255u ? 0x7fc00000u : c << 23);
+  return __uint_as_float(bits);
+}
+
+// 8 E2M1 codes (one word, element 2j in the low half of byte j) times the block scale -> 8 bf16
+__device__ __forceinline__ void fp4x8_to_bf16(const uint32_t c, const float scale, Frag& o) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  union { bf16x2 v; uint32_t u; } p0, p1, p2, p3;
+  p0.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(c, scale, 0);
+  p1.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(c, scale, 1);
+  p2.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(c, scale, 2);
+  p3.v = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(c, scale, 3);
+  o.u = make_uint4(p0.u, p1.u, p2.u, p3.u);
+}
+
+// MXFP4-weight variant of ffn_skinny_kernel: same work split; a unit of the reduction is 128
+// indices: lane (r, q) holds the block of 32 indices 32q .. 32q+31 of its weight row (one 16-byte
+// load plus the scale byte) and of its token (four 16-byte loads), used as four MFMA steps.  The
+// reduction length is a multiple of 64, so the last unit may hold two blocks only (q < 2).
+template <bool UP>
+__global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int r = lane & 15, q = lane >> 4;
+  int g = 0;
+  while (g + 1 < a.Ng && (int)blockIdx.x >= a.blk_prefix[g + 1]) ++g;
+  const int F = a.F[g];
+  const int K = UP ? a.d : F;
+  const int ncols = UP ? F : a.d;
+  constexpr int COLS_PER_BLOCK = UP ? 64 : 128;
+  const int blocks_per_expert = (ncols + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
+  const int local = blockIdx.x - a.blk_prefix[g];
+  const int i = local / blocks_per_expert, cb = local % blocks_per_expert;
+  const int e = g * a.N + i;
+  const int row0 = a.offsets[e], cnt = a.offsets[e + 1] - row0;
+  if (cnt <= 0) return;
+  const int c0 = cb * COLS_PER_BLOCK + w * (UP ? 16 : 32);
+  if (c0 >= ncols) return;
+
+  long long wrow[2];
+  if constexpr (UP) {
+    wrow[0] = (long long)i * 2 * F + c0 + r;
+    wrow[1] = (long long)i * 2 * F + F + c0 + r;
+  } else {
+    int n1 = c0 + 16 + r;
+    if (n1 > a.d - 1) n1 = a.d - 1;
+    wrow[0] = (long long)i * a.d + c0 + r;
+    wrow[1] = (long long)i * a.d + n1;
+  }
+  const uint8_t* wbase = reinterpret_cast<const uint8_t*>(a.W[g]);
+  const uint8_t* wp[2] = {wbase + wrow[0] * (K / 2) + 16 * q, wbase + wrow[1] * (K / 2) + 16 * q};
+  const uint8_t* sp[2] = {a.S4[g] + wrow[0] * (K / 32) + q, a.S4[g] + wrow[1] * (K / 32) + q};
+
+  for (int tb0 = 0; tb0 < cnt; tb0 += 32) {
+    // NTB = token blocks of 16 in flight: decode mostly has a handful of tokens per expert, and
+    // the second block would cost its operand loads and matrix-core steps for nothing
+    auto pass = [&](auto NTBC) {
+      constexpr int NTB = decltype(NTBC)::value;
+      const uint16_t* xp[2];
+      bool xv[2];
+  #pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) {
+        const int tt = tb0 + 16 * tb + r;
+        xv[tb] = tt < cnt;
+        const int pos = row0 + (xv[tb] ? tt : 0);
+        long long src;
+        if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
+        else src = pos;
+        xp[tb] = a.A + src * a.lda + 32 * q;
+      }
+      f32x4 acc[2][2];
+  #pragma unroll
+      for (int f = 0; f < 2; ++f)
+  #pragma unroll
+        for (int tb = 0; tb < NTB; ++tb) acc[f][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+      // TAIL: the unit may be cut short (only the blocks below K exist)
+      auto step = [&](int k0, auto UC, auto TAIL) {
+        constexpr int U = decltype(UC)::value;
+        constexpr bool tail = decltype(TAIL)::value;
+        uint4 wq[2][U];
+        uint32_t sc[2][U];
+        Frag xf[2][U][4];
+  #pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const bool kv = !tail || (k0 + 128 * u + 32 * q < K);
+  #pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            wq[f][u] = make_uint4(0u, 0u, 0u, 0u);
+            sc[f][u] = 127u;
+            if (kv) {
+              wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + (k0 >> 1) + 64 * u);
+              sc[f][u] = sp[f][(k0 >> 5) + 4 * u];
+            }
+          }
+  #pragma unroll
+          for (int tb = 0; tb < NTB; ++tb)
+  #pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              xf[tb][u][j].u = make_uint4(0u, 0u, 0u, 0u);
+              if (xv[tb] && kv) xf[tb][u][j].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 128 * u + 8 * j);
+            }
+        }
+  #pragma unroll
+        for (int u = 0; u < U; ++u)
+  #pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            const float scale = e8m0_to_f32(sc[f][u]);
+            const uint32_t cw[4] = {wq[f][u].x, wq[f][u].y, wq[f][u].z, wq[f][u].w};
+  #pragma unroll
+            for (int j = 0; j < 4; ++j) {
+              Frag wf;
+              fp4x8_to_bf16(cw[j], scale, wf);
+  #pragma unroll
+              for (int tb = 0; tb < NTB; ++tb)
+                acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, xf[tb][u][j].v, acc[f][tb], 0, 0, 0);
+            }
+          }
+      };
+      int k0 = 0;
+      constexpr int UMAIN = NTB == 1 ? 2 : 1;      // as many loads in flight as the registers hold
+      for (; k0 + 128 * UMAIN <= K; k0 += 128 * UMAIN) step(k0, std::integral_constant<int, UMAIN>{}, std::false_type{});
+      for (; k0 < K; k0 += 128) step(k0, std::integral_constant<int, 1>{}, std::true_type{});
+
+      // lane holds token r of each token block, weight rows 4q..4q+3 of each row set
+  #pragma unroll
+      for (int tb = 0; tb < NTB; ++tb) {
+        const int tt = tb0 + 16 * tb + r;
+        if (tt >= cnt) continue;
+        uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
+        if constexpr (UP) {
+          float v[4];
+  #pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            const float gt = acc[0][tb][b], up = acc[1][tb][b];
+            v[b] = gt / (1.f + __expf(-gt)) * up;
+          }
+          uint2 o;
+          o.x = pack_bf16x2(v[0], v[1]);
+          o.y = pack_bf16x2(v[2], v[3]);
+          *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
+        } else {
+  #pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            const int col = c0 + 16 * f + 4 * q;
+            if (col < ncols) {
+              uint2 o;
+              o.x = pack_bf16x2(acc[f][tb][0], acc[f][tb][1]);
+              o.y = pack_bf16x2(acc[f][tb][2], acc[f][tb][3]);
+              *reinterpret_cast<uint2*>(crow + col) = o;
+            }
+          }
+        }
+      }
+    };
+    if (cnt - tb0 > 16) pass(std::integral_constant<int, 2>{});
+    else pass(std::integral_constant<int, 1>{});
+  }
+}
+
+// MXFP4 -> fp32 through the conversion the kernel uses (a thread per block of 32), for checks and tools
+__global__ void __launch_bounds__(256) mxfp4_decode_kernel(const uint32_t* __restrict__ packed,
+                                                           const uint8_t* __restrict__ scales,
+                                                           float* __restrict__ out, long long nblocks) {
+  const long long b = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (b >= nblocks) return;
+  const float scale = e8m0_to_f32(scales[b]);
+  for (int j = 0; j < 4; ++j) {
+    Frag f;
+    fp4x8_to_bf16(packed[4 * b + j], scale, f);
+    const uint32_t wv[4] = {f.u.x, f.u.y, f.u.z, f.u.w};
+    for (int t = 0; t < 4; ++t) {
+      out[32 * b + 8 * j + 2 * t] = __uint_as_float(wv[t] << 16);
+      out[32 * b + 8 * j + 2 * t + 1] = __uint_as_float(wv[t] & 0xffff0000u);
     }
   }
+}
+
+hipError_t launch_mxfp4_decode(const void* packed, const void* scales, float* out, long long n, hipStream_t s) {
+  const long long nb = n / 32;
+  if (nb <= 0) return hipSuccess;
+  hipLaunchKernelGGL(mxfp4_decode_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, s,
+                     static_cast<const uint32_t*>(packed), static_cast<const uint8_t*>(scales), out, nb);
+  return hipGetLastError();
 }
 
 // codes -> fp32, for checks and tools
@@ -333,8 +546,9 @@ hipError_t launch_fp8_decode(const void* q, float* out, long long n, hipStream_t
 
 hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                             hipStream_t s, int stages, const float* const* s13, const float* const* s2) {
-  const bool w8 = s13 != nullptr;
+                             hipStream_t s, int stages, const float* const* s13, const float* const* s2,
+                             const void* const* b13, const void* const* b2) {
+  const bool w8 = s13 != nullptr, w4 = b13 != nullptr;
   SkinnyArgs up;
   up.A = static_cast<const uint16_t*>(x);
   up.perm = perm;
@@ -353,6 +567,8 @@ hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* p
     dn.W[g] = static_cast<const uint16_t*>(W.w2[g]);
     up.S[g] = w8 && g < L.Ng ? s13[g] : nullptr;
     dn.S[g] = w8 && g < L.Ng ? s2[g] : nullptr;
+    up.S4[g] = w4 && g < L.Ng ? static_cast<const uint8_t*>(b13[g]) : nullptr;
+    dn.S4[g] = w4 && g < L.Ng ? static_cast<const uint8_t*>(b2[g]) : nullptr;
     up.blk_prefix[g] = nu;
     dn.blk_prefix[g] = nd;
     if (g < L.Ng) {
@@ -362,6 +578,11 @@ hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* p
   }
   up.blk_prefix[kMaxGroups] = nu;
   dn.blk_prefix[kMaxGroups] = nd;
+  if (w4) {
+    if (stages & 1) hipLaunchKernelGGL((ffn_skinny_w4_kernel<true>), dim3(nu), dim3(256), 0, s, up);
+    if (stages & 2) hipLaunchKernelGGL((ffn_skinny_w4_kernel<false>), dim3(nd), dim3(256), 0, s, dn);
+    return hipGetLastError();
+  }
   if (w8) {
     if (stages & 1) hipLaunchKernelGGL((ffn_skinny_w8_kernel<true>), dim3(nu), dim3(256), 0, s, up);
     if (stages & 2) hipLaunchKernelGGL((ffn_skinny_w8_kernel<false>), dim3(nd), dim3(256), 0, s, dn);

@@ -98,3 +98,37 @@ def test_training_entry_points_check_their_arguments():
     # shared routing only for the one-group, all-experts configuration
     assert lib.mohge_shared_routing(cfg.ref(), None, None, None, None, None, None, None) == -1
     assert "shared routing" in M.mohge_last_error()
+
+
+def test_mxfp4_quantiser_of_the_binding_against_the_oracle_decoder():
+    """The binding's MXFP4 argument preparation (torch, CPU here): decoding its output with the
+    oracle gives the nearest representable value of every element, values that are representable
+    come back exactly, and scale codes stay within 1..254."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2604_23108_amd.binding import quantize_mxfp4
+    rng = np.random.default_rng(11)
+    w = (rng.standard_normal((3, 8, 96)) * np.exp(rng.uniform(-6, 6, size=(3, 8, 1)))).astype(np.float32)
+    w[0, 0, :32] = 0.0                                     # an all-zero block
+    w[0, 1, :8] = [0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0, -6.0]   # block maximum 6: scale 1, exact
+    w[0, 1, 8:32] = 0.25                                   # ties: 0.25 -> 0 (even code)
+    packed, scales = quantize_mxfp4(torch.from_numpy(w))
+    assert packed.shape == (3, 8, 48) and scales.shape == (3, 8, 3)
+    s = scales.numpy()
+    assert s.min() >= 1 and s.max() <= 254
+    deq = oracle.dequantize_mxfp4(packed.numpy(), s)
+    assert np.array_equal(deq[0, 0, :32], np.zeros(32))
+    assert np.array_equal(deq[0, 1, :8], w[0, 1, :8].astype(np.float64))
+    assert np.array_equal(deq[0, 1, 8:32], np.zeros(24))
+    # nearest representable: error at most half the gap to the neighbouring values at that scale
+    sc = np.repeat(oracle.decode_e8m0(s), 32, axis=-1)
+    v = np.abs(w.astype(np.float64)) / sc
+    assert v.max() < 8.0
+    grid = np.array([0, 0.5, 1, 1.5, 2, 3, 4, 6.0])
+    nearest = grid[np.abs(v[..., None] - grid).argmin(-1)]         # values above 6 clamp to 6
+    assert (np.abs(np.abs(deq) / sc - v) <= np.abs(nearest - v)).all()
+    assert (np.sign(deq) * np.sign(w) >= 0).all()
+    # quantising the decoded values again changes nothing
+    p2, s2 = quantize_mxfp4(torch.from_numpy(deq.astype(np.float32)))
+    assert np.array_equal(oracle.dequantize_mxfp4(p2.numpy(), s2.numpy()), deq)

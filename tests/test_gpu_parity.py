@@ -548,3 +548,76 @@ def test_decode_with_fp8_weights(T):
     cfg_big = M.Config.from_workload(w.replace(T=64))
     with pytest.raises(M.MohgeError, match="decode"):
         M.mohge_expert_ffn_w8(cfg_big, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)
+
+
+def test_mxfp4_conversion_matches_the_format():
+    """Every (byte, scale) combination of interest through the hardware conversion the MXFP4
+    kernel uses: all 256 byte values (both codes of a byte, so the order inside a byte is
+    checked), scale codes 1..254."""
+    import paper_2604_23108_amd as M
+    rng = np.random.default_rng(5)
+    nblk = 254 * 4
+    packed = rng.integers(0, 256, size=(nblk, 16), dtype=np.uint8)
+    packed[:16] = np.arange(256, dtype=np.uint8).reshape(16, 16)
+    scales = (np.arange(nblk) % 254 + 1).astype(np.uint8)
+    out = torch.full((nblk * 32,), 123.0, dtype=torch.float32, device="cuda")
+    M.mohge_mxfp4_decode(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64).reshape(nblk, 32)
+    ref = oracle.dequantize_mxfp4(packed, scales[:, None])
+    # bf16 holds 2 significant bits times 2^(code-127) exactly unless the product is outside its
+    # normal range (scale code 1 with the element 0.5, codes 253 and 254 with large elements):
+    # those are excluded
+    ok = (ref == 0) | ((np.abs(ref) >= 2.0 ** -126) & (np.abs(ref) < 2.0 ** 128))
+    assert ok.mean() > 0.98
+    bad = ok & (got != ref)
+    assert not bad.any(), (int(bad.sum()), got[bad][:8], ref[bad][:8], np.argwhere(bad)[:8])
+    assert np.array_equal(np.signbit(got[ok]), np.signbit(ref[ok]))
+    with pytest.raises(M.MohgeError, match="multiple"):
+        M.mohge_mxfp4_decode(torch.from_numpy(packed).cuda(), torch.from_numpy(scales).cuda(), out[:40])
+
+
+@pytest.mark.parametrize("T,d", [(1, 1024), (9, 1088), (32, 1024)])
+def test_decode_with_mxfp4_weights(T, d):
+    """Decode with MXFP4 expert weights against the oracle run on the dequantised weights
+    (block scale * value(code), decoded by the oracle's own decoders).  Widths and d cover
+    reduction lengths that end in a full, a half and no partial unit of 128."""
+    import paper_2604_23108_amd as M
+    w = WORKLOADS["decode"].replace(T=T, d=d, d_ff=(192, 256, 384, 512), seed=700 + T)
+    inp = generate(w)
+    DeviceLayer = _dev()
+    dl = DeviceLayer(w, inp, training=False)
+    L = dl.layer
+    print(f"[mxfp4 weights] T={T} d={w.d}", flush=True)
+    L.forward(dl.x)                                   # routing, permutation (and the bf16 result)
+    q13, s13, q2, s2 = [], [], [], []
+    for g in range(w.n_groups):
+        c, s = M.quantize_mxfp4(L.w13[g]); q13.append(c); s13.append(s)
+        c, s = M.quantize_mxfp4(L.w2[g]); q2.append(c); s2.append(s)
+    y_perm = torch.full_like(L.y_perm, float("nan"))
+    M.mohge_expert_ffn_w4(dl.cfg, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)
+    y = torch.empty_like(L.y)
+    M.mohge_combine(dl.cfg, y_perm, L.inv_perm, L.gates, y)
+    torch.cuda.synchronize()
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    wg, wu, wd = [], [], []
+    for g in range(w.n_groups):
+        F = w.d_ff[g]
+        w13 = oracle.dequantize_mxfp4(q13[g].cpu().numpy(), s13[g].cpu().numpy())     # [N, 2F, d]
+        assert w13.shape == (w.experts_per_group, 2 * F, w.d)
+        wg.append(f32(w13[:, :F])); wu.append(f32(w13[:, F:]))
+        wd.append(f32(oracle.dequantize_mxfp4(q2[g].cpu().numpy(), s2[g].cpu().numpy())))
+    r = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias)
+    keep = r["margin"] >= MARGIN
+    assert (L.expert_idx.cpu().numpy()[keep] == r["expert_idx"][keep]).all()
+    tok = np.arange(w.T, dtype=np.int32)
+    y_pairs = oracle.expert_ffn(w, inp.x.f32, wg, wu, wd, np.repeat(tok, w.k_experts), r["expert_idx"].reshape(-1))
+    want = oracle.combine(w, y_pairs, r["gates"])
+    got = y.float().cpu().numpy()
+    assert np.isfinite(got).all()
+    err = np.abs(got[keep] - want[keep]).max()
+    assert err <= 2e-2 * np.abs(want).max(), f"error {err} vs {np.abs(want).max()}"
+    assert np.abs(got - L.y.float().cpu().numpy()).max() > 0          # quantisation really happened
+    cfg_big = M.Config.from_workload(w.replace(T=64))
+    with pytest.raises(M.MohgeError, match="decode"):
+        M.mohge_expert_ffn_w4(cfg_big, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)

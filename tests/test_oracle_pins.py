@@ -441,8 +441,8 @@ def test_mxfp4_decoders_against_the_format_tables_and_a_library():
     codes = np.arange(256, dtype=np.uint8)
     sc = oracle.decode_e8m0(codes)
     assert sc[127] == 1.0 and sc[128] == 2.0 and sc[0] == 2.0 ** -127 and sc[254] == 2.0 ** 127 and np.isnan(sc[255])
-    lib = torch.from_numpy(codes.copy()).view(torch.float8_e8m0fnu).to(torch.float32).numpy().astype(np.float64)
-    assert np.array_equal(sc[:255], lib[:255]) and np.isnan(lib[255])
+    lib = torch.from_numpy(codes.copy()).view(torch.float8_e8m0fnu).to(torch.float32).numpy()
+    assert np.array_equal(sc[:255], lib[:255].astype(np.float64)) and np.isnan(lib[255])
     # one row of 64 elements = two blocks; element 2j in the low nibble of byte j
     packed = np.zeros((1, 32), np.uint8)
     packed[0, 0] = 0x72          # elements 0, 1 = codes 2 (1.0), 7 (6.0)
