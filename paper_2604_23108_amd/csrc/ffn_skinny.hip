@@ -352,12 +352,31 @@ __device__ __forceinline__ void fp4x8_to_bf16(const uint32_t c, const float scal
   o.u = make_uint4(p0.u, p1.u, p2.u, p3.u);
 }
 
-// MXFP4-weight variant of ffn_skinny_kernel: same work split; a unit of the reduction is 128
-// indices: lane (r, q) holds the block of 32 indices 32q .. 32q+31 of its weight row (one 16-byte
-// load plus the scale byte) and of its token (four 16-byte loads), used as four MFMA steps.  The
-// reduction length is a multiple of 64, so the last unit may hold two blocks only (q < 2).
+// MXFP4-weight variant of ffn_skinny_kernel: same split of the weight rows over workgroups and
+// waves.  A unit of the reduction is 128 indices: lane (r, q) holds the block of 32 indices
+// 32q .. 32q+31 of its weight row (one 16-byte load plus the scale byte), used as four MFMA steps.
+// With a quarter of the bytes per weight, keeping the memory system busy takes more loads in
+// flight per wave than the token fragments leave registers for, so here
+//  - the expert's tokens (16 per pass) are staged once per workgroup in LDS, in chunks of the
+//    reduction dimension sized to the token count (all of it for a handful of tokens), and read
+//    from there right before each MFMA; rows are padded by 16 bytes against bank conflicts and
+//    zero-filled past the reduction length, so that cut-short units need no special case;
+//  - the block scales of the workgroup's 128 weight rows are staged in LDS with the tokens (a
+//    scale byte per lane and block straight from memory is a 16-line request for 64 bytes, and
+//    those lines do not survive in the vector cache between steps);
+//  - the weights of the next step (4 units) are requested before the current one is converted
+//    and multiplied.
+// Token columns past the expert's count hold copies of its last staged token; MFMA columns are
+// independent and those outputs are never stored.
+constexpr int kStageBytes = 24064;            // token rows; with the scales 40 KB: four workgroups per CU
+constexpr int kScaleChunk = 4096;             // longest chunk of the reduction dimension
+constexpr int kScalePitch = kScaleChunk / 32 + 4;
+constexpr int kScaleBytes = 128 * kScalePitch;
+
 template <bool UP>
 __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) {
+  __shared__ uint4 xs[kStageBytes / 16];
+  __shared__ uint32_t ss[kScaleBytes / 4];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
   int g = 0;
@@ -371,128 +390,181 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
   const int i = local / blocks_per_expert, cb = local % blocks_per_expert;
   const int e = g * a.N + i;
   const int row0 = a.offsets[e], cnt = a.offsets[e + 1] - row0;
-  if (cnt <= 0) return;
+  if (cnt <= 0) return;                       // the whole workgroup
   const int c0 = cb * COLS_PER_BLOCK + w * (UP ? 16 : 32);
-  if (c0 >= ncols) return;
+  const bool active = c0 < ncols;             // idle waves still stage tokens and meet the barriers
 
-  long long wrow[2];
-  if constexpr (UP) {
-    wrow[0] = (long long)i * 2 * F + c0 + r;
-    wrow[1] = (long long)i * 2 * F + F + c0 + r;
-  } else {
-    int n1 = c0 + 16 + r;
-    if (n1 > a.d - 1) n1 = a.d - 1;
-    wrow[0] = (long long)i * a.d + c0 + r;
-    wrow[1] = (long long)i * a.d + n1;
+  long long wrow[2] = {0, 0};
+  if (active) {
+    if constexpr (UP) {
+      wrow[0] = (long long)i * 2 * F + c0 + r;
+      wrow[1] = (long long)i * 2 * F + F + c0 + r;
+    } else {
+      int n1 = c0 + 16 + r;
+      if (n1 > a.d - 1) n1 = a.d - 1;
+      wrow[0] = (long long)i * a.d + c0 + r;
+      wrow[1] = (long long)i * a.d + n1;
+    }
   }
   const uint8_t* wbase = reinterpret_cast<const uint8_t*>(a.W[g]);
   const uint8_t* wp[2] = {wbase + wrow[0] * (K / 2) + 16 * q, wbase + wrow[1] * (K / 2) + 16 * q};
-  const uint8_t* sp[2] = {a.S4[g] + wrow[0] * (K / 32) + q, a.S4[g] + wrow[1] * (K / 32) + q};
+  // rows of the staged scales: this lane's two weight rows
+  const uint8_t* const slds = reinterpret_cast<const uint8_t*>(ss);
+  const uint8_t* sp[2];
+  if constexpr (UP) {
+    sp[0] = slds + (16 * w + r) * kScalePitch + q;
+    sp[1] = slds + (64 + 16 * w + r) * kScalePitch + q;
+  } else {
+    sp[0] = slds + (32 * w + r) * kScalePitch + q;
+    sp[1] = slds + (32 * w + 16 + r) * kScalePitch + q;
+  }
 
-  for (int tb0 = 0; tb0 < cnt; tb0 += 32) {
-    // NTB = token blocks of 16 in flight: decode mostly has a handful of tokens per expert, and
-    // the second block would cost its operand loads and matrix-core steps for nothing
-    auto pass = [&](auto NTBC) {
-      constexpr int NTB = decltype(NTBC)::value;
-      const uint16_t* xp[2];
-      bool xv[2];
-  #pragma unroll
-      for (int tb = 0; tb < NTB; ++tb) {
-        const int tt = tb0 + 16 * tb + r;
-        xv[tb] = tt < cnt;
-        const int pos = row0 + (xv[tb] ? tt : 0);
-        long long src;
-        if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
-        else src = pos;
-        xp[tb] = a.A + src * a.lda + 32 * q;
-      }
-      f32x4 acc[2][2];
-  #pragma unroll
-      for (int f = 0; f < 2; ++f)
-  #pragma unroll
-        for (int tb = 0; tb < NTB; ++tb) acc[f][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  constexpr int U = 4;                        // units per step
+  const int Kp = (K + 127) & ~127;            // staged length: zero-filled past K
+  unsigned char* const lds = reinterpret_cast<unsigned char*>(xs);
 
-      // TAIL: the unit may be cut short (only the blocks below K exist)
-      auto step = [&](int k0, auto UC, auto TAIL) {
-        constexpr int U = decltype(UC)::value;
-        constexpr bool tail = decltype(TAIL)::value;
-        uint4 wq[2][U];
-        uint32_t sc[2][U];
-        Frag xf[2][U][4];
-  #pragma unroll
-        for (int u = 0; u < U; ++u) {
-          const bool kv = !tail || (k0 + 128 * u + 32 * q < K);
-  #pragma unroll
-          for (int f = 0; f < 2; ++f) {
-            wq[f][u] = make_uint4(0u, 0u, 0u, 0u);
-            sc[f][u] = 127u;
-            if (kv) {
-              wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + (k0 >> 1) + 64 * u);
-              sc[f][u] = sp[f][(k0 >> 5) + 4 * u];
-            }
-          }
-  #pragma unroll
-          for (int tb = 0; tb < NTB; ++tb)
-  #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              xf[tb][u][j].u = make_uint4(0u, 0u, 0u, 0u);
-              if (xv[tb] && kv) xf[tb][u][j].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 128 * u + 8 * j);
-            }
-        }
-  #pragma unroll
-        for (int u = 0; u < U; ++u)
-  #pragma unroll
-          for (int f = 0; f < 2; ++f) {
-            const float scale = e8m0_to_f32(sc[f][u]);
-            const uint32_t cw[4] = {wq[f][u].x, wq[f][u].y, wq[f][u].z, wq[f][u].w};
-  #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-              Frag wf;
-              fp4x8_to_bf16(cw[j], scale, wf);
-  #pragma unroll
-              for (int tb = 0; tb < NTB; ++tb)
-                acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, xf[tb][u][j].v, acc[f][tb], 0, 0, 0);
-            }
-          }
-      };
-      int k0 = 0;
-      constexpr int UMAIN = NTB == 1 ? 2 : 1;      // as many loads in flight as the registers hold
-      for (; k0 + 128 * UMAIN <= K; k0 += 128 * UMAIN) step(k0, std::integral_constant<int, UMAIN>{}, std::false_type{});
-      for (; k0 < K; k0 += 128) step(k0, std::integral_constant<int, 1>{}, std::true_type{});
+  for (int tb0 = 0; tb0 < cnt; tb0 += 16) {
+    const int ns = min(cnt - tb0, 16);        // tokens of this pass
+    // chunk of the reduction dimension whose ns rows fit the staging buffer
+    int KC = Kp < kScaleChunk ? Kp : kScaleChunk;
+    while (ns * (KC * 2 + 16) > kStageBytes) KC = ((KC >> 1) + 127) & ~127;
+    const int pitch = KC * 2 + 16;
+    const unsigned char* xrow = lds + (r < ns ? r : ns - 1) * pitch + 64 * q;
 
-      // lane holds token r of each token block, weight rows 4q..4q+3 of each row set
-  #pragma unroll
-      for (int tb = 0; tb < NTB; ++tb) {
-        const int tt = tb0 + 16 * tb + r;
-        if (tt >= cnt) continue;
-        uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
-        if constexpr (UP) {
-          float v[4];
-  #pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const float gt = acc[0][tb][b], up = acc[1][tb][b];
-            v[b] = gt / (1.f + __expf(-gt)) * up;
-          }
-          uint2 o;
-          o.x = pack_bf16x2(v[0], v[1]);
-          o.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
-        } else {
-  #pragma unroll
-          for (int f = 0; f < 2; ++f) {
-            const int col = c0 + 16 * f + 4 * q;
-            if (col < ncols) {
-              uint2 o;
-              o.x = pack_bf16x2(acc[f][tb][0], acc[f][tb][1]);
-              o.y = pack_bf16x2(acc[f][tb][2], acc[f][tb][3]);
-              *reinterpret_cast<uint2*>(crow + col) = o;
-            }
-          }
+    f32x4 acc[2];
+    acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // weights of the step at k0 inside the chunk that ends at cend
+    auto load = [&](uint4 (&wq)[2][U], int k0, int cend) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int k = k0 + 128 * u;
+        const bool kv = k < cend && k + 32 * q < K;
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+          wq[f][u] = make_uint4(0u, 0u, 0u, 0u);
+          if (kv) wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + (k >> 1));
         }
       }
     };
-    if (cnt - tb0 > 16) pass(std::integral_constant<int, 2>{});
-    else pass(std::integral_constant<int, 1>{});
+
+    uint4 wq[2][U];
+    int k0 = 0, cend = min(KC, Kp);
+    if (active) load(wq, k0, cend);
+
+    for (int kc = 0; kc < Kp; kc += KC) {
+      const int klen = min(KC, Kp - kc);
+      __syncthreads();                        // the previous chunk (or pass) has been consumed
+      const int ppr = klen >> 3;              // 16-byte pieces per row
+      for (int rr = 0; rr < ns; ++rr) {
+        const int pos = row0 + tb0 + rr;
+        long long src;
+        if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
+        else src = pos;
+        const uint16_t* xsrc = a.A + src * a.lda + kc;
+        for (int c = threadIdx.x; c < ppr; c += 256) {
+          uint4 v = make_uint4(0u, 0u, 0u, 0u);
+          if (kc + 8 * c < K) v = *reinterpret_cast<const uint4*>(xsrc + 8 * c);
+          *reinterpret_cast<uint4*>(lds + rr * pitch + 16 * c) = v;
+        }
+      }
+      // block scales of the chunk for the 128 weight rows of the workgroup (1 = code 127 past K)
+      {
+        const int nb = klen >> 5;                                  // blocks per row in the chunk
+        const int nbv = ((K < kc + klen ? K : kc + klen) - kc) >> 5;   // of which exist
+        const int spitch = K >> 5;
+        uint8_t* const sdst = reinterpret_cast<uint8_t*>(ss);
+        auto grow = [&](int lr) -> long long {
+          if constexpr (UP) return (long long)i * 2 * F + (long long)(lr >> 6) * F + cb * 64 + (lr & 63);
+          else {
+            int n = cb * 128 + lr;
+            if (n > a.d - 1) n = a.d - 1;
+            return (long long)i * a.d + n;
+          }
+        };
+        if (nb == nbv && !(spitch & 3) && !((kc >> 5) & 3) && !(nb & 3)) {
+          const int nw = nb >> 2;                                  // dwords per row
+          for (int idx = threadIdx.x; idx < 128 * nw; idx += 256) {
+            const int lr = idx / nw, c = idx - lr * nw;
+            const uint32_t v = *reinterpret_cast<const uint32_t*>(a.S4[g] + grow(lr) * spitch + (kc >> 5) + 4 * c);
+            *reinterpret_cast<uint32_t*>(sdst + lr * kScalePitch + 4 * c) = v;
+          }
+        } else {
+          for (int idx = threadIdx.x; idx < 128 * nb; idx += 256) {
+            const int lr = idx / nb, c = idx - lr * nb;
+            sdst[lr * kScalePitch + c] = c < nbv ? a.S4[g][grow(lr) * spitch + (kc >> 5) + c] : (uint8_t)127;
+          }
+        }
+      }
+      __syncthreads();
+      if (!active) continue;
+      const int chunk_end = kc + klen;        // == cend of the steps of this chunk
+      while (true) {
+        // request the next step (the first of the next chunk after the last of this one)
+        const bool last = k0 + 128 * U >= chunk_end;
+        const int nk = last ? chunk_end : k0 + 128 * U;
+        const int ncend = last ? min(chunk_end + KC, Kp) : chunk_end;
+        uint4 wn[2][U];
+        load(wn, nk, ncend);                  // loads nothing once nk == Kp
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          if (k0 + 128 * u < chunk_end) {     // wave-uniform
+            const unsigned char* xu = xrow + (k0 - kc + 128 * u) * 2;
+            Frag xf[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) xf[j].u = *reinterpret_cast<const uint4*>(xu + 16 * j);
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+              const float scale = e8m0_to_f32(sp[f][(k0 - kc + 128 * u) >> 5]);
+              const uint32_t cw[4] = {wq[f][u].x, wq[f][u].y, wq[f][u].z, wq[f][u].w};
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                Frag wf;
+                fp4x8_to_bf16(cw[j], scale, wf);
+                acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, xf[j].v, acc[f], 0, 0, 0);
+              }
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+          for (int f = 0; f < 2; ++f) wq[f][u] = wn[f][u];
+        k0 = nk;
+        cend = ncend;
+        if (last) break;
+      }
+    }
+
+    // lane holds token r of the pass, weight rows 4q..4q+3 of each row set
+    const int tt = tb0 + r;
+    if (active && tt < cnt) {
+      uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
+      if constexpr (UP) {
+        float v[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          const float gt = acc[0][b], up = acc[1][b];
+          v[b] = gt / (1.f + __expf(-gt)) * up;
+        }
+        uint2 o;
+        o.x = pack_bf16x2(v[0], v[1]);
+        o.y = pack_bf16x2(v[2], v[3]);
+        *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
+      } else {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+          const int col = c0 + 16 * f + 4 * q;
+          if (col < ncols) {
+            uint2 o;
+            o.x = pack_bf16x2(acc[f][0], acc[f][1]);
+            o.y = pack_bf16x2(acc[f][2], acc[f][3]);
+            *reinterpret_cast<uint2*>(crow + col) = o;
+          }
+        }
+      }
+    }
   }
 }
 

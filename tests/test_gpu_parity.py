@@ -621,3 +621,62 @@ def test_decode_with_mxfp4_weights(T, d):
     cfg_big = M.Config.from_workload(w.replace(T=64))
     with pytest.raises(M.MohgeError, match="decode"):
         M.mohge_expert_ffn_w4(cfg_big, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)
+
+
+def test_mxfp4_decode_with_many_tokens_on_one_expert():
+    """The MXFP4 kernel stages an expert's tokens in LDS 16 at a time, in chunks of the reduction
+    dimension that shrink as the token count grows: a hand-made, heavily skewed assignment
+    (experts with 23, 17, 16, 5, 3 tokens, most with none) against the oracle."""
+    import paper_2604_23108_amd as M
+    w = WORKLOADS["decode"].replace(T=32, d=2048, d_ff=(192, 320, 512, 1024), seed=741)
+    inp = generate(w)
+    DeviceLayer = _dev()
+    dl = DeviceLayer(w, inp, training=False)
+    L = dl.layer
+    rng = np.random.default_rng(3)
+    Ne = w.n_groups * w.experts_per_group
+    eidx = np.zeros((w.T, w.k_experts), np.int32)
+    heavy = [(0, 23), (Ne - 1, 17), (17, 16), (34, 5), (50, 3)]       # (expert, tokens), slot s of token t
+    free = [[s for s in range(w.k_experts)] for _ in range(w.T)]
+    eidx[:] = -1
+    for e, n in heavy:
+        for t in rng.permutation(w.T)[:n]:
+            if free[t]:
+                eidx[t, free[t].pop(0)] = e
+    others = [e for e in range(Ne) if e not in dict(heavy)]
+    for t in range(w.T):
+        for s in free[t]:
+            eidx[t, s] = others[rng.integers(len(others))]
+    ed = torch.from_numpy(eidx).cuda()
+    M.mohge_permute(dl.cfg, ed, L.counts, L.offsets, L.perm, L.inv_perm, None, None, L.ws_permute)
+    q13, s13, q2, s2 = [], [], [], []
+    for g in range(w.n_groups):
+        c, s = M.quantize_mxfp4(L.w13[g]); q13.append(c); s13.append(s)
+        c, s = M.quantize_mxfp4(L.w2[g]); q2.append(c); s2.append(s)
+    y_perm = torch.full_like(L.y_perm, float("nan"))
+    print("[mxfp4 skewed] counts", np.bincount(eidx.reshape(-1), minlength=Ne).max(), flush=True)
+    M.mohge_expert_ffn_w4(dl.cfg, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)
+    torch.cuda.synchronize()
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    wg, wu, wd = [], [], []
+    for g in range(w.n_groups):
+        F = w.d_ff[g]
+        w13 = oracle.dequantize_mxfp4(q13[g].cpu().numpy(), s13[g].cpu().numpy())
+        wg.append(f32(w13[:, :F])); wu.append(f32(w13[:, F:]))
+        wd.append(f32(oracle.dequantize_mxfp4(q2[g].cpu().numpy(), s2[g].cpu().numpy())))
+    tok = np.arange(w.T, dtype=np.int32)
+    y_pairs = oracle.expert_ffn(w, inp.x.f32, wg, wu, wd, np.repeat(tok, w.k_experts), eidx.reshape(-1))
+    perm = L.perm.cpu().numpy()
+    got = y_perm.float().cpu().numpy()
+    want = y_pairs[perm]                               # sorted position p holds pair perm[p]
+    assert np.isfinite(got).all()
+    err = np.abs(got - want).max()
+    assert err <= 2e-2 * np.abs(want).max(), f"error {err} vs {np.abs(want).max()}"
+    # and the bf16 and FP8 kernels on the same skewed assignment
+    y16 = torch.full_like(L.y_perm, float("nan"))
+    M.mohge_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y16, L.ws_ffn)
+    torch.cuda.synchronize()
+    y_pairs16 = oracle.expert_ffn(w, inp.x.f32, [t.f32 for t in inp.w_gate], [t.f32 for t in inp.w_up],
+                                  [t.f32 for t in inp.w_down], np.repeat(tok, w.k_experts), eidx.reshape(-1))
+    err16 = np.abs(y16.float().cpu().numpy() - y_pairs16[perm]).max()
+    assert err16 <= 2e-2 * np.abs(y_pairs16).max()
