@@ -27,7 +27,9 @@ PEAK_HBM = 8.0e12           # B/s
 # that have not been profiled.
 MEASURED_TRAFFIC = {
     "mid_prefill": (308250 * 2.0 + 98620 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
-    "decode": (628760 * 2.0 + 379 * 1.0) * 1024,          # ffn_skinny_kernel<up>
+    "decode": (636950 * 2.0 + 377 * 1.0) * 1024,          # ffn_skinny_kernel<up>
+    "decode/fp8": ((317340 + 156380) * 2.0 + (363 + 1049) * 1.0) * 1024,    # ffn_skinny_w8_kernel<up> + <down>
+    "decode/mxfp4": ((169930 + 83349) * 2.0 + (354 + 1024) * 1.0) * 1024,   # ffn_skinny_w4_kernel<up> + <down>
     "training": (639010 * 2.0 + 326870 * 1.0) * 1024,     # ffn_fused_kernel<up that saves + down>
     "large_prefill_skewed": (5145300 * 2.0 + 696360 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
 }
@@ -191,7 +193,7 @@ def main():
         kname = "ffn_skinny_w8_kernel" if args.fp8_weights else "ffn_skinny_w4_kernel"
         roof = {"kernel": kname + "<up> + <down> (one call of the quantised-weight entry point)", "bound": "hbm",
                 "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": ach / PEAK_HBM,
-                "traffic": None}
+                "traffic": MEASURED_TRAFFIC.get(args.workload + ("/fp8" if args.fp8_weights else "/mxfp4"))}
     elif decode:
         ach = bytes_up / (call_ms["ffn_up"] * 1e-3)
         roof = {"kernel": "ffn_skinny_kernel<up> (one mohge_expert_ffn_up call)", "bound": "hbm",

@@ -369,12 +369,13 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
 #endif
 }
 
-// Second kernel of the split form: one workgroup per 16 tokens adds the dsplit partial logit
+// Second kernel of the split form: a workgroup takes as many tokens as it has waves (phase 2 is
+// one wave per token, and with few tokens its latency is the cost), adds the dsplit partial logit
 // sums of its tokens in index order and runs phase 2.
 __global__ void __launch_bounds__(512) route_finish_kernel(const RouteArgs a) {
   extern __shared__ __align__(16) unsigned char smem[];
-  constexpr int BT = 16;
   const int NW = blockDim.x >> 6;
+  const int BT = NW;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int t0 = blockIdx.x * BT;
   float* lg = reinterpret_cast<float*>(smem + a.region0);         // [BT][NOpad]
@@ -483,7 +484,7 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  hipLaunchKernelGGL(route_finish_kernel, dim3((L.T + 15) / 16), block, smem, s, a);
+  hipLaunchKernelGGL(route_finish_kernel, dim3((L.T + NW - 1) / NW), block, smem, s, a);
   return hipGetLastError();
 }
 
