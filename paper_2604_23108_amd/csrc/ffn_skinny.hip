@@ -368,9 +368,9 @@ __device__ __forceinline__ void fp4x8_to_bf16(const uint32_t c, const float scal
 //    and multiplied.
 // Token columns past the expert's count hold copies of its last staged token; MFMA columns are
 // independent and those outputs are never stored.
-constexpr int kStageBytes = 24064;            // token rows; with the scales 40 KB: four workgroups per CU
+constexpr int kStageBytes = 22528;            // token rows; with the scales 40 KB: four workgroups per CU
 constexpr int kScaleChunk = 4096;             // longest chunk of the reduction dimension
-constexpr int kScalePitch = kScaleChunk / 32 + 4;
+constexpr int kScalePitch = kScaleChunk / 32 + 16;   // 16-byte aligned rows, 36 dwords apart: no bank conflicts
 constexpr int kScaleBytes = 128 * kScalePitch;
 
 template <bool UP>
@@ -455,46 +455,104 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
 
     for (int kc = 0; kc < Kp; kc += KC) {
       const int klen = min(KC, Kp - kc);
-      __syncthreads();                        // the previous chunk (or pass) has been consumed
-      const int ppr = klen >> 3;              // 16-byte pieces per row
-      for (int rr = 0; rr < ns; ++rr) {
-        const int pos = row0 + tb0 + rr;
-        long long src;
-        if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
-        else src = pos;
-        const uint16_t* xsrc = a.A + src * a.lda + kc;
-        for (int c = threadIdx.x; c < ppr; c += 256) {
-          uint4 v = make_uint4(0u, 0u, 0u, 0u);
-          if (kc + 8 * c < K) v = *reinterpret_cast<const uint4*>(xsrc + 8 * c);
-          *reinterpret_cast<uint4*>(lds + rr * pitch + 16 * c) = v;
+      // Staging: every global load is issued before the first LDS store, so that a chunk costs
+      // about one memory latency; the barrier that protects the previous chunk's readers sits
+      // between the loads and the stores.
+      const int ppr = klen >> 3;              // 16-byte pieces per token row
+      const int npieces = ns * ppr;           // <= kStageBytes / 16 <= 6 * 256 by the choice of KC
+      uint4 tv[6];
+#pragma unroll
+      for (int it = 0; it < 6; ++it) {
+        const int idx = threadIdx.x + 256 * it;
+        tv[it] = make_uint4(0u, 0u, 0u, 0u);
+        if (idx < npieces) {
+          const int rr = idx / ppr, c = idx - rr * ppr;
+          if (kc + 8 * c < K) {
+            const int pos = row0 + tb0 + rr;
+            long long src;
+            if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
+            else src = pos;
+            tv[it] = *reinterpret_cast<const uint4*>(a.A + src * a.lda + kc + 8 * c);
+          }
         }
       }
-      // block scales of the chunk for the 128 weight rows of the workgroup (1 = code 127 past K)
-      {
-        const int nb = klen >> 5;                                  // blocks per row in the chunk
-        const int nbv = ((K < kc + klen ? K : kc + klen) - kc) >> 5;   // of which exist
-        const int spitch = K >> 5;
-        uint8_t* const sdst = reinterpret_cast<uint8_t*>(ss);
-        auto grow = [&](int lr) -> long long {
-          if constexpr (UP) return (long long)i * 2 * F + (long long)(lr >> 6) * F + cb * 64 + (lr & 63);
-          else {
-            int n = cb * 128 + lr;
-            if (n > a.d - 1) n = a.d - 1;
-            return (long long)i * a.d + n;
+      // block scales of the chunk for the 128 weight rows of the workgroup (code 127 = 1 past K)
+      const int nb = klen >> 5;                                  // blocks per row in the chunk
+      const int nbv = ((K < kc + klen ? K : kc + klen) - kc) >> 5;   // of which exist
+      const int spitch = K >> 5;
+      uint8_t* const sdst = reinterpret_cast<uint8_t*>(ss);
+      auto grow = [&](int lr) -> long long {
+        if constexpr (UP) return (long long)i * 2 * F + (long long)(lr >> 6) * F + cb * 64 + (lr & 63);
+        else {
+          int n = cb * 128 + lr;
+          if (n > a.d - 1) n = a.d - 1;
+          return (long long)i * a.d + n;
+        }
+      };
+      const uint8_t* const sbase = a.S4[g] + (kc >> 5);
+      // widest aligned access the shape allows: 16 bytes, 4 bytes, else bytes
+      const int sw = nb != nbv ? 1
+                     : (!(spitch & 15) && !((kc >> 5) & 15) && !(nb & 15)) ? 16
+                     : (!(spitch & 3) && !((kc >> 5) & 3) && !(nb & 3)) ? 4 : 1;
+      uint32_t sv[16];                        // 4 x 16 bytes or 16 x 4 bytes per thread
+      if (sw == 16) {
+        const int nq = nb >> 4;                                  // <= 8: at most 4 pieces per thread
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int idx = threadIdx.x + 256 * it;
+          uint4 v = make_uint4(0u, 0u, 0u, 0u);
+          if (idx < 128 * nq) {
+            const int lr = idx / nq, c = idx - lr * nq;
+            v = *reinterpret_cast<const uint4*>(sbase + grow(lr) * spitch + 16 * c);
           }
-        };
-        if (nb == nbv && !(spitch & 3) && !((kc >> 5) & 3) && !(nb & 3)) {
-          const int nw = nb >> 2;                                  // dwords per row
-          for (int idx = threadIdx.x; idx < 128 * nw; idx += 256) {
+          sv[4 * it] = v.x; sv[4 * it + 1] = v.y; sv[4 * it + 2] = v.z; sv[4 * it + 3] = v.w;
+        }
+      } else if (sw == 4) {
+        const int nw = nb >> 2;                                  // <= 32: at most 16 pieces per thread
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+          const int idx = threadIdx.x + 256 * it;
+          sv[it] = 0u;
+          if (idx < 128 * nw) {
             const int lr = idx / nw, c = idx - lr * nw;
-            const uint32_t v = *reinterpret_cast<const uint32_t*>(a.S4[g] + grow(lr) * spitch + (kc >> 5) + 4 * c);
-            *reinterpret_cast<uint32_t*>(sdst + lr * kScalePitch + 4 * c) = v;
+            sv[it] = *reinterpret_cast<const uint32_t*>(sbase + grow(lr) * spitch + 4 * c);
           }
-        } else {
-          for (int idx = threadIdx.x; idx < 128 * nb; idx += 256) {
-            const int lr = idx / nb, c = idx - lr * nb;
-            sdst[lr * kScalePitch + c] = c < nbv ? a.S4[g][grow(lr) * spitch + (kc >> 5) + c] : (uint8_t)127;
+        }
+      }
+      __syncthreads();                        // the previous chunk (or pass) has been consumed
+#pragma unroll
+      for (int it = 0; it < 6; ++it) {
+        const int idx = threadIdx.x + 256 * it;
+        if (idx < npieces) {
+          const int rr = idx / ppr, c = idx - rr * ppr;
+          *reinterpret_cast<uint4*>(lds + rr * pitch + 16 * c) = tv[it];
+        }
+      }
+      if (sw == 16) {
+        const int nq = nb >> 4;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int idx = threadIdx.x + 256 * it;
+          if (idx < 128 * nq) {
+            const int lr = idx / nq, c = idx - lr * nq;
+            *reinterpret_cast<uint4*>(sdst + lr * kScalePitch + 16 * c) =
+                make_uint4(sv[4 * it], sv[4 * it + 1], sv[4 * it + 2], sv[4 * it + 3]);
           }
+        }
+      } else if (sw == 4) {
+        const int nw = nb >> 2;
+#pragma unroll
+        for (int it = 0; it < 16; ++it) {
+          const int idx = threadIdx.x + 256 * it;
+          if (idx < 128 * nw) {
+            const int lr = idx / nw, c = idx - lr * nw;
+            *reinterpret_cast<uint32_t*>(sdst + lr * kScalePitch + 4 * c) = sv[it];
+          }
+        }
+      } else {
+        for (int idx = threadIdx.x; idx < 128 * nb; idx += 256) {
+          const int lr = idx / nb, c = idx - lr * nb;
+          sdst[lr * kScalePitch + c] = c < nbv ? sbase[grow(lr) * spitch + c] : (uint8_t)127;
         }
       }
       __syncthreads();
