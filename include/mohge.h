@@ -214,6 +214,22 @@ int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
  */
 
 /*
+ * mohge_expert_ffn in two steps, for callers that time or place them separately.  On the
+ * matrix-core path the call is two launches: a small kernel that turns `offsets` into the tile
+ * lists and hand-out counters (kept in the workspace), and the launch that computes both
+ * projections from them.  parts = 1 issues the first, parts = 2 the second, parts = 3 both
+ * (exactly mohge_expert_ffn).  A parts = 2 call consumes the lists: each needs a parts = 1 call
+ * with the same cfg, offsets and workspace before it, on the same stream or ordered after it;
+ * without one it writes nothing useful to y_perm (no other harm).  Arguments as for
+ * mohge_expert_ffn (all are checked in either step).  Only where the two launches exist:
+ * cfg->dtype == MOHGE_BF16, T > 32 and the fused form enabled (mohge_tune knob 2, the default);
+ * otherwise parts 1 and 2 return MOHGE_EINVAL.
+ */
+int mohge_expert_ffn_parts(const mohge_config* cfg, const void* x, const int32_t* perm,
+                           const int32_t* offsets, const void* const* w13, const void* const* w2,
+                           void* y_perm, void* workspace, size_t workspace_bytes, int parts, void* stream);
+
+/*
  * mohge_expert_ffn for decode with quantised expert weights (not in the paper: halves the bytes
  * the memory-bound decode step streams).  w13q[g] DEVICE [N, 2*F_g, d] and w2q[g] DEVICE
  * [N, d, F_g] hold FP8 E4M3 codes (the OCP 8-bit format: 1 sign, 4 exponent bits with bias 7,

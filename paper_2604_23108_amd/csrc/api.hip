@@ -164,6 +164,38 @@ int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm
                 "mohge_expert_ffn");
 }
 
+int mohge_expert_ffn_parts(const mohge_config* cfg, const void* x, const int32_t* perm,
+                           const int32_t* offsets, const void* const* w13, const void* const* w2,
+                           void* y_perm, void* workspace, size_t workspace_bytes, int parts, void* stream) {
+  if (parts == 3) return mohge_expert_ffn(cfg, x, perm, offsets, w13, w2, y_perm, workspace, workspace_bytes, stream);
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if (parts != 1 && parts != 2) { set_error("mohge_expert_ffn_parts: parts = %d (1, 2 or 3)", parts); return MOHGE_EINVAL; }
+  if (!ffn_parts_supported(L, cfg->dtype)) {
+    set_error("mohge_expert_ffn_parts: schedule and product launch are separate launches only on the fused "
+              "matrix-core path (MOHGE_BF16, T > 32, mohge_tune(2, 1))");
+    return MOHGE_EINVAL;
+  }
+  NEED(x); OPT(perm); NEED(offsets); NEED(y_perm); NEED(workspace);
+  if (!w13 || !w2) { set_error("w13 / w2 pointer table is NULL"); return MOHGE_ENULL; }
+  GroupPtrs W;
+  memset(&W, 0, sizeof(W));
+  for (int g = 0; g < L.Ng; ++g) {
+    NEED(w13[g]); NEED(w2[g]);
+    W.w13[g] = w13[g];
+    W.w2[g] = w2[g];
+  }
+  if (workspace_bytes < ffn_workspace_bytes(L, cfg->dtype)) {
+    set_error("expert_ffn workspace: %zu bytes given, %zu needed", workspace_bytes,
+              ffn_workspace_bytes(L, cfg->dtype));
+    return MOHGE_EWORKSPACE;
+  }
+  return hip_rc(launch_expert_ffn(L, cfg->dtype, x, perm, offsets, W, y_perm, workspace,
+                                  (hipStream_t)stream, 3, parts),
+                "mohge_expert_ffn_parts");
+}
+
 static int need_bf16(const mohge_config* cfg, const char* what) {
   if (cfg->dtype != MOHGE_BF16) {
     set_error("%s is implemented for dtype MOHGE_BF16 only", what);

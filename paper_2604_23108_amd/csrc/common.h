@@ -74,7 +74,8 @@ hipError_t launch_permute(const LayerDesc& L, int dtype, const int32_t* expert_i
 size_t ffn_workspace_bytes(const LayerDesc& L, int dtype);
 hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                             hipStream_t s, int stages);   // stages: bit 0 = up, bit 1 = down
+                             hipStream_t s, int stages, int parts = 3);   // stages: bit 0 = up, bit 1 = down
+bool ffn_parts_supported(const LayerDesc& L, int dtype);
 hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
                           const int32_t* inv_perm, const float* gates, const void* y_add, void* y,
                           hipStream_t s);

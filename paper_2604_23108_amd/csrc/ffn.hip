@@ -1,12 +1,13 @@
 // Expert feed-forward networks: choice of kernel family, workspace size, and the plain
 // fp32 kernels used when the layer is stored in fp32.
 #include "common.h"
+#include "tiled.h"
 
 namespace mohge {
 
 hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* perm,
                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                            hipStream_t s, int stages, void* pre);
+                            hipStream_t s, int stages, void* pre, int parts = 3);
 hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
                              hipStream_t s, int stages, const float* const* s13, const float* const* s2,
@@ -106,12 +107,18 @@ size_t ffn_workspace_bytes(const LayerDesc& L, int dtype) {
 
 hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                             hipStream_t s, int stages) {
+                             hipStream_t s, int stages, int parts) {
   if (dtype == MOHGE_F32) return launch_ffn_f32(L, x, perm, offsets, W, y_perm, ws, s, stages);
   // With at most 32 tokens no expert can receive more than 32 rows: one pass of the
   // weight-streaming kernel covers it.  Otherwise the tiled matrix-core kernel.
   if (use_skinny(L)) return launch_ffn_skinny(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr, nullptr);
-  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr);
+  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr, parts);
+}
+
+// the schedule and the product launch of the forward can be issued separately only where they
+// are two launches: the fused matrix-core path
+bool ffn_parts_supported(const LayerDesc& L, int dtype) {
+  return dtype == MOHGE_BF16 && !use_skinny(L) && fused_launches();
 }
 
 // Decode with FP8 E4M3 weights (one fp32 scale per weight row): the weight-streaming kernel only

@@ -1173,7 +1173,7 @@ hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s) {
 // SiLU(a) as rows of [P, 2*Fmax] for the backward pass.
 hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* perm,
                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                            hipStream_t s, int stages, void* pre) {
+                            hipStream_t s, int stages, void* pre, int parts) {
   unsigned char* base = static_cast<unsigned char*>(ws);
   uint16_t* H = reinterpret_cast<uint16_t*>(base + tiled_sched_bytes(L));
   TileArgs up{};
@@ -1225,11 +1225,17 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
 #ifdef MOHGE_PROBE
     if (g_probe_plain_stores) up.coherent_out = 0;      // timing experiment of the instrumented build only
 #endif
-    hipLaunchKernelGGL(ffn_schedule_kernel, dim3(2), dim3(256), 0, s, up, dn, 7);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    // parts: 1 = the tile schedule only, 2 = the product launch only (on a schedule that no
+    // launch has consumed yet), 3 = both
+    if (parts & 1) {
+      hipLaunchKernelGGL(ffn_schedule_kernel, dim3(2), dim3(256), 0, s, up, dn, 7);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+    }
+    if (!(parts & 2)) return hipSuccess;
     return pre ? launch_fused<kUpSave, kDown, true>(up, dn, s) : launch_fused<kUp, kDown, true>(up, dn, s);
   }
+  if (parts != 3) return hipErrorInvalidValue;       // (the API checks this before it gets here)
   // both schedules depend only on `offsets`: one launch builds whichever are needed
   hipLaunchKernelGGL(ffn_schedule_kernel, dim3(stages == 3 ? 2 : 1), dim3(256), 0, s, up, dn, stages);
   hipError_t e = hipGetLastError();

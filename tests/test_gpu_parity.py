@@ -680,3 +680,35 @@ def test_mxfp4_decode_with_many_tokens_on_one_expert():
                                   [t.f32 for t in inp.w_down], np.repeat(tok, w.k_experts), eidx.reshape(-1))
     err16 = np.abs(y16.float().cpu().numpy() - y_pairs16[perm]).max()
     assert err16 <= 2e-2 * np.abs(y_pairs16).max()
+
+
+def test_ffn_schedule_and_product_launch_issued_separately():
+    """mohge_expert_ffn_parts: schedule (1) then product launch (2) gives the bits of the one-call
+    form, twice in a row; the decode path, where there is one launch only, refuses parts 1 and 2."""
+    import paper_2604_23108_amd as M
+    w = WORKLOADS["mid_prefill"].replace(T=700, d=512, d_ff=(128, 256, 384), seed=811)
+    inp = generate(w)
+    DeviceLayer = _dev()
+    dl = DeviceLayer(w, inp, training=False)
+    L = dl.layer
+    L.forward(dl.x)
+    torch.cuda.synchronize()
+    ref = L.y_perm.clone()
+    for rep in range(2):
+        y_perm = torch.full_like(L.y_perm, float("nan"))
+        M.mohge_expert_ffn_parts(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y_perm, L.ws_ffn, 1)
+        M.mohge_expert_ffn_parts(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y_perm, L.ws_ffn, 2)
+        torch.cuda.synchronize()
+        assert torch.equal(y_perm.view(torch.int16), ref.view(torch.int16)), rep
+    y3 = torch.full_like(L.y_perm, float("nan"))
+    M.mohge_expert_ffn_parts(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y3, L.ws_ffn, 3)
+    torch.cuda.synchronize()
+    assert torch.equal(y3.view(torch.int16), ref.view(torch.int16))
+    with pytest.raises(M.MohgeError, match="parts"):
+        M.mohge_expert_ffn_parts(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y3, L.ws_ffn, 4)
+    wd = WORKLOADS["decode"].replace(T=8, d=512, d_ff=(128, 256, 384, 512), seed=812)
+    dd = DeviceLayer(wd, generate(wd), training=False)
+    dd.layer.forward(dd.x)
+    with pytest.raises(M.MohgeError, match="separate launches"):
+        M.mohge_expert_ffn_parts(dd.cfg, dd.x, dd.layer.perm, dd.layer.offsets, dd.layer.w13, dd.layer.w2,
+                                 dd.layer.y_perm, dd.layer.ws_ffn, 2)
