@@ -31,7 +31,7 @@ MEASURED_TRAFFIC = {
     "decode/fp8": ((317340 + 156380) * 2.0 + (363 + 1049) * 1.0) * 1024,    # ffn_skinny_w8_kernel<up> + <down>
     "decode/mxfp4": ((169930 + 83349) * 2.0 + (354 + 1024) * 1.0) * 1024,   # ffn_skinny_w4_kernel<up> + <down>
     "training": (639010 * 2.0 + 326870 * 1.0) * 1024,     # ffn_fused_kernel<up that saves + down>
-    "large_prefill_skewed": (5145300 * 2.0 + 696360 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
+    "large_prefill_skewed": (5156100 * 2.0 + 696360 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
 }
 
 
