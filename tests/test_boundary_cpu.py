@@ -132,3 +132,33 @@ def test_mxfp4_quantiser_of_the_binding_against_the_oracle_decoder():
     # quantising the decoded values again changes nothing
     p2, s2 = quantize_mxfp4(torch.from_numpy(deq.astype(np.float32)))
     assert np.array_equal(oracle.dequantize_mxfp4(p2.numpy(), s2.numpy()), deq)
+
+
+def test_quantised_and_split_entry_points_check_their_arguments():
+    """Argument checks of the decode-only quantised-weight calls and of the two-step form of
+    mohge_expert_ffn return before anything touches a GPU."""
+    lib = M.lib()
+    prefill = M.Config(T=4096, d=2048, n_groups=3, experts_per_group=8, d_ff=(512, 1024, 1536), k_groups=2, k_experts=4)
+    decode = M.Config(T=32, d=4096, n_groups=4, experts_per_group=16, d_ff=(768, 1024, 1536, 2048), k_groups=2, k_experts=4)
+    f32 = M.Config(T=16, d=128, n_groups=3, experts_per_group=4, d_ff=(64, 128, 256), k_groups=2, k_experts=2, dtype=M.F32)
+    for fn in (lib.mohge_expert_ffn_w8, lib.mohge_expert_ffn_w4):
+        assert fn(prefill.ref(), *([None] * 9), 0, None) == -1          # prefill sizes: refused
+        assert "decode" in M.mohge_last_error()
+        assert fn(f32.ref(), *([None] * 9), 0, None) == -1              # fp32 activations: refused
+        assert "MOHGE_BF16" in M.mohge_last_error()
+        assert fn(decode.ref(), *([None] * 9), 0, None) == -2           # NULL arguments
+        assert "NULL" in M.mohge_last_error()
+    assert lib.mohge_fp8_decode(None, None, 0, None) == 0                # nothing to do
+    assert lib.mohge_fp8_decode(None, None, 8, None) == -2
+    assert lib.mohge_mxfp4_decode(None, None, None, 0, None) == 0
+    assert lib.mohge_mxfp4_decode(None, None, None, 48, None) == -1      # not whole blocks of 32
+    assert "multiple" in M.mohge_last_error()
+    assert lib.mohge_mxfp4_decode(None, None, None, 64, None) == -2
+    # the two-step form exists on the fused matrix-core path only
+    import ctypes as C
+    assert lib.mohge_expert_ffn_parts(decode.ref(), *([None] * 7), 0, C.c_int(1), None) == -1
+    assert "separate launches" in M.mohge_last_error()
+    assert lib.mohge_expert_ffn_parts(prefill.ref(), *([None] * 7), 0, C.c_int(5), None) == -1
+    assert "parts" in M.mohge_last_error()
+    assert lib.mohge_expert_ffn_parts(prefill.ref(), *([None] * 7), 0, C.c_int(2), None) == -2
+    assert lib.mohge_expert_ffn_parts(prefill.ref(), *([None] * 7), 0, C.c_int(3), None) == -2
