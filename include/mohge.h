@@ -44,7 +44,8 @@ enum {
   MOHGE_ENULL = -2,       /* a required pointer is NULL                             */
   MOHGE_EALIGN = -3,      /* a device pointer is not 16-byte aligned                */
   MOHGE_EWORKSPACE = -4,  /* workspace smaller than mohge_workspace_size()          */
-  MOHGE_EHIP = -5         /* the HIP runtime reported an error at launch            */
+  MOHGE_EHIP = -5,        /* the HIP runtime reported an error at launch            */
+  MOHGE_ETIMEOUT = -6     /* mohge_fused_status: a tile gave up waiting for the tiles it depends on */
 };
 
 enum { MOHGE_SELECT_GLOBAL = 0, MOHGE_SELECT_PER_GROUP = 1 };
@@ -338,11 +339,28 @@ int mohge_route_bwd(const mohge_config* cfg, const void* x, const float* w_group
  * 0 for an invalid configuration or call id. */
 size_t mohge_workspace_size(const mohge_config* cfg, int which_call);
 
+/*
+ * Diagnostic for the launches that run two dependent tile lists at once (the fused forms of
+ * mohge_expert_ffn, mohge_expert_ffn_train and mohge_expert_ffn_bwd): a tile of the second list
+ * waits, for a bounded number of polls, until the tiles it depends on are complete; the design
+ * guarantees they are already running, and a tile that gives up all the same computes anyway and
+ * leaves a flag in the workspace.  This call SYNCHRONISES `stream`, reads the flag left by the
+ * last call of `which_call` (MOHGE_CALL_EXPERT_FFN, MOHGE_CALL_FFN_SAVED or
+ * MOHGE_CALL_EXPERT_FFN_BWD) on `workspace` (DEVICE; for MOHGE_CALL_FFN_SAVED the `saved`
+ * buffer) and returns MOHGE_OK, or MOHGE_ETIMEOUT when that call's output must not be trusted.
+ * MOHGE_OK at once where the call has no such launch for cfg (fp32, decode sizes, knob 2 = 0).
+ */
+int mohge_fused_status(const mohge_config* cfg, int which_call, const void* workspace,
+                       size_t workspace_bytes, void* stream);
+
 /* Tuning hook for benchmarks: knob 0 / 1 forces the token-tile height (64, 128, 192 or
  * 256 rows; 0 = chosen per call from the routed counts) of the up / down projection of the
  * bf16 prefill path; knob 2 = 0 runs the up and the down projection of mohge_expert_ffn /
  * mohge_expert_ffn_train as two launches instead of one fused launch (1, the default).
- * Results do not depend on any of them.  Process-wide, not thread-safe. */
+ * Knob 3 (test hook) sets the number of polls a dependent tile of a fused launch waits (0 = the
+ * default, about a second; negative = give up without looking, which makes mohge_fused_status
+ * report MOHGE_ETIMEOUT and the output unreliable).  Results do not depend on knobs 0-2.
+ * Process-wide, not thread-safe. */
 int mohge_tune(int knob, int value);
 
 /* Message of the last error on this thread ("" if none); valid until the next call. */

@@ -21,7 +21,7 @@ CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
 CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE = 3, 4, 5, 6
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
-           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_expert_ffn_parts", "mohge_tune",
+           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_expert_ffn_parts", "mohge_tune", "mohge_fused_status",
            "mohge_expert_ffn_train", "mohge_expert_ffn_w8", "mohge_fp8_decode", "mohge_expert_ffn_w4",
            "mohge_mxfp4_decode", "mohge_combine_bwd",
            "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_shared_routing", "mohge_combine_add",
@@ -162,6 +162,14 @@ def mohge_expert_ffn(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], w2: Seq
                                   _ptr_table(w2), _ptr(y_perm), _ptr(workspace),
                                   C.c_size_t(workspace.numel() * workspace.element_size()),
                                   _stream()), "mohge_expert_ffn")
+
+
+def mohge_fused_status(cfg, which_call: int, workspace) -> int:
+    """Synchronises; 0, or MOHGE_ETIMEOUT (-6) when a tile of the last fused launch gave up waiting."""
+    rc = lib().mohge_fused_status(cfg.ref(), C.c_int(which_call), _ptr(workspace), _nbytes(workspace), _stream())
+    if rc not in (0, -6):
+        _check(rc, "mohge_fused_status")
+    return rc
 
 
 def mohge_expert_ffn_parts(cfg, x, perm, offsets, w13, w2, y_perm, workspace, parts: int):

@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include "common.h"
+#include "tiled.h"
 
 namespace mohge {
 
@@ -82,6 +83,36 @@ using namespace mohge;
 extern "C" {
 
 const char* mohge_last_error(void) { return g_err; }
+
+int mohge_fused_status(const mohge_config* cfg, int which_call, const void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if (which_call != MOHGE_CALL_EXPERT_FFN && which_call != MOHGE_CALL_FFN_SAVED &&
+      which_call != MOHGE_CALL_EXPERT_FFN_BWD) {
+    set_error("mohge_fused_status: call id %d has no fused launch", which_call);
+    return MOHGE_EINVAL;
+  }
+  const long long off = fused_flag_offset(L, cfg->dtype, which_call);
+  if (off < 0 || L.T == 0) return MOHGE_OK;
+  NEED(workspace);
+  if (workspace_bytes < mohge_workspace_size(cfg, which_call)) {
+    set_error("mohge_fused_status: workspace of %zu bytes, the call uses %zu", workspace_bytes,
+              mohge_workspace_size(cfg, which_call));
+    return MOHGE_EWORKSPACE;
+  }
+  hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return hip_rc(e, "mohge_fused_status (synchronise)");
+  SchedHeader h;
+  e = hipMemcpy(&h, static_cast<const unsigned char*>(workspace) + off, sizeof(h), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_rc(e, "mohge_fused_status (copy)");
+  if (h.pad[0] != 0) {
+    set_error("a dependent tile of the fused launch gave up waiting for its row block: output unreliable");
+    return MOHGE_ETIMEOUT;
+  }
+  return MOHGE_OK;
+}
 
 int mohge_tune(int knob, int value) {
   if (tune_tiled(knob, value)) { set_error("mohge_tune: knob %d / value %d out of range", knob, value); return MOHGE_EINVAL; }

@@ -76,6 +76,9 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
                              hipStream_t s, int stages, int parts = 3);   // stages: bit 0 = up, bit 1 = down
 bool ffn_parts_supported(const LayerDesc& L, int dtype);
+// byte offset of the schedule header that carries the "gave up waiting" flag of a fused launch in
+// the workspace of call `which_call`, or -1 where the call has no fused launch
+long long fused_flag_offset(const LayerDesc& L, int dtype, int which_call);
 hipError_t launch_combine(const LayerDesc& L, int dtype, const void* y_perm,
                           const int32_t* inv_perm, const float* gates, const void* y_add, void* y,
                           hipStream_t s);

@@ -115,6 +115,18 @@ hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const
   return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr, parts);
 }
 
+size_t ffn_bwd_waiting_header_offset(const LayerDesc& L);
+
+long long fused_flag_offset(const LayerDesc& L, int dtype, int which_call) {
+  if (dtype != MOHGE_BF16 || !fused_launches()) return -1;
+  switch (which_call) {
+    case MOHGE_CALL_EXPERT_FFN: return use_skinny(L) ? -1 : (long long)tiled_waiting_header_offset(L);
+    case MOHGE_CALL_FFN_SAVED: return (long long)tiled_waiting_header_offset(L);   // training forward: tile path for every T
+    case MOHGE_CALL_EXPERT_FFN_BWD: return (long long)ffn_bwd_waiting_header_offset(L);
+    default: return -1;
+  }
+}
+
 // the schedule and the product launch of the forward can be issued separately only where they
 // are two launches: the fused matrix-core path
 bool ffn_parts_supported(const LayerDesc& L, int dtype) {

@@ -59,6 +59,8 @@ static BwdLayout bwd_layout(const LayerDesc& L) {
 }
 
 size_t ffn_bwd_workspace_bytes(const LayerDesc& L) { return bwd_layout(L).total; }
+// header of the list whose tiles wait in the fused dH / dX launch
+size_t ffn_bwd_waiting_header_offset(const LayerDesc& L) { return bwd_layout(L).sched[1]; }
 
 hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_t* perm,
                                  const int32_t* offsets, const GroupPtrs& W, const void* saved,

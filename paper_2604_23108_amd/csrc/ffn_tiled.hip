@@ -291,7 +291,7 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   // every tile is handed out by the counter, so that the tiles a waiting workgroup depends on
   // never sit with a workgroup that has not started yet)
   if (v < kXcds) a.hdr->counters[v] = fused ? 0 : a.ncu / kXcds;
-  if (v == 0) { a.hdr->tile_rows = h; a.hdr->total = total; }
+  if (v == 0) { a.hdr->tile_rows = h; a.hdr->total = total; a.hdr->pad[0] = 0; }
   // fused forward: the row-block counters start at zero (the up list's workgroup clears them)
   if (fused && (is_up(MODE) || MODE == kDgradH))
     for (int i = v; i < sh.fp[256]; i += 256) a.fam_done[i] = 0;
@@ -921,7 +921,9 @@ __global__ void __launch_bounds__(Shape<MODE>::THREADS) ffn_tile_kernel(const Ti
 // before its down tiles, and an up tile never waits for anything; a down tile whose row block
 // belongs to another XCD's range waits for tiles that were handed out there before any of
 // that XCD's down tiles.  The wait is bounded all the same (kSpinLimit polls, about a second);
-// if it ever expires the tile is computed regardless and a flag is left in the down header.
+// if it ever expires the tile is computed regardless and a flag is left in the header of the
+// waiting list, which mohge_fused_status reports.  A negative limit (test hook, mohge_tune knob
+// 3) makes every dependent tile give up without looking.
 constexpr int kSpinLimit = 1 << 22;
 
 // One phase of a fused launch: the tiles of one list in MODE.  ROLE 1: producer (every finished
@@ -979,10 +981,12 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
           const long long w0 = __builtin_amdgcn_s_memtime();
 #endif
           int polls = 0;
-          while (__hip_atomic_load(&a.fam_done[rec.fam], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < rec.need) {
-            if (++polls > kSpinLimit) { a.hdr->pad[0] = 1; break; }
-            __builtin_amdgcn_s_sleep(8);
-          }
+          if (a.spin_limit < 0) a.hdr->pad[0] = 1;
+          else
+            while (__hip_atomic_load(&a.fam_done[rec.fam], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < rec.need) {
+              if (++polls > a.spin_limit) { a.hdr->pad[0] = 1; break; }
+              __builtin_amdgcn_s_sleep(8);
+            }
 #ifdef MOHGE_PROBE
           if (a.dbg) {
             a.dbg[(size_t)blockIdx.x * 8 + 6] += __builtin_amdgcn_s_memtime() - w0;
@@ -1026,6 +1030,7 @@ __global__ void __launch_bounds__(Shape<M0>::THREADS) ffn_fused_kernel(const Til
 // host side
 // ---------------------------------------------------------------------------------------
 static int g_force_rows[2] = {0, 0};
+static int g_spin_limit = kSpinLimit;   // polls a dependent tile of a fused launch waits
 static int g_fused_forward = 1;      // 0: separate up and down launches
 #ifdef MOHGE_PROBE
 static int g_probe_plain_stores = 0;
@@ -1040,6 +1045,7 @@ extern "C" void mohge_probe_buffer(void* p) { g_dbg = static_cast<long long*>(p)
 
 int tune_tiled(int knob, int value) {
   if (knob == 2) { g_fused_forward = value != 0; return 0; }
+  if (knob == 3) { g_spin_limit = value == 0 ? kSpinLimit : value; return 0; }
   if (knob < 0 || knob > 1) return -1;
   if (value != 0 && value != 64 && value != 128 && value != 192 && value != 256) return -1;
   g_force_rows[knob] = value;
@@ -1107,7 +1113,9 @@ static hipError_t launch_stage(const TileArgs& a, hipStream_t s) {
 }
 
 template <int M0, int M1, bool DEP>
-static hipError_t launch_fused(const TileArgs& up, const TileArgs& dn, hipStream_t s) {
+static hipError_t launch_fused(const TileArgs& up, const TileArgs& dn_in, hipStream_t s) {
+  TileArgs dn = dn_in;
+  dn.spin_limit = g_spin_limit;
   constexpr size_t smem = (size_t)(kStagesA * kBM + kStagesB * kBN) * kBK * 2;
   auto kern = ffn_fused_kernel<M0, M1, DEP>;
   static bool attr_done = false;
@@ -1139,6 +1147,11 @@ hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const Ti
 }
 
 bool fused_launches() { return g_fused_forward != 0; }
+
+// byte offset, inside the workspace of the forward, of the header of the list whose tiles wait
+size_t tiled_waiting_header_offset(const LayerDesc& L) {
+  return 256 + ((size_t)max_tiles(L, true) * sizeof(TileRec) + 255) / 256 * 256;
+}
 
 // dH and dX in one launch (dX tiles wait for the dH tiles of their row block)
 hipError_t launch_dgrad_pair(const TileArgs& dh, const TileArgs& dx, hipStream_t s) {

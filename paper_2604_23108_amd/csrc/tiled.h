@@ -37,7 +37,7 @@ struct SchedHeader {
   int xcd_begin[kXcds + 1];  // tile ranges per XCD
   int counters[kXcds];       // next tile of each range not yet handed out
   int tail[kXcds];           // tiles at the end of each range whose expert continues in the next range
-  int pad[5];
+  int pad[5];                // pad[0]: set by a tile of a fused launch that gave up waiting for its row block
 };
 static_assert(sizeof(SchedHeader) <= 256, "header area");
 
@@ -58,6 +58,7 @@ struct TileArgs {
   int force_rows;             // 0 = choose, else 64/128/192/256
   // --- fused forward (up and down tiles in one launch) ------------------------------------
   int* fam_done;              // [row blocks] finished up tiles per row block (zeroed by the schedule)
+  int spin_limit;             // fused launches: polls a dependent tile waits (set by launch_fused)
   int coherent_out;           // kUp*: store H at device scope, so that a down tile running on
                               //   another XCD reads what an up tile wrote in the same launch
   // --- backward extensions -------------------------------------------------------------
@@ -93,6 +94,7 @@ hipError_t launch_tiles(int mode, const TileArgs& a, hipStream_t s);
 // Fused launches (default; mohge_tune knob 2 = 0 turns them off): dH then dX in one launch, the
 // two weight gradients in one launch.  The schedules must have been built in the same form.
 bool fused_launches();
+size_t tiled_waiting_header_offset(const LayerDesc& L);
 hipError_t launch_dgrad_pair(const TileArgs& dh, const TileArgs& dx, hipStream_t s);
 hipError_t launch_wgrad_pair(const TileArgs& w2, const TileArgs& w13, hipStream_t s);
 // Largest number of tiles a schedule of `mode` can hold for layer L (sizes the record area).

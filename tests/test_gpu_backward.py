@@ -398,3 +398,50 @@ def test_fused_backward_launches_equal_separate_launches():
                 assert torch.isfinite(a.float()).all()
     finally:
         M.mohge_tune(2, 1)
+
+
+def test_fused_status_reports_a_tile_that_gave_up_waiting():
+    """mohge_fused_status: MOHGE_OK after ordinary fused launches (inference forward, training
+    forward, backward); with the test hook that makes every dependent tile give up without
+    looking (the host forces the condition, the kernels run to their normal end) it reports
+    MOHGE_ETIMEOUT for each of them; afterwards everything is back to normal and bit-identical."""
+    import paper_2604_23108_amd as M
+    w = WORKLOADS["training"].replace(T=1500, d=512, d_ff=(128, 256, 384), seed=97)
+    inp = generate(w)
+    dl = DeviceLayer(w, inp, training=True, backward=True)
+    L = dl.layer
+    dy = to_dev(inp.dy, True)
+    calls = ((M.CALL_FFN_SAVED, lambda: L.saved), (M.CALL_EXPERT_FFN_BWD, lambda: L.ws_ffn_bwd))
+
+    def step():
+        L.forward(dl.x)
+        L.backward(dl.x, dy)
+        # the inference form on its own workspace
+        M.mohge_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, ws_inf)
+        torch.cuda.synchronize()
+
+    ws_inf = torch.empty(M.mohge_workspace_size(dl.cfg, M.CALL_EXPERT_FFN), dtype=torch.uint8, device="cuda")
+    step()
+    ref = (L.y.clone(), L.dx.clone(), [t.clone() for t in L.dw13])
+    for call, ws in calls + ((M.CALL_EXPERT_FFN, lambda: ws_inf),):
+        assert M.mohge_fused_status(dl.cfg, call, ws()) == 0, call
+    try:
+        print("[fused status] forcing every dependent tile to give up", flush=True)
+        M.mohge_tune(3, -1)
+        step()
+        for call, ws in calls + ((M.CALL_EXPERT_FFN, lambda: ws_inf),):
+            assert M.mohge_fused_status(dl.cfg, call, ws()) == -6, call
+        assert "gave up" in M.mohge_last_error()
+    finally:
+        M.mohge_tune(3, 0)
+    step()
+    for call, ws in calls + ((M.CALL_EXPERT_FFN, lambda: ws_inf),):
+        assert M.mohge_fused_status(dl.cfg, call, ws()) == 0, call
+    assert torch.equal(L.y, ref[0]) and torch.equal(L.dx, ref[1])
+    for a, b in zip(L.dw13, ref[2]):
+        assert torch.equal(a, b)
+    # calls without such a launch answer at once
+    wd = WORKLOADS["decode"].replace(T=8, d=512, d_ff=(128, 256, 384, 512), seed=98)
+    cd = M.Config.from_workload(wd)
+    assert M.lib().mohge_fused_status(cd.ref(), M.CALL_EXPERT_FFN, None, 0, None) == 0
+    assert M.lib().mohge_fused_status(dl.cfg.ref(), M.CALL_PERMUTE, None, 0, None) == -1
