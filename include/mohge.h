@@ -254,8 +254,8 @@ int mohge_fp8_decode(const void* codes, float* out, size_t n, void* stream);
  * every block of 32 consecutive elements of a weight row shares one E8M0 scale 2^(code - 127)).
  * w13q[g] DEVICE [N, 2*F_g, d/2] and w2q[g] DEVICE [N, d, F_g/2] bytes: two codes per byte, the
  * element with the even index in the low four bits; 16-byte aligned.  w13_scale[g] DEVICE
- * [N, 2*F_g, d/32] and w2_scale[g] DEVICE [N, d, F_g/32] bytes, 4-byte aligned: the scale
- * codes.  The weight is scale(block) * value(code), formed as a bf16 matrix-core operand: exact
+ * [N, 2*F_g, d/32] and w2_scale[g] DEVICE [N, d, F_g/32] bytes (16-byte aligned like every
+ * device pointer): the scale codes.  The weight is scale(block) * value(code), formed as a bf16 matrix-core operand: exact
  * whenever the product lies in bf16's normal range, which scale codes 2..252 guarantee (beyond
  * them small products may lose their value and large ones overflow; code 255 is NaN); sums are
  * fp32.  Same restrictions, workspace and error behaviour as mohge_expert_ffn_w8.
