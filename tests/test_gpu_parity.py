@@ -623,7 +623,7 @@ def test_decode_with_mxfp4_weights(T, d):
         M.mohge_expert_ffn_w4(cfg_big, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)
 
 
-def test_mxfp4_decode_with_many_tokens_on_one_expert():
+def test_decode_kernels_with_many_tokens_on_one_expert():
     """The MXFP4 kernel stages an expert's tokens in LDS 16 at a time, in chunks of the reduction
     dimension that shrink as the token count grows: a hand-made, heavily skewed assignment
     (experts with 23, 17, 16, 5, 3 tokens, most with none) against the oracle."""
@@ -680,6 +680,22 @@ def test_mxfp4_decode_with_many_tokens_on_one_expert():
                                   [t.f32 for t in inp.w_down], np.repeat(tok, w.k_experts), eidx.reshape(-1))
     err16 = np.abs(y16.float().cpu().numpy() - y_pairs16[perm]).max()
     assert err16 <= 2e-2 * np.abs(y_pairs16).max()
+    q13, s13, q2, s2 = [], [], [], []
+    for g in range(w.n_groups):
+        c, s = M.quantize_rows_e4m3(L.w13[g]); q13.append(c); s13.append(s)
+        c, s = M.quantize_rows_e4m3(L.w2[g]); q2.append(c); s2.append(s)
+    y8 = torch.full_like(L.y_perm, float("nan"))
+    M.mohge_expert_ffn_w8(dl.cfg, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y8, L.ws_ffn)
+    torch.cuda.synchronize()
+    wg, wu, wd = [], [], []
+    for g in range(w.n_groups):
+        F = w.d_ff[g]
+        w13 = oracle.dequantize_rows(q13[g].cpu().numpy(), s13[g].cpu().numpy())
+        wg.append(f32(w13[:, :F])); wu.append(f32(w13[:, F:]))
+        wd.append(f32(oracle.dequantize_rows(q2[g].cpu().numpy(), s2[g].cpu().numpy())))
+    y_pairs8 = oracle.expert_ffn(w, inp.x.f32, wg, wu, wd, np.repeat(tok, w.k_experts), eidx.reshape(-1))
+    err8 = np.abs(y8.float().cpu().numpy() - y_pairs8[perm]).max()
+    assert err8 <= 2e-2 * np.abs(y_pairs8).max()
 
 
 def test_ffn_schedule_and_product_launch_issued_separately():
