@@ -28,8 +28,8 @@ PEAK_HBM = 8.0e12           # B/s
 MEASURED_TRAFFIC = {
     "mid_prefill": (299860 * 2.0 + 98602 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
     "decode": (636950 * 2.0 + 377 * 1.0) * 1024,          # ffn_skinny_kernel<up>
-    "decode/fp8": ((317340 + 156380) * 2.0 + (363 + 1049) * 1.0) * 1024,    # ffn_skinny_w8_kernel<up> + <down>
-    "decode/mxfp4": ((169930 + 83349) * 2.0 + (354 + 1024) * 1.0) * 1024,   # ffn_skinny_w4_kernel<up> + <down>
+    "decode/fp8": ((313350 + 156510) * 2.0 + (361 + 1047) * 1.0) * 1024,    # ffn_skinny_q_kernel<up, 8> + <down, 8>
+    "decode/mxfp4": ((170060 + 83430) * 2.0 + (355 + 1025) * 1.0) * 1024,   # ffn_skinny_q_kernel<up, 4> + <down, 4>
     "training": (639010 * 2.0 + 326870 * 1.0) * 1024,     # ffn_fused_kernel<up that saves + down>
     "large_prefill_skewed": (5156100 * 2.0 + 696360 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
 }
@@ -214,8 +214,8 @@ def main():
         b8_up = float((touched * wb_up).sum() + w.T * w.d * elt + (counts * F_e * elt).sum())
         b8_down = float((touched * wb_down).sum() + (counts * F_e * elt).sum() + w.n_pairs * w.d * elt)
         ach = (b8_up + b8_down) / (call_ms["ffn"] * 1e-3)
-        kname = "ffn_skinny_w8_kernel" if args.fp8_weights else "ffn_skinny_w4_kernel"
-        roof = {"kernel": kname + "<up> + <down> (one call of the quantised-weight entry point)", "bound": "hbm",
+        kname = "ffn_skinny_q_kernel<up, %d> + <down, %d>" % ((8, 8) if args.fp8_weights else (4, 4))
+        roof = {"kernel": kname + " (one call of the quantised-weight entry point)", "bound": "hbm",
                 "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": ach / PEAK_HBM,
                 "traffic": MEASURED_TRAFFIC.get(args.workload + ("/fp8" if args.fp8_weights else "/mxfp4"))}
     elif decode:

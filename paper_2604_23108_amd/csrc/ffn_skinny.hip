@@ -9,17 +9,14 @@
 // LDS traffic; token rows come through L1/L2 (lanes past the token count load nothing).
 // Experts without tokens are skipped on the device: their workgroups exit at once.
 //
-// W8 variant: the weights are stored as FP8 E4M3 codes with one fp32 scale per weight row, which
-// halves the bytes the decode step streams.  A lane loads 16 codes (16 bytes) of its row, the
-// hardware conversion turns them into two bf16 operand fragments (E4M3 values are exact in bf16)
-// and the token operand is read with the same assignment of reduction indices to operand slots;
-// the row scale multiplies the fp32 sum in the epilogue.
-//
-// W4 variant: MXFP4 weights (E2M1 codes, two to a byte; an E8M0 scale per block of 32 elements of
-// the reduction dimension).  A lane loads 16 bytes = one block of its row and the block's scale
-// byte; the hardware conversion (E2M1 pair x power-of-two scale -> packed bf16, exact) turns them
-// into four operand fragments, so the scaling happens before the matrix core and nothing is left
-// for the epilogue.
+// Quantised weights (ffn_skinny_q_kernel): FP8 E4M3 codes with one fp32 scale per weight row, or
+// MXFP4 (E2M1 codes, two to a byte, an E8M0 scale per block of 32 elements of the reduction
+// dimension).  A lane still loads 16 contiguous bytes of its weight row: 16 FP8 codes, which the
+// hardware conversion turns into two bf16 operand fragments (E4M3 values are exact in bf16; the
+// row scale multiplies the fp32 sum in the epilogue), or one MXFP4 block, which the hardware
+// conversion (E2M1 pair x power-of-two scale -> packed bf16, exact) turns into four, so that the
+// scaling happens before the matrix core.  The token operand is read with the same assignment of
+// reduction indices to operand slots.
 #include <type_traits>
 
 #include "common.h"
@@ -186,155 +183,6 @@ __device__ __forceinline__ void fp8x16_to_bf16(const uint4 c, Frag& lo, Frag& hi
   hi.u = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
-// FP8-weight variant of ffn_skinny_kernel: same work split; a unit of the reduction is 64
-// indices: lane (r, q) holds indices 16q .. 16q+15 of its weight row (one 16-byte load) and of
-// its token (two 16-byte loads), used as two MFMA steps (16q+0..7, then 16q+8..15).
-template <bool UP>
-__global__ void __launch_bounds__(256) ffn_skinny_w8_kernel(const SkinnyArgs a) {
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int r = lane & 15, q = lane >> 4;
-  int g = 0;
-  while (g + 1 < a.Ng && (int)blockIdx.x >= a.blk_prefix[g + 1]) ++g;
-  const int F = a.F[g];
-  const int K = UP ? a.d : F;
-  const int ncols = UP ? F : a.d;
-  constexpr int COLS_PER_BLOCK = UP ? 64 : 128;
-  const int blocks_per_expert = (ncols + COLS_PER_BLOCK - 1) / COLS_PER_BLOCK;
-  const int local = blockIdx.x - a.blk_prefix[g];
-  const int i = local / blocks_per_expert, cb = local % blocks_per_expert;
-  const int e = g * a.N + i;
-  const int row0 = a.offsets[e], cnt = a.offsets[e + 1] - row0;
-  if (cnt <= 0) return;
-  const int c0 = cb * COLS_PER_BLOCK + w * (UP ? 16 : 32);
-  if (c0 >= ncols) return;
-
-  // the two weight-row sets of this wave (bytes: one code per element) and their row indices
-  const uint8_t* wbase = reinterpret_cast<const uint8_t*>(a.W[g]);
-  const uint8_t* wp[2];
-  long long wrow[2];
-  if constexpr (UP) {
-    wrow[0] = (long long)i * 2 * F + c0 + r;
-    wrow[1] = (long long)i * 2 * F + F + c0 + r;
-  } else {
-    int n1 = c0 + 16 + r;
-    if (n1 > a.d - 1) n1 = a.d - 1;
-    wrow[0] = (long long)i * a.d + c0 + r;
-    wrow[1] = (long long)i * a.d + n1;
-  }
-  wp[0] = wbase + wrow[0] * K + 16 * q;
-  wp[1] = wbase + wrow[1] * K + 16 * q;
-
-  for (int tb0 = 0; tb0 < cnt; tb0 += 32) {
-    // NTB = token blocks of 16 in flight: decode mostly has a handful of tokens per expert, and
-    // the second block would cost its operand loads and matrix-core steps for nothing
-    auto pass = [&](auto NTBC) {
-      constexpr int NTB = decltype(NTBC)::value;
-      const uint16_t* xp[2];
-      bool xv[2];
-  #pragma unroll
-      for (int tb = 0; tb < NTB; ++tb) {
-        const int tt = tb0 + 16 * tb + r;
-        xv[tb] = tt < cnt;
-        const int pos = row0 + (xv[tb] ? tt : 0);
-        long long src;
-        if constexpr (UP) src = a.perm ? (long long)(a.perm[pos] / a.Ke) : (long long)pos;
-        else src = pos;
-        xp[tb] = a.A + src * a.lda + 16 * q;
-      }
-      f32x4 acc[2][2];
-  #pragma unroll
-      for (int f = 0; f < 2; ++f)
-  #pragma unroll
-        for (int tb = 0; tb < NTB; ++tb) acc[f][tb] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-      auto step = [&](int k0, auto UC) {
-        constexpr int U = decltype(UC)::value;
-        uint4 wq[2][U];
-        Frag xf[2][U][2];
-  #pragma unroll
-        for (int u = 0; u < U; ++u) {
-  #pragma unroll
-          for (int f = 0; f < 2; ++f) wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + k0 + 64 * u);
-  #pragma unroll
-          for (int tb = 0; tb < NTB; ++tb) {
-            xf[tb][u][0].u = make_uint4(0u, 0u, 0u, 0u);
-            xf[tb][u][1].u = make_uint4(0u, 0u, 0u, 0u);
-            if (xv[tb]) {
-              xf[tb][u][0].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 64 * u);
-              xf[tb][u][1].u = *reinterpret_cast<const uint4*>(xp[tb] + k0 + 64 * u + 8);
-            }
-          }
-        }
-  #pragma unroll
-        for (int u = 0; u < U; ++u)
-  #pragma unroll
-          for (int f = 0; f < 2; ++f) {
-            Frag wlo, whi;
-            fp8x16_to_bf16(wq[f][u], wlo, whi);
-  #pragma unroll
-            for (int tb = 0; tb < NTB; ++tb) {
-              acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wlo.v, xf[tb][u][0].v, acc[f][tb], 0, 0, 0);
-              acc[f][tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whi.v, xf[tb][u][1].v, acc[f][tb], 0, 0, 0);
-            }
-          }
-      };
-      int k0 = 0;
-      if constexpr (NTB == 1)
-        for (; k0 + 256 <= K; k0 += 256) step(k0, std::integral_constant<int, 4>{});
-      for (; k0 + 128 <= K; k0 += 128) step(k0, std::integral_constant<int, 2>{});
-      for (; k0 < K; k0 += 64) step(k0, std::integral_constant<int, 1>{});
-
-      // lane holds token r of each token block, weight rows 4q..4q+3 of each row set: their scales
-      float sc[2][4];
-  #pragma unroll
-      for (int f = 0; f < 2; ++f)
-  #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          // row of accumulator element b: set f, row c0 (+16 for the down projection's second set) + 4q + b
-          long long row;
-          if constexpr (UP) row = (long long)i * 2 * F + (long long)f * F + c0 + 4 * q + b;
-          else {
-            int n = c0 + 16 * f + 4 * q + b;
-            if (n > a.d - 1) n = a.d - 1;
-            row = (long long)i * a.d + n;
-          }
-          sc[f][b] = a.S[g][row];
-        }
-  #pragma unroll
-      for (int tb = 0; tb < NTB; ++tb) {
-        const int tt = tb0 + 16 * tb + r;
-        if (tt >= cnt) continue;
-        uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
-        if constexpr (UP) {
-          float v[4];
-  #pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const float gt = acc[0][tb][b] * sc[0][b], up = acc[1][tb][b] * sc[1][b];
-            v[b] = gt / (1.f + __expf(-gt)) * up;
-          }
-          uint2 o;
-          o.x = pack_bf16x2(v[0], v[1]);
-          o.y = pack_bf16x2(v[2], v[3]);
-          *reinterpret_cast<uint2*>(crow + c0 + 4 * q) = o;
-        } else {
-  #pragma unroll
-          for (int f = 0; f < 2; ++f) {
-            const int col = c0 + 16 * f + 4 * q;
-            if (col < ncols) {
-              uint2 o;
-              o.x = pack_bf16x2(acc[f][tb][0] * sc[f][0], acc[f][tb][1] * sc[f][1]);
-              o.y = pack_bf16x2(acc[f][tb][2] * sc[f][2], acc[f][tb][3] * sc[f][3]);
-              *reinterpret_cast<uint2*>(crow + col) = o;
-            }
-          }
-        }
-      }
-    };
-    if (cnt - tb0 > 16) pass(std::integral_constant<int, 2>{});
-    else pass(std::integral_constant<int, 1>{});
-  }
-}
-
 // E8M0 code -> the power of two as fp32 bits (code 0: 2^-127, a subnormal; 255: NaN)
 __device__ __forceinline__ float e8m0_to_f32(uint32_t c) {
   const uint32_t bits = c == 0u ? 0x00400000u : (c == 255u ? 0x7fc00000u : c << 23);
@@ -352,18 +200,18 @@ __device__ __forceinline__ void fp4x8_to_bf16(const uint32_t c, const float scal
   o.u = make_uint4(p0.u, p1.u, p2.u, p3.u);
 }
 
-// MXFP4-weight variant of ffn_skinny_kernel: same split of the weight rows over workgroups and
-// waves.  A unit of the reduction is 128 indices: lane (r, q) holds the block of 32 indices
-// 32q .. 32q+31 of its weight row (one 16-byte load plus the scale byte), used as four MFMA steps.
-// With a quarter of the bytes per weight, keeping the memory system busy takes more loads in
-// flight per wave than the token fragments leave registers for, so here
+// Quantised-weight variant of ffn_skinny_kernel (BITS = 8: FP8 E4M3, BITS = 4: MXFP4): same split
+// of the weight rows over workgroups and waves.  A unit of the reduction is 64 bytes of a weight
+// row: lane (r, q) holds 16 bytes of its row, 16 (FP8) or 32 (MXFP4) consecutive indices, used as
+// two or four MFMA steps.  With fewer bytes per weight, keeping the memory system busy takes more
+// loads in flight per wave than token fragments held in registers leave room for, so here
 //  - the expert's tokens (16 per pass) are staged once per workgroup in LDS, in chunks of the
 //    reduction dimension sized to the token count (all of it for a handful of tokens), and read
 //    from there right before each MFMA; rows are padded by 16 bytes against bank conflicts and
 //    zero-filled past the reduction length, so that cut-short units need no special case;
-//  - the block scales of the workgroup's 128 weight rows are staged in LDS with the tokens (a
-//    scale byte per lane and block straight from memory is a 16-line request for 64 bytes, and
-//    those lines do not survive in the vector cache between steps);
+//  - MXFP4: the block scales of the workgroup's 128 weight rows are staged in LDS with the tokens
+//    (a scale byte per lane and block straight from memory is a 16-line request for 64 bytes,
+//    and those lines do not survive in the vector cache between steps);
 //  - the weights of the next step (4 units) are requested before the current one is converted
 //    and multiplied.
 // Token columns past the expert's count hold copies of its last staged token; MFMA columns are
@@ -373,10 +221,14 @@ constexpr int kScaleChunk = 4096;             // longest chunk of the reduction 
 constexpr int kScalePitch = kScaleChunk / 32 + 16;   // 16-byte aligned rows, 36 dwords apart: no bank conflicts
 constexpr int kScaleBytes = 128 * kScalePitch;
 
-template <bool UP>
-__global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) {
+template <bool UP, int BITS>
+__global__ void __launch_bounds__(256) ffn_skinny_q_kernel(const SkinnyArgs a) {
+  static_assert(BITS == 4 || BITS == 8, "MXFP4 or FP8 codes");
+  constexpr int UK = BITS == 4 ? 128 : 64;   // reduction indices per unit: 64 bytes of a weight row
+  constexpr int LK = UK / 4;                  // ... per lane
+  constexpr int NJ = LK / 8;                  // MFMA steps per unit
   __shared__ uint4 xs[kStageBytes / 16];
-  __shared__ uint32_t ss[kScaleBytes / 4];
+  __shared__ uint32_t ss[BITS == 4 ? kScaleBytes / 4 : 4];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int r = lane & 15, q = lane >> 4;
   int g = 0;
@@ -407,7 +259,7 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
     }
   }
   const uint8_t* wbase = reinterpret_cast<const uint8_t*>(a.W[g]);
-  const uint8_t* wp[2] = {wbase + wrow[0] * (K / 2) + 16 * q, wbase + wrow[1] * (K / 2) + 16 * q};
+  const uint8_t* wp[2] = {wbase + wrow[0] * (K * BITS / 8) + 16 * q, wbase + wrow[1] * (K * BITS / 8) + 16 * q};
   // rows of the staged scales: this lane's two weight rows
   const uint8_t* const slds = reinterpret_cast<const uint8_t*>(ss);
   const uint8_t* sp[2];
@@ -429,7 +281,7 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
     int KC = Kp < kScaleChunk ? Kp : kScaleChunk;
     while (ns * (KC * 2 + 16) > kStageBytes) KC = ((KC >> 1) + 127) & ~127;
     const int pitch = KC * 2 + 16;
-    const unsigned char* xrow = lds + (r < ns ? r : ns - 1) * pitch + 64 * q;
+    const unsigned char* xrow = lds + (r < ns ? r : ns - 1) * pitch + 2 * LK * q;
 
     f32x4 acc[2];
     acc[0] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -439,12 +291,12 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
     auto load = [&](uint4 (&wq)[2][U], int k0, int cend) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
-        const int k = k0 + 128 * u;
-        const bool kv = k < cend && k + 32 * q < K;
+        const int k = k0 + UK * u;
+        const bool kv = k < cend && k + LK * q < K;
 #pragma unroll
         for (int f = 0; f < 2; ++f) {
           wq[f][u] = make_uint4(0u, 0u, 0u, 0u);
-          if (kv) wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + (k >> 1));
+          if (kv) wq[f][u] = *reinterpret_cast<const uint4*>(wp[f] + k * BITS / 8);
         }
       }
     };
@@ -476,8 +328,8 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
           }
         }
       }
-      // block scales of the chunk for the 128 weight rows of the workgroup (code 127 = 1 past K)
-      const int nb = klen >> 5;                                  // blocks per row in the chunk
+      // MXFP4: block scales of the chunk for the 128 weight rows of the workgroup (code 127 = 1 past K)
+      const int nb = BITS == 4 ? klen >> 5 : 0;                                  // blocks per row in the chunk
       const int nbv = ((K < kc + klen ? K : kc + klen) - kc) >> 5;   // of which exist
       const int spitch = K >> 5;
       uint8_t* const sdst = reinterpret_cast<uint8_t*>(ss);
@@ -491,7 +343,7 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
       };
       const uint8_t* const sbase = a.S4[g] + (kc >> 5);
       // widest aligned access the shape allows: 16 bytes, 4 bytes, else bytes
-      const int sw = nb != nbv ? 1
+      const int sw = BITS != 4 ? 0 : nb != nbv ? 1
                      : (!(spitch & 15) && !((kc >> 5) & 15) && !(nb & 15)) ? 16
                      : (!(spitch & 3) && !((kc >> 5) & 3) && !(nb & 3)) ? 4 : 1;
       uint32_t sv[16];                        // 4 x 16 bytes or 16 x 4 bytes per thread
@@ -549,7 +401,7 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
             *reinterpret_cast<uint32_t*>(sdst + lr * kScalePitch + 4 * c) = sv[it];
           }
         }
-      } else {
+      } else if (sw == 1) {
         for (int idx = threadIdx.x; idx < 128 * nb; idx += 256) {
           const int lr = idx / nb, c = idx - lr * nb;
           sdst[lr * kScalePitch + c] = c < nbv ? sbase[grow(lr) * spitch + c] : (uint8_t)127;
@@ -560,27 +412,34 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
       const int chunk_end = kc + klen;        // == cend of the steps of this chunk
       while (true) {
         // request the next step (the first of the next chunk after the last of this one)
-        const bool last = k0 + 128 * U >= chunk_end;
-        const int nk = last ? chunk_end : k0 + 128 * U;
+        const bool last = k0 + UK * U >= chunk_end;
+        const int nk = last ? chunk_end : k0 + UK * U;
         const int ncend = last ? min(chunk_end + KC, Kp) : chunk_end;
         uint4 wn[2][U];
         load(wn, nk, ncend);                  // loads nothing once nk == Kp
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-          if (k0 + 128 * u < chunk_end) {     // wave-uniform
-            const unsigned char* xu = xrow + (k0 - kc + 128 * u) * 2;
-            Frag xf[4];
+          if (k0 + UK * u < chunk_end) {      // wave-uniform
+            const unsigned char* xu = xrow + (k0 - kc + UK * u) * 2;
+            Frag xf[NJ];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) xf[j].u = *reinterpret_cast<const uint4*>(xu + 16 * j);
+            for (int j = 0; j < NJ; ++j) xf[j].u = *reinterpret_cast<const uint4*>(xu + 16 * j);
 #pragma unroll
             for (int f = 0; f < 2; ++f) {
-              const float scale = e8m0_to_f32(sp[f][(k0 - kc + 128 * u) >> 5]);
-              const uint32_t cw[4] = {wq[f][u].x, wq[f][u].y, wq[f][u].z, wq[f][u].w};
+              if constexpr (BITS == 4) {
+                const float scale = e8m0_to_f32(sp[f][(k0 - kc + UK * u) >> 5]);
+                const uint32_t cw[4] = {wq[f][u].x, wq[f][u].y, wq[f][u].z, wq[f][u].w};
 #pragma unroll
-              for (int j = 0; j < 4; ++j) {
-                Frag wf;
-                fp4x8_to_bf16(cw[j], scale, wf);
-                acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, xf[j].v, acc[f], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) {
+                  Frag wf;
+                  fp4x8_to_bf16(cw[j], scale, wf);
+                  acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf.v, xf[j].v, acc[f], 0, 0, 0);
+                }
+              } else {
+                Frag wlo, whi;
+                fp8x16_to_bf16(wq[f][u], wlo, whi);
+                acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wlo.v, xf[0].v, acc[f], 0, 0, 0);
+                acc[f] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(whi.v, xf[1].v, acc[f], 0, 0, 0);
               }
             }
           }
@@ -597,6 +456,24 @@ __global__ void __launch_bounds__(256) ffn_skinny_w4_kernel(const SkinnyArgs a) 
 
     // lane holds token r of the pass, weight rows 4q..4q+3 of each row set
     const int tt = tb0 + r;
+    if constexpr (BITS == 8) {
+      if (active) {
+        // FP8: the scale of the weight row of accumulator element b multiplies the sum
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+          for (int b = 0; b < 4; ++b) {
+            long long row;
+            if constexpr (UP) row = (long long)i * 2 * F + (long long)f * F + c0 + 4 * q + b;
+            else {
+              int n = c0 + 16 * f + 4 * q + b;
+              if (n > a.d - 1) n = a.d - 1;
+              row = (long long)i * a.d + n;
+            }
+            acc[f][b] *= a.S[g][row];
+          }
+      }
+    }
     if (active && tt < cnt) {
       uint16_t* crow = a.C + (long long)(row0 + tt) * a.ldc;
       if constexpr (UP) {
@@ -709,13 +586,13 @@ hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* p
   up.blk_prefix[kMaxGroups] = nu;
   dn.blk_prefix[kMaxGroups] = nd;
   if (w4) {
-    if (stages & 1) hipLaunchKernelGGL((ffn_skinny_w4_kernel<true>), dim3(nu), dim3(256), 0, s, up);
-    if (stages & 2) hipLaunchKernelGGL((ffn_skinny_w4_kernel<false>), dim3(nd), dim3(256), 0, s, dn);
+    if (stages & 1) hipLaunchKernelGGL((ffn_skinny_q_kernel<true, 4>), dim3(nu), dim3(256), 0, s, up);
+    if (stages & 2) hipLaunchKernelGGL((ffn_skinny_q_kernel<false, 4>), dim3(nd), dim3(256), 0, s, dn);
     return hipGetLastError();
   }
   if (w8) {
-    if (stages & 1) hipLaunchKernelGGL((ffn_skinny_w8_kernel<true>), dim3(nu), dim3(256), 0, s, up);
-    if (stages & 2) hipLaunchKernelGGL((ffn_skinny_w8_kernel<false>), dim3(nd), dim3(256), 0, s, dn);
+    if (stages & 1) hipLaunchKernelGGL((ffn_skinny_q_kernel<true, 8>), dim3(nu), dim3(256), 0, s, up);
+    if (stages & 2) hipLaunchKernelGGL((ffn_skinny_q_kernel<false, 8>), dim3(nd), dim3(256), 0, s, dn);
     return hipGetLastError();
   }
   if (stages & 1) hipLaunchKernelGGL((ffn_skinny_kernel<true>), dim3(nu), dim3(256), 0, s, up);
