@@ -191,20 +191,36 @@ __global__ void __launch_bounds__(256) permute_small_kernel(const PermArgs a) {
   __syncthreads();
   wave_histogram(a, w, lane, hist[w]);
   __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int e = 0; e < a.Ne; ++e) {
-      int c = 0;
-      for (int ww = 0; ww < kWavesPerBlock; ++ww) {
-        const int h = hist[ww][e];
-        hist[ww][e] = run + c;      // becomes the base of (segment ww, expert e)
-        c += h;
-      }
-      a.counts[e] = c;
-      a.offsets[e] = run;
-      run += c;
+  // one expert per thread (Ne <= 256): its count over the four segments, then an exclusive scan
+  // over the experts (inside the waves by shuffles, across them through LDS)
+  __shared__ int wtot[kWavesPerBlock];
+  const int e = threadIdx.x;
+  int h[kWavesPerBlock], c = 0;
+#pragma unroll
+  for (int ww = 0; ww < kWavesPerBlock; ++ww) {
+    h[ww] = e < a.Ne ? hist[ww][e] : 0;
+    c += h[ww];
+  }
+  int incl = c;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int up = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += up;
+  }
+  if (lane == 63) wtot[w] = incl;
+  __syncthreads();
+  int off_e = incl - c;
+  for (int ww = 0; ww < w; ++ww) off_e += wtot[ww];
+  if (e < a.Ne) {
+    int run = off_e;
+#pragma unroll
+    for (int ww = 0; ww < kWavesPerBlock; ++ww) {
+      hist[ww][e] = run;            // becomes the base of (segment ww, expert e)
+      run += h[ww];
     }
-    a.offsets[a.Ne] = run;
+    a.counts[e] = c;
+    a.offsets[e] = off_e;
+    if (e == a.Ne - 1) a.offsets[a.Ne] = off_e + c;
   }
   __syncthreads();
   wave_scatter(a, w, lane, hist[w]);
