@@ -108,6 +108,9 @@ def main():
                     help="decode workloads: stream per-row quantised FP8 E4M3 expert weights (mohge_expert_ffn_w8)")
     ap.add_argument("--mxfp4-weights", action="store_true",
                     help="decode workloads: stream MXFP4 expert weights (mohge_expert_ffn_w4)")
+    ap.add_argument("--alternate-weights", action="store_true",
+                    help="decode workloads: keep two copies of the expert weights and alternate between them "
+                         "step by step, so that nothing of a step's weights can be left in the last-level cache")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -135,7 +138,23 @@ def main():
             sys.exit("bench.py: --fp8-weights / --mxfp4-weights (one of them) are for decode workloads (T <= 32), forward only")
         L.use_fp8_weights() if args.fp8_weights else L.use_mxfp4_weights()
 
+    weight_sets = None
+    if args.alternate_weights:
+        if w.T > 32:
+            sys.exit("bench.py: --alternate-weights is for decode workloads (T <= 32)")
+        clone = lambda ts: None if ts is None else tuple([t.clone() for t in part] for part in ts)
+        weight_sets = [(L.w13, L.w2, L.w8, L.w4),
+                       ([t.clone() for t in L.w13], [t.clone() for t in L.w2], clone(L.w8), clone(L.w4))]
+        flip = [0]
+
+    def flipw():
+        if weight_sets:
+            flip[0] ^= 1
+            L.w13, L.w2, L.w8, L.w4 = weight_sets[flip[0]]
+        return True
+
     def step():
+        flipw()
         L.forward(x)
         if args.backward:
             L.backward(x, dy)
@@ -152,17 +171,27 @@ def main():
         step()
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    # the same steps once more, each between its own pair of HIP events: median and minimum
+    pairs = []
+    for _ in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        step()
+        e1.record()
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    step_ms = sorted(a.elapsed_time(b) for a, b in pairs)
 
     # per-call timing with HIP events (state from the last step is valid input for each call)
     it = max(10, args.steps)
     calls = {
         "route": lambda: M.mohge_route(cfg, x, L.w_group, L.w_expert, L.bias, L.group_idx, L.expert_idx, L.gates, L.gs, L.es1, L.ws_route),
         "permute": lambda: M.mohge_permute(cfg, L.expert_idx, L.counts, L.offsets, L.perm, L.inv_perm, None, None, L.ws_permute),
-        "ffn": (lambda: M.mohge_expert_ffn_w8(cfg, x, L.perm, L.offsets, *L.w8, L.y_perm, L.ws_ffn)) if args.fp8_weights
-               else (lambda: M.mohge_expert_ffn_w4(cfg, x, L.perm, L.offsets, *L.w4, L.y_perm, L.ws_ffn)) if args.mxfp4_weights
-               else (lambda: M.mohge_expert_ffn(cfg, x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, L.ws_ffn)),
-        "ffn_up": lambda: M.mohge_expert_ffn_up(cfg, x, L.perm, L.offsets, L.w13, L.ws_ffn),
-        "ffn_down": lambda: M.mohge_expert_ffn_down(cfg, L.ws_ffn, L.offsets, L.w2, L.y_perm),
+        "ffn": (lambda: flipw() and M.mohge_expert_ffn_w8(cfg, x, L.perm, L.offsets, *L.w8, L.y_perm, L.ws_ffn)) if args.fp8_weights
+               else (lambda: flipw() and M.mohge_expert_ffn_w4(cfg, x, L.perm, L.offsets, *L.w4, L.y_perm, L.ws_ffn)) if args.mxfp4_weights
+               else (lambda: flipw() and M.mohge_expert_ffn(cfg, x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, L.ws_ffn)),
+        "ffn_up": lambda: flipw() and M.mohge_expert_ffn_up(cfg, x, L.perm, L.offsets, L.w13, L.ws_ffn),
+        "ffn_down": lambda: flipw() and M.mohge_expert_ffn_down(cfg, L.ws_ffn, L.offsets, L.w2, L.y_perm),
         "combine": lambda: M.mohge_combine(cfg, L.y_perm, L.inv_perm, L.gates, L.y),
     }
     if args.backward:
@@ -234,6 +263,7 @@ def main():
                 "frac": ach / PEAK_MFMA_BF16, "traffic": MEASURED_TRAFFIC.get(args.workload)}
     t_ffn = (call_ms["ffn_up"] + call_ms["ffn_down"]) * 1e-3
     parts = {
+        "step_ms_median": round(step_ms[len(step_ms) // 2], 5), "step_ms_min": round(step_ms[0], 5),
         "call_ms": {k: round(v, 5) for k, v in call_ms.items()},
         "ffn_up_down_tflops": (flops_up + flops_down) / t_ffn / 1e12,
         "ffn_up_down_frac_mfma": (flops_up + flops_down) / t_ffn / PEAK_MFMA_BF16,
@@ -259,7 +289,8 @@ def main():
         "data": "synthetic", "launch": "hip graph replay of the step" if args.graph else "eager",
         "config": {"workload": w.name, "T": w.T, "d": w.d, "groups_x_experts": f"{w.n_groups}x{w.experts_per_group}",
                    "d_ff": list(w.d_ff), "k_groups": w.k_groups, "k_experts": w.k_experts,
-                   "select_mode": "per_group" if w.select_mode == 1 else "global", "seed": w.seed},
+                   "select_mode": "per_group" if w.select_mode == 1 else "global", "seed": w.seed,
+                   **({"alternate_weights": True} if args.alternate_weights else {})},
         "roofline": roof,
         "parts": parts,
     }
