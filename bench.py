@@ -66,6 +66,38 @@ def event_time_inner(before, fn, iters, torch):
     return sum(a.elapsed_time(b) for a, b in pairs) / iters
 
 
+def box_probe(torch, M):
+    """Ceilings of this box: TB/s of kernels that only read (1.25 GiB, every byte once), TFLOP/s of a
+    kernel that only issues bf16 MFMAs; HIP events around 10 launches each."""
+    buf = torch.ones(1280 << 20, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    res = {}
+
+    def timed(fn):
+        for _ in range(3):
+            work = fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(10):
+            fn()
+        b.record()
+        b.synchronize()
+        return work / (a.elapsed_time(b) / 10 * 1e-3) / 1e12
+
+    res["read_contiguous_TBs"] = round(timed(lambda: M.mohge_probe_read(buf, 0, False, out)), 3)
+    for row in (2048, 4096, 8192):
+        for stag in (False, True):
+            key = "read_rows_%d%s_TBs" % (row, "_staggered" if stag else "")
+            res[key] = round(timed(lambda: M.mohge_probe_read(buf, row, stag, out)), 3)
+    # one round of workgroups of the decode up projection's size (about 940 active workgroups)
+    small = buf[: 940 * 128 * 8192]
+    res["read_rows_8192_940_workgroups_TBs"] = round(timed(lambda: M.mohge_probe_read(small, 8192, False, out)), 3)
+    tf = timed(lambda: M.mohge_probe_mfma(out, 20000))
+    res["mfma_bf16_only_TFLOPs"] = round(tf, 1)
+    res["mfma_clock_implied_GHz"] = round(tf * 1e12 / (256 * 4 * 1024.0) / 1e9, 3)   # 1024 FLOP per clock and SIMD
+    return res
+
+
 def cpu_baseline(w, inp, budget_s=12.0):
     """The oracle as it stands on a bounded sample: the first n tokens of the workload
     through route -> permute -> experts -> combine, n sized to about `budget_s` seconds."""
@@ -111,6 +143,9 @@ def main():
     ap.add_argument("--alternate-weights", action="store_true",
                     help="decode workloads: keep two copies of the expert weights and alternate between them "
                          "step by step, so that nothing of a step's weights can be left in the last-level cache")
+    ap.add_argument("--box-probe", action="store_true",
+                    help="instead of the layer: measure what the box delivers (pure reads in several access "
+                         "patterns, back-to-back bf16 MFMAs) and print one JSON line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -123,6 +158,9 @@ def main():
     from synth import WORKLOADS, generate
     from gpu_harness import DeviceLayer
 
+    if args.box_probe:
+        print(json.dumps({"box_probe": box_probe(torch, M)}))
+        return
     w = WORKLOADS[args.workload]
     inp = generate(w)
     dl = DeviceLayer(w, inp, training=args.backward, backward=args.backward)

@@ -353,6 +353,22 @@ size_t mohge_workspace_size(const mohge_config* cfg, int which_call);
 int mohge_fused_status(const mohge_config* cfg, int which_call, const void* workspace,
                        size_t workspace_bytes, void* stream);
 
+/*
+ * Measurement aids (not part of the layer): what the box delivers, for reading the kernels'
+ * fractions against measured ceilings.
+ * mohge_probe_read enqueues a kernel that reads the first *bytes_read <= bytes bytes of buf
+ * (DEVICE) exactly once and does nothing else: row_bytes = 0 as contiguous streams; otherwise
+ * (a multiple of 512) with the access pattern of the decode kernels on rows of that size, the
+ * waves walking their rows in step (staggered = 0) or each from a different start (1).  out:
+ * DEVICE, at least 16 bytes, may receive a dummy value.  bytes_read: HOST.
+ * mohge_probe_mfma enqueues 1024 workgroups that issue nothing but independent chains of
+ * v_mfma_f32_32x32x16_bf16, `iters` per chain; *flops (HOST) receives the FLOPs of the launch;
+ * out: DEVICE, at least 1 MiB.  Time either with events on `stream`.
+ */
+int mohge_probe_read(const void* buf, size_t bytes, int row_bytes, int staggered, void* out,
+                     size_t* bytes_read, void* stream);
+int mohge_probe_mfma(void* out, size_t out_bytes, int iters, double* flops, void* stream);
+
 /* Tuning hook for benchmarks: knob 0 / 1 forces the token-tile height (64, 128, 192 or
  * 256 rows; 0 = chosen per call from the routed counts) of the up / down projection of the
  * bf16 prefill path; knob 2 = 0 runs the up and the down projection of mohge_expert_ffn /

@@ -21,7 +21,7 @@ CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
 CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE = 3, 4, 5, 6
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
-           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_expert_ffn_parts", "mohge_tune", "mohge_fused_status",
+           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_expert_ffn_parts", "mohge_tune", "mohge_fused_status", "mohge_probe_read", "mohge_probe_mfma",
            "mohge_expert_ffn_train", "mohge_expert_ffn_w8", "mohge_fp8_decode", "mohge_expert_ffn_w4",
            "mohge_mxfp4_decode", "mohge_combine_bwd",
            "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_shared_routing", "mohge_combine_add",
@@ -162,6 +162,21 @@ def mohge_expert_ffn(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], w2: Seq
                                   _ptr_table(w2), _ptr(y_perm), _ptr(workspace),
                                   C.c_size_t(workspace.numel() * workspace.element_size()),
                                   _stream()), "mohge_expert_ffn")
+
+
+def mohge_probe_read(buf: torch.Tensor, row_bytes: int, staggered: bool, out: torch.Tensor) -> int:
+    """Enqueues the read probe on buf; returns the bytes the kernel reads."""
+    n = C.c_size_t(0)
+    _check(lib().mohge_probe_read(_ptr(buf), _nbytes(buf), C.c_int(row_bytes), C.c_int(int(staggered)), _ptr(out),
+                                  C.byref(n), _stream()), "mohge_probe_read")
+    return n.value
+
+
+def mohge_probe_mfma(out: torch.Tensor, iters: int) -> float:
+    """Enqueues the MFMA probe; returns the FLOPs of the launch."""
+    f = C.c_double(0.0)
+    _check(lib().mohge_probe_mfma(_ptr(out), _nbytes(out), C.c_int(iters), C.byref(f), _stream()), "mohge_probe_mfma")
+    return f.value
 
 
 def mohge_fused_status(cfg, which_call: int, workspace) -> int:

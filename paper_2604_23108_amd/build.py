@@ -13,7 +13,7 @@ LIB = os.path.join(HERE, "libmohge.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 SOURCES = ["api.hip", "route.hip", "permute.hip", "ffn.hip", "ffn_tiled.hip", "ffn_skinny.hip",
-           "combine.hip", "aux_loss.hip", "ffn_bwd.hip", "route_bwd.hip"]
+           "combine.hip", "aux_loss.hip", "ffn_bwd.hip", "route_bwd.hip", "box_probe.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]

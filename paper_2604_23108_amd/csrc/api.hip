@@ -114,6 +114,30 @@ int mohge_fused_status(const mohge_config* cfg, int which_call, const void* work
   return MOHGE_OK;
 }
 
+int mohge_probe_read(const void* buf, size_t bytes, int row_bytes, int staggered, void* out,
+                     size_t* bytes_read, void* stream) {
+  NEED(buf); NEED(out);
+  if (!bytes_read) { set_error("bytes_read is NULL"); return MOHGE_ENULL; }
+  if (row_bytes < 0 || (row_bytes != 0 && (row_bytes % 512 != 0 || row_bytes > (1 << 20)))) {
+    set_error("mohge_probe_read: row_bytes = %d (0, or a multiple of 512 up to 1 MiB)", row_bytes);
+    return MOHGE_EINVAL;
+  }
+  return hip_rc(launch_probe_read(buf, bytes, row_bytes, staggered != 0, out, bytes_read, (hipStream_t)stream),
+                "mohge_probe_read");
+}
+
+int mohge_probe_mfma(void* out, size_t out_bytes, int iters, double* flops, void* stream) {
+  NEED(out);
+  if (!flops) { set_error("flops is NULL"); return MOHGE_ENULL; }
+  const int blocks = 1024;
+  if (out_bytes < (size_t)blocks * 256 * sizeof(float)) {
+    set_error("mohge_probe_mfma: out holds %zu bytes, %zu needed", out_bytes, (size_t)blocks * 256 * sizeof(float));
+    return MOHGE_EWORKSPACE;
+  }
+  if (iters < 1 || iters > (1 << 20)) { set_error("mohge_probe_mfma: iters = %d outside 1..2^20", iters); return MOHGE_EINVAL; }
+  return hip_rc(launch_probe_mfma(out, blocks, iters, flops, (hipStream_t)stream), "mohge_probe_mfma");
+}
+
 int mohge_tune(int knob, int value) {
   if (tune_tiled(knob, value)) { set_error("mohge_tune: knob %d / value %d out of range", knob, value); return MOHGE_EINVAL; }
   return MOHGE_OK;

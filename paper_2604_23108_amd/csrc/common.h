@@ -75,6 +75,9 @@ size_t ffn_workspace_bytes(const LayerDesc& L, int dtype);
 hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
                              hipStream_t s, int stages, int parts = 3);   // stages: bit 0 = up, bit 1 = down
+hipError_t launch_probe_read(const void* buf, size_t bytes, int row_bytes, int staggered, void* out,
+                             size_t* bytes_read, hipStream_t s);
+hipError_t launch_probe_mfma(void* out, int blocks, int iters, double* flops, hipStream_t s);
 bool ffn_parts_supported(const LayerDesc& L, int dtype);
 // byte offset of the schedule header that carries the "gave up waiting" flag of a fused launch in
 // the workspace of call `which_call`, or -1 where the call has no fused launch

@@ -728,3 +728,25 @@ def test_ffn_schedule_and_product_launch_issued_separately():
     with pytest.raises(M.MohgeError, match="separate launches"):
         M.mohge_expert_ffn_parts(dd.cfg, dd.x, dd.layer.perm, dd.layer.offsets, dd.layer.w13, dd.layer.w2,
                                  dd.layer.y_perm, dd.layer.ws_ffn, 2)
+
+
+def test_box_probes_run_and_report_their_work():
+    """The measurement aids: every pattern of the read probe on a buffer that is not a whole number
+    of its units, and the MFMA probe; argument errors."""
+    import paper_2604_23108_amd as M
+    buf = torch.ones(3 * (1 << 20) + 4096, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    n = M.mohge_probe_read(buf, 0, False, out)
+    assert 0 < n <= buf.numel() and n % (256 * 8 * 16) == 0
+    for row in (512, 2048, 8192):
+        for stag in (False, True):
+            n = M.mohge_probe_read(buf, row, stag, out)
+            assert n == (buf.numel() // row // 128) * 128 * row, (row, stag)
+    assert M.mohge_probe_read(buf[:4096], 8192, False, out) == 0          # less than one unit: nothing launched
+    flops = M.mohge_probe_mfma(out, 100)
+    assert flops == 1024 * 4 * 4 * 100 * 2.0 * 32 * 32 * 16
+    torch.cuda.synchronize()
+    with pytest.raises(M.MohgeError, match="row_bytes"):
+        M.mohge_probe_read(buf, 1000, False, out)
+    with pytest.raises(M.MohgeError, match="needed"):
+        M.mohge_probe_mfma(out[:4096], 10)
