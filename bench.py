@@ -299,6 +299,31 @@ def main():
                           ("mohge_expert_ffn_train" if args.backward else "mohge_expert_ffn"),
                 "bound": "mfma", "achieved": ach / 1e12, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
                 "frac": ach / PEAK_MFMA_BF16, "traffic": MEASURED_TRAFFIC.get(args.workload)}
+    # the same kind of work with nothing else going on, measured now on this machine (see box_probe)
+    if w.dtype == "bf16":
+        out = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+
+        def timed(fn):
+            for _ in range(3):
+                work = fn()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(10):
+                fn()
+            b.record()
+            b.synchronize()
+            return work / (a.elapsed_time(b) / 10 * 1e-3)
+
+        if roof["bound"] == "mfma":
+            ceil = timed(lambda: M.mohge_probe_mfma(out, 20000)) / 1e12
+            what = "a kernel of nothing but bf16 MFMAs on operands with full mantissas (clock under that load)"
+        else:
+            buf = torch.ones(1 << 30, dtype=torch.uint8, device="cuda")
+            ceil = timed(lambda: M.mohge_probe_read(buf, 0, False, out)) / 1e9
+            what = "a kernel that only reads 1 GiB in contiguous streams"
+            del buf
+        roof["measured_ceiling"] = {"value": ceil, "unit": roof["unit"], "what": what}
+        roof["frac_of_measured_ceiling"] = roof["achieved"] / ceil
     t_ffn = (call_ms["ffn_up"] + call_ms["ffn_down"]) * 1e-3
     parts = {
         "step_ms_median": round(step_ms[len(step_ms) // 2], 5), "step_ms_min": round(step_ms[0], 5),
