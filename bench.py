@@ -26,12 +26,12 @@ PEAK_HBM = 8.0e12           # B/s
 # of FETCH_SIZE (factor 2.0) and 262144 KiB of WRITE_SIZE (factor 1.0).  None for workloads
 # that have not been profiled.
 MEASURED_TRAFFIC = {
-    "mid_prefill": (299860 * 2.0 + 98602 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
-    "decode": (636950 * 2.0 + 377 * 1.0) * 1024,          # ffn_skinny_kernel<up>
+    "mid_prefill": (300220 * 2.0 + 98602 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
+    "decode": (635140 * 2.0 + 377 * 1.0) * 1024,          # ffn_skinny_kernel<up>
     "decode/fp8": ((313350 + 156510) * 2.0 + (361 + 1047) * 1.0) * 1024,    # ffn_skinny_q_kernel<up, 8> + <down, 8>
     "decode/mxfp4": ((170060 + 83430) * 2.0 + (355 + 1025) * 1.0) * 1024,   # ffn_skinny_q_kernel<up, 4> + <down, 4>
-    "training": (639010 * 2.0 + 326870 * 1.0) * 1024,     # ffn_fused_kernel<up that saves + down>
-    "large_prefill_skewed": (5156100 * 2.0 + 696360 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
+    "training": (647030 * 2.0 + 326870 * 1.0) * 1024,     # ffn_fused_kernel<up that saves + down>
+    "large_prefill_skewed": (5157500 * 2.0 + 696360 * 1.0) * 1024,   # ffn_fused_kernel<up + down>
 }
 
 
