@@ -9,7 +9,8 @@
 // Integer LDS atomics only feed counts, so nothing depends on execution order.
 // Up to 2048 pairs the three steps run in one single-workgroup kernel;
 // while segments x experts <= 8192 the scan is folded into the scatter kernel (two launches
-// instead of three).
+// instead of three).  (One workgroup of sixteen waves for up to 32768 pairs, a single launch, was
+// slower than the two launches: 15 against 11 us at 16384 pairs, 28 against 12 us at 32768.)
 #include "common.h"
 
 namespace mohge {
@@ -72,10 +73,14 @@ __device__ __forceinline__ void wave_scatter(const PermArgs& a, int seg, int lan
         a.inv_perm[p] = r;
       }
     }
-    __syncthreads();
+    // `base` belongs to this wave and LDS operations of one wave complete in order: only the
+    // compiler has to be kept from moving the cursor update across the reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     // the highest lane of each set of equal experts advances the bucket cursor
     if (active && (m >> lane) == 1ull) base[e] = r + 1;
-    __syncthreads();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   }
 }
 

@@ -265,8 +265,8 @@ def test_route_and_permute_many_pairs_three_kernel_path():
     check_permutation(w, out)
 
 
-@pytest.mark.parametrize("T,Ng,N", [(25, 3, 4), (512, 3, 8), (513, 16, 16), (17500, 16, 16), (32768, 3, 8),
-                                    (32769, 3, 8), (41000, 8, 8)])
+@pytest.mark.parametrize("T,Ng,N", [(25, 3, 4), (512, 3, 8), (513, 16, 16), (4096, 16, 16), (8192, 3, 8), (8193, 3, 8),
+                                    (17500, 16, 16), (32768, 3, 8), (32769, 3, 8), (41000, 8, 8)])
 def test_permute_every_launch_path(T, Ng, N):
     # K_e = 4: P = 100 and 2048 (one workgroup), 2052 ... 131076 (histogram launch + scatter
     # launch with the scan folded in, while segments x experts <= 8192: 24 experts up to the
