@@ -750,3 +750,58 @@ def test_box_probes_run_and_report_their_work():
         M.mohge_probe_read(buf, 1000, False, out)
     with pytest.raises(M.MohgeError, match="needed"):
         M.mohge_probe_mfma(out[:4096], 10)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_quantised_decode_random_shapes(seed):
+    """Seeded random decode shapes (hidden sizes and widths that are odd multiples of 64, one to
+    four groups, 1 to 32 tokens) through both quantised-weight kernels against the oracle on the
+    dequantised weights: reduction lengths that end in partial units, chunked token staging."""
+    import paper_2604_23108_amd as M
+    from synth import SELECT_GLOBAL, SELECT_PER_GROUP
+    rng = np.random.default_rng(5000 + seed)
+    Ng = int(rng.integers(1, 5))
+    N = int(rng.integers(1, 7))
+    d = int(rng.choice([64, 128, 192, 320, 448, 1024, 2112]))
+    d_ff = tuple(int(64 * rng.integers(1, 9)) for _ in range(Ng))
+    kg = int(rng.integers(1, Ng + 1))
+    per = int(rng.integers(1, N + 1))
+    mode = SELECT_PER_GROUP if rng.integers(2) else SELECT_GLOBAL
+    ke = kg * per if mode == SELECT_PER_GROUP else int(rng.integers(1, kg * N + 1))
+    T = int(rng.integers(1, 33))
+    w = WORKLOADS["decode"].replace(T=T, d=d, n_groups=Ng, experts_per_group=N, d_ff=d_ff, k_groups=kg,
+                                    k_experts=ke, select_mode=mode, seed=5100 + seed)
+    inp = generate(w)
+    DeviceLayer = _dev()
+    dl = DeviceLayer(w, inp, training=False)
+    L = dl.layer
+    print(f"[quantised decode] seed={seed} T={T} d={d} d_ff={d_ff} {Ng}x{N} kg={kg} ke={ke} mode={mode}", flush=True)
+    L.forward(dl.x)
+    r = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias)
+    keep = r["margin"] >= MARGIN
+    tok = np.arange(w.T, dtype=np.int32)
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    for name, quant, deq, call in (("fp8", M.quantize_rows_e4m3, oracle.dequantize_rows, M.mohge_expert_ffn_w8),
+                                   ("mxfp4", M.quantize_mxfp4, oracle.dequantize_mxfp4, M.mohge_expert_ffn_w4)):
+        q13, s13, q2, s2 = [], [], [], []
+        for g in range(w.n_groups):
+            c, s = quant(L.w13[g]); q13.append(c); s13.append(s)
+            c, s = quant(L.w2[g]); q2.append(c); s2.append(s)
+        y_perm = torch.full_like(L.y_perm, float("nan"))
+        call(dl.cfg, dl.x, L.perm, L.offsets, q13, s13, q2, s2, y_perm, L.ws_ffn)
+        y = torch.empty_like(L.y)
+        M.mohge_combine(dl.cfg, y_perm, L.inv_perm, L.gates, y)
+        torch.cuda.synchronize()
+        wg, wu, wd = [], [], []
+        for g in range(w.n_groups):
+            F = w.d_ff[g]
+            w13 = deq(q13[g].cpu().numpy(), s13[g].cpu().numpy())
+            wg.append(f32(w13[:, :F])); wu.append(f32(w13[:, F:]))
+            wd.append(f32(deq(q2[g].cpu().numpy(), s2[g].cpu().numpy())))
+        y_pairs = oracle.expert_ffn(w, inp.x.f32, wg, wu, wd, np.repeat(tok, w.k_experts), r["expert_idx"].reshape(-1))
+        want = oracle.combine(w, y_pairs, r["gates"])
+        got = y.float().cpu().numpy()
+        assert np.isfinite(got).all(), name
+        if keep.any():
+            err = np.abs(got[keep] - want[keep]).max()
+            assert err <= 2e-2 * max(np.abs(want).max(), 1e-6), f"{name}: error {err} vs {np.abs(want).max()}"
