@@ -202,19 +202,6 @@ int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
                    float* stats, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * ---- Training: backward pass of the layer (dtype MOHGE_BF16 only; MOHGE_EINVAL otherwise) ----
- *
- * The paper trains the layer with  L_task + L_G + L_E  (sections 3.3, 3.4.2) and prints no
- * backward formulas; these calls apply the chain rule to the forward definitions of section
- * 3.2 and of the two losses.  The routing decisions and the routing frequencies f are
- * constants.  Given dy = dL_task/dy, one backward pass is
- *     mohge_combine_bwd -> mohge_expert_ffn_bwd -> mohge_route_bwd
- * after a forward pass that used mohge_expert_ffn_train in place of mohge_expert_ffn and kept
- * gs, es1, gates, the indices and the permutation.  Gradients of bf16 tensors are bf16 (one
- * rounding of an fp32 accumulator); router gradients are fp32.
- */
-
-/*
  * mohge_expert_ffn in two steps, for callers that time or place them separately.  On the
  * matrix-core path the call is two launches: a small kernel that turns `offsets` into the tile
  * lists and hand-out counters (kept in the workspace), and the launch that computes both
@@ -267,6 +254,19 @@ int mohge_expert_ffn_w4(const mohge_config* cfg, const void* x, const int32_t* p
                         const void* const* w2q, const void* const* w2_scale, void* y_perm,
                         void* workspace, size_t workspace_bytes, void* stream);
 int mohge_mxfp4_decode(const void* packed, const void* scales, float* out, size_t n, void* stream);
+
+/*
+ * ---- Training: backward pass of the layer (dtype MOHGE_BF16 only; MOHGE_EINVAL otherwise) ----
+ *
+ * The paper trains the layer with  L_task + L_G + L_E  (sections 3.3, 3.4.2) and prints no
+ * backward formulas; these calls apply the chain rule to the forward definitions of section
+ * 3.2 and of the two losses.  The routing decisions and the routing frequencies f are
+ * constants.  Given dy = dL_task/dy, one backward pass is
+ *     mohge_combine_bwd -> mohge_expert_ffn_bwd -> mohge_route_bwd
+ * after a forward pass that used mohge_expert_ffn_train in place of mohge_expert_ffn and kept
+ * gs, es1, gates, the indices and the permutation.  Gradients of bf16 tensors are bf16 (one
+ * rounding of an fp32 accumulator); router gradients are fp32.
+ */
 
 /*
  * mohge_expert_ffn with the same results, which additionally keeps, in `saved` (DEVICE,
