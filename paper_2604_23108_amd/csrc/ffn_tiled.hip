@@ -176,8 +176,11 @@ __device__ __forceinline__ int choose_tile_rows(const TileArgs& a, SchedShared& 
 
 // Tile list of a launch of MODE with tile height h.  FUSED: the list belongs to a launch that
 // runs up and down tiles together; down tiles then carry the number of up tiles they wait for.
+// part / nparts: several workgroups may build one list together: each derives the (cheap) per-expert
+// prefix sums itself and writes every nparts-th stretch of 256 records; part 0 writes the header.
 template <int MODE>
-__device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& sh, int h, bool fused) {
+__device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& sh, int h, bool fused,
+                                               int part = 0, int nparts = 1) {
   constexpr int NCPT = Shape<MODE>::NCOLS_PER_TILE;
   const int v = threadIdx.x, lane = v & 63, w = v >> 6;
   int e = 0, cnt = 0, nt = 0, kc = 0, row0 = 0;
@@ -218,7 +221,7 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
     }
     return lo;
   };
-  for (int t = v; t < total; t += 256) {
+  for (int t = v + 256 * part; t < total; t += 256 * nparts) {
     const int ve = expert_of(t);
     const int c = sh.cnt[ve], mt = (c + h - 1) / h;
     const int rel = t - (int)sh.tp[ve], ni = rel / mt, mi = rel % mt;
@@ -237,6 +240,7 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
              : MODE == kDgradX ? (a.F[r.e / a.N] / 2 + kBN - 1) / kBN : 0;
     a.recs[t] = r;
   }
+  if (part != 0) return;                     // (workgroup-uniform: everything below is part 0's)
   // XCD x starts at the first tile whose preceding cost is >= x/8 of the total.  Inside an
   // expert tiles run column tile major, row tile minor, and the cost before tile (ni, mi) is
   // (ni*units + min(mi*h/64, units)) * kc, so the tile is found arithmetically once the expert
@@ -309,9 +313,11 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
 __global__ void __launch_bounds__(256) ffn_schedule_kernel(const TileArgs up, const TileArgs dn, int mask) {
   __shared__ SchedShared sh;
   if (mask == 7) {
+    // four workgroups per list (blockIdx.x = list + 2 * part)
     const int h = choose_tile_rows<kUp>(up, sh, true);
-    if (blockIdx.x == 0) build_schedule<kUp>(up, sh, h, true);
-    else build_schedule<kDown>(dn, sh, h, true);
+    const int part = blockIdx.x >> 1, nparts = gridDim.x >> 1;
+    if ((blockIdx.x & 1) == 0) build_schedule<kUp>(up, sh, h, true, part, nparts);
+    else build_schedule<kDown>(dn, sh, h, true, part, nparts);
     return;
   }
   const int which = (mask == 3) ? (int)blockIdx.x : (mask == 2 ? 1 : 0);
@@ -1241,7 +1247,7 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
     // parts: 1 = the tile schedule only, 2 = the product launch only (on a schedule that no
     // launch has consumed yet), 3 = both
     if (parts & 1) {
-      hipLaunchKernelGGL(ffn_schedule_kernel, dim3(2), dim3(256), 0, s, up, dn, 7);
+      hipLaunchKernelGGL(ffn_schedule_kernel, dim3(8), dim3(256), 0, s, up, dn, 7);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
     }
