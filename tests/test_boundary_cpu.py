@@ -162,3 +162,15 @@ def test_quantised_and_split_entry_points_check_their_arguments():
     assert "parts" in M.mohge_last_error()
     assert lib.mohge_expert_ffn_parts(prefill.ref(), *([None] * 7), 0, C.c_int(2), None) == -2
     assert lib.mohge_expert_ffn_parts(prefill.ref(), *([None] * 7), 0, C.c_int(3), None) == -2
+
+
+def test_bench_refuses_more_than_one_gpu_and_graft_entry_has_both_functions():
+    """bench.py --gpus N > 1 exits with a message (one GPU only, by design); the entry file has
+    build() and smoke()."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode != 0 and "one GPU" in (p.stderr + p.stdout)
+    src = open(os.path.join(root, "__graft_entry__.py")).read()
+    assert "def build(" in src and "def smoke(" in src
