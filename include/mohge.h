@@ -116,6 +116,23 @@ int mohge_permute(const mohge_config* cfg, const int32_t* expert_idx, int32_t* c
                   void* x_perm, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * mohge_permute for callers that cannot allocate device memory or hand over a workspace (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): same
+ * arguments, kernels and results as mohge_permute, with the segment histograms (the call's only
+ * scratch memory) in a static device array of MOHGE_PERMUTE_STATIC_BYTES inside the library,
+ * which every GPU the library runs on holds until the process ends.  The call allocates and
+ * frees nothing.  MOHGE_EWORKSPACE when mohge_workspace_size(cfg, MOHGE_CALL_PERMUTE) exceeds
+ * MOHGE_PERMUTE_STATIC_BYTES (at N_e = 64 that is beyond 2^21 pairs); nothing is enqueued then.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two threads) race on it and must be serialised by the caller; calls in stream order
+ * need no clearing in between (every cell that is read is overwritten first).
+ */
+#define MOHGE_PERMUTE_STATIC_BYTES (1u << 20)
+int mohge_permute_static(const mohge_config* cfg, const int32_t* expert_idx, int32_t* counts,
+                         int32_t* offsets, int32_t* perm, int32_t* inv_perm, const void* x,
+                         void* x_perm, void* stream);
+
+/*
  * Expert networks on the bucketed tokens (section 3.1: every expert of group g has
  * width F_g; the form is a SwiGLU feed-forward network without bias):
  *   for sorted position r in [offsets[e], offsets[e+1]), expert e = g*N + i:

@@ -6,7 +6,7 @@ of the layer runs in the HIP kernels of `csrc/`.  There is no CPU or PyTorch fal
 if `libmohge.so` has not been built, loading fails.
 """
 from .binding import (  # noqa: F401
-    MohgeError, Config, lib, lib_path, mohge_route, mohge_permute, mohge_expert_ffn, mohge_expert_ffn_up, mohge_expert_ffn_down,
+    MohgeError, Config, lib, lib_path, mohge_route, mohge_permute, mohge_permute_static, mohge_expert_ffn, mohge_expert_ffn_up, mohge_expert_ffn_down,
     mohge_combine, mohge_aux_loss, mohge_workspace_size, mohge_tune, mohge_last_error, pack_w13,
     MoHGELayer, CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS, SELECT_GLOBAL, SELECT_PER_GROUP,
     F32, BF16, CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE, mohge_expert_ffn_train,

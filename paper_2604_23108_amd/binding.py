@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
 CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE = 3, 4, 5, 6
 
-EXPORTS = ["mohge_route", "mohge_permute", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
+EXPORTS = ["mohge_route", "mohge_permute", "mohge_permute_static", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
            "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_expert_ffn_parts", "mohge_tune", "mohge_fused_status", "mohge_probe_read", "mohge_probe_mfma",
            "mohge_expert_ffn_train", "mohge_expert_ffn_w8", "mohge_fp8_decode", "mohge_expert_ffn_w4",
            "mohge_mxfp4_decode", "mohge_combine_bwd",
@@ -148,6 +148,12 @@ def mohge_permute(cfg, expert_idx, counts, offsets, perm, inv_perm, x, x_perm, w
                                _ptr(inv_perm), _ptr(x), _ptr(x_perm), _ptr(workspace),
                                C.c_size_t(workspace.numel() * workspace.element_size()), _stream()),
            "mohge_permute")
+
+
+def mohge_permute_static(cfg, expert_idx, counts, offsets, perm, inv_perm, x, x_perm):
+    _check(lib().mohge_permute_static(cfg.ref(), _ptr(expert_idx), _ptr(counts), _ptr(offsets), _ptr(perm),
+                                      _ptr(inv_perm), _ptr(x), _ptr(x_perm), _stream()),
+           "mohge_permute_static")
 
 
 def _ptr_table(ts: Sequence[torch.Tensor]):

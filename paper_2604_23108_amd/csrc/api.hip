@@ -193,6 +193,26 @@ int mohge_permute(const mohge_config* cfg, const int32_t* expert_idx, int32_t* c
                 "mohge_permute");
 }
 
+int mohge_permute_static(const mohge_config* cfg, const int32_t* expert_idx, int32_t* counts,
+                         int32_t* offsets, int32_t* perm, int32_t* inv_perm, const void* x,
+                         void* x_perm, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  NEED(expert_idx); NEED(counts); NEED(offsets); NEED(perm); NEED(inv_perm);
+  OPT(x); OPT(x_perm);
+  if (x_perm && !x) { set_error("x_perm requested but x is NULL"); return MOHGE_ENULL; }
+  if (permute_workspace_bytes(L) > (size_t)MOHGE_PERMUTE_STATIC_BYTES) {
+    set_error("mohge_permute_static: this configuration needs %zu bytes of scratch, the static buffer holds %zu "
+              "(use mohge_permute with a workspace)", permute_workspace_bytes(L),
+              (size_t)MOHGE_PERMUTE_STATIC_BYTES);
+    return MOHGE_EWORKSPACE;
+  }
+  return hip_rc(launch_permute_static(L, cfg->dtype, expert_idx, counts, offsets, perm, inv_perm, x,
+                                      x_perm, (hipStream_t)stream),
+                "mohge_permute_static");
+}
+
 int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm,
                      const int32_t* offsets, const void* const* w13, const void* const* w2,
                      void* y_perm, void* workspace, size_t workspace_bytes, void* stream) {

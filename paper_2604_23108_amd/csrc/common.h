@@ -71,6 +71,9 @@ size_t permute_workspace_bytes(const LayerDesc& L);
 hipError_t launch_permute(const LayerDesc& L, int dtype, const int32_t* expert_idx,
                           int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
                           const void* x, void* x_perm, void* ws, hipStream_t s);
+hipError_t launch_permute_static(const LayerDesc& L, int dtype, const int32_t* expert_idx,
+                                 int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                                 const void* x, void* x_perm, hipStream_t s);
 size_t ffn_workspace_bytes(const LayerDesc& L, int dtype);
 hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,

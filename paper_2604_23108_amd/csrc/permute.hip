@@ -11,9 +11,38 @@
 // while segments x experts <= 8192 the scan is folded into the scatter kernel (two launches
 // instead of three).  (One workgroup of sixteen waves for up to 32768 pairs, a single launch, was
 // slower than the two launches: 15 against 11 us at 16384 pairs, 28 against 12 us at 32768.)
+#include <mutex>
+
 #include "common.h"
 
 namespace mohge {
+
+// Segment histograms of mohge_permute_static: the one scratch buffer of the permutation, held in
+// the library's own device memory so that the call needs no workspace from the caller.  Every GPU
+// the library runs on holds its own copy at its own address; host code never uses the array's
+// name as an address, only the pointer hipGetSymbolAddress returned for the current device.
+static __device__ __align__(256) unsigned char scratch[MOHGE_PERMUTE_STATIC_BYTES];
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device (looked up once per device)
+static hipError_t static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 constexpr int kSegPairs = 512;                 // pairs per wave segment
 constexpr int kWavesPerBlock = 4;
@@ -282,6 +311,19 @@ hipError_t launch_permute(const LayerDesc& L, int dtype, const int32_t* expert_i
     e = hipGetLastError();
   }
   return e;
+}
+
+// The same launches with the segment histograms in the library's static device array.  The
+// histogram kernel overwrites every cell the later kernels read, so nothing has to be cleared
+// between calls.
+hipError_t launch_permute_static(const LayerDesc& L, int dtype, const int32_t* expert_idx,
+                                 int32_t* counts, int32_t* offsets, int32_t* perm, int32_t* inv_perm,
+                                 const void* x, void* x_perm, hipStream_t s) {
+  if (permute_workspace_bytes(L) > (size_t)MOHGE_PERMUTE_STATIC_BYTES) return hipErrorInvalidValue;
+  void* ws = nullptr;
+  hipError_t e = static_scratch(&ws);
+  if (e != hipSuccess) return e;
+  return launch_permute(L, dtype, expert_idx, counts, offsets, perm, inv_perm, x, x_perm, ws, s);
 }
 
 }  // namespace mohge
