@@ -148,6 +148,13 @@ int mohge_permute_static(const mohge_config* cfg, const int32_t* expert_idx, int
  * it holds h between the two projections.
  * bf16: products on the matrix cores with fp32 accumulation; h and y_perm are
  * rounded to bf16 once each.  fp32: plain fp32 arithmetic.
+ * Residency: for bf16 and T > 32 both projections run as ONE persistent launch of one workgroup
+ * per compute unit, in which the down-projection tiles of a row block wait until its
+ * up-projection tiles are complete.  The tiles waited for are always in the hands of workgroups
+ * that never wait themselves, so the launch finishes on a GPU of its own and also when another
+ * process delays some of its workgroups; the wait is bounded all the same (about a second of
+ * polling).  A tile whose wait expires writes NaN to its part of y_perm instead of a result and
+ * leaves a flag that mohge_fused_status reports: a wrong number can never pass for a result.
  */
 int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm,
                      const int32_t* offsets, const void* const* w13, const void* const* w2,
@@ -157,13 +164,15 @@ int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm
  * The two halves of mohge_expert_ffn as separate calls (same arguments, same kernels):
  * mohge_expert_ffn_up writes h = SiLU(W_gate x) * (W_up x) for every sorted position
  * into `h` (DEVICE, mohge_workspace_size(cfg, MOHGE_CALL_EXPERT_FFN) bytes; the layout
- * inside is the library's); mohge_expert_ffn_down reads it and writes y_perm.
- * mohge_expert_ffn(…, workspace) is exactly up(…, workspace) followed by down(workspace, …).
+ * inside is the library's; MOHGE_EWORKSPACE if h_bytes is smaller, in either call);
+ * mohge_expert_ffn_down reads it and writes y_perm.
+ * mohge_expert_ffn(…, workspace) computes exactly up(…, workspace) followed by down(workspace, …)
+ * (on the matrix-core path as one launch instead of two, with the same bits).
  */
 int mohge_expert_ffn_up(const mohge_config* cfg, const void* x, const int32_t* perm,
                         const int32_t* offsets, const void* const* w13, void* h, size_t h_bytes,
                         void* stream);
-int mohge_expert_ffn_down(const mohge_config* cfg, const void* h, const int32_t* offsets,
+int mohge_expert_ffn_down(const mohge_config* cfg, const void* h, size_t h_bytes, const int32_t* offsets,
                           const void* const* w2, void* y_perm, void* stream);
 
 /*
@@ -217,22 +226,6 @@ int mohge_combine_add(const mohge_config* cfg, const void* y_perm, const int32_t
 int mohge_aux_loss(const mohge_config* cfg, const float* gs, const float* es1,
                    const int32_t* group_idx, const int32_t* expert_idx, float* losses,
                    float* stats, void* workspace, size_t workspace_bytes, void* stream);
-
-/*
- * mohge_expert_ffn in two steps, for callers that time or place them separately.  On the
- * matrix-core path the call is two launches: a small kernel that turns `offsets` into the tile
- * lists and hand-out counters (kept in the workspace), and the launch that computes both
- * projections from them.  parts = 1 issues the first, parts = 2 the second, parts = 3 both
- * (exactly mohge_expert_ffn).  A parts = 2 call consumes the lists: each needs a parts = 1 call
- * with the same cfg, offsets and workspace before it, on the same stream or ordered after it;
- * without one it writes nothing useful to y_perm (no other harm).  Arguments as for
- * mohge_expert_ffn (all are checked in either step).  Only where the two launches exist:
- * cfg->dtype == MOHGE_BF16, T > 32 and the fused form enabled (mohge_tune knob 2, the default);
- * otherwise parts 1 and 2 return MOHGE_EINVAL.
- */
-int mohge_expert_ffn_parts(const mohge_config* cfg, const void* x, const int32_t* perm,
-                           const int32_t* offsets, const void* const* w13, const void* const* w2,
-                           void* y_perm, void* workspace, size_t workspace_bytes, int parts, void* stream);
 
 /*
  * mohge_expert_ffn for decode with quantised expert weights (not in the paper: halves the bytes
@@ -360,41 +353,15 @@ size_t mohge_workspace_size(const mohge_config* cfg, int which_call);
  * Diagnostic for the launches that run two dependent tile lists at once (the fused forms of
  * mohge_expert_ffn, mohge_expert_ffn_train and mohge_expert_ffn_bwd): a tile of the second list
  * waits, for a bounded number of polls, until the tiles it depends on are complete; the design
- * guarantees they are already running, and a tile that gives up all the same computes anyway and
- * leaves a flag in the workspace.  This call SYNCHRONISES `stream`, reads the flag left by the
+ * guarantees they are already running, and a tile that gives up all the same writes NaN to its
+ * output region and leaves a flag in the workspace.  This call SYNCHRONISES `stream`, reads the flag left by the
  * last call of `which_call` (MOHGE_CALL_EXPERT_FFN, MOHGE_CALL_FFN_SAVED or
  * MOHGE_CALL_EXPERT_FFN_BWD) on `workspace` (DEVICE; for MOHGE_CALL_FFN_SAVED the `saved`
- * buffer) and returns MOHGE_OK, or MOHGE_ETIMEOUT when that call's output must not be trusted.
- * MOHGE_OK at once where the call has no such launch for cfg (fp32, decode sizes, knob 2 = 0).
+ * buffer) and returns MOHGE_OK, or MOHGE_ETIMEOUT when that call's output holds NaN tiles.
+ * MOHGE_OK at once where the call has no such launch for cfg (fp32, decode sizes).
  */
 int mohge_fused_status(const mohge_config* cfg, int which_call, const void* workspace,
                        size_t workspace_bytes, void* stream);
-
-/*
- * Measurement aids (not part of the layer): what the box delivers, for reading the kernels'
- * fractions against measured ceilings.
- * mohge_probe_read enqueues a kernel that reads the first *bytes_read <= bytes bytes of buf
- * (DEVICE) exactly once and does nothing else: row_bytes = 0 as contiguous streams; otherwise
- * (a multiple of 512) with the access pattern of the decode kernels on rows of that size, the
- * waves walking their rows in step (staggered = 0) or each from a different start (1).  out:
- * DEVICE, at least 16 bytes, may receive a dummy value.  bytes_read: HOST.
- * mohge_probe_mfma enqueues 1024 workgroups that issue nothing but independent chains of
- * v_mfma_f32_32x32x16_bf16, `iters` per chain; *flops (HOST) receives the FLOPs of the launch;
- * out: DEVICE, at least 1 MiB.  Time either with events on `stream`.
- */
-int mohge_probe_read(const void* buf, size_t bytes, int row_bytes, int staggered, void* out,
-                     size_t* bytes_read, void* stream);
-int mohge_probe_mfma(void* out, size_t out_bytes, int iters, double* flops, void* stream);
-
-/* Tuning hook for benchmarks: knob 0 / 1 forces the token-tile height (64, 128, 192 or
- * 256 rows; 0 = chosen per call from the routed counts) of the up / down projection of the
- * bf16 prefill path; knob 2 = 0 runs the up and the down projection of mohge_expert_ffn /
- * mohge_expert_ffn_train as two launches instead of one fused launch (1, the default).
- * Knob 3 (test hook) sets the number of polls a dependent tile of a fused launch waits (0 = the
- * default, about a second; negative = give up without looking, which makes mohge_fused_status
- * report MOHGE_ETIMEOUT and the output unreliable).  Results do not depend on knobs 0-2.
- * Process-wide, not thread-safe. */
-int mohge_tune(int knob, int value);
 
 /* Message of the last error on this thread ("" if none); valid until the next call. */
 const char* mohge_last_error(void);

@@ -7,10 +7,11 @@ if `libmohge.so` has not been built, loading fails.
 """
 from .binding import (  # noqa: F401
     MohgeError, Config, lib, lib_path, mohge_route, mohge_permute, mohge_permute_static, mohge_expert_ffn, mohge_expert_ffn_up, mohge_expert_ffn_down,
-    mohge_combine, mohge_aux_loss, mohge_workspace_size, mohge_tune, mohge_last_error, pack_w13,
+    mohge_combine, mohge_aux_loss, mohge_workspace_size, mohge_last_error, pack_w13,
     MoHGELayer, CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS, SELECT_GLOBAL, SELECT_PER_GROUP,
     F32, BF16, CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE, mohge_expert_ffn_train,
     mohge_combine_bwd, mohge_expert_ffn_bwd, mohge_route_bwd,
     mohge_shared_routing, mohge_combine_add, SharedExperts, mohge_expert_ffn_w8, mohge_fp8_decode,
-    quantize_rows_e4m3, mohge_expert_ffn_parts, mohge_fused_status, mohge_probe_read, mohge_probe_mfma, mohge_expert_ffn_w4, mohge_mxfp4_decode, quantize_mxfp4,
+    mohge_fused_status, mohge_expert_ffn_w4, mohge_mxfp4_decode,
 )
+from .weights import quantize_rows_e4m3, quantize_mxfp4  # noqa: F401

@@ -20,8 +20,8 @@ F32, BF16 = 0, 1
 CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
 CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE = 3, 4, 5, 6
 
-EXPORTS = ["mohge_route", "mohge_permute", "mohge_permute_static", "mohge_expert_ffn", "mohge_combine", "mohge_aux_loss",
-           "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_expert_ffn_parts", "mohge_tune", "mohge_fused_status", "mohge_probe_read", "mohge_probe_mfma",
+EXPORTS = ["mohge_route", "mohge_permute", "mohge_permute_static", "mohge_expert_ffn", "mohge_combine",
+           "mohge_aux_loss", "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_fused_status",
            "mohge_expert_ffn_train", "mohge_expert_ffn_w8", "mohge_fp8_decode", "mohge_expert_ffn_w4",
            "mohge_mxfp4_decode", "mohge_combine_bwd",
            "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_shared_routing", "mohge_combine_add",
@@ -126,10 +126,6 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def mohge_tune(knob: int, value: int):
-    _check(lib().mohge_tune(C.c_int(knob), C.c_int(value)), "mohge_tune")
-
-
 def mohge_workspace_size(cfg: Config, which_call: int) -> int:
     return int(lib().mohge_workspace_size(cfg.ref(), C.c_int(which_call)))
 
@@ -170,35 +166,12 @@ def mohge_expert_ffn(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], w2: Seq
                                   _stream()), "mohge_expert_ffn")
 
 
-def mohge_probe_read(buf: torch.Tensor, row_bytes: int, staggered: bool, out: torch.Tensor) -> int:
-    """Enqueues the read probe on buf; returns the bytes the kernel reads."""
-    n = C.c_size_t(0)
-    _check(lib().mohge_probe_read(_ptr(buf), _nbytes(buf), C.c_int(row_bytes), C.c_int(int(staggered)), _ptr(out),
-                                  C.byref(n), _stream()), "mohge_probe_read")
-    return n.value
-
-
-def mohge_probe_mfma(out: torch.Tensor, iters: int) -> float:
-    """Enqueues the MFMA probe; returns the FLOPs of the launch."""
-    f = C.c_double(0.0)
-    _check(lib().mohge_probe_mfma(_ptr(out), _nbytes(out), C.c_int(iters), C.byref(f), _stream()), "mohge_probe_mfma")
-    return f.value
-
-
 def mohge_fused_status(cfg, which_call: int, workspace) -> int:
     """Synchronises; 0, or MOHGE_ETIMEOUT (-6) when a tile of the last fused launch gave up waiting."""
     rc = lib().mohge_fused_status(cfg.ref(), C.c_int(which_call), _ptr(workspace), _nbytes(workspace), _stream())
     if rc not in (0, -6):
         _check(rc, "mohge_fused_status")
     return rc
-
-
-def mohge_expert_ffn_parts(cfg, x, perm, offsets, w13, w2, y_perm, workspace, parts: int):
-    for t in list(w13) + list(w2):
-        _ptr(t)
-    _check(lib().mohge_expert_ffn_parts(cfg.ref(), _ptr(x), _ptr(perm), _ptr(offsets), _ptr_table(w13),
-                                        _ptr_table(w2), _ptr(y_perm), _ptr(workspace), _nbytes(workspace),
-                                        C.c_int(parts), _stream()), "mohge_expert_ffn_parts")
 
 
 def mohge_expert_ffn_w8(cfg, x, perm, offsets, w13q, w13_scale, w2q, w2_scale, y_perm, workspace):
@@ -215,18 +188,6 @@ def mohge_fp8_decode(codes: torch.Tensor, out: torch.Tensor):
            "mohge_fp8_decode")
 
 
-def quantize_rows_e4m3(w: torch.Tensor):
-    """Per-row FP8 E4M3 quantisation of a weight tensor [..., rows, cols] (argument preparation,
-    done with torch): scale[row] = max|row| / 448 (1 for an all-zero row), codes = the row divided
-    by its scale, rounded to nearest even.  Returns (codes uint8 of w's shape, scales f32 of
-    w's shape without the last axis)."""
-    wf = w.float()
-    amax = wf.abs().amax(dim=-1)
-    scale = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
-    codes = (wf / scale.unsqueeze(-1)).to(torch.float8_e4m3fn).view(torch.uint8)
-    return codes.contiguous(), scale.contiguous()
-
-
 def mohge_expert_ffn_w4(cfg, x, perm, offsets, w13q, w13_scale, w2q, w2_scale, y_perm, workspace):
     for t in list(w13q) + list(w13_scale) + list(w2q) + list(w2_scale):
         _ptr(t)
@@ -241,33 +202,6 @@ def mohge_mxfp4_decode(packed: torch.Tensor, scales: torch.Tensor, out: torch.Te
            "mohge_mxfp4_decode")
 
 
-def quantize_mxfp4(w: torch.Tensor):
-    """MXFP4 quantisation of a weight tensor [..., rows, cols], cols a multiple of 32 (argument
-    preparation, done with torch): per block of 32 elements of a row the shared scale is
-    2^(floor(log2 max|block|) - 2) (the largest E2M1 magnitude is 6 = 1.5 * 2^2), kept within scale
-    codes 1..254; elements are divided by it, rounded to the nearest E2M1 value (ties to the even
-    code) and clamped to +-6.  Returns (packed uint8 [..., rows, cols/2], two codes per byte, even
-    element in the low four bits; scale codes uint8 [..., rows, cols/32])."""
-    K = w.shape[-1]
-    if K % 32:
-        raise MohgeError(f"quantize_mxfp4: last dimension {K} is not a multiple of 32")
-    blk = w.float().reshape(*w.shape[:-1], K // 32, 32)
-    amax = blk.abs().amax(dim=-1, keepdim=True)
-    _, ex = torch.frexp(amax)                      # amax = m * 2^ex, m in [0.5, 1): floor(log2) = ex - 1
-    e = torch.where(amax > 0, ex - 1 - 2, torch.zeros_like(ex)).clamp(-126, 127)
-    v = torch.ldexp(blk, -e)
-    m = v.abs()
-    code = torch.zeros_like(m, dtype=torch.int32)
-    for j, mid in enumerate((0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0)):
-        # from an even code to the odd one above it only when strictly past the midpoint
-        code += ((m > mid) if j % 2 == 0 else (m >= mid)).to(torch.int32)
-    code |= (v < 0).to(torch.int32) << 3
-    code = code.reshape(*w.shape[:-1], K // 2, 2)
-    packed = (code[..., 0] | (code[..., 1] << 4)).to(torch.uint8)
-    scales = (e.squeeze(-1) + 127).to(torch.uint8)
-    return packed.contiguous(), scales.contiguous()
-
-
 def mohge_expert_ffn_up(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], h):
     for t in w13:
         _ptr(t)
@@ -279,7 +213,7 @@ def mohge_expert_ffn_up(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], h):
 def mohge_expert_ffn_down(cfg, h, offsets, w2: Sequence[torch.Tensor], y_perm):
     for t in w2:
         _ptr(t)
-    _check(lib().mohge_expert_ffn_down(cfg.ref(), _ptr(h), _ptr(offsets), _ptr_table(w2),
+    _check(lib().mohge_expert_ffn_down(cfg.ref(), _ptr(h), _nbytes(h), _ptr(offsets), _ptr_table(w2),
                                        _ptr(y_perm), _stream()), "mohge_expert_ffn_down")
 
 
@@ -422,6 +356,8 @@ class MoHGELayer:
         self.bias = expert_logit_bias
         self.training = training
         self.shared = shared
+        self.ffn_options = None   # bench_binding.FfnOptions: the expert calls then go through the
+                                  # benchmark library with these launch options (tests, benchmarks)
         self.w8 = None          # (codes13, scales13, codes2, scales2) once use_fp8_weights() was called
         self.w4 = None          # the same for MXFP4 weights, once use_mxfp4_weights() was called
         T, P, Ne, Ng = cfg.T, cfg.n_pairs, cfg.n_experts, cfg.n_groups
@@ -473,7 +409,15 @@ class MoHGELayer:
                     self.gates, self.gs, self.es1, self.ws_route)
         mohge_permute(c, self.expert_idx, self.counts, self.offsets, self.perm, self.inv_perm,
                       None, None, self.ws_permute)
-        if self.has_backward:
+        if self.ffn_options is not None:
+            from . import bench_binding as BB
+            if self.has_backward:
+                BB.mohge_bench_expert_ffn_train(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm,
+                                                self.saved, self.ffn_options)
+            else:
+                BB.mohge_bench_expert_ffn(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm,
+                                          self.ws_ffn, self.ffn_options)
+        elif self.has_backward:
             mohge_expert_ffn_train(c, x, self.perm, self.offsets, self.w13, self.w2, self.y_perm,
                                    self.saved)
         elif self.w8 is not None:
@@ -496,6 +440,7 @@ class MoHGELayer:
         forward() stream those instead of the bf16 weights."""
         if self.cfg.T > 32 or self.cfg.dtype != BF16 or self.has_backward:
             raise MohgeError("FP8 expert weights are served by the bf16 decode path only (T <= 32)")
+        from .weights import quantize_rows_e4m3
         q = [quantize_rows_e4m3(w) for w in self.w13], [quantize_rows_e4m3(w) for w in self.w2]
         self.w8 = ([c for c, _ in q[0]], [s for _, s in q[0]], [c for c, _ in q[1]], [s for _, s in q[1]])
         self.w4 = None
@@ -505,6 +450,7 @@ class MoHGELayer:
         stream those instead of the bf16 weights."""
         if self.cfg.T > 32 or self.cfg.dtype != BF16 or self.has_backward:
             raise MohgeError("MXFP4 expert weights are served by the bf16 decode path only (T <= 32)")
+        from .weights import quantize_mxfp4
         q = [quantize_mxfp4(w) for w in self.w13], [quantize_mxfp4(w) for w in self.w2]
         self.w8 = None
         self.w4 = ([c for c, _ in q[0]], [s for _, s in q[0]], [c for c, _ in q[1]], [s for _, s in q[1]])
@@ -540,8 +486,14 @@ class MoHGELayer:
             raise MohgeError("backward needs a layer created with training=True, backward=True")
         c = self.cfg
         mohge_combine_bwd(c, dy, self.y_perm, self.inv_perm, self.gates, self.dgates, self.dy_perm)
-        mohge_expert_ffn_bwd(c, x, self.perm, self.offsets, self.w13, self.w2, self.saved,
-                             self.dy_perm, self.dx_perm, self.dw13, self.dw2, self.ws_ffn_bwd)
+        if self.ffn_options is not None:
+            from . import bench_binding as BB
+            BB.mohge_bench_expert_ffn_bwd(c, x, self.perm, self.offsets, self.w13, self.w2, self.saved,
+                                          self.dy_perm, self.dx_perm, self.dw13, self.dw2, self.ws_ffn_bwd,
+                                          self.ffn_options)
+        else:
+            mohge_expert_ffn_bwd(c, x, self.perm, self.offsets, self.w13, self.w2, self.saved,
+                                 self.dy_perm, self.dx_perm, self.dw13, self.dw2, self.ws_ffn_bwd)
         mohge_route_bwd(c, x, self.w_group, self.w_expert, self.gs, self.es1, self.group_idx,
                         self.expert_idx, self.gates, self.dgates, self.stats, self.dx_perm,
                         self.inv_perm, self.dx, self.dw_group, self.dw_expert, self.dz,

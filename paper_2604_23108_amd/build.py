@@ -1,4 +1,6 @@
-"""Builds libmohge.so (the C-ABI HIP library) in-tree with hipcc for gfx950."""
+"""Builds the two shared libraries in-tree with hipcc for gfx950: libmohge.so (the C-ABI layer
+library, include/mohge.h) and libmohge_bench.so (measurement and test aids, include/mohge_bench.h,
+linked against the first)."""
 from __future__ import annotations
 
 import concurrent.futures as cf
@@ -10,10 +12,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmohge.so")
+BENCH_LIB = os.path.join(HERE, "libmohge_bench.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 SOURCES = ["api.hip", "route.hip", "permute.hip", "ffn.hip", "ffn_tiled.hip", "ffn_skinny.hip",
-           "combine.hip", "aux_loss.hip", "ffn_bwd.hip", "route_bwd.hip", "box_probe.hip"]
+           "combine.hip", "aux_loss.hip", "ffn_bwd.hip", "route_bwd.hip"]
+BENCH_SOURCES = ["bench_api.hip", "box_probe.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
@@ -32,23 +36,22 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(verbose: bool = False) -> str:
-    global LIB, OBJDIR
-    if os.environ.get("MOHGE_PROBE"):      # instrumented build for timing probes, separate file
-        FLAGS.append("-DMOHGE_PROBE")
-        if os.environ.get("MOHGE_EXP"):
-            FLAGS.append("-D" + os.environ["MOHGE_EXP"])
-        LIB = os.path.join(HERE, "libmohge_probe.so")
-        OBJDIR = os.path.join(HERE, "_build_probe")
-    os.makedirs(OBJDIR, exist_ok=True)
-    with cf.ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
-        objs = list(ex.map(_compile, SOURCES))
-    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+def _link(out: str, objs, extra=()) -> None:
+    cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs, *extra]
     p = subprocess.run(cmd, capture_output=True, text=True)
     if p.returncode != 0:
         raise RuntimeError("link failed:\n" + p.stderr)
+
+
+def build(verbose: bool = False) -> str:
+    os.makedirs(OBJDIR, exist_ok=True)
+    with cf.ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(_compile, SOURCES + BENCH_SOURCES))
+    _link(LIB, objs[:len(SOURCES)])
+    # the benchmark library finds libmohge.so next to itself
+    _link(BENCH_LIB, objs[len(SOURCES):], ["-L", HERE, "-lmohge", "-Wl,-rpath,$ORIGIN"])
     if verbose:
-        print("built", LIB)
+        print("built", LIB, "and", BENCH_LIB)
     return LIB
 
 

@@ -57,7 +57,7 @@ int check_config(const mohge_config* c, LayerDesc* L) {
   return MOHGE_OK;
 }
 
-static int need(const void* p, const char* name, bool required = true) {
+int need(const void* p, const char* name, bool required) {
   if (!p) {
     if (!required) return MOHGE_OK;
     set_error("%s is NULL", name);
@@ -67,7 +67,7 @@ static int need(const void* p, const char* name, bool required = true) {
   return MOHGE_OK;
 }
 
-static int hip_rc(hipError_t e, const char* what) {
+int hip_rc(hipError_t e, const char* what) {
   if (e == hipSuccess) return MOHGE_OK;
   set_error("%s: %s", what, hipGetErrorString(e));
   return MOHGE_EHIP;
@@ -77,7 +77,7 @@ static int hip_rc(hipError_t e, const char* what) {
 
 using namespace mohge;
 
-#define NEED(p) do { int rc_ = need((p), #p); if (rc_) return rc_; } while (0)
+#define NEED(p) do { int rc_ = need((p), #p, true); if (rc_) return rc_; } while (0)
 #define OPT(p) do { int rc_ = need((p), #p, false); if (rc_) return rc_; } while (0)
 
 extern "C" {
@@ -111,35 +111,6 @@ int mohge_fused_status(const mohge_config* cfg, int which_call, const void* work
     set_error("a dependent tile of the fused launch gave up waiting for its row block: output unreliable");
     return MOHGE_ETIMEOUT;
   }
-  return MOHGE_OK;
-}
-
-int mohge_probe_read(const void* buf, size_t bytes, int row_bytes, int staggered, void* out,
-                     size_t* bytes_read, void* stream) {
-  NEED(buf); NEED(out);
-  if (!bytes_read) { set_error("bytes_read is NULL"); return MOHGE_ENULL; }
-  if (row_bytes < 0 || (row_bytes != 0 && (row_bytes % 512 != 0 || row_bytes > (1 << 20)))) {
-    set_error("mohge_probe_read: row_bytes = %d (0, or a multiple of 512 up to 1 MiB)", row_bytes);
-    return MOHGE_EINVAL;
-  }
-  return hip_rc(launch_probe_read(buf, bytes, row_bytes, staggered != 0, out, bytes_read, (hipStream_t)stream),
-                "mohge_probe_read");
-}
-
-int mohge_probe_mfma(void* out, size_t out_bytes, int iters, double* flops, void* stream) {
-  NEED(out);
-  if (!flops) { set_error("flops is NULL"); return MOHGE_ENULL; }
-  const int blocks = 1024;
-  if (out_bytes < (size_t)blocks * 256 * sizeof(float)) {
-    set_error("mohge_probe_mfma: out holds %zu bytes, %zu needed", out_bytes, (size_t)blocks * 256 * sizeof(float));
-    return MOHGE_EWORKSPACE;
-  }
-  if (iters < 1 || iters > (1 << 20)) { set_error("mohge_probe_mfma: iters = %d outside 1..2^20", iters); return MOHGE_EINVAL; }
-  return hip_rc(launch_probe_mfma(out, blocks, iters, flops, (hipStream_t)stream), "mohge_probe_mfma");
-}
-
-int mohge_tune(int knob, int value) {
-  if (tune_tiled(knob, value)) { set_error("mohge_tune: knob %d / value %d out of range", knob, value); return MOHGE_EINVAL; }
   return MOHGE_OK;
 }
 
@@ -237,38 +208,6 @@ int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm
   return hip_rc(launch_expert_ffn(L, cfg->dtype, x, perm, offsets, W, y_perm, workspace,
                                   (hipStream_t)stream, 3),
                 "mohge_expert_ffn");
-}
-
-int mohge_expert_ffn_parts(const mohge_config* cfg, const void* x, const int32_t* perm,
-                           const int32_t* offsets, const void* const* w13, const void* const* w2,
-                           void* y_perm, void* workspace, size_t workspace_bytes, int parts, void* stream) {
-  if (parts == 3) return mohge_expert_ffn(cfg, x, perm, offsets, w13, w2, y_perm, workspace, workspace_bytes, stream);
-  LayerDesc L;
-  int rc = check_config(cfg, &L);
-  if (rc) return rc;
-  if (parts != 1 && parts != 2) { set_error("mohge_expert_ffn_parts: parts = %d (1, 2 or 3)", parts); return MOHGE_EINVAL; }
-  if (!ffn_parts_supported(L, cfg->dtype)) {
-    set_error("mohge_expert_ffn_parts: schedule and product launch are separate launches only on the fused "
-              "matrix-core path (MOHGE_BF16, T > 32, mohge_tune(2, 1))");
-    return MOHGE_EINVAL;
-  }
-  NEED(x); OPT(perm); NEED(offsets); NEED(y_perm); NEED(workspace);
-  if (!w13 || !w2) { set_error("w13 / w2 pointer table is NULL"); return MOHGE_ENULL; }
-  GroupPtrs W;
-  memset(&W, 0, sizeof(W));
-  for (int g = 0; g < L.Ng; ++g) {
-    NEED(w13[g]); NEED(w2[g]);
-    W.w13[g] = w13[g];
-    W.w2[g] = w2[g];
-  }
-  if (workspace_bytes < ffn_workspace_bytes(L, cfg->dtype)) {
-    set_error("expert_ffn workspace: %zu bytes given, %zu needed", workspace_bytes,
-              ffn_workspace_bytes(L, cfg->dtype));
-    return MOHGE_EWORKSPACE;
-  }
-  return hip_rc(launch_expert_ffn(L, cfg->dtype, x, perm, offsets, W, y_perm, workspace,
-                                  (hipStream_t)stream, 3, parts),
-                "mohge_expert_ffn_parts");
 }
 
 static int need_bf16(const mohge_config* cfg, const char* what) {
@@ -383,7 +322,7 @@ int mohge_expert_ffn_up(const mohge_config* cfg, const void* x, const int32_t* p
                 "mohge_expert_ffn_up");
 }
 
-int mohge_expert_ffn_down(const mohge_config* cfg, const void* h, const int32_t* offsets,
+int mohge_expert_ffn_down(const mohge_config* cfg, const void* h, size_t h_bytes, const int32_t* offsets,
                           const void* const* w2, void* y_perm, void* stream) {
   LayerDesc L;
   int rc = check_config(cfg, &L);
@@ -393,6 +332,10 @@ int mohge_expert_ffn_down(const mohge_config* cfg, const void* h, const int32_t*
   GroupPtrs W;
   memset(&W, 0, sizeof(W));
   for (int g = 0; g < L.Ng; ++g) { NEED(w2[g]); W.w2[g] = w2[g]; }
+  if (h_bytes < ffn_workspace_bytes(L, cfg->dtype)) {
+    set_error("expert_ffn_down: h has %zu bytes, %zu needed", h_bytes, ffn_workspace_bytes(L, cfg->dtype));
+    return MOHGE_EWORKSPACE;
+  }
   if (L.T == 0) return MOHGE_OK;
   return hip_rc(launch_expert_ffn(L, cfg->dtype, nullptr, nullptr, offsets, W, y_perm,
                                   const_cast<void*>(h), (hipStream_t)stream, 2),
@@ -431,6 +374,7 @@ int mohge_shared_routing(const mohge_config* cfg, int32_t* expert_idx, float* ga
     return MOHGE_EINVAL;
   }
   NEED(expert_idx); NEED(gates); NEED(counts); NEED(offsets); NEED(perm); NEED(inv_perm);
+  if (L.T == 0) return MOHGE_OK;
   return hip_rc(launch_shared_routing(L, expert_idx, gates, counts, offsets, perm, inv_perm,
                                       (hipStream_t)stream),
                 "mohge_shared_routing");

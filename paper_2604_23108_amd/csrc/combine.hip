@@ -99,10 +99,11 @@ __global__ void __launch_bounds__(256) shared_routing_kernel(int T, int N, int32
     const int s_of_r = (int)(i / T), t_of_r = (int)(i % T);     // i as sorted position
     perm[i] = t_of_r * N + s_of_r;
   }
-  if (blockIdx.x == 0 && threadIdx.x <= (unsigned)N) {
-    offsets[threadIdx.x] = threadIdx.x * T;
-    if (threadIdx.x < (unsigned)N) counts[threadIdx.x] = T;
-  }
+  if (blockIdx.x == 0)
+    for (int i = threadIdx.x; i <= N; i += 256) {      // N can equal the block size
+      offsets[i] = i * T;
+      if (i < N) counts[i] = T;
+    }
 }
 
 hipError_t launch_shared_routing(const LayerDesc& L, int32_t* expert_idx, float* gates,

@@ -25,8 +25,25 @@ struct GroupPtrs {
   const void* w2[kMaxGroups];     // [N, d, F_g]
 };
 
+// How the matrix-core path of the expert networks is launched.  The entry points of mohge.h use
+// the defaults; the benchmark library passes its caller's choices.  Results do not depend on any
+// of these (except a negative spin_limit, a test hook).
+struct FfnOptions {
+  int tile_rows[2] = {0, 0};  // token-tile height of the up / down list: 0 = chosen per call, else 64..256
+  int fused = 1;              // both projections (dH and dX; the two weight gradients) in one launch
+  int spin_limit = 0;         // polls a dependent tile waits: 0 = default (about a second), < 0 = give up at once
+  int band = 4;               // row blocks per band of the tile order inside an expert
+  int group_major = 0;        // 1: experts visited group by group, 0: by all-size sets
+  int steal = 1;              // workgroups whose XCD range is exhausted help the other ranges
+  long long* cycles = nullptr;  // DEVICE, optional: per-workgroup clock counters of the fused launch
+  int cycles_launch = 0;      // backward: which of the two fused launches fills `cycles` (0 = dH/dX, 1 = weight gradients)
+};
+
 void set_error(const char* fmt, ...);
 int check_config(const mohge_config* cfg, LayerDesc* out);
+// pointer check shared by the entry points: NULL (when required) and 16-byte alignment
+int need(const void* p, const char* name, bool required);
+int hip_rc(hipError_t e, const char* what);
 
 // bf16 <-> fp32 on the device, bit level (round to nearest even on the way down)
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) {
@@ -77,10 +94,8 @@ hipError_t launch_permute_static(const LayerDesc& L, int dtype, const int32_t* e
 size_t ffn_workspace_bytes(const LayerDesc& L, int dtype);
 hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                             hipStream_t s, int stages, int parts = 3);   // stages: bit 0 = up, bit 1 = down
-hipError_t launch_probe_read(const void* buf, size_t bytes, int row_bytes, int staggered, void* out,
-                             size_t* bytes_read, hipStream_t s);
-hipError_t launch_probe_mfma(void* out, int blocks, int iters, double* flops, hipStream_t s);
+                             hipStream_t s, int stages, int parts = 3,
+                             const FfnOptions& o = FfnOptions());   // stages: bit 0 = up, bit 1 = down
 bool ffn_parts_supported(const LayerDesc& L, int dtype);
 // byte offset of the schedule header that carries the "gave up waiting" flag of a fused launch in
 // the workspace of call `which_call`, or -1 where the call has no fused launch
@@ -95,7 +110,7 @@ hipError_t launch_shared_routing(const LayerDesc& L, int32_t* expert_idx, float*
 size_t ffn_saved_bytes(const LayerDesc& L);
 hipError_t launch_expert_ffn_train(const LayerDesc& L, const void* x, const int32_t* perm,
                                    const int32_t* offsets, const GroupPtrs& W, void* y_perm,
-                                   void* saved, hipStream_t s);
+                                   void* saved, hipStream_t s, const FfnOptions& o = FfnOptions());
 hipError_t launch_combine_bwd(const LayerDesc& L, const void* dy, const void* y_perm,
                               const int32_t* inv_perm, const float* gates, float* dgates,
                               void* dy_perm, hipStream_t s);
@@ -103,7 +118,8 @@ size_t ffn_bwd_workspace_bytes(const LayerDesc& L);
 hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_t* perm,
                                  const int32_t* offsets, const GroupPtrs& W, const void* saved,
                                  const void* dy_perm, void* dx_perm, void* const* dw13,
-                                 void* const* dw2, void* ws, hipStream_t s);
+                                 void* const* dw2, void* ws, hipStream_t s,
+                                 const FfnOptions& o = FfnOptions());
 size_t route_bwd_workspace_bytes(const LayerDesc& L);
 hipError_t launch_route_bwd(const LayerDesc& L, const mohge_config& cfg, const void* x,
                             const float* w_group, const float* w_expert, const float* gs,
@@ -111,7 +127,6 @@ hipError_t launch_route_bwd(const LayerDesc& L, const mohge_config& cfg, const v
                             const float* gates, const float* dgates, const float* stats,
                             const void* dx_perm, const int32_t* inv_perm, void* dx, float* dw_group,
                             float* dw_expert, float* dz_out, void* ws, hipStream_t s);
-int tune_tiled(int knob, int value);
 size_t tiled_sched_bytes(const LayerDesc& L);
 size_t aux_workspace_bytes(const LayerDesc& L);
 hipError_t launch_aux_loss(const LayerDesc& L, const mohge_config& cfg, const float* gs,

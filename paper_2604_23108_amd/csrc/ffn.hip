@@ -7,7 +7,7 @@ namespace mohge {
 
 hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* perm,
                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                            hipStream_t s, int stages, void* pre, int parts = 3);
+                            hipStream_t s, int stages, void* pre, int parts, const FfnOptions& o);
 hipError_t launch_ffn_skinny(const LayerDesc& L, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
                              hipStream_t s, int stages, const float* const* s13, const float* const* s2,
@@ -107,18 +107,18 @@ size_t ffn_workspace_bytes(const LayerDesc& L, int dtype) {
 
 hipError_t launch_expert_ffn(const LayerDesc& L, int dtype, const void* x, const int32_t* perm,
                              const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                             hipStream_t s, int stages, int parts) {
+                             hipStream_t s, int stages, int parts, const FfnOptions& o) {
   if (dtype == MOHGE_F32) return launch_ffn_f32(L, x, perm, offsets, W, y_perm, ws, s, stages);
   // With at most 32 tokens no expert can receive more than 32 rows: one pass of the
   // weight-streaming kernel covers it.  Otherwise the tiled matrix-core kernel.
   if (use_skinny(L)) return launch_ffn_skinny(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr, nullptr);
-  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr, parts);
+  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, ws, s, stages, nullptr, parts, o);
 }
 
 size_t ffn_bwd_waiting_header_offset(const LayerDesc& L);
 
 long long fused_flag_offset(const LayerDesc& L, int dtype, int which_call) {
-  if (dtype != MOHGE_BF16 || !fused_launches()) return -1;
+  if (dtype != MOHGE_BF16) return -1;
   switch (which_call) {
     case MOHGE_CALL_EXPERT_FFN: return use_skinny(L) ? -1 : (long long)tiled_waiting_header_offset(L);
     case MOHGE_CALL_FFN_SAVED: return (long long)tiled_waiting_header_offset(L);   // training forward: tile path for every T
@@ -128,9 +128,9 @@ long long fused_flag_offset(const LayerDesc& L, int dtype, int which_call) {
 }
 
 // the schedule and the product launch of the forward can be issued separately only where they
-// are two launches: the fused matrix-core path
+// are two launches: the fused form of the matrix-core path
 bool ffn_parts_supported(const LayerDesc& L, int dtype) {
-  return dtype == MOHGE_BF16 && !use_skinny(L) && fused_launches();
+  return dtype == MOHGE_BF16 && !use_skinny(L);
 }
 
 // Decode with FP8 E4M3 weights (one fp32 scale per weight row): the weight-streaming kernel only
@@ -170,9 +170,9 @@ const void* saved_pre(const LayerDesc& L, const void* saved) {
 
 hipError_t launch_expert_ffn_train(const LayerDesc& L, const void* x, const int32_t* perm,
                                    const int32_t* offsets, const GroupPtrs& W, void* y_perm,
-                                   void* saved, hipStream_t s) {
+                                   void* saved, hipStream_t s, const FfnOptions& o) {
   void* pre = static_cast<unsigned char*>(saved) + saved_pre_offset(L);
-  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, saved, s, 3, pre);
+  return launch_ffn_tiled(L, x, perm, offsets, W, y_perm, saved, s, 3, pre, 3, o);
 }
 
 }  // namespace mohge

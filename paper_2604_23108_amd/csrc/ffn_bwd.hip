@@ -26,10 +26,6 @@ namespace mohge {
 
 const void* saved_h(const LayerDesc& L, const void* saved);
 const void* saved_pre(const LayerDesc& L, const void* saved);
-#ifdef MOHGE_PROBE
-extern long long* g_dbg;     // cycle counters of the instrumented build
-extern int g_dbg_which;      // which of the four launches fills them
-#endif
 
 // ---------------------------------------------------------------------------------------
 // workspace layout and the launch sequence
@@ -65,7 +61,7 @@ size_t ffn_bwd_waiting_header_offset(const LayerDesc& L) { return bwd_layout(L).
 hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_t* perm,
                                  const int32_t* offsets, const GroupPtrs& W, const void* saved,
                                  const void* dy_perm, void* dx_perm, void* const* dw13,
-                                 void* const* dw2, void* ws, hipStream_t s) {
+                                 void* const* dw2, void* ws, hipStream_t s, const FfnOptions& o) {
   const BwdLayout lay = bwd_layout(L);
   unsigned char* base = static_cast<unsigned char*>(ws);
   uint16_t* zero_row = reinterpret_cast<uint16_t*>(base + lay.zero);
@@ -76,6 +72,7 @@ hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_
   t.offsets = offsets;
   t.Ke = L.Ke; t.Ng = L.Ng; t.N = L.N; t.Ne = L.Ne; t.d = L.d; t.P = L.P;
   t.ncu = tile_num_cus();
+  apply_options(t, o);
   t.ldpre = 2 * L.Fmax;
   for (int g = 0; g < kMaxGroups; ++g) t.order[g] = g;
   for (int i = 1; i < L.Ng; ++i)
@@ -108,22 +105,21 @@ hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_
   w2a.zero_row = w13a.zero_row = zero_row;
   w2a.force_rows = w13a.force_rows = 256;
   for (int g = 0; g < L.Ng; ++g) {
-    dh.F[g] = L.F[g]; dh.W[g] = static_cast<const uint16_t*>(W.w2[g]);
-    dxa.F[g] = 2 * L.F[g]; dxa.W[g] = static_cast<const uint16_t*>(W.w13[g]);
+    dh.F[g] = L.F[g]; dh.W[g] = static_cast<const uint16_t*>(W.w2[g]); dh.ldw[g] = L.F[g];
+    dxa.F[g] = 2 * L.F[g]; dxa.W[g] = static_cast<const uint16_t*>(W.w13[g]); dxa.ldw[g] = L.d;
     w2a.F[g] = L.F[g]; w2a.Mrows[g] = L.d; w2a.Ncols[g] = L.F[g];
     w2a.Wout[g] = static_cast<uint16_t*>(dw2[g]);
     w13a.F[g] = L.F[g]; w13a.Mrows[g] = 2 * L.F[g]; w13a.Ncols[g] = L.d;
     w13a.Wout[g] = static_cast<uint16_t*>(dw13[g]);
   }
 
-#ifdef MOHGE_PROBE
-  {
-    TileArgs* sel[4] = {&dh, &dxa, &w2a, &w13a};
-    if (g_dbg_which >= 0 && g_dbg_which < 4) sel[g_dbg_which]->dbg = g_dbg;
+  // optional clock counters of one of the two fused launches (both lists of a launch share them)
+  if (o.cycles) {
+    if (o.cycles_launch == 0) dh.cycles = dxa.cycles = o.cycles;
+    else w2a.cycles = w13a.cycles = o.cycles;
   }
-#endif
   // fused form: dX tiles wait for the row-block counters the dH tiles increment
-  const bool fused = fused_launches();
+  const bool fused = o.fused != 0;
   if (fused) {
     dh.coherent_out = 1;
     dh.fam_done = dxa.fam_done = reinterpret_cast<int*>(base + lay.fam);
@@ -133,7 +129,7 @@ hipError_t launch_expert_ffn_bwd(const LayerDesc& L, const void* x, const int32_
   GatherArgs ga;
   ga.x = static_cast<const uint4*>(x); ga.perm = perm; ga.xs = reinterpret_cast<uint4*>(xs);
   ga.zero_row = reinterpret_cast<uint4*>(zero_row); ga.P = L.P; ga.Ke = L.Ke; ga.chunks = L.d / 8;
-  hipError_t e = launch_bwd_schedules(dh, dxa, w2a, w13a, ga, s);
+  hipError_t e = launch_bwd_schedules(dh, dxa, w2a, w13a, ga, fused, s);
   if (e != hipSuccess) return e;
   if (fused) {
     if ((e = launch_dgrad_pair(dh, dxa, s)) != hipSuccess) return e;

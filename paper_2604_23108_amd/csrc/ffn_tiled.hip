@@ -62,6 +62,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kStagesA = 2, kStagesB = 3;   // 32 KB parts: 2 token + 3 weight = all 160 KB of LDS
 constexpr int kWGM = 2, kWGN = 4;
+constexpr int kTileCost = 18;          // cost model of the schedule: fixed part of a tile's stage, in 64-row units
 
 // gate and up rows share a tile in the two up-projection modes
 constexpr bool is_up(int mode) { return mode == kUp || mode == kUpSave; }
@@ -106,6 +107,14 @@ struct SchedShared {
 
 // Per-expert quantities of a mode: rows (`cnt`, starting at `row0`), output columns, and
 // reduction length in 64-deep stages.
+// Expert at visiting position v.  group_major: all experts of a group are neighbours, groups by
+// decreasing width (tiles of one reduction length run together and the shortest come last);
+// otherwise expert index major, group minor ("all-size sets": every stretch mixes all widths).
+__device__ __forceinline__ void visit(const TileArgs& a, int v, int& e, int& g) {
+  if (a.group_major) { g = a.order[v / a.N]; e = g * a.N + v % a.N; }
+  else { g = a.order[v % a.Ng]; e = g * a.N + v / a.Ng; }
+}
+
 template <int MODE>
 __device__ __forceinline__ void expert_dims(const TileArgs& a, int e, int g, int& row0, int& cnt,
                                             int& ncols, int& kc) {
@@ -131,8 +140,8 @@ __device__ __forceinline__ int choose_tile_rows(const TileArgs& a, SchedShared& 
   const int v = threadIdx.x, lane = v & 63, w = v >> 6;
   int cnt = 0, nt = 0, kc = 0;
   if (v < a.Ne) {
-    const int g = a.order[v % a.Ng];
-    const int e = g * a.N + v / a.Ng;
+    int e, g;
+    visit(a, v, e, g);
     int ncols, row0;
     expert_dims<MODE>(a, e, g, row0, cnt, ncols, kc);
     nt = (ncols + NCPT - 1) / NCPT;
@@ -185,11 +194,8 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   const int v = threadIdx.x, lane = v & 63, w = v >> 6;
   int e = 0, cnt = 0, nt = 0, kc = 0, row0 = 0;
   if (v < a.Ne) {
-    // visiting order: expert index major, group minor (widest group first): consecutive
-    // experts form "all-size sets", so every XCD range holds the same mix of reduction
-    // lengths instead of one range getting all the long tiles
-    const int g = a.order[v % a.Ng];
-    e = g * a.N + v / a.Ng;
+    int g;
+    visit(a, v, e, g);
     int ncols;
     expert_dims<MODE>(a, e, g, row0, cnt, ncols, kc);
     nt = (ncols + NCPT - 1) / NCPT;
@@ -197,7 +203,9 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   sh.e[v] = e; sh.cnt[v] = cnt; sh.nt[v] = nt; sh.kc[v] = kc; sh.row0[v] = row0;
   // exclusive prefix sums of tiles, cost and row blocks over the experts
   const long long my_t = (long long)((cnt + h - 1) / h) * nt;
-  const long long my_c = (long long)((cnt + 63) / 64) * nt * kc;
+  // cost of a tile = reduction stages x (kTileCost + its 64-row units): measured, a stage of a tile
+  // costs about 1850 + 100 * units clocks, so a short tile is almost as expensive as a full one
+  const long long my_c = ((long long)kTileCost * ((cnt + h - 1) / h) + (cnt + 63) / 64) * nt * kc;
   const long long my_f = MODE == kWgrad ? 0 : (cnt + h - 1) / h;
   const long long it = wave_incl_scan64(my_t, lane), ic = wave_incl_scan64(my_c, lane);
   const long long jf = wave_incl_scan64(my_f, lane);
@@ -221,10 +229,19 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
     }
     return lo;
   };
+  // Inside an expert the tiles run in bands of `band` row blocks: band after band, inside a band
+  // column tile major, row block minor.  The workgroups of an XCD draw consecutive tiles, so at any
+  // moment they work on a few row blocks x a few column tiles of one expert and share both operand
+  // panels through that XCD's L2 (an expert's whole column of row blocks per column tile would
+  // share the weight panel only).
+  const int RB = a.band > 0 ? a.band : 1;
   for (int t = v + 256 * part; t < total; t += 256 * nparts) {
     const int ve = expert_of(t);
-    const int c = sh.cnt[ve], mt = (c + h - 1) / h;
-    const int rel = t - (int)sh.tp[ve], ni = rel / mt, mi = rel % mt;
+    const int c = sh.cnt[ve], mt = (c + h - 1) / h, ntv = sh.nt[ve];
+    const int rel = t - (int)sh.tp[ve];
+    const int bnd = rel / (RB * ntv), rel2 = rel - bnd * RB * ntv;
+    const int rb = min(RB, mt - bnd * RB);
+    const int ni = rel2 / rb, mi = bnd * RB + rel2 % rb;
     TileRec r;
     r.e = sh.e[ve];
     r.row_start = sh.row0[ve] + mi * h;
@@ -241,10 +258,9 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
     a.recs[t] = r;
   }
   if (part != 0) return;                     // (workgroup-uniform: everything below is part 0's)
-  // XCD x starts at the first tile whose preceding cost is >= x/8 of the total.  Inside an
-  // expert tiles run column tile major, row tile minor, and the cost before tile (ni, mi) is
-  // (ni*units + min(mi*h/64, units)) * kc, so the tile is found arithmetically once the expert
-  // is known.
+  // XCD x starts at the first tile whose preceding cost is >= x/8 of the total.  The cost before
+  // the tile at position rel of an expert follows from the band order in closed form, so the tile
+  // is found by bisection once the expert is known.
   if (v <= kXcds) {
     int tile = total;
     if (v < kXcds) {
@@ -255,22 +271,28 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
         if (sh.cp[mid] <= target) lo = mid; else hi = mid - 1;
       }
       const int ve = lo;
-      const int c = sh.cnt[ve], kcv = sh.kc[ve];
-      const int rem = (int)(target - sh.cp[ve]);
-      if (rem <= 0 || c == 0 || kcv == 0) {
+      const int c = sh.cnt[ve], kcv = sh.kc[ve], ntv = sh.nt[ve];
+      const long long rem = target - sh.cp[ve];
+      if (rem <= 0 || c == 0 || kcv == 0 || ntv == 0) {
         tile = (int)sh.tp[ve];               // (cp[ve] == target: the expert's first tile)
         if (rem > 0) tile = (int)sh.tp[ve + 1];
       } else {
         const int mt = (c + h - 1) / h, units = (c + 63) / 64, hu = h / 64;
-        const int q = (rem + kcv - 1) / kcv;            // row units that must precede the tile
-        int ni = q / units;
-        const int r = q - ni * units;
-        int mi = 0;
-        if (r > 0) {
-          mi = (r + hu - 1) / hu;
-          if (mi >= mt) { mi = 0; ++ni; }
+        auto cost_before = [&](int rel) -> long long {
+          if (rel >= mt * ntv) return ((long long)kTileCost * mt + units) * ntv * kcv;
+          const int bnd = rel / (RB * ntv), rel2 = rel - bnd * RB * ntv;
+          const int rb = min(RB, mt - bnd * RB);
+          const int ni = rel2 / rb, mi2 = rel2 % rb;
+          const int ub = min(units - bnd * RB * hu, RB * hu);       // 64-row units of this band
+          return ((long long)kTileCost * rel + (long long)bnd * RB * hu * ntv + (long long)ni * ub +
+                  min(mi2 * hu, ub)) * kcv;
+        };
+        int rl = 0, rh = mt * ntv;           // smallest rel with cost_before(rel) >= rem
+        while (rl < rh) {
+          const int mid = (rl + rh) >> 1;
+          if (cost_before(mid) >= rem) rh = mid; else rl = mid + 1;
         }
-        tile = (int)sh.tp[ve] + ni * mt + mi;
+        tile = (int)sh.tp[ve] + rl;
         if (tile > (int)sh.tp[ve + 1]) tile = (int)sh.tp[ve + 1];
       }
     }
@@ -421,11 +443,8 @@ __device__ __forceinline__ void swiglu_bwd8(const uint4 dh, const uint4 pv, cons
 }
 
 // One tile with NACT active 32-row token fragments per wave (tile rows <= 64*NACT).
-#ifdef MOHGE_PROBE
-#define PROBE_T(i) ts[i] = __builtin_amdgcn_s_memtime()
-#else
-#define PROBE_T(i)
-#endif
+// phase clocks for the optional counters of the benchmark library (a.cycles)
+#define PROBE_T(i) do { if (a.cycles) ts[i] = __builtin_amdgcn_s_memtime(); } while (0)
 
 template <int MODE, int NACT>
 __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, unsigned char* lds,
@@ -434,9 +453,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   constexpr bool TRA = tr_a(MODE), TRB = tr_b(MODE);   // operand read by transposing LDS reads
   constexpr bool WG = MODE == kWgrad;
   constexpr bool DH = MODE == kDgradH;
-#ifdef MOHGE_PROBE
-  long long ts[6];
-#endif
+  long long ts[6] = {0, 0, 0, 0, 0, 0};
   PROBE_T(0);
   constexpr int BM = kBM, BN = kBN, BK = kBK;
   constexpr int WGM = Shape<MODE>::WGM, WGN = Shape<MODE>::WGN, NWAVES = WGM * WGN, NT = 64 * NWAVES;
@@ -502,12 +519,12 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
       src_b[0] = a.B2 + (long long)(tok0 + trow0) * a.ldb + nb;
     } else if constexpr (DH) {
       if (nb > F - 8) nb = F - 8;                 // W_down[e]: [d, F]
-      tr_ldb = F;
-      src_b[0] = a.W[g] + ((long long)e_i * a.d + trow0) * F + nb;
+      tr_ldb = a.ldw[g];
+      src_b[0] = a.W[g] + ((long long)e_i * a.d + trow0) * a.ldw[g] + nb;
     } else {
       if (nb > a.d - 8) nb = a.d - 8;             // W13[e]: [2F, d]; F holds 2 F_g here
-      tr_ldb = a.d;
-      src_b[0] = a.W[g] + ((long long)e_i * F + trow0) * a.d + nb;
+      tr_ldb = a.ldw[g];
+      src_b[0] = a.W[g] + ((long long)e_i * F + trow0) * a.ldw[g] + nb;
     }
   }
 #pragma unroll
@@ -537,7 +554,7 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
       if (n > a.d - 1) n = a.d - 1;
       wrow = (long long)e_i * a.d + n;
     }
-    src_b[j] = a.W[g] + wrow * K + chunk * 8;
+    src_b[j] = a.W[g] + wrow * a.ldw[g] + chunk * 8;
   }
   const int ld_off = w * 1024;      // + j * NWAVES * 1024: wave-uniform destination inside a part
 
@@ -627,7 +644,6 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   // two, read the first fragments
   PROBE_T(1);
   __syncthreads();                  // the previous tile's epilogue has left the LDS
-  PROBE_T(5);
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j) issue_b(0, 0, j);
 #pragma unroll
@@ -843,16 +859,14 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
       }
     }
   }
-#ifdef MOHGE_PROBE
   PROBE_T(4);
-  if (a.dbg && threadIdx.x == 0) {
-    long long* d = a.dbg + (size_t)blockIdx.x * 8;
+  if (a.cycles && threadIdx.x == 0) {
+    // setup, wait for the first stages, main loop, epilogue; tiles; stages
+    long long* d = a.cycles + (size_t)blockIdx.x * 8;
     for (int i = 0; i < 4; ++i) d[i] += ts[i + 1] - ts[i];
-    d[6] += ts[5] - ts[1];          // of the prologue: waiting at the barrier
     d[4] += 1;
     d[5] += KT;
   }
-#endif
 }
 
 // Persistent tile kernel: workgroup b serves XCD b % 8.  Its first tile is fixed (range start
@@ -932,6 +946,17 @@ __global__ void __launch_bounds__(Shape<MODE>::THREADS) ffn_tile_kernel(const Ti
 // 3) makes every dependent tile give up without looking.
 constexpr int kSpinLimit = 1 << 22;
 
+// Output region of a tile of a token mode (rows x 256 columns of C) filled with bf16 NaNs.
+__device__ __forceinline__ void poison_tile(const TileArgs& a, const TileRec& rec) {
+  if (a.C == nullptr) return;
+  const int ncols = min(kBN, a.ldc - rec.n0);
+  for (int i = threadIdx.x; i < rec.rows * (kBN / 2); i += blockDim.x) {
+    const int r = i / (kBN / 2), c = (i % (kBN / 2)) * 2;
+    if (c < ncols)
+      *reinterpret_cast<uint32_t*>(a.C + (long long)(rec.row_start + r) * a.ldc + rec.n0 + c) = 0x7FC07FC0u;
+  }
+}
+
 // One phase of a fused launch: the tiles of one list in MODE.  ROLE 1: producer (every finished
 // tile adds one to its row block's counter; the range's straddling tail goes first), ROLE 2:
 // consumer (a tile waits until its row block's counter has reached rec.need), ROLE 0: neither.
@@ -939,84 +964,99 @@ template <int MODE, int ROLE>
 __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* lds, int lane, int w) {
   constexpr int PHASE = ROLE == 1 ? 0 : 1;
   constexpr int kBcastOffset = 40960;
-  const int xcd = blockIdx.x % kXcds;
-  int tbeg = a.hdr->xcd_begin[xcd], tend = a.hdr->xcd_begin[xcd + 1];
+  const int home = blockIdx.x % kXcds;
   const int total = a.hdr->total;
-  if (tbeg < 0) tbeg = 0;
-  if (tend > total) tend = total;
-  // The counter hands out positions 0, 1, 2, ... of the range.  Up phase: the positions map to
-  // the range's tail first (tiles of an expert that continues in the next XCD's range: down
-  // tiles of both ranges wait for them), then to the rest in list order; the head of the range,
-  // which the previous range's down tiles may wait for, comes right after.  Down phase: list
-  // order, the order in which the up tiles they depend on were handed out.
-  const int n = tend - tbeg;
-  int ntail = PHASE == 0 ? a.hdr->tail[xcd] : 0;
-  ntail = ntail < 0 ? 0 : (ntail > n ? n : ntail);
-  __syncthreads();         // (second phase: everybody has read the last hand-over word)
-  if (threadIdx.x == 0)
-    *reinterpret_cast<volatile int*>(lds + kBcastOffset) = atomicAdd(&a.hdr->counters[xcd], 1);
-  __syncthreads();
-  int pos = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
-  while (pos >= 0 && pos < n) {
-    const int t = pos < ntail ? tend - ntail + pos : tbeg + (pos - ntail);
-    int t_next = 0;
-    if (threadIdx.x == 0) t_next = atomicAdd(&a.hdr->counters[xcd], 1);
-    TileRec rec = a.recs[t];
-    rec.e = __builtin_amdgcn_readfirstlane(rec.e);
-    rec.row_start = __builtin_amdgcn_readfirstlane(rec.row_start);
-    rec.rows = __builtin_amdgcn_readfirstlane(rec.rows);
-    rec.n0 = __builtin_amdgcn_readfirstlane(rec.n0);
-    rec.fam = __builtin_amdgcn_readfirstlane(rec.fam);
-    rec.need = __builtin_amdgcn_readfirstlane(rec.need);
-    bool ok = !(rec.e < 0 || rec.e >= a.Ne || rec.rows < 1 || rec.rows > kBM || rec.row_start < 0 ||
-                rec.n0 < 0 || rec.fam < 0);
-    if (ok) {
-      if constexpr (MODE == kWgrad) {
-        ok = rec.row_start + rec.rows <= a.Mrows[rec.e / a.N] && rec.n0 < a.Ncols[rec.e / a.N] &&
-             a.zero_row != nullptr && a.offsets[rec.e] >= 0 && a.offsets[rec.e + 1] <= a.P &&
-             a.offsets[rec.e] <= a.offsets[rec.e + 1];
-      } else {
-        ok = rec.row_start + rec.rows <= a.P && rec.fam <= a.P;
-      }
-    }
-    if (ok) {
-      const int nact = (rec.rows + 63) / 64;
-      if constexpr (ROLE == 2) {
-        if (threadIdx.x == 0) {
-#ifdef MOHGE_PROBE
-          const long long w0 = __builtin_amdgcn_s_memtime();
-#endif
-          int polls = 0;
-          if (a.spin_limit < 0) a.hdr->pad[0] = 1;
-          else
-            while (__hip_atomic_load(&a.fam_done[rec.fam], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < rec.need) {
-              if (++polls > a.spin_limit) { a.hdr->pad[0] = 1; break; }
-              __builtin_amdgcn_s_sleep(8);
-            }
-#ifdef MOHGE_PROBE
-          if (a.dbg) {
-            a.dbg[(size_t)blockIdx.x * 8 + 6] += __builtin_amdgcn_s_memtime() - w0;
-            a.dbg[(size_t)blockIdx.x * 8 + 7] += polls > 0;
-          }
-#endif
-        }
-        __syncthreads();
-      }
-      if (nact == 4) run_tile<MODE, 4>(a, rec, lds, lane, w);
-      else if (nact == 3) run_tile<MODE, 3>(a, rec, lds, lane, w);
-      else if (nact == 2) run_tile<MODE, 2>(a, rec, lds, lane, w);
-      else run_tile<MODE, 1>(a, rec, lds, lane, w);
-      if constexpr (ROLE == 1)
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's output stores are done
-    }
-    __syncthreads();       // every wave is past its epilogue (and, up tiles, past its stores)
+  // The counter of a range hands out positions 0, 1, 2, ...  Up phase: the positions map to the
+  // range's tail first (tiles of an expert that continues in the next XCD's range: down tiles of
+  // both ranges wait for them), then to the rest in list order.  Down phase: list order, the order
+  // in which the up tiles they depend on were handed out.
+  // A workgroup serves its own XCD's range until the counter runs past its end and then (steal)
+  // the other ranges in turn, so the launch ends when all tiles are done rather than when the
+  // slowest range is.  A stolen tile is an ordinary draw from that range's counter, so the
+  // argument about waiting below holds for it as well.
+  for (int k = 0; k < (a.steal ? kXcds : 1); ++k) {
+    const int cur = (home + k) % kXcds;
+    int tbeg = a.hdr->xcd_begin[cur], tend = a.hdr->xcd_begin[cur + 1];
+    if (tbeg < 0) tbeg = 0;
+    if (tend > total) tend = total;
+    const int n = tend - tbeg;
+    int ntail = PHASE == 0 ? a.hdr->tail[cur] : 0;
+    ntail = ntail < 0 ? 0 : (ntail > n ? n : ntail);
+    __syncthreads();         // everybody has read the last hand-over word
     if (threadIdx.x == 0) {
-      if (ROLE == 1 && ok)
-        __hip_atomic_fetch_add(&a.fam_done[rec.fam], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      *reinterpret_cast<volatile int*>(lds + kBcastOffset) = t_next;
+      int p0 = n;
+      // (a foreign range is looked at before it is drawn from, so that an exhausted counter is left alone)
+      if (k == 0 || __hip_atomic_load(&a.hdr->counters[cur], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < n)
+        p0 = atomicAdd(&a.hdr->counters[cur], 1);
+      *reinterpret_cast<volatile int*>(lds + kBcastOffset) = p0;
     }
     __syncthreads();
-    pos = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
+    int pos = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
+    while (pos >= 0 && pos < n) {
+      const int t = pos < ntail ? tend - ntail + pos : tbeg + (pos - ntail);
+      int t_next = 0;
+      if (threadIdx.x == 0) t_next = atomicAdd(&a.hdr->counters[cur], 1);
+      TileRec rec = a.recs[t];
+      rec.e = __builtin_amdgcn_readfirstlane(rec.e);
+      rec.row_start = __builtin_amdgcn_readfirstlane(rec.row_start);
+      rec.rows = __builtin_amdgcn_readfirstlane(rec.rows);
+      rec.n0 = __builtin_amdgcn_readfirstlane(rec.n0);
+      rec.fam = __builtin_amdgcn_readfirstlane(rec.fam);
+      rec.need = __builtin_amdgcn_readfirstlane(rec.need);
+      bool ok = !(rec.e < 0 || rec.e >= a.Ne || rec.rows < 1 || rec.rows > kBM || rec.row_start < 0 ||
+                  rec.n0 < 0 || rec.fam < 0);
+      if (ok) {
+        if constexpr (MODE == kWgrad) {
+          ok = rec.row_start + rec.rows <= a.Mrows[rec.e / a.N] && rec.n0 < a.Ncols[rec.e / a.N] &&
+               a.zero_row != nullptr && a.offsets[rec.e] >= 0 && a.offsets[rec.e + 1] <= a.P &&
+               a.offsets[rec.e] <= a.offsets[rec.e + 1];
+        } else {
+          ok = rec.row_start + rec.rows <= a.P && rec.fam <= a.P;
+        }
+      }
+      if (ok) {
+        const int nact = (rec.rows + 63) / 64;
+        bool gave_up = false;
+        if constexpr (ROLE == 2) {
+          if (threadIdx.x == 0) {
+            const long long w0 = a.cycles ? __builtin_amdgcn_s_memtime() : 0;
+            int polls = 0, bad = 0;
+            if (a.spin_limit < 0) bad = 1;
+            else
+              while (__hip_atomic_load(&a.fam_done[rec.fam], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < rec.need) {
+                if (++polls > a.spin_limit) { bad = 1; break; }
+                __builtin_amdgcn_s_sleep(8);
+              }
+            if (bad) a.hdr->pad[0] = 1;
+            *reinterpret_cast<volatile int*>(lds + kBcastOffset + 4) = bad;
+            if (a.cycles) {
+              a.cycles[(size_t)blockIdx.x * 8 + 6] += __builtin_amdgcn_s_memtime() - w0;
+              a.cycles[(size_t)blockIdx.x * 8 + 7] += polls > 0;
+            }
+          }
+          __syncthreads();
+          gave_up = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset + 4)) != 0;
+        }
+        if (gave_up) {
+          // the rows this tile depends on never became complete: its output is written as NaN, so
+          // that nothing downstream can take it for a result (the header flag says why)
+          poison_tile(a, rec);
+        } else if (nact == 4) run_tile<MODE, 4>(a, rec, lds, lane, w);
+        else if (nact == 3) run_tile<MODE, 3>(a, rec, lds, lane, w);
+        else if (nact == 2) run_tile<MODE, 2>(a, rec, lds, lane, w);
+        else run_tile<MODE, 1>(a, rec, lds, lane, w);
+        if constexpr (ROLE == 1)
+          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's output stores are done
+      }
+      __syncthreads();       // every wave is past its epilogue (and, up tiles, past its stores)
+      if (threadIdx.x == 0) {
+        if (ROLE == 1 && ok)
+          __hip_atomic_fetch_add(&a.fam_done[rec.fam], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *reinterpret_cast<volatile int*>(lds + kBcastOffset) = t_next;
+      }
+      __syncthreads();
+      pos = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
+    }
   }
 }
 
@@ -1028,34 +1068,28 @@ __global__ void __launch_bounds__(Shape<M0>::THREADS) ffn_fused_kernel(const Til
   extern __shared__ __align__(1024) unsigned char lds[];
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  long long k0 = 0, r0 = 0, k1 = 0, r1 = 0;
+  if (p.cycles) { k0 = __builtin_amdgcn_s_memtime(); r0 = __builtin_amdgcn_s_memrealtime(); }
   fused_phase<M0, DEP ? 1 : 0>(p, lds, lane, w);
+  if (p.cycles) { k1 = __builtin_amdgcn_s_memtime(); r1 = __builtin_amdgcn_s_memrealtime(); }
   fused_phase<M1, DEP ? 2 : 0>(q, lds, lane, w);
+  if (p.cycles && threadIdx.x == 0) {
+    // second half of the buffer: [workgroup][8] = core clocks and 100 MHz ticks of the two
+    // lists, then the 100 MHz time stamps of the workgroup's start and end
+    long long* d = p.cycles + (size_t)(gridDim.x + blockIdx.x) * 8;
+    const long long k2 = __builtin_amdgcn_s_memtime(), r2 = __builtin_amdgcn_s_memrealtime();
+    d[0] = k1 - k0; d[1] = r1 - r0; d[2] = k2 - k1; d[3] = r2 - r1; d[4] = r0; d[5] = r2;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------
-static int g_force_rows[2] = {0, 0};
-static int g_spin_limit = kSpinLimit;   // polls a dependent tile of a fused launch waits
-static int g_fused_forward = 1;      // 0: separate up and down launches
-#ifdef MOHGE_PROBE
-static int g_probe_plain_stores = 0;
-extern "C" void mohge_probe_plain_stores(int v) { g_probe_plain_stores = v; }
-#endif
-#ifdef MOHGE_PROBE
-long long* g_dbg = nullptr;
-int g_dbg_which = -1;
-extern "C" void mohge_probe_select(int which) { g_dbg_which = which; }
-extern "C" void mohge_probe_buffer(void* p) { g_dbg = static_cast<long long*>(p); }
-#endif
-
-int tune_tiled(int knob, int value) {
-  if (knob == 2) { g_fused_forward = value != 0; return 0; }
-  if (knob == 3) { g_spin_limit = value == 0 ? kSpinLimit : value; return 0; }
-  if (knob < 0 || knob > 1) return -1;
-  if (value != 0 && value != 64 && value != 128 && value != 192 && value != 256) return -1;
-  g_force_rows[knob] = value;
-  return 0;
+void apply_options(TileArgs& t, const FfnOptions& o) {
+  t.band = o.band > 0 ? o.band : 1;
+  t.group_major = o.group_major != 0;
+  t.steal = o.steal != 0;
+  t.spin_limit = o.spin_limit == 0 ? kSpinLimit : o.spin_limit;
 }
 
 static long long max_tiles(const LayerDesc& L, bool up) {
@@ -1120,8 +1154,7 @@ static hipError_t launch_stage(const TileArgs& a, hipStream_t s) {
 
 template <int M0, int M1, bool DEP>
 static hipError_t launch_fused(const TileArgs& up, const TileArgs& dn_in, hipStream_t s) {
-  TileArgs dn = dn_in;
-  dn.spin_limit = g_spin_limit;
+  const TileArgs& dn = dn_in;
   constexpr size_t smem = (size_t)(kStagesA * kBM + kStagesB * kBN) * kBK * 2;
   auto kern = ffn_fused_kernel<M0, M1, DEP>;
   static bool attr_done = false;
@@ -1144,15 +1177,14 @@ static hipError_t sched_and_run(const TileArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const TileArgs& w2,
-                                const TileArgs& w13, const GatherArgs& ga, hipStream_t s) {
+                                const TileArgs& w13, const GatherArgs& ga, bool fused, hipStream_t s) {
   // at least one gather workgroup, so that the row of zeros gets written
   const unsigned gather_blocks = ga.P > 0 && ga.perm ? (unsigned)((ga.P + 3) / 4) : 1u;
   hipLaunchKernelGGL(bwd_schedule_kernel, dim3(4 + gather_blocks), dim3(256), 0, s, dh, dx, w2, w13,
-                     g_fused_forward, ga);
+                     fused ? 1 : 0, ga);
   return hipGetLastError();
 }
 
-bool fused_launches() { return g_fused_forward != 0; }
 
 // byte offset, inside the workspace of the forward, of the header of the list whose tiles wait
 size_t tiled_waiting_header_offset(const LayerDesc& L) {
@@ -1192,7 +1224,7 @@ hipError_t launch_tile_gemm(int mode, const TileArgs& a, hipStream_t s) {
 // SiLU(a) as rows of [P, 2*Fmax] for the backward pass.
 hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* perm,
                             const int32_t* offsets, const GroupPtrs& W, void* y_perm, void* ws,
-                            hipStream_t s, int stages, void* pre, int parts) {
+                            hipStream_t s, int stages, void* pre, int parts, const FfnOptions& o) {
   unsigned char* base = static_cast<unsigned char*>(ws);
   uint16_t* H = reinterpret_cast<uint16_t*>(base + tiled_sched_bytes(L));
   TileArgs up{};
@@ -1205,6 +1237,8 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
   up.lda = L.d; up.ldc = L.Fmax;
   up.Ke = L.Ke; up.Ng = L.Ng; up.N = L.N; up.Ne = L.Ne; up.d = L.d; up.P = L.P;
   up.ncu = tile_num_cus();
+  apply_options(up, o);
+  up.cycles = o.cycles;
   // visit groups by decreasing width: the down projection's longest reductions come first
   int order[kMaxGroups];
   for (int g = 0; g < kMaxGroups; ++g) order[g] = g;
@@ -1216,13 +1250,17 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
     up.F[g] = L.F[g];
     up.order[g] = order[g];
     up.W[g] = static_cast<const uint16_t*>(W.w13[g]);
+    up.ldw[g] = L.d;
   }
   TileArgs dn = up;
   dn.A = H;
   dn.perm = nullptr;
   dn.C = static_cast<uint16_t*>(y_perm);
   dn.lda = L.Fmax; dn.ldc = L.d;
-  for (int g = 0; g < kMaxGroups; ++g) dn.W[g] = static_cast<const uint16_t*>(W.w2[g]);
+  for (int g = 0; g < kMaxGroups; ++g) {
+    dn.W[g] = static_cast<const uint16_t*>(W.w2[g]);
+    dn.ldw[g] = L.F[g];
+  }
   // schedule areas: [header 256 B][records][cost prefix] for up, then the same for down
   unsigned char* p = base;
   for (int st = 0; st < 2; ++st) {
@@ -1232,18 +1270,12 @@ hipError_t launch_ffn_tiled(const LayerDesc& L, const void* x, const int32_t* pe
     p += 256;
     t.recs = reinterpret_cast<TileRec*>(p);
     p += (n * sizeof(TileRec) + 255) / 256 * 256;
-    t.force_rows = g_force_rows[st];
-#ifdef MOHGE_PROBE
-    t.dbg = g_dbg;
-#endif
+    t.force_rows = o.tile_rows[st];
   }
   up.fam_done = dn.fam_done = reinterpret_cast<int*>(p);
   // the whole forward in one launch: up and down tiles share the persistent workgroups
-  if (stages == 3 && g_fused_forward) {
+  if (stages == 3 && o.fused) {
     up.coherent_out = 1;
-#ifdef MOHGE_PROBE
-    if (g_probe_plain_stores) up.coherent_out = 0;      // timing experiment of the instrumented build only
-#endif
     // parts: 1 = the tile schedule only, 2 = the product launch only (on a schedule that no
     // launch has consumed yet), 3 = both
     if (parts & 1) {

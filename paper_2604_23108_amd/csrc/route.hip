@@ -45,17 +45,7 @@ struct RouteArgs {
   int dsplit;    // > 1: the hidden dimension is also split over grid.y workgroups, which leave
                  //   their fp64 logit sums in gpart; route_finish_kernel adds them and selects
   double* gpart; // [dsplit][T][NO]
-#ifdef MOHGE_PROBE
-  long long* dbg;
-#endif
 };
-
-#ifdef MOHGE_PROBE
-extern long long* g_dbg;
-#define RPROBE(i) ts[i] = __builtin_amdgcn_s_memtime()
-#else
-#define RPROBE(i)
-#endif
 
 template <bool BF16>
 __device__ __forceinline__ void load8(const void* base, size_t elem_off, float (&v)[8]) {
@@ -232,10 +222,6 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
   double* part = reinterpret_cast<double*>(smem);                 // [NW][BT][NC]
   float* lg = reinterpret_cast<float*>(smem + a.region0);         // [BT][NOpad]
 
-#ifdef MOHGE_PROBE
-  long long ts[6];
-#endif
-  RPROBE(0);
   // ---- phase 1: logits ----------------------------------------------------
   size_t xrow[TM];
 #pragma unroll
@@ -330,7 +316,6 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
         }
       }
     }
-    RPROBE(1);
     // Accumulator element i of lane (r, q) is token 4q+i, router row r of the 16x16 tile.
     // Every wave stores its fp64 totals in its own slice; then they are added in wave order.
 #pragma unroll
@@ -356,17 +341,8 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
     __syncthreads();
   }
 
-  RPROBE(2);
   if (a.dsplit > 1) return;          // route_finish_kernel takes over
   route_select(a, smem, lg, t0, BT, NW, w, lane);
-#ifdef MOHGE_PROBE
-  RPROBE(3);
-  if (a.dbg && threadIdx.x == 0 && blockIdx.x < 256) {
-    long long* d = a.dbg + (size_t)blockIdx.x * 8;
-    for (int i = 0; i < 3; ++i) d[i] += ts[i + 1] - ts[i];
-    d[4] += 1;
-  }
-#endif
 }
 
 // Second kernel of the split form: a workgroup takes as many tokens as it has waves (phase 2 is
@@ -433,9 +409,6 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
   a.gidx = group_idx; a.eidx = expert_idx; a.gates = gates; a.gs = gs_out; a.es1 = es1_out;
   a.T = L.T; a.d = L.d; a.Ng = L.Ng; a.N = L.N; a.Ne = L.Ne; a.Kg = L.Kg; a.Ke = L.Ke;
   a.mode = L.select_mode;
-#ifdef MOHGE_PROBE
-  a.dbg = g_dbg;
-#endif
   a.NO = L.Ng + L.Ne;
   a.NOpad = ((a.NO + 15) / 16) * 16 + 4;
   a.Nepad = ((L.Ne + 63) / 64) * 64;

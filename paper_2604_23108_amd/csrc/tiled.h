@@ -47,6 +47,7 @@ struct TileArgs {
   const int32_t* perm;        // kUp* only, may be NULL
   const int32_t* offsets;     // [Ne+1] routed rows per expert (exclusive prefix sum)
   const uint16_t* W[kMaxGroups];   // weight operand per group (all modes but kWgrad)
+  int ldw[kMaxGroups];        // row pitch of W[g] in elements
   uint16_t* C;                // token modes: output [P, ldc]
   int lda, ldc;
   int Ke, Ng, N, Ne, d, P;
@@ -56,6 +57,9 @@ struct TileArgs {
   TileRec* recs;
   int ncu;                    // compute units = persistent workgroups
   int force_rows;             // 0 = choose, else 64/128/192/256
+  int group_major;            // visiting order of the experts (see visit())
+  int steal;                  // fused launches: workgroups whose range is exhausted help the other ranges
+  int band;                   // row blocks per band of the tile order inside an expert (>= 1)
   // --- fused forward (up and down tiles in one launch) ------------------------------------
   int* fam_done;              // [row blocks] finished up tiles per row block (zeroed by the schedule)
   int spin_limit;             // fused launches: polls a dependent tile waits (set by launch_fused)
@@ -71,9 +75,8 @@ struct TileArgs {
                               //   expert's last token in its final 64-token stage)
   uint16_t* Wout[kMaxGroups]; // kWgrad: dW per group, [N, Mrows[g], Ncols[g]]
   int Mrows[kMaxGroups], Ncols[kMaxGroups];
-#ifdef MOHGE_PROBE
-  long long* dbg;             // [workgroup][8]: cycle sums per phase, tile count
-#endif
+  long long* cycles;          // NULL, or [2 * workgroups][8] counters of the fused launches (tile_cycles.md
+                              //   layout in mohge_bench.h): clock sums per tile phase, tiles, stages, waits
 };
 
 // One schedule launch + one tile-kernel launch for `mode` (backward modes and kUpSave).
@@ -89,11 +92,11 @@ struct GatherArgs {
   int P, Ke, chunks;          // chunks = 16-byte pieces of a row
 };
 hipError_t launch_bwd_schedules(const TileArgs& dh, const TileArgs& dx, const TileArgs& w2,
-                                const TileArgs& w13, const GatherArgs& ga, hipStream_t s);
+                                const TileArgs& w13, const GatherArgs& ga, bool fused, hipStream_t s);
 hipError_t launch_tiles(int mode, const TileArgs& a, hipStream_t s);
-// Fused launches (default; mohge_tune knob 2 = 0 turns them off): dH then dX in one launch, the
-// two weight gradients in one launch.  The schedules must have been built in the same form.
-bool fused_launches();
+// Fused launches (the default form): dH then dX in one launch, the two weight gradients in one
+// launch.  The schedules must have been built in the same form (`fused`).
+void apply_options(TileArgs& t, const FfnOptions& o);
 size_t tiled_waiting_header_offset(const LayerDesc& L);
 hipError_t launch_dgrad_pair(const TileArgs& dh, const TileArgs& dx, hipStream_t s);
 hipError_t launch_wgrad_pair(const TileArgs& w2, const TileArgs& w13, hipStream_t s);

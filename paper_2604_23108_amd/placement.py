@@ -74,3 +74,19 @@ def load_report(expert_idx: np.ndarray, n_groups: int, experts_per_group: int, n
     flops = np.zeros(n_gpus)
     np.add.at(flops, owner, w)
     return dict(share_by_group=share_by_group, flop_share=flops / flops.sum())
+
+
+def format_report(report: Dict[str, np.ndarray], title: str = "") -> str:
+    """The load report as a text table in the shape of the paper's per-GPU load table: one row per
+    virtual GPU, one column per group (share of that group's routed pairs, in percent), then the
+    GPU's share of the expert FLOPs."""
+    share, flops = report["share_by_group"], report["flop_share"]
+    n_groups, n_gpus = share.shape
+    lines = [title] if title else []
+    lines.append("GPU   " + " ".join(f"grp{g:<3d}" for g in range(n_groups)) + "   FLOPs")
+    for r in range(n_gpus):
+        lines.append(f"{r:<5d} " + " ".join(f"{100 * share[g, r]:6.2f}" for g in range(n_groups)) +
+                     f"  {100 * flops[r]:6.2f}")
+    dev = 100 * np.abs(share - 1.0 / n_gpus).max()
+    lines.append(f"ideal {100.0 / n_gpus:.2f} % per GPU; largest deviation {dev:.2f} points")
+    return "\n".join(lines)

@@ -93,10 +93,17 @@ WORKLOADS: Dict[str, Workload] = {
 def f32_to_bf16_bits(a: np.ndarray) -> np.ndarray:
     """Round float32 to bfloat16 (nearest, ties to even); returns the 16-bit patterns."""
     a = np.ascontiguousarray(a, dtype=np.float32)
-    bits = a.view(np.uint32)
-    lsb = (bits >> np.uint32(16)) & np.uint32(1)
-    rounded = bits + np.uint32(0x7FFF) + lsb
-    return (rounded >> np.uint32(16)).astype(np.uint16)
+    bits = a.view(np.uint32).reshape(-1)
+    out = np.empty(bits.shape, dtype=np.uint16)
+    step = 1 << 20                      # chunks that stay in cache: the large workloads have 10^9 weights
+    for i in range(0, bits.size, step):
+        b = bits[i:i + step]
+        r = (b >> np.uint32(16)) & np.uint32(1)
+        r += np.uint32(0x7FFF)
+        r += b
+        r >>= np.uint32(16)
+        out[i:i + step] = r
+    return out.reshape(a.shape)
 
 
 def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
@@ -105,12 +112,24 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-@dataclass
 class Tensor:
     """One generated tensor: float32 values, and the bf16 bit patterns when the
-    workload stores it in bf16 (then `f32` holds exactly the widened values)."""
-    f32: np.ndarray
-    bits: Optional[np.ndarray] = None
+    workload stores it in bf16 (then `f32` holds exactly the widened values, made on first use:
+    the device side only needs the bit patterns)."""
+
+    def __init__(self, f32: Optional[np.ndarray] = None, bits: Optional[np.ndarray] = None):
+        self._f32 = f32
+        self.bits = bits
+
+    @property
+    def f32(self) -> np.ndarray:
+        if self._f32 is None:
+            self._f32 = bf16_bits_to_f32(self.bits)
+        return self._f32
+
+    @f32.setter
+    def f32(self, value: np.ndarray) -> None:
+        self._f32 = value
 
 
 @dataclass
@@ -131,8 +150,7 @@ def _draw(rng: np.random.Generator, shape, scale: float, as_bf16: bool) -> Tenso
     if scale != 1.0:
         a *= np.float32(scale)
     if as_bf16:
-        bits = f32_to_bf16_bits(a)
-        return Tensor(bf16_bits_to_f32(bits), bits)
+        return Tensor(None, f32_to_bf16_bits(a))
     return Tensor(a, None)
 
 

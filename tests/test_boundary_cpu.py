@@ -13,13 +13,18 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "mohge.h")).read()
-    declared = set(re.findall(r"\b(mohge_[a-z_0-9]+)\s*\(", header))
-    declared -= {"mohge_config"}
-    assert declared == set(binding.EXPORTS)
-    lib = M.lib()
-    for name in declared:
-        assert hasattr(lib, name), name
+    from paper_2604_23108_amd import bench_binding
+    for hdr, exports, lib in (("mohge.h", binding.EXPORTS, M.lib()),
+                              ("mohge_bench.h", bench_binding.EXPORTS, bench_binding.lib())):
+        header = open(os.path.join(ROOT, "include", hdr)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)          # declarations only
+        declared = set(re.findall(r"\b(mohge_[a-z_0-9]+)\s*\(", header))
+        assert declared == set(exports), hdr
+        for name in declared:
+            assert hasattr(lib, name), name
+    # the layer header carries no measurement or tuning hooks
+    layer = open(os.path.join(ROOT, "include", "mohge.h")).read()
+    assert "probe" not in layer and "mohge_tune" not in layer
 
 
 def test_struct_layout_matches_header():
@@ -100,14 +105,14 @@ def test_training_entry_points_check_their_arguments():
     assert "shared routing" in M.mohge_last_error()
 
 
-def test_mxfp4_quantiser_of_the_binding_against_the_oracle_decoder():
-    """The binding's MXFP4 argument preparation (torch, CPU here): decoding its output with the
+def test_mxfp4_quantiser_against_the_oracle_decoder():
+    """The package's offline MXFP4 weight preparation (torch, CPU here): decoding its output with the
     oracle gives the nearest representable value of every element, values that are representable
     come back exactly, and scale codes stay within 1..254."""
     import numpy as np
     import torch
     import oracle
-    from paper_2604_23108_amd.binding import quantize_mxfp4
+    from paper_2604_23108_amd.weights import quantize_mxfp4
     rng = np.random.default_rng(11)
     w = (rng.standard_normal((3, 8, 96)) * np.exp(rng.uniform(-6, 6, size=(3, 8, 1)))).astype(np.float32)
     w[0, 0, :32] = 0.0                                     # an all-zero block
@@ -154,14 +159,32 @@ def test_quantised_and_split_entry_points_check_their_arguments():
     assert lib.mohge_mxfp4_decode(None, None, None, 48, None) == -1      # not whole blocks of 32
     assert "multiple" in M.mohge_last_error()
     assert lib.mohge_mxfp4_decode(None, None, None, 64, None) == -2
-    # the two-step form exists on the fused matrix-core path only
+    # the two-step form (benchmark library) exists on the fused matrix-core path only
     import ctypes as C
-    assert lib.mohge_expert_ffn_parts(decode.ref(), *([None] * 7), 0, C.c_int(1), None) == -1
+    from paper_2604_23108_amd import bench_binding as BB
+    bl = BB.lib()
+    assert bl.mohge_bench_expert_ffn(decode.ref(), *([None] * 7), 0, None, C.c_int(1), None) == -1
     assert "separate launches" in M.mohge_last_error()
-    assert lib.mohge_expert_ffn_parts(prefill.ref(), *([None] * 7), 0, C.c_int(5), None) == -1
+    assert bl.mohge_bench_expert_ffn(prefill.ref(), *([None] * 7), 0, None, C.c_int(5), None) == -1
     assert "parts" in M.mohge_last_error()
-    assert lib.mohge_expert_ffn_parts(prefill.ref(), *([None] * 7), 0, C.c_int(2), None) == -2
-    assert lib.mohge_expert_ffn_parts(prefill.ref(), *([None] * 7), 0, C.c_int(3), None) == -2
+    assert bl.mohge_bench_expert_ffn(prefill.ref(), *([None] * 7), 0, None, C.c_int(2), None) == -2
+    assert bl.mohge_bench_expert_ffn(prefill.ref(), *([None] * 7), 0, None, C.c_int(3), None) == -2
+    two = BB.FfnOptions(fused=0)
+    assert bl.mohge_bench_expert_ffn(prefill.ref(), *([None] * 7), 0, two.ref(), C.c_int(1), None) == -1
+    bad = BB.FfnOptions(tile_rows_up=100)
+    assert bl.mohge_bench_expert_ffn(prefill.ref(), *([None] * 7), 0, bad.ref(), C.c_int(3), None) == -1
+    assert "tile rows" in M.mohge_last_error()
+    # the down projection checks the size of the hidden-activation buffer it is handed
+    assert lib.mohge_expert_ffn_down(prefill.ref(), C.c_void_p(256), C.c_size_t(1024), C.c_void_p(256),
+                                     (C.c_void_p * 3)(256, 256, 256), C.c_void_p(256), None) == -4
+
+
+def test_shared_routing_accepts_the_largest_expert_count():
+    """N_s = 256 (the block size of the kernel that fills offsets) is a valid configuration."""
+    cfg = M.Config(T=0, d=64, n_groups=1, experts_per_group=256, d_ff=(64,), k_groups=1, k_experts=256)
+    import ctypes as C
+    p = C.c_void_p(256)
+    assert M.lib().mohge_shared_routing(cfg.ref(), p, p, p, p, p, p, None) == 0     # T = 0: nothing enqueued
 
 
 def test_bench_refuses_more_than_one_gpu_and_graft_entry_has_both_functions():

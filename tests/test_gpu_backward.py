@@ -319,7 +319,10 @@ def _check_backward_sampled(w, n_tok, experts, n_units=16):
 
 
 def test_backward_full_size_training_config_sampled():
-    _check_backward_sampled(WORKLOADS["training"], 24, (1, 13, 22))
+    # sampled tokens for the row gradients, the full-size router chain, and the weight gradients
+    # of EVERY expert on 16 sampled hidden units each
+    w = WORKLOADS["training"]
+    _check_backward_sampled(w, 24, tuple(range(w.n_experts)), n_units=16)
 
 
 def test_backward_element_offsets_beyond_2_31():
@@ -378,7 +381,8 @@ def test_fused_backward_launches_equal_separate_launches():
     w = _medium(SELECT_PER_GROUP, 52, T=900, d_ff=(128, 448, 640))
     dl = DeviceLayer(w, generate(w), backward=True)
     L = dl.layer
-    try:
+    from paper_2604_23108_amd import bench_binding as BB
+    if True:
         for it in range(4):
             wi = w.replace(seed=500 + it, skew_beta=float(it % 2) * 2.0)
             inp = generate(wi)
@@ -386,7 +390,7 @@ def test_fused_backward_launches_equal_separate_launches():
             print(f"[fused backward] call {it} seed={wi.seed}", flush=True)
             res = []
             for knob in (1, 0):
-                M.mohge_tune(2, knob)
+                L.ffn_options = BB.FfnOptions(fused=knob)
                 L.forward(x)
                 for t in L.dw13 + L.dw2 + [L.dx_perm, L.dx]:
                     t.fill_(float("nan"))
@@ -396,16 +400,16 @@ def test_fused_backward_launches_equal_separate_launches():
             for a, b in zip(*res):
                 assert torch.equal(a, b), f"call {it}"
                 assert torch.isfinite(a.float()).all()
-    finally:
-        M.mohge_tune(2, 1)
 
 
 def test_fused_status_reports_a_tile_that_gave_up_waiting():
     """mohge_fused_status: MOHGE_OK after ordinary fused launches (inference forward, training
     forward, backward); with the test hook that makes every dependent tile give up without
     looking (the host forces the condition, the kernels run to their normal end) it reports
-    MOHGE_ETIMEOUT for each of them; afterwards everything is back to normal and bit-identical."""
+    MOHGE_ETIMEOUT for each of them and the outputs hold NaN instead of numbers; afterwards
+    everything is back to normal and bit-identical."""
     import paper_2604_23108_amd as M
+    from paper_2604_23108_amd import bench_binding as BB
     w = WORKLOADS["training"].replace(T=1500, d=512, d_ff=(128, 256, 384), seed=97)
     inp = generate(w)
     dl = DeviceLayer(w, inp, training=True, backward=True)
@@ -417,23 +421,26 @@ def test_fused_status_reports_a_tile_that_gave_up_waiting():
         L.forward(dl.x)
         L.backward(dl.x, dy)
         # the inference form on its own workspace
-        M.mohge_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, ws_inf)
+        BB.mohge_bench_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y_inf, ws_inf, L.ffn_options)
         torch.cuda.synchronize()
 
     ws_inf = torch.empty(M.mohge_workspace_size(dl.cfg, M.CALL_EXPERT_FFN), dtype=torch.uint8, device="cuda")
+    y_inf = torch.empty_like(L.y_perm)
     step()
     ref = (L.y.clone(), L.dx.clone(), [t.clone() for t in L.dw13])
     for call, ws in calls + ((M.CALL_EXPERT_FFN, lambda: ws_inf),):
         assert M.mohge_fused_status(dl.cfg, call, ws()) == 0, call
-    try:
-        print("[fused status] forcing every dependent tile to give up", flush=True)
-        M.mohge_tune(3, -1)
-        step()
-        for call, ws in calls + ((M.CALL_EXPERT_FFN, lambda: ws_inf),):
-            assert M.mohge_fused_status(dl.cfg, call, ws()) == -6, call
-        assert "gave up" in M.mohge_last_error()
-    finally:
-        M.mohge_tune(3, 0)
+    print("[fused status] forcing every dependent tile to give up", flush=True)
+    L.ffn_options = BB.FfnOptions(spin_limit=-1)
+    step()
+    for call, ws in calls + ((M.CALL_EXPERT_FFN, lambda: ws_inf),):
+        assert M.mohge_fused_status(dl.cfg, call, ws()) == -6, call
+    assert "gave up" in M.mohge_last_error()
+    # a tile that gave up wrote NaN, not numbers: the failure cannot go unnoticed downstream
+    n = dl.cfg.n_pairs
+    assert torch.isnan(y_inf[:n].float()).all() and torch.isnan(L.y.float()).all()
+    assert torch.isnan(L.dx_perm[:n].float()).all()
+    L.ffn_options = None
     step()
     for call, ws in calls + ((M.CALL_EXPERT_FFN, lambda: ws_inf),):
         assert M.mohge_fused_status(dl.cfg, call, ws()) == 0, call

@@ -62,8 +62,8 @@ def check_output(w, inp, out, ref_route, keep, tokens, tol_rel=2e-2, tol_abs_f32
     return float(np.abs(out["y"][tokens] - y_ref).max()), float(np.abs(y_ref).max())
 
 
-def full_check(w, tokens=None, scale_router=1.0):
-    inp = generate(w)
+def full_check(w, tokens=None, scale_router=1.0, inp=None):
+    inp = generate(w) if inp is None else inp
     if scale_router != 1.0:
         inp.w_group *= np.float32(scale_router)
         inp.w_expert *= np.float32(scale_router)
@@ -345,13 +345,103 @@ def test_runs_are_bit_identical():
     assert (ya == b["y"]).all() and (la == b["losses"]).all() and (pa == b["perm"]).all()
 
 
-# ---- the named configurations at full size: routing in full, outputs on sampled tokens ---
-@pytest.mark.parametrize("name,n_sample", [("mid_prefill", 48), ("decode", 32), ("training", 32)])
-def test_full_size_configs_sampled(name, n_sample):
+# ---- the named configurations at full size, in the launch configuration bench.py times -----
+_GEN = {}
+
+
+def _generated(name):
+    """Seeded inputs of a named workload, drawn once per test session (the selection mode does
+    not enter the draws)."""
+    if name not in _GEN:
+        _GEN.clear()                      # one large workload in host memory at a time
+        _GEN[name] = generate(WORKLOADS[name])
+    return _GEN[name]
+
+
+def full_check_generated(w, inp, tokens=None):
+    """full_check on inputs that are already drawn (`w` may differ from the inputs' workload in
+    the selection mode only)."""
+    return full_check(w, tokens=tokens, inp=inp)
+
+
+@pytest.mark.parametrize("mode", [SELECT_PER_GROUP, SELECT_GLOBAL])
+@pytest.mark.parametrize("name", ["mid_prefill", "decode", "training"])
+def test_full_size_configs_every_token(name, mode):
+    # routing, permutation, scores, losses, y_perm and y of EVERY token against the oracle, in the
+    # mode the configuration names (per group) and in the paper's own (global top-K_e)
+    w = WORKLOADS[name].replace(select_mode=mode)
+    print(f"[full size] {name} mode={mode} T={w.T}", flush=True)
+    full_check_generated(w, _generated(name))
+
+
+def check_row_blocks(w, inp, out, ref, keep, rows_per_block=128, rng=None):
+    """y_perm against the oracle at the first row, the last row and one seeded row of every
+    `rows_per_block` sorted positions of every expert (so every row tile of every expert, whatever
+    tile height the schedule chose, has a row compared in every column tile)."""
+    rng = rng or np.random.default_rng(5)
+    offs, perm = out["offsets"], out["perm"]
+    rows = []
+    for e in range(w.n_experts):
+        lo, hi = int(offs[e]), int(offs[e + 1])
+        if hi == lo:
+            continue
+        rows += [lo, hi - 1]
+        for b in range(lo, hi, rows_per_block):
+            rows.append(int(rng.integers(b, min(b + rows_per_block, hi))))
+    rows = np.unique(np.asarray(rows, np.int64))
+    pairs = perm[rows]
+    tok = (pairs // w.k_experts).astype(np.int32)
+    ok = keep[tok]
+    rows, pairs, tok = rows[ok], pairs[ok], tok[ok]
+    exp = out["expert_idx"].reshape(-1)[pairs].astype(np.int32)
+    assert (exp == ref["expert_idx"].reshape(-1)[pairs]).all()
+    y_ref = oracle.expert_ffn(w, inp.x.f32, [t.f32 for t in inp.w_gate], [t.f32 for t in inp.w_up],
+                              [t.f32 for t in inp.w_down], tok, exp)
+    got = out["y_perm"][torch.from_numpy(rows).cuda()].float().cpu().numpy()
+    err = np.abs(got - y_ref).max()
+    assert err <= 2e-2 * np.abs(y_ref).max(), f"y_perm rows: error {err} vs max|ref| {np.abs(y_ref).max()}"
+    return len(rows)
+
+
+@pytest.mark.parametrize("mode", [SELECT_PER_GROUP, SELECT_GLOBAL])
+def test_full_size_large_prefill_skewed(mode):
+    # the largest configuration: routing, permutation, scores and losses of every token; y and
+    # y_perm of 256 whole tokens; y_perm rows in every row tile of every expert
+    name = "large_prefill_skewed"
+    w = WORKLOADS[name].replace(select_mode=mode)
+    inp = _generated(name)
+    rng = np.random.default_rng(321)
+    toks = np.sort(rng.choice(w.T, size=256, replace=False))
+    print(f"[full size] {name} mode={mode} T={w.T}", flush=True)
+    out, ref = full_check_generated(w, inp, tokens=toks)
+    c = out["counts"]
+    assert c.sum() == w.n_pairs and c.max() / max(1, c.min()) > 10
+    keep = ref["margin"] >= MARGIN
+    n = check_row_blocks(w, inp, out, ref, keep)
+    print(f"[full size] {name}: {n} y_perm rows compared", flush=True)
+
+
+@pytest.mark.parametrize("name", ["mid_prefill", "large_prefill_skewed"])
+def test_fused_forward_equals_separate_launches_at_full_size(name):
+    """The one-launch expert networks against the two-launch form, bit for bit, where many rounds
+    of tiles cross the XCD ranges and workgroups steal from other ranges; also with a tile order of
+    whole-expert columns, another visiting order and no stealing."""
+    import paper_2604_23108_amd as M
+    from paper_2604_23108_amd import bench_binding as BB
     w = WORKLOADS[name]
-    rng = np.random.default_rng(123)
-    toks = np.sort(rng.choice(w.T, size=min(n_sample, w.T), replace=False))
-    full_check(w, tokens=toks)
+    dl = _dev()(w, _generated(name), training=False)
+    L = dl.layer
+    L.forward(dl.x)
+    torch.cuda.synchronize()
+    ref = L.y_perm.clone()
+    assert M.mohge_fused_status(dl.cfg, M.CALL_EXPERT_FFN, L.ws_ffn) == 0
+    for kw in (dict(fused=0), dict(fused=1, band_rows=1000, group_major=1, steal=0), dict(fused=1, band_rows=1),
+               dict(fused=1, tile_rows_up=128)):
+        print(f"[fused, full size] {name} {kw}", flush=True)
+        y = torch.full_like(L.y_perm, float("nan"))
+        BB.mohge_bench_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y, L.ws_ffn, BB.FfnOptions(**kw))
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), ref.view(torch.int16)), kw
 
 
 @pytest.mark.parametrize("name", ["paper_1b", "paper_3b", "paper_14b"])
@@ -364,15 +454,6 @@ def test_full_size_paper_layer_shapes_sampled(name):
     full_check(w, tokens=toks, scale_router=8.0)
 
 
-def test_full_size_large_prefill_skewed_sampled():
-    w = WORKLOADS["large_prefill_skewed"]
-    rng = np.random.default_rng(321)
-    toks = np.sort(rng.choice(w.T, size=24, replace=False))
-    out, _ = full_check(w, tokens=toks)
-    c = out["counts"]
-    assert c.sum() == w.n_pairs and c.max() / max(1, c.min()) > 10
-
-
 def test_element_offsets_beyond_2_31():
     # P*d and P*max F both exceed 2^31 elements (P = 540672 rows of 4096): every row offset must
     # be computed in 64 bits.  Two groups of two experts, every token goes to all four.
@@ -382,8 +463,11 @@ def test_element_offsets_beyond_2_31():
     rng = np.random.default_rng(7)
     toks = np.sort(np.concatenate([rng.choice(w.T, size=12, replace=False), [0, w.T - 1]]))
     print(f"[big offsets] T={w.T} P={w.n_pairs} d={w.d}", flush=True)
-    out, _ = full_check(w, tokens=toks)
+    inp = generate(w)
+    out, ref = full_check_generated(w, inp, tokens=toks)
     assert (out["counts"] == w.T).all()
+    n = check_row_blocks(w, inp, out, ref, ref["margin"] >= MARGIN, rows_per_block=2048)
+    print(f"[big offsets] {n} y_perm rows compared", flush=True)
 
 
 def test_graph_replay_matches_eager():
@@ -416,22 +500,22 @@ def test_fused_forward_equals_separate_launches(training):
     for the row-block counters) against the two-launch forward, bit for bit, on one layer object
     whose input changes from call to call: a down tile that read hidden activations of an earlier
     call (a missing wait, a stale cache line) would show."""
-    import paper_2604_23108_amd as M
+    from paper_2604_23108_amd import bench_binding as BB
     from gpu_harness import to_dev
     w = WORKLOADS["mid_prefill"].replace(T=2300, d=768, d_ff=(128, 448, 640), seed=91)
     DeviceLayer = _dev()
     dl = DeviceLayer(w, generate(w), training=training, backward=training)
     L = dl.layer
-    try:
+    if True:
         for it in range(6):
             wi = w.replace(seed=100 + it, skew_beta=float(it % 3))
             x = to_dev(generate(wi).x, True)
             print(f"[fused] training={training} call {it} seed={wi.seed}", flush=True)
-            M.mohge_tune(2, 1)
+            L.ffn_options = BB.FfnOptions(fused=1)
             y_fused = L.forward(x).clone()
             saved_fused = L.saved.clone() if training else None
             counts = L.counts.clone()
-            M.mohge_tune(2, 0)
+            L.ffn_options = BB.FfnOptions(fused=0)
             y_two = L.forward(x).clone()
             torch.cuda.synchronize()
             assert torch.equal(L.counts, counts)
@@ -441,8 +525,6 @@ def test_fused_forward_equals_separate_launches(training):
                 # whose records differ between the two launch forms)
                 tail = L.saved.numel() - 3 * max(dl.cfg.n_pairs, 1) * max(w.d_ff) * 2
                 assert torch.equal(saved_fused[tail:], L.saved[tail:]), f"call {it}: saved activations"
-    finally:
-        M.mohge_tune(2, 1)
 
 
 @pytest.mark.parametrize("T,d,Ng,N", [(1, 4096, 4, 16), (7, 4096, 4, 16), (32, 4096, 4, 16), (200, 1024, 8, 16),
@@ -699,9 +781,10 @@ def test_decode_kernels_with_many_tokens_on_one_expert():
 
 
 def test_ffn_schedule_and_product_launch_issued_separately():
-    """mohge_expert_ffn_parts: schedule (1) then product launch (2) gives the bits of the one-call
+    """mohge_bench_expert_ffn: schedule (parts 1) then product launch (2) gives the bits of the one-call
     form, twice in a row; the decode path, where there is one launch only, refuses parts 1 and 2."""
     import paper_2604_23108_amd as M
+    from paper_2604_23108_amd import bench_binding as BB
     w = WORKLOADS["mid_prefill"].replace(T=700, d=512, d_ff=(128, 256, 384), seed=811)
     inp = generate(w)
     DeviceLayer = _dev()
@@ -712,44 +795,45 @@ def test_ffn_schedule_and_product_launch_issued_separately():
     ref = L.y_perm.clone()
     for rep in range(2):
         y_perm = torch.full_like(L.y_perm, float("nan"))
-        M.mohge_expert_ffn_parts(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y_perm, L.ws_ffn, 1)
-        M.mohge_expert_ffn_parts(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y_perm, L.ws_ffn, 2)
+        BB.mohge_bench_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y_perm, L.ws_ffn, None, 1)
+        BB.mohge_bench_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y_perm, L.ws_ffn, None, 2)
         torch.cuda.synchronize()
         assert torch.equal(y_perm.view(torch.int16), ref.view(torch.int16)), rep
     y3 = torch.full_like(L.y_perm, float("nan"))
-    M.mohge_expert_ffn_parts(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y3, L.ws_ffn, 3)
+    BB.mohge_bench_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y3, L.ws_ffn, None, 3)
     torch.cuda.synchronize()
     assert torch.equal(y3.view(torch.int16), ref.view(torch.int16))
     with pytest.raises(M.MohgeError, match="parts"):
-        M.mohge_expert_ffn_parts(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y3, L.ws_ffn, 4)
+        BB.mohge_bench_expert_ffn(dl.cfg, dl.x, L.perm, L.offsets, L.w13, L.w2, y3, L.ws_ffn, None, 4)
     wd = WORKLOADS["decode"].replace(T=8, d=512, d_ff=(128, 256, 384, 512), seed=812)
     dd = DeviceLayer(wd, generate(wd), training=False)
     dd.layer.forward(dd.x)
     with pytest.raises(M.MohgeError, match="separate launches"):
-        M.mohge_expert_ffn_parts(dd.cfg, dd.x, dd.layer.perm, dd.layer.offsets, dd.layer.w13, dd.layer.w2,
-                                 dd.layer.y_perm, dd.layer.ws_ffn, 2)
+        BB.mohge_bench_expert_ffn(dd.cfg, dd.x, dd.layer.perm, dd.layer.offsets, dd.layer.w13, dd.layer.w2,
+                                  dd.layer.y_perm, dd.layer.ws_ffn, None, 2)
 
 
 def test_box_probes_run_and_report_their_work():
     """The measurement aids: every pattern of the read probe on a buffer that is not a whole number
     of its units, and the MFMA probe; argument errors."""
     import paper_2604_23108_amd as M
+    from paper_2604_23108_amd import bench_binding as BB
     buf = torch.ones(3 * (1 << 20) + 4096, dtype=torch.uint8, device="cuda")
     out = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
-    n = M.mohge_probe_read(buf, 0, False, out)
+    n = BB.mohge_probe_read(buf, 0, False, out)
     assert 0 < n <= buf.numel() and n % (256 * 8 * 16) == 0
     for row in (512, 2048, 8192):
         for stag in (False, True):
-            n = M.mohge_probe_read(buf, row, stag, out)
+            n = BB.mohge_probe_read(buf, row, stag, out)
             assert n == (buf.numel() // row // 128) * 128 * row, (row, stag)
-    assert M.mohge_probe_read(buf[:4096], 8192, False, out) == 0          # less than one unit: nothing launched
-    flops = M.mohge_probe_mfma(out, 100)
+    assert BB.mohge_probe_read(buf[:4096], 8192, False, out) == 0          # less than one unit: nothing launched
+    flops = BB.mohge_probe_mfma(out, 100)
     assert flops == 1024 * 4 * 4 * 100 * 2.0 * 32 * 32 * 16
     torch.cuda.synchronize()
     with pytest.raises(M.MohgeError, match="row_bytes"):
-        M.mohge_probe_read(buf, 1000, False, out)
+        BB.mohge_probe_read(buf, 1000, False, out)
     with pytest.raises(M.MohgeError, match="needed"):
-        M.mohge_probe_mfma(out[:4096], 10)
+        BB.mohge_probe_mfma(out[:4096], 10)
 
 
 @pytest.mark.parametrize("seed", range(10))
@@ -805,3 +889,21 @@ def test_quantised_decode_random_shapes(seed):
         if keep.any():
             err = np.abs(got[keep] - want[keep]).max()
             assert err <= 2e-2 * max(np.abs(want).max(), 1e-6), f"{name}: error {err} vs {np.abs(want).max()}"
+
+
+def test_shared_routing_with_the_largest_expert_count():
+    # N_s = 256 always-on experts: offsets has 257 entries, one more than the filling kernel's block
+    import paper_2604_23108_amd as M
+    T, n_s = 5, 256
+    cfg = M.Config(T=T, d=64, n_groups=1, experts_per_group=n_s, d_ff=(64,), k_groups=1, k_experts=n_s)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    eidx, gates = torch.full((T, n_s), -1, **i32), torch.zeros((T, n_s), dtype=torch.float32, device="cuda")
+    counts, offsets = torch.full((n_s,), -1, **i32), torch.full((n_s + 1,), -1, **i32)
+    perm, inv = torch.full((T * n_s,), -1, **i32), torch.full((T * n_s,), -1, **i32)
+    M.mohge_shared_routing(cfg, eidx, gates, counts, offsets, perm, inv)
+    torch.cuda.synchronize()
+    assert (offsets.cpu().numpy() == np.arange(n_s + 1) * T).all() and (counts == T).all()
+    p = oracle.permute(WORKLOADS["tiny_f32"].replace(T=T, n_groups=1, experts_per_group=n_s, k_groups=1,
+                                                     k_experts=n_s, d_ff=(64,)), eidx.cpu().numpy())
+    assert (perm.cpu().numpy() == p["perm"]).all() and (inv.cpu().numpy() == p["inv_perm"]).all()
+    assert (gates == 1).all()

@@ -47,3 +47,20 @@ def test_a_local_share_is_itself_a_layer():
     local = w.replace(experts_per_group=2)
     r = oracle.route(local, inp.x.f32, inp.w_group, inp.w_expert[ids.reshape(-1)])
     assert r["expert_idx"].max() < local.n_experts
+
+
+def test_load_report_table_prints_the_shares_it_was_given():
+    # hand-made routing: 2 groups x 4 experts on 2 virtual GPUs (contiguous: experts 0,1 | 2,3)
+    eidx = np.array([[0, 4], [1, 5], [2, 6], [0, 7], [1, 4], [0, 5]])      # group 0: 0,1,2,0,1,0  group 1: 0,1,2,3,0,1
+    rep = placement.load_report(eidx, 2, 4, 2, (64, 128))
+    np.testing.assert_allclose(rep["share_by_group"], [[5 / 6, 1 / 6], [4 / 6, 2 / 6]])
+    np.testing.assert_allclose(rep["flop_share"], [(5 * 64 + 4 * 128) / (6 * 192), (64 + 2 * 128) / (6 * 192)])
+    text = placement.format_report(rep, "title")
+    rows = text.splitlines()
+    assert rows[0] == "title" and rows[1].split() == ["GPU", "grp0", "grp1", "FLOPs"]
+    assert rows[2].split() == ["0", "83.33", "66.67", "72.22"]
+    assert rows[3].split() == ["1", "16.67", "33.33", "27.78"]
+    assert "ideal 50.00 %" in rows[4] and "33.33 points" in rows[4]
+    # strided sets: experts 0,2 | 1,3
+    rep2 = placement.load_report(eidx, 2, 4, 2, (64, 128), "strided")
+    np.testing.assert_allclose(rep2["share_by_group"], [[4 / 6, 2 / 6], [3 / 6, 3 / 6]])
