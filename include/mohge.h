@@ -88,12 +88,16 @@ typedef struct mohge_config {
  * Out: group_idx DEVICE [T,K_g] and expert_idx DEVICE [T,K_e], ascending ids;
  *      gates DEVICE [T,K_e] aligned with expert_idx; gs_out DEVICE [T,N_g] (GS) and
  *      es1_out DEVICE [T,N_e] (ES', zero outside kept groups), each may be NULL.
- * Logits are accumulated in fp32 (fp64 across 64-wide slices of d).
- * workspace DEVICE, optional (NULL / 0 allowed): with at least
- * mohge_workspace_size(cfg, MOHGE_CALL_ROUTE) bytes and few tokens (decode) the reduction over d
- * is spread over many workgroups, which leave partial sums there, instead of running on one
- * workgroup per 16 tokens.  The logits of the two forms can differ in the last bit (the fp64
- * partial sums are grouped differently); each form is deterministic.
+ * Logits are accumulated in fp32 over 64 hidden elements at a time and in fp64 across those
+ * slices (error about 1e-7).
+ * workspace DEVICE, optional (NULL / 0 allowed), mohge_workspace_size(cfg, MOHGE_CALL_ROUTE) bytes
+ * (0 where it has no use).  Without it the logits come from the fp32 matrix cores, one workgroup
+ * per 16 tokens.  With it, two other forms are chosen by size: for few tokens (decode) the
+ * reduction over d is spread over many workgroups, which leave partial sums there; from 8192
+ * bf16 tokens on, the router rows are first split there into three bf16 parts that add up to the
+ * fp32 weight exactly, and the logits come from the bf16 matrix cores with exact products.  The
+ * logits of the forms can differ in the last bit (the fp64 partial sums are grouped
+ * differently); each form is deterministic.
  */
 int mohge_route(const mohge_config* cfg, const void* x, const float* w_group,
                 const float* w_expert, const float* expert_logit_bias, int32_t* group_idx,

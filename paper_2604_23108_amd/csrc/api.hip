@@ -124,7 +124,7 @@ size_t mohge_workspace_size(const mohge_config* cfg, int which_call) {
     case MOHGE_CALL_FFN_SAVED: return ffn_saved_bytes(L);
     case MOHGE_CALL_EXPERT_FFN_BWD: return ffn_bwd_workspace_bytes(L);
     case MOHGE_CALL_ROUTE_BWD: return route_bwd_workspace_bytes(L);
-    case MOHGE_CALL_ROUTE: return route_workspace_bytes(L);
+    case MOHGE_CALL_ROUTE: return route_workspace_bytes(L, cfg->dtype);
     default: set_error("unknown call id %d", which_call); return 0;
   }
 }

@@ -74,7 +74,7 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
                         const float* w_expert, const float* bias, int32_t* group_idx,
                         int32_t* expert_idx, float* gates, float* gs_out, float* es1_out,
                         void* ws, size_t ws_bytes, hipStream_t s);
-size_t route_workspace_bytes(const LayerDesc& L);
+size_t route_workspace_bytes(const LayerDesc& L, int dtype);
 bool ffn_w8_supported(const LayerDesc& L);
 hipError_t launch_expert_ffn_w8(const LayerDesc& L, const void* x, const int32_t* perm,
                                 const int32_t* offsets, const GroupPtrs& Wq, const float* const* s13,

@@ -80,8 +80,16 @@ __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* 
   float* krow = e2row + a.Nepad;                                            // selection key
   float* xrow = krow + a.Nepad;                                             // exp(z - max of the group)
   const int klimit = (a.mode == MOHGE_SELECT_GLOBAL) ? a.Ke : a.Ke / a.Kg;
+  const bool vec4 = (a.N & 3) == 0;      // group rows can be read four members at a time
   const int iters = (BT + NW - 1) / NW;
   const float NEG_INF = -__builtin_inff();
+  // the logit bias does not depend on the token: fetched once (a load inside the token loop would
+  // also wait for the previous token's result stores)
+  float bias_r[4] = {0.f, 0.f, 0.f, 0.f};
+  if (a.bias)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (lane + 64 * j < a.Ne) bias_r[j] = a.bias[lane + 64 * j];
   for (int it = 0; it < iters; ++it) {
     const int tl = it * NW + w;
     const int t = t0 + tl;
@@ -108,7 +116,9 @@ __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* 
 
     // zrow / e1row / e2row / krow are private to this wave: LDS operations of one wave
     // complete in order, so only the compiler has to be kept from reordering them
-    for (int e = lane; e < a.Ne; e += 64) zrow[e] = lrow[a.Ng + e] + (a.bias ? a.bias[e] : 0.f);
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      if (lane + 64 * j < a.Ne) zrow[lane + 64 * j] = lrow[a.Ng + lane + 64 * j] + bias_r[j];
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
 
@@ -120,8 +130,17 @@ __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* 
       if ((gmask >> g) & 1ull) {
         const float* zg_row = zrow + g * a.N;
         float mx = NEG_INF;
+        if (vec4) {
+          // (rows of a group start on a 16-byte boundary when N is a multiple of 4)
+#pragma unroll 4
+          for (int i = 0; i < a.N; i += 4) {
+            const float4 v = *reinterpret_cast<const float4*>(zg_row + i);
+            mx = fmaxf(fmaxf(mx, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+          }
+        } else {
 #pragma unroll 8
-        for (int i = 0; i < a.N; ++i) mx = fmaxf(mx, zg_row[i]);
+          for (int i = 0; i < a.N; ++i) mx = fmaxf(mx, zg_row[i]);
+        }
         ex = expf(zrow[e] - mx);
       }
       xrow[e] = ex;
@@ -136,8 +155,16 @@ __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* 
       if (in) {
         const float* xg_row = xrow + g * a.N;
         float sum = 0.f;
+        if (vec4) {
+#pragma unroll 4
+          for (int i = 0; i < a.N; i += 4) {         // same member order as the scalar loop
+            const float4 v = *reinterpret_cast<const float4*>(xg_row + i);
+            sum += v.x; sum += v.y; sum += v.z; sum += v.w;
+          }
+        } else {
 #pragma unroll 8
-        for (int i = 0; i < a.N; ++i) sum += xg_row[i];
+          for (int i = 0; i < a.N; ++i) sum += xg_row[i];
+        }
         e1 = xrow[e] / sum;
         e2 = e1 * (1.f / (1.f + expf(-lrow[g])));
       }
@@ -167,6 +194,16 @@ __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* 
           if (a.mode == MOHGE_SELECT_GLOBAL) {
 #pragma unroll 8
             for (int e2i = 0; e2i < a.Nepad; e2i += 4) {
+              const float4 k4 = *reinterpret_cast<const float4*>(krow + e2i);
+              rank += (k4.x > key) || (k4.x == key && e2i < e);
+              rank += (k4.y > key) || (k4.y == key && e2i + 1 < e);
+              rank += (k4.z > key) || (k4.z == key && e2i + 2 < e);
+              rank += (k4.w > key) || (k4.w == key && e2i + 3 < e);
+            }
+          } else if (vec4) {
+#pragma unroll 4
+            for (int i = 0; i < a.N; i += 4) {
+              const int e2i = g * a.N + i;
               const float4 k4 = *reinterpret_cast<const float4*>(krow + e2i);
               rank += (k4.x > key) || (k4.x == key && e2i < e);
               rank += (k4.y > key) || (k4.y == key && e2i + 1 < e);
@@ -345,6 +382,202 @@ __global__ void __launch_bounds__(512) route_kernel(const RouteArgs a) {
   route_select(a, smem, lg, t0, BT, NW, w, lane);
 }
 
+// ---------------------------------------------------------------------------------------
+// Prefill form (bf16 tokens, many tokens): the logits on the bf16 matrix cores, exactly.
+// A router weight (fp32, 24 significant bits) is the exact sum of three bf16 numbers (its
+// leading 8 bits, the next 8, the rest: each taken by truncation, the remainders are exact
+// in fp32), a token element is one bf16 number, and a product of two bf16 numbers is exact in
+// fp32.  So  x . w = x . w_hi + x . w_mid + x . w_lo  with v_mfma_f32_16x16x32_bf16, whose only
+// rounding is the fp32 accumulation; the large part (w_hi) is accumulated over 64 hidden
+// elements at a time and then added to an fp64 total, as in the fp32 form above, which keeps
+// the logit error below 1e-7.  Sixteen times the fp32 matrix rate at three times the work.
+//
+// A small kernel first splits the router rows into the three bf16 planes (workspace:
+// [3][rows padded to whole passes][d], padding rows zero).  In the main kernel a workgroup of 8
+// waves owns 16*TG tokens: waves = TG token groups of 16 x (8/TG) parts of every 128-deep chunk
+// of the hidden dimension.  A wave loads its token fragments straight from global memory in
+// operand layout (several chunks ahead); the three planes of a chunk go global -> LDS without
+// passing registers (global_load_lds, double buffered, 16-byte pieces XOR-swizzled by the row so
+// that the 128-bit fragment reads are conflict free).  The waves of a token group add their fp64
+// totals through LDS in fixed order.  Router rows are processed 16*TN at a time (TN <= 5 column
+// tiles: more would not fit the registers); wider routers make several passes over the token rows.
+// ---------------------------------------------------------------------------------------
+typedef __bf16 rbf16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int kPfChunk = 128;            // hidden elements per chunk
+
+// planes[p][row][k], p = 0 (leading bits), 1, 2; rows >= NO are zero
+__global__ void __launch_bounds__(256) route_split_kernel(const float* __restrict__ wg, const float* __restrict__ we,
+                                                          uint16_t* __restrict__ planes, int Ng, int NO,
+                                                          int rows, int d) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;      // one thread per 4 hidden elements
+  const int per_row = d / 4;
+  if (idx >= (long long)rows * per_row) return;
+  const int o = (int)(idx / per_row), k = (int)(idx % per_row) * 4;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (o < NO) v = *reinterpret_cast<const float4*>(((o < Ng) ? wg + (size_t)o * d : we + (size_t)(o - Ng) * d) + k);
+  const float f[4] = {v.x, v.y, v.z, v.w};
+  uint32_t hi[4], mid[4], lo[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    hi[i] = __float_as_uint(f[i]) & 0xffff0000u;
+    const float r1 = f[i] - __uint_as_float(hi[i]);          // exact
+    mid[i] = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(mid[i]);           // exact, at most 8 significant bits
+    lo[i] = __float_as_uint(r2) & 0xffff0000u;
+  }
+  const size_t plane = (size_t)rows * d, at = (size_t)o * d + k;
+  *reinterpret_cast<uint2*>(planes + at) = make_uint2((hi[0] >> 16) | hi[1], (hi[2] >> 16) | hi[3]);
+  *reinterpret_cast<uint2*>(planes + plane + at) = make_uint2((mid[0] >> 16) | mid[1], (mid[2] >> 16) | mid[3]);
+  *reinterpret_cast<uint2*>(planes + 2 * plane + at) = make_uint2((lo[0] >> 16) | lo[1], (lo[2] >> 16) | lo[3]);
+}
+
+template <int TG, int TN>
+__global__ void __launch_bounds__(512) route_prefill_kernel(const RouteArgs a, const uint16_t* __restrict__ planes,
+                                                            int plane_rows) {
+  extern __shared__ __align__(1024) unsigned char smem[];
+  constexpr int KQ = 8 / TG;                 // waves along the hidden dimension
+  constexpr int KS = 4 / KQ;                 // 32-deep MFMA steps of a wave per chunk
+  constexpr int BT = 16 * TG, NC = 16 * TN;
+  constexpr int PLANE = NC * 256, BUF = 3 * PLANE;
+  constexpr int NCOPY = 3 * NC / 4;          // wave-wide copies (4 rows x 256 bytes) per chunk
+  constexpr int XP = 4;                      // token chunks in flight
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int tg = w / KQ, kq = w % KQ;
+  const int r = lane & 15, q = lane >> 4;
+  const int t0 = blockIdx.x * BT;
+  float* lg = reinterpret_cast<float*>(smem + a.region0);         // [BT][NOpad]
+  double* red = reinterpret_cast<double*>(smem);                  // [BT][NC], after the chunk loop
+  const int nchunks = a.d / kPfChunk;
+
+  const int tok = t0 + tg * 16 + r;
+  const uint16_t* xrow = static_cast<const uint16_t*>(a.x) + (size_t)(tok < a.T ? tok : a.T - 1) * a.d +
+                         kq * 32 * KS + 8 * q;
+  const size_t plane_elems = (size_t)plane_rows * a.d;
+
+  for (int nc = 0; nc < a.NO; nc += NC) {
+    f32x4 acc_h[TN], acc_l[TN];
+    double tot[TN][4];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+      acc_h[tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+      acc_l[tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) tot[tn][i] = 0.0;
+    }
+    // copy idx (wave-uniform) of a chunk: plane idx / (NC/4), rows 4*(idx % (NC/4)) .. +3 of the
+    // pass; lane l fills row l/16, physical piece l%16, which holds logical piece (l%16) ^ (row & 15)
+    auto copy_w = [&](int c, int b) {
+      for (int idx = w; idx < NCOPY; idx += 8) {
+        const int p = idx / (NC / 4), row = 4 * (idx % (NC / 4)) + (lane >> 4);
+        const int piece = (lane & 15) ^ (row & 15);
+        const uint16_t* src = planes + p * plane_elems + (size_t)(nc + row) * a.d + (size_t)c * kPfChunk + piece * 8;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(smem + b * BUF + idx * 1024),
+                                         16, 0, 0);
+      }
+    };
+    uint4 xr[XP][KS];
+    auto load_x = [&](int c, int slot) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks)
+        xr[slot][ks] = *reinterpret_cast<const uint4*>(xrow + (size_t)c * kPfChunk + 32 * ks);
+    };
+
+    __syncthreads();                     // the previous pass has left the buffers
+    copy_w(0, 0);
+#pragma unroll
+    for (int u = 0; u < XP; ++u)
+      if (u < nchunks) load_x(u, u);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    for (int c0 = 0; c0 < nchunks; c0 += XP) {
+#pragma unroll
+      for (int u = 0; u < XP; ++u) {
+        const int c = c0 + u;
+        if (c < nchunks) {
+          rbf16x8 xa[KS];
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) xa[ks] = __builtin_bit_cast(rbf16x8, xr[u][ks]);
+          // the next chunk's planes into the other buffer (nobody reads it any more: barrier at
+          // the end of the previous chunk), then the token fragments of a later chunk
+          if (c + 1 < nchunks) copy_w(c + 1, (u + 1) & 1);
+          __builtin_amdgcn_sched_barrier(0);
+          if (c + XP < nchunks) load_x(c + XP, u);
+          __builtin_amdgcn_sched_barrier(0);
+          const unsigned char* fb = smem + (u & 1) * BUF + r * 256;
+#pragma unroll
+          for (int ks = 0; ks < KS; ++ks) {
+            const int piece = ((kq * KS + ks) * 4 + q) ^ r;
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+              const unsigned char* f = fb + 16 * tn * 256 + piece * 16;
+              const rbf16x8 bh = *reinterpret_cast<const rbf16x8*>(f);
+              const rbf16x8 bm = *reinterpret_cast<const rbf16x8*>(f + PLANE);
+              const rbf16x8 bl = *reinterpret_cast<const rbf16x8*>(f + 2 * PLANE);
+              acc_h[tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[ks], bh, acc_h[tn], 0, 0, 0);
+              acc_l[tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[ks], bm, acc_l[tn], 0, 0, 0);
+              acc_l[tn] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xa[ks], bl, acc_l[tn], 0, 0, 0);
+            }
+            // the large part goes into the fp64 totals after every 64 hidden elements of this wave
+            if (KS == 2 ? ks == 1 : ((u & 1) || c + 1 == nchunks)) {
+#pragma unroll
+              for (int tn = 0; tn < TN; ++tn) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) tot[tn][i] += (double)acc_h[tn][i];
+                acc_h[tn] = f32x4{0.f, 0.f, 0.f, 0.f};
+              }
+            }
+          }
+          // my pieces of the next chunk's planes have landed when at most the token loads issued
+          // after them are outstanding (loads complete in order)
+          if (c + XP < nchunks) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(KS) : "memory");
+          else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+          __syncthreads();
+        }
+      }
+    }
+    // the small parts, then the waves of a token group in fixed order
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) tot[tn][i] += (double)acc_l[tn][i];
+    for (int step = 0; step < KQ; ++step) {
+      if (kq == step) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            // accumulator element i of lane (r, q): token 4q+i, router row r of the tile
+            const int tl = tg * 16 + 4 * q + i, ol = 16 * tn + r;
+            double v = tot[tn][i];
+            if (step > 0) v += red[tl * NC + ol];
+            if (step < KQ - 1) red[tl * NC + ol] = v;
+            else if (nc + ol < a.NO) lg[tl * a.NOpad + nc + ol] = (float)v;
+          }
+      }
+      __syncthreads();
+    }
+  }
+  route_select(a, smem, lg, t0, BT, 8, w, lane);
+}
+
+template <int TG, int TN>
+static hipError_t launch_prefill(const RouteArgs& a, int T, const uint16_t* planes, int plane_rows, size_t smem,
+                                 hipStream_t s) {
+  auto kern = route_prefill_kernel<TG, TN>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  constexpr int BT = 16 * TG;
+  hipLaunchKernelGGL(kern, dim3((T + BT - 1) / BT), dim3(512), smem, s, a, planes, plane_rows);
+  return hipGetLastError();
+}
+
 // Second kernel of the split form: a workgroup takes as many tokens as it has waves (phase 2 is
 // one wave per token, and with few tokens its latency is the cost), adds the dsplit partial logit
 // sums of its tokens in index order and runs phase 2.
@@ -394,8 +627,32 @@ static hipError_t launch_tn(const RouteArgs& a, int TN, dim3 grid, dim3 block, s
 // Split form: used for at most kSplitMaxT tokens; the workspace holds up to kSplitMax partial
 // sums of every logit.
 constexpr int kSplitMaxT = 256, kSplitMax = 16;
+constexpr int kPrefillMinT = 8192;       // from here on the bf16 matrix-core form (measured: 96 against
+                                         // 190 us at 16384 tokens, even at 8192, slower below)
 
-size_t route_workspace_bytes(const LayerDesc& L) {
+static int tile_cus() {
+  static int n = 0;
+  if (!n) {
+    int dev = 0;
+    hipDeviceProp_t p;
+    n = (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess && p.multiProcessorCount > 0)
+            ? p.multiProcessorCount : 256;
+  }
+  return n;
+}
+
+// the bf16 matrix-core form: bf16 tokens, enough of them, whole 128-deep chunks
+static bool prefill_form(const LayerDesc& L, int dtype) {
+  return dtype == MOHGE_BF16 && L.T >= kPrefillMinT && L.d % kPfChunk == 0;
+}
+
+size_t route_workspace_bytes(const LayerDesc& L, int dtype) {
+  if (prefill_form(L, dtype)) {
+    // the three bf16 planes of the router rows, rows padded to whole passes of 16 * TN
+    const int tiles = (L.Ng + L.Ne + 15) / 16, TNp = tiles >= 5 ? 5 : tiles;
+    const size_t rows = (size_t)(tiles + TNp - 1) / TNp * TNp * 16;
+    return (3 * rows * L.d * sizeof(uint16_t) + 255) / 256 * 256;
+  }
   if (L.T > kSplitMaxT) return 0;
   return ((size_t)kSplitMax * (L.T > 0 ? L.T : 1) * (L.Ng + L.Ne) * sizeof(double) + 255) / 256 * 256;
 }
@@ -418,7 +675,7 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
   // 32-element steps) until there are about 128 of them
   a.dsplit = 1;
   a.gpart = nullptr;
-  if (ws && L.T <= kSplitMaxT && ws_bytes >= route_workspace_bytes(L)) {
+  if (ws && L.T <= kSplitMaxT && ws_bytes >= route_workspace_bytes(L, dtype)) {
     const int blocks = (L.T + 15) / 16;
     int ds = 1;
     while (ds * 2 <= kSplitMax && blocks * ds * 2 <= 128 && (a.kslice / (ds * 2)) % 32 == 0 &&
@@ -431,6 +688,40 @@ hipError_t launch_route(const LayerDesc& L, int dtype, const void* x, const floa
     }
   }
   const int tiles = (a.NO + 15) / 16;
+  // many bf16 tokens and a workspace for the split router rows: the bf16 matrix-core form
+  if (prefill_form(L, dtype) && ws && ws_bytes >= route_workspace_bytes(L, dtype)) {
+    const int TNp = tiles >= 5 ? 5 : tiles;                       // column tiles per pass
+    const int plane_rows = (tiles + TNp - 1) / TNp * TNp * 16;
+    uint16_t* planes = static_cast<uint16_t*>(ws);
+    const long long quads = (long long)plane_rows * (L.d / 4);
+    hipLaunchKernelGGL(route_split_kernel, dim3((unsigned)((quads + 255) / 256)), dim3(256), 0, s, w_group, w_expert,
+                       planes, L.Ng, a.NO, plane_rows, L.d);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t buf = (size_t)2 * 3 * 16 * TNp * 256;
+    const size_t rows_bytes = (size_t)8 * 5 * a.Nepad * sizeof(float);
+    // 64 tokens per workgroup when that still gives every compute unit one, else 32
+    for (int TG = (L.T >= 64 * tile_cus()) ? 4 : 2; TG >= 2; TG -= 2) {
+      const size_t red = (size_t)16 * TG * 16 * TNp * sizeof(double);
+      size_t r0 = buf > rows_bytes ? buf : rows_bytes;
+      if (red > r0) r0 = red;
+      a.region0 = (int)((r0 + 15) / 16 * 16);
+      const size_t smem_p = (size_t)a.region0 + (size_t)16 * TG * a.NOpad * sizeof(float);
+      if (smem_p > 160 * 1024) continue;
+      switch (TNp * 2 + (TG == 4)) {
+        case 2: return launch_prefill<2, 1>(a, L.T, planes, plane_rows, smem_p, s);
+        case 3: return launch_prefill<4, 1>(a, L.T, planes, plane_rows, smem_p, s);
+        case 4: return launch_prefill<2, 2>(a, L.T, planes, plane_rows, smem_p, s);
+        case 5: return launch_prefill<4, 2>(a, L.T, planes, plane_rows, smem_p, s);
+        case 6: return launch_prefill<2, 3>(a, L.T, planes, plane_rows, smem_p, s);
+        case 7: return launch_prefill<4, 3>(a, L.T, planes, plane_rows, smem_p, s);
+        case 8: return launch_prefill<2, 4>(a, L.T, planes, plane_rows, smem_p, s);
+        case 9: return launch_prefill<4, 4>(a, L.T, planes, plane_rows, smem_p, s);
+        case 10: return launch_prefill<2, 5>(a, L.T, planes, plane_rows, smem_p, s);
+        default: return launch_prefill<4, 5>(a, L.T, planes, plane_rows, smem_p, s);
+      }
+    }
+  }
   const int TN = tiles <= 1 ? 1 : tiles == 2 ? 2 : tiles == 3 ? 3 : 5;
   int TM = (L.T >= 16384 && TN <= 2) ? 2 : 1;   // wider combinations would spill registers
   size_t smem = 0;

@@ -907,3 +907,40 @@ def test_shared_routing_with_the_largest_expert_count():
                                                      k_experts=n_s, d_ff=(64,)), eidx.cpu().numpy())
     assert (perm.cpu().numpy() == p["perm"]).all() and (inv.cpu().numpy() == p["inv_perm"]).all()
     assert (gates == 1).all()
+
+
+@pytest.mark.parametrize("Ng,N,mode", [(3, 3, SELECT_PER_GROUP), (4, 16, SELECT_PER_GROUP), (4, 16, SELECT_GLOBAL),
+                                       (8, 16, SELECT_GLOBAL), (16, 16, SELECT_PER_GROUP)])
+def test_router_matrix_core_form_many_tokens(Ng, N, mode):
+    # from 8192 bf16 tokens on the logits come from the bf16 matrix cores (router rows split into
+    # three bf16 parts): 12 router rows (one column tile), 68 (one pass of five), 136 and 272
+    # (several passes), a token count that is not a multiple of the 32 / 64 a workgroup takes
+    import paper_2604_23108_amd as M
+    from gpu_harness import to_dev
+    w = Workload("route_mfma", T=8192 + 37, d=256, n_groups=Ng, experts_per_group=N, d_ff=(64,) * Ng,
+                 k_groups=2, k_experts=4, select_mode=mode, seed=300 + Ng * N, skew_beta=1.0)
+    inp = generate(w)
+    inp.w_group *= np.float32(12)
+    inp.w_expert *= np.float32(12)
+    cfg = M.Config.from_workload(w)
+    assert M.mohge_workspace_size(cfg, M.CALL_ROUTE) >= 3 * (Ng + Ng * N) * w.d * 2
+    x = to_dev(inp.x, True)
+    wg, we = torch.from_numpy(inp.w_group).cuda(), torch.from_numpy(inp.w_expert).cuda()
+    bias = torch.from_numpy(inp.expert_logit_bias).cuda()
+    i32 = dict(dtype=torch.int32, device="cuda")
+    f32 = dict(dtype=torch.float32, device="cuda")
+    outs = []
+    for use_ws in (True, False):            # without the workspace: the fp32 matrix-core form
+        gidx, eidx = torch.full((w.T, w.k_groups), -1, **i32), torch.full((w.T, w.k_experts), -1, **i32)
+        gates, gs, es1 = torch.zeros((w.T, w.k_experts), **f32), torch.zeros((w.T, Ng), **f32), torch.zeros((w.T, Ng * N), **f32)
+        ws = torch.empty(M.mohge_workspace_size(cfg, M.CALL_ROUTE), dtype=torch.uint8, device="cuda") if use_ws else None
+        print(f"[router] Ng={Ng} N={N} mode={mode} workspace={use_ws}", flush=True)
+        M.mohge_route(cfg, x, wg, we, bias, gidx, eidx, gates, gs, es1, ws)
+        torch.cuda.synchronize()
+        outs.append(dict(group_idx=gidx.cpu().numpy(), expert_idx=eidx.cpu().numpy(), gates=gates.cpu().numpy(),
+                         gs=gs.cpu().numpy(), es1=es1.cpu().numpy()))
+    ref = oracle.route(w, inp.x.f32, inp.w_group, inp.w_expert, inp.expert_logit_bias)
+    for out in outs:
+        keep, _ = check_routing(w, out, ref, "router, many tokens")
+        np.testing.assert_allclose(out["gs"], ref["gs"], atol=1e-6)
+        np.testing.assert_allclose(out["es1"][keep], ref["es1"][keep], atol=1e-6, rtol=2e-6)
