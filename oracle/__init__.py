@@ -31,6 +31,27 @@ def build(force: bool = True) -> str:
     return _LIB
 
 
+_LIB_SAN = os.path.join(_HERE, "libmohge_oracle_san.so")
+
+
+def build_sanitized() -> str:
+    """The oracle under AddressSanitizer + UndefinedBehaviorSanitizer (gcc), as a separate file.
+    A process that loads it needs gcc's libasan first in its library list (LD_PRELOAD); the
+    environment variable MOHGE_ORACLE_SANITIZED=1 makes this module load it instead of the
+    plain build."""
+    cmd = ["gcc", "-O1", "-g", "-fopenmp", "-fno-fast-math", "-ffp-contract=off", "-fsanitize=address,undefined",
+           "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-shared", "-fPIC", "-o", _LIB_SAN,
+           _SRC, _SRC_BWD, "-lm"]
+    subprocess.run(cmd, check=True)
+    return _LIB_SAN
+
+
+def gcc_asan_runtime() -> str:
+    p = subprocess.run(["gcc", "-print-file-name=libasan.so"], capture_output=True, text=True)
+    path = p.stdout.strip()
+    return path if p.returncode == 0 and os.path.isabs(path) and os.path.exists(path) else ""
+
+
 class _Cfg(C.Structure):
     _fields_ = [("T", C.c_int32), ("d", C.c_int32), ("n_groups", C.c_int32),
                 ("n_per_group", C.c_int32), ("d_ff", C.POINTER(C.c_int32)),
@@ -45,8 +66,11 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        build(force=False)
-        _lib = C.CDLL(_LIB)
+        if os.environ.get("MOHGE_ORACLE_SANITIZED") == "1":
+            _lib = C.CDLL(_LIB_SAN)
+        else:
+            build(force=False)
+            _lib = C.CDLL(_LIB)
         _lib.oracle_num_threads.restype = C.c_int
         for name in ("oracle_route", "oracle_permute", "oracle_expert_ffn", "oracle_combine",
                      "oracle_aux_loss", "oracle_combine_bwd", "oracle_expert_ffn_bwd",

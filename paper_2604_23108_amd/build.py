@@ -55,5 +55,42 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+# ---- host code under AddressSanitizer + UndefinedBehaviorSanitizer -------------------------------
+# Separate files (never loaded by the package): the same sources with the HOST pass instrumented
+# (device code is compiled as usual; sanitizers for GPU code are not used).  A process that loads
+# them needs the sanitizer runtime first in its library list: run it with LD_PRELOAD=asan_runtime().
+SAN_DIR = os.path.join(HERE, "_build_san")
+SAN_LIB = os.path.join(SAN_DIR, "libmohge.so")
+SAN_BENCH_LIB = os.path.join(SAN_DIR, "libmohge_bench.so")
+SAN_FLAGS = ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+
+
+def asan_runtime() -> str:
+    """Path of the shared AddressSanitizer runtime of the compiler hipcc drives ('' if absent)."""
+    p = subprocess.run(["hipcc", "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    path = p.stdout.strip()
+    return path if p.returncode == 0 and os.path.isabs(path) and os.path.exists(path) else ""
+
+
+def _compile_san(src: str) -> str:
+    obj = os.path.join(SAN_DIR, src.replace(".hip", ".o"))
+    p = subprocess.run(["hipcc", *FLAGS, *SAN_FLAGS, "-c", os.path.join(CSRC, src), "-o", obj],
+                       capture_output=True, text=True)
+    if p.returncode != 0:
+        raise RuntimeError(f"hipcc (sanitized host pass) failed for {src}:\n{p.stderr}")
+    return obj
+
+
+def build_sanitized() -> str:
+    os.makedirs(SAN_DIR, exist_ok=True)
+    with cf.ThreadPoolExecutor(max_workers=8) as ex:
+        objs = list(ex.map(_compile_san, SOURCES + BENCH_SOURCES))
+    san = ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"]
+    _link(SAN_LIB, objs[:len(SOURCES)], san)
+    _link(SAN_BENCH_LIB, objs[len(SOURCES):], san + ["-L", SAN_DIR, "-lmohge", "-Wl,-rpath,$ORIGIN"])
+    return SAN_LIB
+
+
 if __name__ == "__main__":
     build(verbose=True)

@@ -38,6 +38,7 @@ def _run_backward(w, inp):
     dy = to_dev(inp.dy, True)
     L.backward(dl.x, dy)
     torch.cuda.synchronize()
+    dl.check_guards()            # nothing was written outside dx, dx_perm, dy_perm, dgates, the weight gradients
     return dl, fwd, dy
 
 

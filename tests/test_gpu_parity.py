@@ -944,3 +944,17 @@ def test_router_matrix_core_form_many_tokens(Ng, N, mode):
         keep, _ = check_routing(w, out, ref, "router, many tokens")
         np.testing.assert_allclose(out["gs"], ref["gs"], atol=1e-6)
         np.testing.assert_allclose(out["es1"][keep], ref["es1"][keep], atol=1e-6, rtol=2e-6)
+
+
+def test_guard_bands_notice_a_write_outside_a_tensor():
+    # the canaries the harness puts around every output tensor do report a stray write (made here
+    # by the host, next to the tensor: no kernel is asked to misbehave)
+    from gpu_harness import GuardBands
+    g = GuardBands()
+    t = g.wrap(torch.zeros((5, 3), dtype=torch.float32, device="cuda"), "t")
+    t.fill_(1.0)
+    g.check()
+    buf = g.items[0][1]
+    buf[GuardBands.PAD + 5 * 3 * 4] = 0          # first byte behind the tensor
+    with pytest.raises(AssertionError, match="behind t"):
+        g.check()
