@@ -54,7 +54,8 @@ enum {
   MOHGE_CALL_PERMUTE = 0, MOHGE_CALL_EXPERT_FFN = 1, MOHGE_CALL_AUX_LOSS = 2,
   MOHGE_CALL_FFN_SAVED = 3,       /* `saved` of mohge_expert_ffn_train                      */
   MOHGE_CALL_EXPERT_FFN_BWD = 4, MOHGE_CALL_ROUTE_BWD = 5,
-  MOHGE_CALL_ROUTE = 6            /* optional workspace of mohge_route (0 when it has no use) */
+  MOHGE_CALL_ROUTE = 6,           /* optional workspace of mohge_route (0 when it has no use) */
+  MOHGE_CALL_DECODE_LAYER = 7     /* workspace of mohge_decode_layer                          */
 };
 
 typedef struct mohge_config {
@@ -270,6 +271,38 @@ int mohge_expert_ffn_w4(const mohge_config* cfg, const void* x, const int32_t* p
 int mohge_mxfp4_decode(const void* packed, const void* scales, float* out, size_t n, void* stream);
 
 /*
+ * The whole layer for a decode-sized call as ONE launch (not in the paper, which gives no kernel
+ * design: at a handful of tokens the layer is bound by streaming the touched experts' weights, and
+ * the gaps between five dependent launches are a measurable share of the step):
+ *     y = mohge_combine(mohge_expert_ffn(x, mohge_permute(mohge_route(x))))
+ * with the definitions of those calls (sections 3.2.1, 3.2.2 and 3.1 of the paper; appendix,
+ * first equation).  The pieces of work (partial logits, selection + permutation, units of the up
+ * and of the down projection, the gated sums) are workgroups of one grid that wait for each other
+ * through counters in the workspace; every wait is bounded.
+ * Only for cfg->dtype == MOHGE_BF16, T <= 32 and T*K_e <= 2048 (MOHGE_EINVAL otherwise).
+ * In:  x DEVICE [T,d] bf16; w_group DEVICE [N_g,d] f32; w_expert DEVICE [N_e,d] f32;
+ *      expert_logit_bias DEVICE [N_e] f32 or NULL; w13 / w2 HOST [N_g] of DEVICE pointers as for
+ *      mohge_expert_ffn.
+ * Out: y DEVICE [T,d] bf16; group_idx DEVICE [T,K_g], expert_idx DEVICE [T,K_e], gates DEVICE
+ *      [T,K_e] as mohge_route writes them.  The logits are those of the router's split form up to
+ *      the grouping of the fp64 partial sums; given equal routing, y is bit-identical to the four
+ *      separate calls.
+ * workspace DEVICE, mohge_workspace_size(cfg, MOHGE_CALL_DECODE_LAYER) bytes.  Its first
+ * mohge_decode_layer_ctl_bytes(cfg) bytes hold the counters: they MUST BE ZERO when the call
+ * starts and the call leaves them zero, so a workspace cleared once (hipMemset) serves any number
+ * of calls issued in stream order; calls that overlap on one workspace race.  If the counters
+ * are not zero at the start, or a wait expires, nothing hangs: y is overwritten with NaN and
+ * mohge_fused_status(cfg, MOHGE_CALL_DECODE_LAYER, workspace, ...) reports MOHGE_EINVAL or
+ * MOHGE_ETIMEOUT.
+ */
+int mohge_decode_layer(const mohge_config* cfg, const void* x, const float* w_group,
+                       const float* w_expert, const float* expert_logit_bias,
+                       const void* const* w13, const void* const* w2, int32_t* group_idx,
+                       int32_t* expert_idx, float* gates, void* y, void* workspace,
+                       size_t workspace_bytes, void* stream);
+size_t mohge_decode_layer_ctl_bytes(const mohge_config* cfg);
+
+/*
  * ---- Training: backward pass of the layer (dtype MOHGE_BF16 only; MOHGE_EINVAL otherwise) ----
  *
  * The paper trains the layer with  L_task + L_G + L_E  (sections 3.3, 3.4.2) and prints no
@@ -359,9 +392,11 @@ size_t mohge_workspace_size(const mohge_config* cfg, int which_call);
  * waits, for a bounded number of polls, until the tiles it depends on are complete; the design
  * guarantees they are already running, and a tile that gives up all the same writes NaN to its
  * output region and leaves a flag in the workspace.  This call SYNCHRONISES `stream`, reads the flag left by the
- * last call of `which_call` (MOHGE_CALL_EXPERT_FFN, MOHGE_CALL_FFN_SAVED or
- * MOHGE_CALL_EXPERT_FFN_BWD) on `workspace` (DEVICE; for MOHGE_CALL_FFN_SAVED the `saved`
- * buffer) and returns MOHGE_OK, or MOHGE_ETIMEOUT when that call's output holds NaN tiles.
+ * last call of `which_call` (MOHGE_CALL_EXPERT_FFN, MOHGE_CALL_FFN_SAVED,
+ * MOHGE_CALL_EXPERT_FFN_BWD or MOHGE_CALL_DECODE_LAYER) on `workspace` (DEVICE; for
+ * MOHGE_CALL_FFN_SAVED the `saved` buffer) and returns MOHGE_OK, or MOHGE_ETIMEOUT when that
+ * call's output holds NaN (MOHGE_CALL_DECODE_LAYER: also MOHGE_EINVAL when the counters in the
+ * workspace were not zero at the start).
  * MOHGE_OK at once where the call has no such launch for cfg (fp32, decode sizes).
  */
 int mohge_fused_status(const mohge_config* cfg, int which_call, const void* workspace,

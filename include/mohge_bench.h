@@ -76,6 +76,17 @@ int mohge_bench_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int
                                const mohge_ffn_options* options, void* stream);
 
 /*
+ * mohge_decode_layer (same arguments, same kernel) with the number of polls a waiting workgroup
+ * makes: 0 = the default (about a second), > 0 = that many, < 0 = give up without waiting (test
+ * hook: the launch drains, y is NaN and mohge_fused_status reports MOHGE_ETIMEOUT).
+ */
+int mohge_bench_decode_layer(const mohge_config* cfg, const void* x, const float* w_group,
+                             const float* w_expert, const float* expert_logit_bias,
+                             const void* const* w13, const void* const* w2, int32_t* group_idx,
+                             int32_t* expert_idx, float* gates, void* y, void* workspace,
+                             size_t workspace_bytes, int spin_limit, void* stream);
+
+/*
  * What the box delivers, for reading the kernels' fractions against measured ceilings.
  * mohge_probe_read enqueues a kernel that reads the first *bytes_read <= bytes bytes of buf
  * (DEVICE) exactly once and does nothing else: row_bytes = 0 as contiguous streams; otherwise

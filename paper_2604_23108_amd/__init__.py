@@ -12,6 +12,7 @@ from .binding import (  # noqa: F401
     F32, BF16, CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE, mohge_expert_ffn_train,
     mohge_combine_bwd, mohge_expert_ffn_bwd, mohge_route_bwd,
     mohge_shared_routing, mohge_combine_add, SharedExperts, mohge_expert_ffn_w8, mohge_fp8_decode,
-    mohge_fused_status, mohge_expert_ffn_w4, mohge_mxfp4_decode,
+    mohge_fused_status, mohge_expert_ffn_w4, mohge_mxfp4_decode, mohge_decode_layer,
+    mohge_decode_layer_ctl_bytes, CALL_DECODE_LAYER,
 )
 from .weights import quantize_rows_e4m3, quantize_mxfp4  # noqa: F401

@@ -14,7 +14,8 @@ from .binding import MohgeError, _check, _nbytes, _ptr, _ptr_table, _stream
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmohge_bench.so")
 
 EXPORTS = ["mohge_ffn_default_options", "mohge_bench_cycles_bytes", "mohge_bench_expert_ffn",
-           "mohge_bench_expert_ffn_train", "mohge_bench_expert_ffn_bwd", "mohge_probe_read", "mohge_probe_mfma"]
+           "mohge_bench_expert_ffn_train", "mohge_bench_expert_ffn_bwd", "mohge_probe_read", "mohge_probe_mfma",
+           "mohge_bench_decode_layer"]
 
 
 class _COptions(C.Structure):
@@ -96,6 +97,16 @@ def mohge_bench_expert_ffn_bwd(cfg, x, perm, offsets, w13, w2, saved, dy_perm, d
                                             _ptr_table(w2), _ptr(saved), _ptr(dy_perm), _ptr(dx_perm),
                                             _ptr_table(dw13), _ptr_table(dw2), _ptr(workspace), _nbytes(workspace),
                                             _opt(options), _stream()), "mohge_bench_expert_ffn_bwd")
+
+
+def mohge_bench_decode_layer(cfg, x, w_group, w_expert, expert_logit_bias, w13, w2, group_idx, expert_idx, gates, y,
+                             workspace, spin_limit: int = 0):
+    for t in list(w13) + list(w2):
+        _ptr(t)
+    _check(lib().mohge_bench_decode_layer(cfg.ref(), _ptr(x), _ptr(w_group), _ptr(w_expert), _ptr(expert_logit_bias),
+                                          _ptr_table(w13), _ptr_table(w2), _ptr(group_idx), _ptr(expert_idx),
+                                          _ptr(gates), _ptr(y), _ptr(workspace), _nbytes(workspace),
+                                          C.c_int(spin_limit), _stream()), "mohge_bench_decode_layer")
 
 
 def mohge_probe_read(buf: torch.Tensor, row_bytes: int, staggered: bool, out: torch.Tensor) -> int:

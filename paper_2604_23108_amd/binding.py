@@ -18,14 +18,17 @@ _LIB_PATH = os.path.join(_HERE, "libmohge.so")
 SELECT_GLOBAL, SELECT_PER_GROUP = 0, 1
 F32, BF16 = 0, 1
 CALL_PERMUTE, CALL_EXPERT_FFN, CALL_AUX_LOSS = 0, 1, 2
-CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE = 3, 4, 5, 6
+CALL_FFN_SAVED, CALL_EXPERT_FFN_BWD, CALL_ROUTE_BWD, CALL_ROUTE, CALL_DECODE_LAYER = 3, 4, 5, 6, 7
 
 EXPORTS = ["mohge_route", "mohge_permute", "mohge_permute_static", "mohge_expert_ffn", "mohge_combine",
            "mohge_aux_loss", "mohge_expert_ffn_up", "mohge_expert_ffn_down", "mohge_fused_status",
            "mohge_expert_ffn_train", "mohge_expert_ffn_w8", "mohge_fp8_decode", "mohge_expert_ffn_w4",
            "mohge_mxfp4_decode", "mohge_combine_bwd",
            "mohge_expert_ffn_bwd", "mohge_route_bwd", "mohge_shared_routing", "mohge_combine_add",
+           "mohge_decode_layer", "mohge_decode_layer_ctl_bytes",
            "mohge_workspace_size", "mohge_last_error"]
+
+_SIZE_RETURNS = ("mohge_workspace_size", "mohge_decode_layer_ctl_bytes")
 
 
 class MohgeError(RuntimeError):
@@ -55,9 +58,8 @@ def lib():
             raise MohgeError(f"{_LIB_PATH} is missing: build it with "
                              "`python -m paper_2604_23108_amd.build` (there is no fallback path)")
         l = C.CDLL(_LIB_PATH)
-        for n in EXPORTS[:-2]:
-            getattr(l, n).restype = C.c_int
-        l.mohge_workspace_size.restype = C.c_size_t
+        for n in EXPORTS[:-1]:
+            getattr(l, n).restype = C.c_size_t if n in _SIZE_RETURNS else C.c_int
         l.mohge_last_error.restype = C.c_char_p
         _lib = l
     return _lib
@@ -167,11 +169,26 @@ def mohge_expert_ffn(cfg, x, perm, offsets, w13: Sequence[torch.Tensor], w2: Seq
 
 
 def mohge_fused_status(cfg, which_call: int, workspace) -> int:
-    """Synchronises; 0, or MOHGE_ETIMEOUT (-6) when a tile of the last fused launch gave up waiting."""
+    """Synchronises; 0, or MOHGE_ETIMEOUT (-6) when a tile of the last fused launch gave up waiting
+    (CALL_DECODE_LAYER: also MOHGE_EINVAL (-1) when the workspace counters were not zero)."""
     rc = lib().mohge_fused_status(cfg.ref(), C.c_int(which_call), _ptr(workspace), _nbytes(workspace), _stream())
-    if rc not in (0, -6):
+    if rc not in (0, -6) and not (rc == -1 and which_call == CALL_DECODE_LAYER):
         _check(rc, "mohge_fused_status")
     return rc
+
+
+def mohge_decode_layer(cfg, x, w_group, w_expert, expert_logit_bias, w13, w2, group_idx, expert_idx, gates, y,
+                       workspace):
+    for t in list(w13) + list(w2):
+        _ptr(t)
+    _check(lib().mohge_decode_layer(cfg.ref(), _ptr(x), _ptr(w_group), _ptr(w_expert), _ptr(expert_logit_bias),
+                                    _ptr_table(w13), _ptr_table(w2), _ptr(group_idx), _ptr(expert_idx),
+                                    _ptr(gates), _ptr(y), _ptr(workspace), _nbytes(workspace), _stream()),
+           "mohge_decode_layer")
+
+
+def mohge_decode_layer_ctl_bytes(cfg: Config) -> int:
+    return int(lib().mohge_decode_layer_ctl_bytes(cfg.ref()))
 
 
 def mohge_expert_ffn_w8(cfg, x, perm, offsets, w13q, w13_scale, w2q, w2_scale, y_perm, workspace):
@@ -433,6 +450,19 @@ class MoHGELayer:
         if self.training:
             mohge_aux_loss(c, self.gs, self.es1, self.group_idx, self.expert_idx, self.losses,
                            self.stats, self.ws_aux)
+        return self.y
+
+    def forward_decode(self, x: torch.Tensor) -> torch.Tensor:
+        """The forward pass of a decode-sized bf16 call as one launch (mohge_decode_layer): fills
+        group_idx, expert_idx, gates and y like forward().  The workspace is allocated and cleared
+        on first use."""
+        if getattr(self, "ws_decode", None) is None:
+            n = mohge_workspace_size(self.cfg, CALL_DECODE_LAYER)
+            if n == 0:
+                raise MohgeError("mohge_decode_layer serves bf16 calls of at most 32 tokens")
+            self.ws_decode = torch.zeros(n, dtype=torch.uint8, device=x.device)
+        mohge_decode_layer(self.cfg, x, self.w_group, self.w_expert, self.bias, self.w13, self.w2,
+                           self.group_idx, self.expert_idx, self.gates, self.y, self.ws_decode)
         return self.y
 
     def use_fp8_weights(self):

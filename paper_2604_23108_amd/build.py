@@ -16,7 +16,7 @@ BENCH_LIB = os.path.join(HERE, "libmohge_bench.so")
 OBJDIR = os.path.join(HERE, "_build")
 
 SOURCES = ["api.hip", "route.hip", "permute.hip", "ffn.hip", "ffn_tiled.hip", "ffn_skinny.hip",
-           "combine.hip", "aux_loss.hip", "ffn_bwd.hip", "route_bwd.hip"]
+           "combine.hip", "aux_loss.hip", "ffn_bwd.hip", "route_bwd.hip", "decode_layer.hip"]
 BENCH_SOURCES = ["bench_api.hip", "box_probe.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,

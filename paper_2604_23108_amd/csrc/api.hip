@@ -89,6 +89,30 @@ int mohge_fused_status(const mohge_config* cfg, int which_call, const void* work
   LayerDesc L;
   int rc = check_config(cfg, &L);
   if (rc) return rc;
+  if (which_call == MOHGE_CALL_DECODE_LAYER) {
+    if (!decode_layer_supported(L, cfg->dtype) || L.T == 0) return MOHGE_OK;
+    NEED(workspace);
+    if (workspace_bytes < decode_layer_workspace_bytes(L)) {
+      set_error("mohge_fused_status: workspace of %zu bytes, the call uses %zu", workspace_bytes,
+                decode_layer_workspace_bytes(L));
+      return MOHGE_EWORKSPACE;
+    }
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_rc(e, "mohge_fused_status (synchronise)");
+    int st = 0;
+    e = hipMemcpy(&st, static_cast<const unsigned char*>(workspace) + decode_layer_status_offset(L), sizeof(st),
+                  hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_rc(e, "mohge_fused_status (copy)");
+    if (st & 2) {
+      set_error("mohge_decode_layer: the counters at the start of the workspace were not zero when the call started");
+      return MOHGE_EINVAL;
+    }
+    if (st != 0) {
+      set_error("mohge_decode_layer: a workgroup gave up waiting for the work it depends on: y holds NaN");
+      return MOHGE_ETIMEOUT;
+    }
+    return MOHGE_OK;
+  }
   if (which_call != MOHGE_CALL_EXPERT_FFN && which_call != MOHGE_CALL_FFN_SAVED &&
       which_call != MOHGE_CALL_EXPERT_FFN_BWD) {
     set_error("mohge_fused_status: call id %d has no fused launch", which_call);
@@ -125,6 +149,7 @@ size_t mohge_workspace_size(const mohge_config* cfg, int which_call) {
     case MOHGE_CALL_EXPERT_FFN_BWD: return ffn_bwd_workspace_bytes(L);
     case MOHGE_CALL_ROUTE_BWD: return route_bwd_workspace_bytes(L);
     case MOHGE_CALL_ROUTE: return route_workspace_bytes(L, cfg->dtype);
+    case MOHGE_CALL_DECODE_LAYER: return decode_layer_supported(L, cfg->dtype) ? decode_layer_workspace_bytes(L) : 0;
     default: set_error("unknown call id %d", which_call); return 0;
   }
 }
@@ -208,6 +233,55 @@ int mohge_expert_ffn(const mohge_config* cfg, const void* x, const int32_t* perm
   return hip_rc(launch_expert_ffn(L, cfg->dtype, x, perm, offsets, W, y_perm, workspace,
                                   (hipStream_t)stream, 3),
                 "mohge_expert_ffn");
+}
+
+static int decode_layer_args(const mohge_config* cfg, LayerDesc& L, const void* x, const float* w_group,
+                             const float* w_expert, const float* expert_logit_bias, const void* const* w13,
+                             const void* const* w2, int32_t* group_idx, int32_t* expert_idx, float* gates,
+                             void* y, void* workspace, size_t workspace_bytes, GroupPtrs& W) {
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if (!decode_layer_supported(L, cfg->dtype)) {
+    set_error("mohge_decode_layer serves bf16 calls of at most 32 tokens and 2048 (token, expert) pairs: "
+              "dtype = %d, T = %d, T*K_e = %d", cfg->dtype, L.T, L.P);
+    return MOHGE_EINVAL;
+  }
+  NEED(x); NEED(w_group); NEED(w_expert); OPT(expert_logit_bias);
+  NEED(group_idx); NEED(expert_idx); NEED(gates); NEED(y); NEED(workspace);
+  if (!w13 || !w2) { set_error("w13 / w2 pointer table is NULL"); return MOHGE_ENULL; }
+  memset(&W, 0, sizeof(W));
+  for (int g = 0; g < L.Ng; ++g) {
+    NEED(w13[g]); NEED(w2[g]);
+    W.w13[g] = w13[g];
+    W.w2[g] = w2[g];
+  }
+  if (workspace_bytes < decode_layer_workspace_bytes(L)) {
+    set_error("decode_layer workspace: %zu bytes given, %zu needed", workspace_bytes, decode_layer_workspace_bytes(L));
+    return MOHGE_EWORKSPACE;
+  }
+  return MOHGE_OK;
+}
+
+int mohge_decode_layer(const mohge_config* cfg, const void* x, const float* w_group,
+                       const float* w_expert, const float* expert_logit_bias,
+                       const void* const* w13, const void* const* w2, int32_t* group_idx,
+                       int32_t* expert_idx, float* gates, void* y, void* workspace,
+                       size_t workspace_bytes, void* stream) {
+  LayerDesc L;
+  GroupPtrs W;
+  int rc = decode_layer_args(cfg, L, x, w_group, w_expert, expert_logit_bias, w13, w2, group_idx, expert_idx,
+                             gates, y, workspace, workspace_bytes, W);
+  if (rc) return rc;
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_decode_layer(L, x, w_group, w_expert, expert_logit_bias, W, group_idx, expert_idx, gates,
+                                    y, workspace, 0, (hipStream_t)stream),
+                "mohge_decode_layer");
+}
+
+size_t mohge_decode_layer_ctl_bytes(const mohge_config* cfg) {
+  LayerDesc L;
+  if (check_config(cfg, &L) || !decode_layer_supported(L, cfg->dtype)) return 0;
+  return decode_layer_ctl_bytes(L);
 }
 
 static int need_bf16(const mohge_config* cfg, const char* what) {

@@ -177,4 +177,30 @@ int mohge_probe_mfma(void* out, size_t out_bytes, int iters, double* flops, void
   return hip_rc(launch_probe_mfma(out, blocks, iters, flops, (hipStream_t)stream), "mohge_probe_mfma");
 }
 
+int mohge_bench_decode_layer(const mohge_config* cfg, const void* x, const float* w_group,
+                             const float* w_expert, const float* expert_logit_bias,
+                             const void* const* w13, const void* const* w2, int32_t* group_idx,
+                             int32_t* expert_idx, float* gates, void* y, void* workspace,
+                             size_t workspace_bytes, int spin_limit, void* stream) {
+  LayerDesc L;
+  int rc = check_config(cfg, &L);
+  if (rc) return rc;
+  if (!decode_layer_supported(L, cfg->dtype)) {
+    set_error("mohge_bench_decode_layer: bf16 calls of at most 32 tokens only");
+    return MOHGE_EINVAL;
+  }
+  NEED(x); NEED(w_group); NEED(w_expert); OPT(expert_logit_bias);
+  NEED(group_idx); NEED(expert_idx); NEED(gates); NEED(y); NEED(workspace);
+  GroupPtrs W;
+  if ((rc = weight_tables(L, w13, w2, &W))) return rc;
+  if (workspace_bytes < decode_layer_workspace_bytes(L)) {
+    set_error("decode_layer workspace: %zu bytes given, %zu needed", workspace_bytes, decode_layer_workspace_bytes(L));
+    return MOHGE_EWORKSPACE;
+  }
+  if (L.T == 0) return MOHGE_OK;
+  return hip_rc(launch_decode_layer(L, x, w_group, w_expert, expert_logit_bias, W, group_idx, expert_idx, gates, y,
+                                    workspace, spin_limit, (hipStream_t)stream),
+                "mohge_bench_decode_layer");
+}
+
 }  // extern "C"

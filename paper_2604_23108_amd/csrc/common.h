@@ -128,6 +128,14 @@ hipError_t launch_route_bwd(const LayerDesc& L, const mohge_config& cfg, const v
                             const void* dx_perm, const int32_t* inv_perm, void* dx, float* dw_group,
                             float* dw_expert, float* dz_out, void* ws, hipStream_t s);
 size_t tiled_sched_bytes(const LayerDesc& L);
+// the whole layer of a decode-sized call in one launch (decode_layer.hip)
+bool decode_layer_supported(const LayerDesc& L, int dtype);
+size_t decode_layer_workspace_bytes(const LayerDesc& L);
+size_t decode_layer_ctl_bytes(const LayerDesc& L);
+long long decode_layer_status_offset(const LayerDesc& L);
+hipError_t launch_decode_layer(const LayerDesc& L, const void* x, const float* w_group, const float* w_expert,
+                               const float* bias, const GroupPtrs& W, int32_t* group_idx, int32_t* expert_idx,
+                               float* gates, void* y, void* ws, int spin_limit, hipStream_t s);
 size_t aux_workspace_bytes(const LayerDesc& L);
 hipError_t launch_aux_loss(const LayerDesc& L, const mohge_config& cfg, const float* gs,
                            const float* es1, const int32_t* group_idx, const int32_t* expert_idx,
