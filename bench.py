@@ -171,6 +171,35 @@ def tile_phases(torch, BB, cfg, L, x):
     }
 
 
+def decode_timeline(torch, BB, M, L, x):
+    """When the pieces of the single-launch decode layer ran (time stamps of the benchmark library)."""
+    import numpy as np
+    cfg = L.cfg
+    tr = BB.decode_trace_buffer(cfg)
+    for _ in range(3):
+        tr.zero_()
+        BB.mohge_bench_decode_layer(cfg, x, L.w_group, L.w_expert, L.bias, L.w13, L.w2, L.group_idx, L.expert_idx,
+                                    L.gates, L.y, L.ws_decode, 0, tr)
+        torch.cuda.synchronize()
+    t = tr.cpu().numpy().astype(np.float64) / 100.0                      # microseconds
+    counts = np.bincount(L.expert_idx.cpu().numpy().reshape(-1), minlength=cfg.n_experts)
+    F_e = np.repeat(np.asarray(cfg.d_ff), cfg.experts_per_group)
+    n_route = ((cfg.T + 15) // 16) * ((cfg.n_groups + cfg.n_experts + 15) // 16) * ((cfg.d + 255) // 256)
+    nA = n_route + (cfg.T + 3) // 4
+    U = int(((counts > 0) * (F_e // 64)).sum())
+    D = int((counts > 0).sum()) * ((cfg.d + 127) // 128)
+    t0 = t[:nA + U + D, 0].min()
+    s, a, e = t[:, 0] - t0, t[:, 1] - t0, t[:, 3] - t0
+    up, dn = slice(nA, nA + U), slice(nA + U, nA + U + D)
+    r = lambda v: round(float(v), 1)
+    return {"unit": "us after the first piece started", "route_tasks": n_route, "up_units": U, "down_units": D,
+            "route_done": r(e[:n_route].max()), "routing_published": r(e[n_route:nA].max()),
+            "first_up_unit_streams": r(s[up].min()), "up_unit_us_median_max": [r(np.median((e - s)[up])), r((e - s)[up].max())],
+            "last_up_unit_done": r(e[up].max()), "first_expert_complete": r(a[dn].min()),
+            "down_units_waited_us_median_max": [r(np.median((a - s)[dn])), r((a - s)[dn].max())],
+            "last_down_unit_done": r(e[dn].max())}
+
+
 def measure(args, name, backward, torch, M, BB, steps, warmup, full):
     """One workload: K steps between events, per-call times, roofline of the dominant kernel."""
     import numpy as np
@@ -207,9 +236,16 @@ def measure(args, name, backward, torch, M, BB, steps, warmup, full):
             L.w13, L.w2, L.w8, L.w4 = weight_sets[flip[0]]
         return True
 
+    single = full and args.single_launch
+    if single and (w.T > 32 or backward or quant or w.dtype != "bf16"):
+        sys.exit("bench.py: --single-launch is the bf16 decode layer as one launch (T <= 32, forward only)")
+
     def step():
         flipw()
-        L.forward(x)
+        if single:
+            L.forward_decode(x)
+        else:
+            L.forward(x)
         if backward:
             L.backward(x, dy)
 
@@ -270,8 +306,11 @@ def measure(args, name, backward, torch, M, BB, steps, warmup, full):
                                                    L.expert_idx, L.gates, L.dgates, L.stats, L.dx_perm, L.inv_perm,
                                                    L.dx, L.dw_group, L.dw_expert, L.dz, L.ws_route_bwd),
         })
+    if w.T <= 32 and w.dtype == "bf16" and not quant and not backward:
+        # the same layer as one launch (mohge_decode_layer)
+        calls["decode_layer"] = lambda: flipw() and L.forward_decode(x) is not None
     if not full:
-        keep = ("ffn", "route", "combine", "permute") + (("ffn_up",) if w.T <= 32 else ()) + (("ffn_train_fwd", "ffn_bwd") if backward else ())
+        keep = ("ffn", "route", "combine", "permute", "decode_layer") + (("ffn_up",) if w.T <= 32 else ()) + (("ffn_train_fwd", "ffn_bwd") if backward else ())
         calls = {k: v for k, v in calls.items() if k in keep}
     call_ms = {k: event_time(f, it, torch) for k, f in calls.items()}
     fused_alone = w.T > 32 and w.dtype == "bf16" and not backward
@@ -281,6 +320,10 @@ def measure(args, name, backward, torch, M, BB, steps, warmup, full):
         ffn_part = lambda p: BB.mohge_bench_expert_ffn(cfg, x, L.perm, L.offsets, L.w13, L.w2, L.y_perm, L.ws_ffn, None, p)
         call_ms["ffn_tiles"] = event_time_inner(lambda: ffn_part(1), lambda: ffn_part(2), it, torch)
 
+    if "decode_layer" in call_ms:
+        if M.mohge_fused_status(cfg, M.CALL_DECODE_LAYER, L.ws_decode) != 0:
+            sys.exit(f"bench.py: {name}: {M.mohge_last_error()}")
+        L.forward(x)                       # (the per-call state below is that of the separate calls)
     if full and args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
         for _ in range(3):
@@ -353,6 +396,8 @@ def measure(args, name, backward, torch, M, BB, steps, warmup, full):
         parts["step"] = "forward (activations kept) + aux losses + backward"
     if full and args.tile_phases and fused_alone:
         parts["tile_phases"] = tile_phases(torch, BB, cfg, L, x)
+    if full and args.decode_timeline and "decode_layer" in call_ms:
+        parts["decode_layer_timeline"] = decode_timeline(torch, BB, M, L, x)
     res = dict(w=w, inp=inp, ms_events=ms_events, ms_wall=ms_wall, roof=roof, parts=parts, quant=quant)
     del dl, L
     return res
@@ -409,6 +454,10 @@ def main():
                          "patterns, back-to-back bf16 MFMAs) and print one JSON line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--single-launch", action="store_true",
+                    help="decode workloads: the step is ONE launch (mohge_decode_layer) instead of the four calls")
+    ap.add_argument("--decode-timeline", action="store_true",
+                    help="decode workloads: add when the pieces of the single-launch layer ran (benchmark library's time stamps)")
     ap.add_argument("--tile-phases", action="store_true",
                     help="prefill workloads: add the clock breakdown of the fused expert launch (setup, wait, main "
                          "loop, epilogue, core clock, idle tail) from the benchmark library's counters")
@@ -454,7 +503,8 @@ def main():
                   "around the same K steps between two synchronisations",
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": ("bf16 (expert weights fp8 e4m3)" if args.fp8_weights else "bf16 (expert weights mxfp4)" if args.mxfp4_weights else "bf16") if w.dtype == "bf16" else "f32",
-        "data": "synthetic", "launch": "hip graph replay of the step" if args.graph else "eager",
+        "data": "synthetic", "launch": "hip graph replay of the step" if args.graph else
+                                       "eager, the layer as one launch (mohge_decode_layer)" if args.single_launch else "eager",
         "config": {"workload": w.name, "T": w.T, "d": w.d, "groups_x_experts": f"{w.n_groups}x{w.experts_per_group}",
                    "d_ff": list(w.d_ff), "k_groups": w.k_groups, "k_experts": w.k_experts,
                    "select_mode": "per_group" if w.select_mode == 1 else "global", "seed": w.seed,

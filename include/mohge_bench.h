@@ -76,15 +76,22 @@ int mohge_bench_expert_ffn_bwd(const mohge_config* cfg, const void* x, const int
                                const mohge_ffn_options* options, void* stream);
 
 /*
- * mohge_decode_layer (same arguments, same kernel) with the number of polls a waiting workgroup
- * makes: 0 = the default (about a second), > 0 = that many, < 0 = give up without waiting (test
- * hook: the launch drains, y is NaN and mohge_fused_status reports MOHGE_ETIMEOUT).
+ * mohge_decode_layer (same arguments, same kernel) with
+ *  - spin_limit: the number of polls a waiting workgroup makes: 0 = the default (about a second),
+ *    > 0 = that many, < 0 = give up without waiting (test hook: the launch drains, y is NaN and
+ *    mohge_fused_status reports MOHGE_ETIMEOUT);
+ *  - trace: NULL, or DEVICE int64 [pieces][4], mohge_bench_decode_trace_bytes(cfg) bytes, zeroed by
+ *    the caller: 100 MHz time stamps of every piece of work of the launch.  Pieces are numbered in
+ *    queue order: the route tasks, the select tasks, then the units of the experts that have rows
+ *    (up units expert by expert, then down units in the order in which the experts' up units became
+ *    complete).  [0] the piece was taken up, [1] down units: its expert was available, [3] done.
  */
 int mohge_bench_decode_layer(const mohge_config* cfg, const void* x, const float* w_group,
                              const float* w_expert, const float* expert_logit_bias,
                              const void* const* w13, const void* const* w2, int32_t* group_idx,
                              int32_t* expert_idx, float* gates, void* y, void* workspace,
-                             size_t workspace_bytes, int spin_limit, void* stream);
+                             size_t workspace_bytes, int spin_limit, void* trace, size_t trace_bytes, void* stream);
+size_t mohge_bench_decode_trace_bytes(const mohge_config* cfg);
 
 /*
  * What the box delivers, for reading the kernels' fractions against measured ceilings.

@@ -15,7 +15,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmohge_b
 
 EXPORTS = ["mohge_ffn_default_options", "mohge_bench_cycles_bytes", "mohge_bench_expert_ffn",
            "mohge_bench_expert_ffn_train", "mohge_bench_expert_ffn_bwd", "mohge_probe_read", "mohge_probe_mfma",
-           "mohge_bench_decode_layer"]
+           "mohge_bench_decode_layer", "mohge_bench_decode_trace_bytes"]
 
 
 class _COptions(C.Structure):
@@ -37,7 +37,7 @@ def lib():
             raise MohgeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2604_23108_amd.build`")
         l = C.CDLL(_LIB_PATH)
         for n in EXPORTS[2:]:
-            getattr(l, n).restype = C.c_int
+            getattr(l, n).restype = C.c_size_t if n == "mohge_bench_decode_trace_bytes" else C.c_int
         l.mohge_bench_cycles_bytes.restype = C.c_size_t
         l.mohge_ffn_default_options.restype = None
         _lib = l
@@ -100,13 +100,20 @@ def mohge_bench_expert_ffn_bwd(cfg, x, perm, offsets, w13, w2, saved, dy_perm, d
 
 
 def mohge_bench_decode_layer(cfg, x, w_group, w_expert, expert_logit_bias, w13, w2, group_idx, expert_idx, gates, y,
-                             workspace, spin_limit: int = 0):
+                             workspace, spin_limit: int = 0, trace=None):
     for t in list(w13) + list(w2):
         _ptr(t)
     _check(lib().mohge_bench_decode_layer(cfg.ref(), _ptr(x), _ptr(w_group), _ptr(w_expert), _ptr(expert_logit_bias),
                                           _ptr_table(w13), _ptr_table(w2), _ptr(group_idx), _ptr(expert_idx),
                                           _ptr(gates), _ptr(y), _ptr(workspace), _nbytes(workspace),
-                                          C.c_int(spin_limit), _stream()), "mohge_bench_decode_layer")
+                                          C.c_int(spin_limit), _ptr(trace),
+                                          _nbytes(trace) if trace is not None else C.c_size_t(0), _stream()), "mohge_bench_decode_layer")
+
+
+def decode_trace_buffer(cfg) -> torch.Tensor:
+    """A zeroed trace buffer for mohge_bench_decode_layer: int64 [pieces, 4]."""
+    n = int(lib().mohge_bench_decode_trace_bytes(cfg.ref())) // 32
+    return torch.zeros((n, 4), dtype=torch.int64, device="cuda")
 
 
 def mohge_probe_read(buf: torch.Tensor, row_bytes: int, staggered: bool, out: torch.Tensor) -> int:

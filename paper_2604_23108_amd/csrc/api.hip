@@ -274,7 +274,7 @@ int mohge_decode_layer(const mohge_config* cfg, const void* x, const float* w_gr
   if (rc) return rc;
   if (L.T == 0) return MOHGE_OK;
   return hip_rc(launch_decode_layer(L, x, w_group, w_expert, expert_logit_bias, W, group_idx, expert_idx, gates,
-                                    y, workspace, 0, (hipStream_t)stream),
+                                    y, workspace, 0, nullptr, (hipStream_t)stream),
                 "mohge_decode_layer");
 }
 

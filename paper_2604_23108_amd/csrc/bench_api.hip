@@ -177,11 +177,17 @@ int mohge_probe_mfma(void* out, size_t out_bytes, int iters, double* flops, void
   return hip_rc(launch_probe_mfma(out, blocks, iters, flops, (hipStream_t)stream), "mohge_probe_mfma");
 }
 
+size_t mohge_bench_decode_trace_bytes(const mohge_config* cfg) {
+  LayerDesc L;
+  if (check_config(cfg, &L) || !decode_layer_supported(L, cfg->dtype)) return 0;
+  return (size_t)decode_layer_trace_entries(L) * 4 * sizeof(long long);
+}
+
 int mohge_bench_decode_layer(const mohge_config* cfg, const void* x, const float* w_group,
                              const float* w_expert, const float* expert_logit_bias,
                              const void* const* w13, const void* const* w2, int32_t* group_idx,
                              int32_t* expert_idx, float* gates, void* y, void* workspace,
-                             size_t workspace_bytes, int spin_limit, void* stream) {
+                             size_t workspace_bytes, int spin_limit, void* trace, size_t trace_bytes, void* stream) {
   LayerDesc L;
   int rc = check_config(cfg, &L);
   if (rc) return rc;
@@ -197,9 +203,15 @@ int mohge_bench_decode_layer(const mohge_config* cfg, const void* x, const float
     set_error("decode_layer workspace: %zu bytes given, %zu needed", workspace_bytes, decode_layer_workspace_bytes(L));
     return MOHGE_EWORKSPACE;
   }
+  OPT(trace);
+  if (trace && trace_bytes < (size_t)decode_layer_trace_entries(L) * 4 * sizeof(long long)) {
+    set_error("mohge_bench_decode_layer: trace of %zu bytes, mohge_bench_decode_trace_bytes says %zu", trace_bytes,
+              (size_t)decode_layer_trace_entries(L) * 4 * sizeof(long long));
+    return MOHGE_EWORKSPACE;
+  }
   if (L.T == 0) return MOHGE_OK;
   return hip_rc(launch_decode_layer(L, x, w_group, w_expert, expert_logit_bias, W, group_idx, expert_idx, gates, y,
-                                    workspace, spin_limit, (hipStream_t)stream),
+                                    workspace, spin_limit, static_cast<long long*>(trace), (hipStream_t)stream),
                 "mohge_bench_decode_layer");
 }
 

@@ -133,9 +133,10 @@ bool decode_layer_supported(const LayerDesc& L, int dtype);
 size_t decode_layer_workspace_bytes(const LayerDesc& L);
 size_t decode_layer_ctl_bytes(const LayerDesc& L);
 long long decode_layer_status_offset(const LayerDesc& L);
+long long decode_layer_trace_entries(const LayerDesc& L);
 hipError_t launch_decode_layer(const LayerDesc& L, const void* x, const float* w_group, const float* w_expert,
                                const float* bias, const GroupPtrs& W, int32_t* group_idx, int32_t* expert_idx,
-                               float* gates, void* y, void* ws, int spin_limit, hipStream_t s);
+                               float* gates, void* y, void* ws, int spin_limit, long long* trace, hipStream_t s);
 size_t aux_workspace_bytes(const LayerDesc& L);
 hipError_t launch_aux_loss(const LayerDesc& L, const mohge_config& cfg, const float* gs,
                            const float* es1, const int32_t* group_idx, const int32_t* expert_idx,

@@ -192,3 +192,30 @@ def test_decode_layer_failures_are_loud():
     assert "not zero" in M.mohge_last_error()
     assert bool(torch.isnan(L.y.float()).all())
     dl.check_guards()
+
+
+def test_decode_layer_time_stamps_of_the_benchmark_library():
+    """The optional trace: every piece of work that ran left a start and an end, in that order, and
+    the result is the one of the plain call."""
+    import paper_2604_23108_amd as M
+    from paper_2604_23108_amd import bench_binding as BB
+    w = Workload("dec6", T=11, d=768, n_groups=3, experts_per_group=4, d_ff=(64, 128, 256), k_groups=2, k_experts=4, seed=12)
+    dl = _layer(w, generate(w))
+    L = dl.layer
+    good = L.forward_decode(dl.x).clone()
+    tr = BB.decode_trace_buffer(L.cfg)
+    BB.mohge_bench_decode_layer(L.cfg, dl.x, L.w_group, L.w_expert, L.bias, L.w13, L.w2, L.group_idx, L.expert_idx,
+                                L.gates, L.y, L.ws_decode, 0, tr)
+    torch.cuda.synchronize()
+    assert M.mohge_fused_status(L.cfg, M.CALL_DECODE_LAYER, L.ws_decode) == 0
+    assert torch.equal(L.y.view(torch.int16), good.view(torch.int16))
+    t = tr.cpu().numpy()
+    counts = np.bincount(L.expert_idx.cpu().numpy().reshape(-1), minlength=w.n_experts)
+    F_e = np.repeat(np.asarray(w.d_ff), w.experts_per_group)
+    pieces = 1 * 1 * 3 + 3 + int(((counts > 0) * (F_e // 64)).sum()) + int((counts > 0).sum()) * 6
+    assert pieces <= t.shape[0]
+    assert (t[:pieces, 0] > 0).all() and (t[:pieces, 3] >= t[:pieces, 0]).all() and (t[pieces:] == 0).all()
+    with pytest.raises(M.MohgeError, match="trace"):
+        BB.mohge_bench_decode_layer(L.cfg, dl.x, L.w_group, L.w_expert, L.bias, L.w13, L.w2, L.group_idx, L.expert_idx,
+                                    L.gates, L.y, L.ws_decode, 0, tr[:4])
+    dl.check_guards()
