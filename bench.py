@@ -27,7 +27,7 @@ HEADLINE = "large_prefill_skewed"
 OTHERS = (("mid_prefill", False), ("decode", False), ("training", False), ("training", True),
           ("paper_14b", False))
 
-KERNEL_SOURCES = ("ffn_tiled.hip", "tiled.h", "ffn_skinny.hip", "ffn.hip", "common.h")
+KERNEL_SOURCES = ("ffn_tiled.hip", "tiled.h", "ffn_skinny.hip", "skinny.h", "ffn.hip", "common.h")
 
 
 def kernel_source_hash() -> str:

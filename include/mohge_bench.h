@@ -35,6 +35,8 @@ typedef struct mohge_ffn_options {
   int32_t band_rows;       /* row blocks per band of the tile order inside an expert (0 = default) */
   int32_t group_major;     /* 1: experts visited group by group (widest first); 0: by all-size sets */
   int32_t steal;           /* 1: workgroups whose XCD range is exhausted draw from the other ranges */
+  int32_t short_last;      /* 1: in the second list of a fused launch the tiles with the shortest
+                              reduction come last inside every XCD range                          */
   int32_t cycles_launch;   /* mohge_bench_expert_ffn_bwd: which fused launch fills `cycles`
                               (0 = dH / dX, 1 = the weight gradients)                              */
   void* cycles;            /* DEVICE or NULL: int64 counters of the fused launch, zeroed by the

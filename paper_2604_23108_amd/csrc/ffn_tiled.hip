@@ -100,9 +100,11 @@ struct SchedShared {
   long long cp[kMaxExperts + 1];   // cost before expert v
   int e[kMaxExperts], cnt[kMaxExperts], nt[kMaxExperts], kc[kMaxExperts], row0[kMaxExperts];
   int fp[kMaxExperts + 1];         // row blocks before expert v
-  long long wsum[4][3];
+  int sp[kMaxExperts + 1];         // tiles of the shortest reduction before expert v (see build_schedule)
+  long long wsum[4][4];
   int rows;
   int xb[kXcds + 1];               // tile ranges per XCD (copy of the header's)
+  int xs[kXcds + 1];               // tiles of the shortest reduction before each range
 };
 
 // Per-expert quantities of a mode: rows (`cnt`, starting at `row0`), output columns, and
@@ -207,16 +209,30 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   // costs about 1850 + 100 * units clocks, so a short tile is almost as expensive as a full one
   const long long my_c = ((long long)kTileCost * ((cnt + h - 1) / h) + (cnt + 63) / 64) * nt * kc;
   const long long my_f = MODE == kWgrad ? 0 : (cnt + h - 1) / h;
+  // Second list of a fused launch (its tiles wait for tiles of the first): inside every XCD range
+  // the tiles of the groups with the shortest reduction go last, everything else keeps its order.
+  // The end of a range is then handed out in its smallest pieces (the launch ends when the slowest
+  // workgroup does), and a tile only ever moves to a LATER position, so none meets its row block
+  // earlier than before.
+  int kmin = 1 << 30, kmax = 0;
+  for (int g = 0; g < a.Ng; ++g) {
+    const int k = (red_d(MODE) ? a.d : a.F[g]) / 64;
+    kmin = min(kmin, k);
+    kmax = max(kmax, k);
+  }
+  const bool short_last = fused && a.short_last && (MODE == kDown || MODE == kDgradX) && kmin < kmax;
+  const long long my_s = (short_last && v < a.Ne && kc == kmin) ? my_t : 0;
   const long long it = wave_incl_scan64(my_t, lane), ic = wave_incl_scan64(my_c, lane);
-  const long long jf = wave_incl_scan64(my_f, lane);
-  if (lane == 63) { sh.wsum[w][0] = it; sh.wsum[w][1] = ic; sh.wsum[w][2] = jf; }
+  const long long jf = wave_incl_scan64(my_f, lane), is = wave_incl_scan64(my_s, lane);
+  if (lane == 63) { sh.wsum[w][0] = it; sh.wsum[w][1] = ic; sh.wsum[w][2] = jf; sh.wsum[w][3] = is; }
   __syncthreads();
-  long long bt = 0, bc = 0, bf = 0;
-  for (int ww = 0; ww < w; ++ww) { bt += sh.wsum[ww][0]; bc += sh.wsum[ww][1]; bf += sh.wsum[ww][2]; }
+  long long bt = 0, bc = 0, bf = 0, bs = 0;
+  for (int ww = 0; ww < w; ++ww) { bt += sh.wsum[ww][0]; bc += sh.wsum[ww][1]; bf += sh.wsum[ww][2]; bs += sh.wsum[ww][3]; }
   sh.tp[v] = bt + it - my_t;
   sh.cp[v] = bc + ic - my_c;
   sh.fp[v] = (int)(bf + jf - my_f);
-  if (v == 255) { sh.tp[256] = bt + it; sh.cp[256] = bc + ic; sh.fp[256] = (int)(bf + jf); }
+  sh.sp[v] = (int)(bs + is - my_s);
+  if (v == 255) { sh.tp[256] = bt + it; sh.cp[256] = bc + ic; sh.fp[256] = (int)(bf + jf); sh.sp[256] = (int)(bs + is); }
   __syncthreads();
   const int total = (int)sh.tp[256];
   const long long ctot = sh.cp[256];
@@ -235,29 +251,6 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
   // panels through that XCD's L2 (an expert's whole column of row blocks per column tile would
   // share the weight panel only).
   const int RB = a.band > 0 ? a.band : 1;
-  for (int t = v + 256 * part; t < total; t += 256 * nparts) {
-    const int ve = expert_of(t);
-    const int c = sh.cnt[ve], mt = (c + h - 1) / h, ntv = sh.nt[ve];
-    const int rel = t - (int)sh.tp[ve];
-    const int bnd = rel / (RB * ntv), rel2 = rel - bnd * RB * ntv;
-    const int rb = min(RB, mt - bnd * RB);
-    const int ni = rel2 / rb, mi = bnd * RB + rel2 % rb;
-    TileRec r;
-    r.e = sh.e[ve];
-    r.row_start = sh.row0[ve] + mi * h;
-    r.rows = min(h, c - mi * h);
-    r.n0 = ni * NCPT;
-    r.fam = sh.fp[ve] + mi;
-    // a down tile of the fused forward waits for the up tiles of its row block: one per 128
-    // hidden units of the expert's group (F holds the group's width in kDown)
-    // (kDown: F holds the group's width, the up tiles are 128 hidden units wide; kDgradX: F holds
-    // twice the width, the dH tiles are 256 hidden units wide)
-    r.need = !fused ? 0
-             : MODE == kDown ? (a.F[r.e / a.N] + kBN / 2 - 1) / (kBN / 2)
-             : MODE == kDgradX ? (a.F[r.e / a.N] / 2 + kBN - 1) / kBN : 0;
-    a.recs[t] = r;
-  }
-  if (part != 0) return;                     // (workgroup-uniform: everything below is part 0's)
   // XCD x starts at the first tile whose preceding cost is >= x/8 of the total.  The cost before
   // the tile at position rel of an expert follows from the band order in closed form, so the tile
   // is found by bisection once the expert is known.
@@ -296,10 +289,50 @@ __device__ __forceinline__ void build_schedule(const TileArgs& a, SchedShared& s
         if (tile > (int)sh.tp[ve + 1]) tile = (int)sh.tp[ve + 1];
       }
     }
-    a.hdr->xcd_begin[v] = tile;
+    if (part == 0) a.hdr->xcd_begin[v] = tile;
     sh.xb[v] = tile;
   }
   __syncthreads();
+  // tiles of the shortest reduction before tile t (t may be `total`)
+  auto short_before = [&](int t) {
+    if (t >= total) return sh.sp[256];
+    const int ve = expert_of(t);
+    return sh.sp[ve] + ((sh.sp[ve + 1] > sh.sp[ve]) ? t - (int)sh.tp[ve] : 0);
+  };
+  if (v <= kXcds) sh.xs[v] = short_last ? short_before(sh.xb[v]) : 0;
+  __syncthreads();
+  for (int t = v + 256 * part; t < total; t += 256 * nparts) {
+    const int ve = expert_of(t);
+    const int c = sh.cnt[ve], mt = (c + h - 1) / h, ntv = sh.nt[ve];
+    const int rel = t - (int)sh.tp[ve];
+    const int bnd = rel / (RB * ntv), rel2 = rel - bnd * RB * ntv;
+    const int rb = min(RB, mt - bnd * RB);
+    const int ni = rel2 / rb, mi = bnd * RB + rel2 % rb;
+    TileRec r;
+    r.e = sh.e[ve];
+    r.row_start = sh.row0[ve] + mi * h;
+    r.rows = min(h, c - mi * h);
+    r.n0 = ni * NCPT;
+    r.fam = sh.fp[ve] + mi;
+    // a down tile of the fused forward waits for the up tiles of its row block: one per 128
+    // hidden units of the expert's group (F holds the group's width in kDown)
+    // (kDown: F holds the group's width, the up tiles are 128 hidden units wide; kDgradX: F holds
+    // twice the width, the dH tiles are 256 hidden units wide)
+    r.need = !fused ? 0
+             : MODE == kDown ? (a.F[r.e / a.N] + kBN / 2 - 1) / (kBN / 2)
+             : MODE == kDgradX ? (a.F[r.e / a.N] / 2 + kBN - 1) / kBN : 0;
+    int pos = t;
+    if (short_last) {
+      int x = 0;                                   // the tile's XCD range
+      while (x + 1 < kXcds && t >= sh.xb[x + 1]) ++x;
+      const int sb = short_before(t) - sh.xs[x];   // short tiles of the range before t
+      const int nlong = (sh.xb[x + 1] - sh.xb[x]) - (sh.xs[x + 1] - sh.xs[x]);
+      const bool is_short = sh.sp[ve + 1] > sh.sp[ve];
+      pos = is_short ? sh.xb[x] + nlong + sb : sh.xb[x] + (t - sh.xb[x]) - sb;
+    }
+    a.recs[pos] = r;
+  }
+  if (part != 0) return;                     // (workgroup-uniform: everything below is part 0's)
   // tail[x]: the tiles at the end of range x that belong to an expert whose tiles continue in
   // range x+1.  The fused launch computes them first (see fused_phase).
   if (v < kXcds) {
@@ -1089,6 +1122,7 @@ void apply_options(TileArgs& t, const FfnOptions& o) {
   t.band = o.band > 0 ? o.band : 1;
   t.group_major = o.group_major != 0;
   t.steal = o.steal != 0;
+  t.short_last = o.short_last != 0;
   t.spin_limit = o.spin_limit == 0 ? kSpinLimit : o.spin_limit;
 }
 

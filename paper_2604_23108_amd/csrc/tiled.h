@@ -59,6 +59,7 @@ struct TileArgs {
   int force_rows;             // 0 = choose, else 64/128/192/256
   int group_major;            // visiting order of the experts (see visit())
   int steal;                  // fused launches: workgroups whose range is exhausted help the other ranges
+  int short_last;             // fused launches, second list: shortest reductions last inside every XCD range
   int band;                   // row blocks per band of the tile order inside an expert (>= 1)
   // --- fused forward (up and down tiles in one launch) ------------------------------------
   int* fam_done;              // [row blocks] finished up tiles per row block (zeroed by the schedule)
