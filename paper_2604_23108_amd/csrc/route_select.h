@@ -50,10 +50,99 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// Phase 2 when every expert has a lane (N_e <= 64) and the group size is a power of two, so that a
+// group is an aligned run of N lanes: everything stays in registers.  Group maximum and sum are
+// butterflies over the N lanes (every lane of the group ends with the same bits), the group gate's
+// top-K_g and the expert top-k are rank counts against values fetched from other lanes (readlane
+// for a position all lanes agree on, a lane permutation for the partners inside the group), the
+// ascending output slots come from a ballot and a population count, the normalisation from a
+// wave-wide butterfly.  No LDS beyond the logits row, no barriers.
+__device__ __forceinline__ float lane_value(float v, int uniform_lane) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), uniform_lane));
+}
+
+__device__ __forceinline__ void route_select_small(const RouteArgs& a, const float* lg, int t0, int BT, int NW,
+                                                   int w, int lane) {
+  const int klimit = (a.mode == MOHGE_SELECT_GLOBAL) ? a.Ke : a.Ke / a.Kg;
+  const int iters = (BT + NW - 1) / NW;
+  const float NEG_INF = -__builtin_inff();
+  const int e = lane, N = a.N;
+  const bool valid = e < a.Ne;
+  const int g = valid ? e / N : 0, gb = g * N, li = e - gb;
+  const float bias = (a.bias && valid) ? a.bias[e] : 0.f;
+  for (int it = 0; it < iters; ++it) {
+    const int tl = it * NW + w;
+    const int t = t0 + tl;
+    const bool live = (tl < BT) && (t < a.T);
+    const float* lrow = lg + (size_t)(live ? tl : 0) * a.NOpad;
+    // group gate: rank of each group's logit (ties to the lower id)
+    const float zg = (lane < a.Ng) ? lrow[lane] : NEG_INF;
+    const float z = valid ? lrow[a.Ng + e] + bias : NEG_INF;
+    int grank = 0;
+    for (int g2 = 0; g2 < a.Ng; ++g2) {
+      const float z2 = lane_value(zg, g2);
+      grank += (z2 > zg) || (z2 == zg && g2 < lane);
+    }
+    const bool gsel = (lane < a.Ng) && (grank < a.Kg);
+    const unsigned long long gmask = __ballot(gsel);
+    const float gs_mine = 1.f / (1.f + expf(-zg));            // lanes < N_g: GS of group `lane`
+    if (live && lane < a.Ng) {
+      if (a.gs) a.gs[(size_t)t * a.Ng + lane] = gs_mine;
+      if (gsel) {
+        // (a NaN logit could make more than K_g lanes qualify: never write past the row)
+        const int slot = __popcll(gmask & ((1ull << lane) - 1ull));
+        if (slot < a.Kg) a.gidx[(size_t)t * a.Kg + slot] = lane;
+      }
+    }
+    const bool in = valid && ((gmask >> g) & 1ull);
+    // softmax inside the group: maximum and sum over its N lanes
+    float mx = in ? z : NEG_INF;
+    for (int off = 1; off < N; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    const float ex = in ? expf(z - mx) : 0.f;
+    float sum = ex;
+    for (int off = 1; off < N; off <<= 1) sum += __shfl_xor(sum, off, 64);
+    const float e1 = in ? ex / sum : 0.f;
+    const float gs_g = __shfl(gs_mine, g, 64);                // GS of this lane's group
+    const float e2 = in ? e1 * gs_g : 0.f;
+    const float key = in ? ((a.mode == MOHGE_SELECT_GLOBAL) ? e2 : z) : NEG_INF;
+    // expert top-k: rank among the candidates (ties to the lower id)
+    int rank = 0;
+    if (a.mode == MOHGE_SELECT_GLOBAL) {
+      for (int e2i = 0; e2i < a.Ne; ++e2i) {
+        const float k2 = lane_value(key, e2i);
+        rank += (k2 > key) || (k2 == key && e2i < e);
+      }
+    } else {
+      for (int i = 1; i < N; ++i) {
+        const int other = gb + ((li + i) & (N - 1));
+        const float k2 = __shfl(key, other, 64);
+        rank += (k2 > key) || (k2 == key && other < e);
+      }
+    }
+    const bool sel = in && rank < klimit;
+    const unsigned long long smask = __ballot(sel);
+    const float D = wave_sum(sel ? e2 : 0.f);
+    if (live && valid) {
+      if (a.es1) a.es1[(size_t)t * a.Ne + e] = e1;
+      if (sel) {
+        const int slot = __popcll(smask & ((1ull << lane) - 1ull));
+        if (slot < a.Ke) {
+          a.eidx[(size_t)t * a.Ke + slot] = e;
+          a.gates[(size_t)t * a.Ke + slot] = e2 / D;
+        }
+      }
+    }
+  }
+}
+
 // Phase 2 for the BT tokens from t0 whose logits are in lg ([BT][NOpad], LDS); uses the first
 // LDS region for the per-wave rows.
 __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* smem, const float* lg,
                                              int t0, int BT, int NW, int w, int lane) {
+  if (a.Ne <= 64 && (a.N & (a.N - 1)) == 0) {
+    route_select_small(a, lg, t0, BT, NW, w, lane);
+    return;
+  }
   // ---- phase 2: one wavefront per token, lane <-> expert ---------------------
   float* zrow = reinterpret_cast<float*>(smem) + (size_t)w * 5 * a.Nepad;  // biased expert logits
   float* e1row = zrow + a.Nepad;                                            // ES'
