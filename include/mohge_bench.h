@@ -37,6 +37,9 @@ typedef struct mohge_ffn_options {
   int32_t steal;           /* 1: workgroups whose XCD range is exhausted draw from the other ranges */
   int32_t short_last;      /* 1: in the second list of a fused launch the tiles with the shortest
                               reduction come last inside every XCD range                          */
+  int32_t defer_signal;    /* 1: a tile of the first list is announced to its dependents from the
+                              workgroup's next tile (when that tile's first loads have landed, the
+                              stores before them are complete), 0: after waiting for its stores   */
   int32_t cycles_launch;   /* mohge_bench_expert_ffn_bwd: which fused launch fills `cycles`
                               (0 = dH / dX, 1 = the weight gradients)                              */
   void* cycles;            /* DEVICE or NULL: int64 counters of the fused launch, zeroed by the

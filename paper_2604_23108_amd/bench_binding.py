@@ -21,7 +21,7 @@ EXPORTS = ["mohge_ffn_default_options", "mohge_bench_cycles_bytes", "mohge_bench
 class _COptions(C.Structure):
     _fields_ = [("tile_rows_up", C.c_int32), ("tile_rows_down", C.c_int32), ("fused", C.c_int32),
                 ("spin_limit", C.c_int32), ("band_rows", C.c_int32), ("group_major", C.c_int32),
-                ("steal", C.c_int32), ("short_last", C.c_int32), ("cycles_launch", C.c_int32), ("cycles", C.c_void_p),
+                ("steal", C.c_int32), ("short_last", C.c_int32), ("defer_signal", C.c_int32), ("cycles_launch", C.c_int32), ("cycles", C.c_void_p),
                 ("cycles_bytes", C.c_size_t)]
 
 

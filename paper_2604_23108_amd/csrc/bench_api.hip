@@ -34,6 +34,7 @@ static int to_options(const mohge_ffn_options* in, const LayerDesc& L, FfnOption
   o->group_major = in->group_major != 0;
   o->steal = in->steal != 0;
   o->short_last = in->short_last != 0;
+  o->defer_signal = in->defer_signal != 0;
   if (in->cycles) {
     if (((uintptr_t)in->cycles) & 15) { set_error("mohge_ffn_options: cycles is not 16-byte aligned"); return MOHGE_EALIGN; }
     if (in->cycles_bytes < mohge_bench_cycles_bytes()) {
@@ -69,6 +70,7 @@ void mohge_ffn_default_options(mohge_ffn_options* o) {
   o->group_major = d.group_major;
   o->steal = d.steal;
   o->short_last = d.short_last;
+  o->defer_signal = d.defer_signal;
 }
 
 size_t mohge_bench_cycles_bytes(void) {

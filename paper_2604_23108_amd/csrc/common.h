@@ -36,6 +36,8 @@ struct FfnOptions {
   int group_major = 0;        // 1: experts visited group by group, 0: by all-size sets
   int steal = 1;              // workgroups whose XCD range is exhausted help the other ranges
   int short_last = 1;         // second list of a fused launch: the tiles with the shortest reduction last in every XCD range
+  int defer_signal = 1;       // first list of a fused launch: a finished tile is announced once the workgroup's next tile
+                              //   has its first stage (whose arrival proves the stores complete) instead of after a wait
   long long* cycles = nullptr;  // DEVICE, optional: per-workgroup clock counters of the fused launch
   int cycles_launch = 0;      // backward: which of the two fused launches fills `cycles` (0 = dH/dX, 1 = weight gradients)
 };

@@ -481,7 +481,7 @@ __device__ __forceinline__ void swiglu_bwd8(const uint4 dh, const uint4 pv, cons
 
 template <int MODE, int NACT>
 __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, unsigned char* lds,
-                                         int lane, int w) {
+                                         int lane, int w, int* signal = nullptr) {
   constexpr bool UP = is_up(MODE);
   constexpr bool TRA = tr_a(MODE), TRB = tr_b(MODE);   // operand read by transposing LDS reads
   constexpr bool WG = MODE == kWgrad;
@@ -698,6 +698,13 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   }
   __builtin_amdgcn_s_barrier();
   MOHGE_PIN();
+  // Fused launches: the counter of the row block that this workgroup's PREVIOUS tile completed.
+  // Vector memory operations of a wave complete in issue order, so a wave whose first-stage loads
+  // have landed has seen all its earlier stores complete, and the barrier above makes that true
+  // of every wave: the previous tile's rows are in memory.  (Waiting for those stores at the end of
+  // the previous tile instead cost a memory round trip with nothing to overlap it.)
+  if (signal != nullptr && threadIdx.x == 0)
+    __hip_atomic_fetch_add(signal, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   PROBE_T(2);
   bf16x8 f0[NR], f1[NR];
 #pragma unroll
@@ -1007,6 +1014,7 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
   // the other ranges in turn, so the launch ends when all tiles are done rather than when the
   // slowest range is.  A stolen tile is an ordinary draw from that range's counter, so the
   // argument about waiting below holds for it as well.
+  int* pending = nullptr;      // ROLE 1: counter of the row block of the tile just finished, not yet added to
   for (int k = 0; k < (a.steal ? kXcds : 1); ++k) {
     const int cur = (home + k) % kXcds;
     int tbeg = a.hdr->xcd_begin[cur], tend = a.hdr->xcd_begin[cur + 1];
@@ -1074,22 +1082,35 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
           // the rows this tile depends on never became complete: its output is written as NaN, so
           // that nothing downstream can take it for a result (the header flag says why)
           poison_tile(a, rec);
-        } else if (nact == 4) run_tile<MODE, 4>(a, rec, lds, lane, w);
-        else if (nact == 3) run_tile<MODE, 3>(a, rec, lds, lane, w);
-        else if (nact == 2) run_tile<MODE, 2>(a, rec, lds, lane, w);
-        else run_tile<MODE, 1>(a, rec, lds, lane, w);
-        if constexpr (ROLE == 1)
-          asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // this wave's output stores are done
+        } else if (nact == 4) run_tile<MODE, 4>(a, rec, lds, lane, w, pending);
+        else if (nact == 3) run_tile<MODE, 3>(a, rec, lds, lane, w, pending);
+        else if (nact == 2) run_tile<MODE, 2>(a, rec, lds, lane, w, pending);
+        else run_tile<MODE, 1>(a, rec, lds, lane, w, pending);
+        // ROLE 1: this tile's row-block counter is added to by the workgroup's next tile once its
+        // first stage has landed, or after the loop (a tile of ROLE 1 is never one that gave up);
+        // without `defer_signal` at once, after a wait for this tile's stores
+        if constexpr (ROLE == 1) {
+          pending = &a.fam_done[rec.fam];
+          if (!a.defer_signal) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
       }
-      __syncthreads();       // every wave is past its epilogue (and, up tiles, past its stores)
+      __syncthreads();       // every wave is past its epilogue
       if (threadIdx.x == 0) {
-        if (ROLE == 1 && ok)
-          __hip_atomic_fetch_add(&a.fam_done[rec.fam], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (ROLE == 1 && !a.defer_signal && pending != nullptr)
+          __hip_atomic_fetch_add(pending, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         *reinterpret_cast<volatile int*>(lds + kBcastOffset) = t_next;
       }
+      if (ROLE == 1 && !a.defer_signal) pending = nullptr;
       __syncthreads();
       pos = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
     }
+  }
+  if constexpr (ROLE == 1) {
+    // the last tile of this workgroup in this list: wait for its stores, then add to its counter
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (pending != nullptr && threadIdx.x == 0)
+      __hip_atomic_fetch_add(pending, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
 }
 
@@ -1123,6 +1144,7 @@ void apply_options(TileArgs& t, const FfnOptions& o) {
   t.group_major = o.group_major != 0;
   t.steal = o.steal != 0;
   t.short_last = o.short_last != 0;
+  t.defer_signal = o.defer_signal != 0;
   t.spin_limit = o.spin_limit == 0 ? kSpinLimit : o.spin_limit;
 }
 

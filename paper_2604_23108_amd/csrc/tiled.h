@@ -60,6 +60,7 @@ struct TileArgs {
   int group_major;            // visiting order of the experts (see visit())
   int steal;                  // fused launches: workgroups whose range is exhausted help the other ranges
   int short_last;             // fused launches, second list: shortest reductions last inside every XCD range
+  int defer_signal;           // fused launches, first list: a tile's row-block counter is added to in the next tile's prologue
   int band;                   // row blocks per band of the tile order inside an expert (>= 1)
   // --- fused forward (up and down tiles in one launch) ------------------------------------
   int* fam_done;              // [row blocks] finished up tiles per row block (zeroed by the schedule)
