@@ -21,11 +21,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_MFMA_BF16 = 2.5e15     # FLOP/s, dense bf16, MI355X
+PEAK_VALU_F32 = 157.3e12    # FLOP/s, fp32 vector ALU (256 CUs x 4 SIMDs x 64 lanes x 2 FLOP at 2.4 GHz)
 PEAK_HBM = 8.0e12           # B/s
 HEADLINE = "large_prefill_skewed"
 # (workload, backward) pairs reported under all_configs next to the headline
-OTHERS = (("mid_prefill", False), ("decode", False), ("training", False), ("training", True),
-          ("paper_14b", False))
+OTHERS = (("tiny_f32", False), ("mid_prefill", False), ("decode", False), ("training", False),
+          ("training", True), ("paper_14b", False))
 
 KERNEL_SOURCES = ("ffn_tiled.hip", "tiled.h", "ffn_skinny.hip", "skinny.h", "ffn.hip", "common.h")
 
@@ -359,6 +360,11 @@ def measure(args, name, backward, torch, M, BB, steps, warmup, full):
         tag = name + ("/fp8" if args.fp8_weights else "/mxfp4")
         roof = {"kernel": kname + " (one call of the quantised-weight entry point)", "bound": "hbm",
                 "achieved": ach / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s", "frac": ach / PEAK_HBM}
+    elif w.dtype != "bf16":
+        # the fp32 path (correctness configuration): plain fused multiply-adds on the vector ALUs
+        ach = (flops_up + flops_down) / (call_ms["ffn"] * 1e-3)
+        roof = {"kernel": "ffn_f32_kernel<up> + <down> (one mohge_expert_ffn call)", "bound": "alu",
+                "achieved": ach / 1e12, "peak": PEAK_VALU_F32 / 1e12, "unit": "TFLOP/s", "frac": ach / PEAK_VALU_F32}
     elif decode:
         ach = bytes_up / (call_ms["ffn_up"] * 1e-3)
         roof = {"kernel": "ffn_skinny_kernel<up> (one mohge_expert_ffn_up call)", "bound": "hbm",
@@ -523,7 +529,8 @@ def main():
             o = measure(args, oname, bwd, torch, M, BB, max(10, args.steps // 2), max(3, args.warmup // 2), False)
             ow = o["w"]
             allc[oname + ("_backward" if bwd else "")] = {
-                "T": ow.T, "ms_per_step": round(o["ms_events"], 5), "tokens_per_s": ow.T / (o["ms_events"] * 1e-3),
+                "T": ow.T, "dtype": "bf16" if ow.dtype == "bf16" else "f32",
+                "ms_per_step": round(o["ms_events"], 5), "tokens_per_s": ow.T / (o["ms_events"] * 1e-3),
                 "roofline": {k: o["roof"][k] for k in ("kernel", "bound", "achieved", "peak", "unit", "frac", "traffic", "traffic_source")},
                 "call_ms": o["parts"]["call_ms"],
                 **({"ffn_bwd_frac_mfma": o["parts"]["ffn_bwd_frac_mfma"]} if bwd else {})}
