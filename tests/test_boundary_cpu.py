@@ -197,3 +197,29 @@ def test_bench_refuses_more_than_one_gpu_and_graft_entry_has_both_functions():
     assert p.returncode != 0 and "one GPU" in (p.stderr + p.stdout)
     src = open(os.path.join(root, "__graft_entry__.py")).read()
     assert "def build(" in src and "def smoke(" in src
+
+
+def test_decode_layer_entry_point_checks_its_arguments():
+    """mohge_decode_layer: sizes and refusals that need no GPU."""
+    dec = M.Config(T=32, d=4096, n_groups=4, experts_per_group=16, d_ff=(768, 1024, 1536, 2048), k_groups=2, k_experts=4)
+    P = 32 * 4
+    ws = M.mohge_workspace_size(dec, M.CALL_DECODE_LAYER)
+    ctl = M.mohge_decode_layer_ctl_bytes(dec)
+    # hidden activations, y_perm, the fp64 partial logits, the index arrays; counters first
+    assert P * 2048 * 2 + P * 4096 * 2 <= ws <= P * 2048 * 2 + P * 4096 * 2 + (1 << 20)
+    assert 0 < ctl <= 64 * 1024 and ctl % 256 == 0 and ctl < ws
+    lib = M.lib()
+    assert lib.mohge_decode_layer(dec.ref(), *([None] * 13)) == -2
+    assert "NULL" in M.mohge_last_error()
+    # more than 32 tokens, fp32 layers, too many pairs: no workspace size, and the call refuses
+    for bad in (M.Config(T=33, d=4096, n_groups=4, experts_per_group=16, d_ff=(768, 1024, 1536, 2048), k_groups=2, k_experts=4),
+                M.Config(T=16, d=128, n_groups=3, experts_per_group=4, d_ff=(64, 128, 256), k_groups=2, k_experts=2, dtype=M.F32),
+                M.Config(T=32, d=128, n_groups=16, experts_per_group=16, d_ff=(64,) * 16, k_groups=16, k_experts=128,
+                         select_mode=M.SELECT_GLOBAL)):
+        assert M.mohge_workspace_size(bad, M.CALL_DECODE_LAYER) == 0
+        assert M.mohge_decode_layer_ctl_bytes(bad) == 0
+        assert lib.mohge_decode_layer(bad.ref(), *([None] * 13)) == -1
+        assert "mohge_decode_layer serves" in M.mohge_last_error()
+    # an empty call is sized like a call of one token (nothing is launched)
+    empty = M.Config(T=0, d=4096, n_groups=4, experts_per_group=16, d_ff=(768, 1024, 1536, 2048), k_groups=2, k_experts=4)
+    assert M.mohge_workspace_size(empty, M.CALL_DECODE_LAYER) > 0
