@@ -34,7 +34,9 @@ typedef struct mohge_ffn_options {
                               reports MOHGE_ETIMEOUT)                                              */
   int32_t band_rows;       /* row blocks per band of the tile order inside an expert (0 = default) */
   int32_t group_major;     /* 1: experts visited group by group (widest first); 0: by all-size sets */
-  int32_t steal;           /* 1: workgroups whose XCD range is exhausted draw from the other ranges */
+  int32_t steal;           /* workgroups whose XCD range is exhausted draw from the other ranges:
+                              bit 0 in the first list of a fused launch, bit 1 in the second (and
+                              only where a list has at least four tiles per compute unit)          */
   int32_t short_last;      /* 1: in the second list of a fused launch the tiles with the shortest
                               reduction come last inside every XCD range                          */
   int32_t defer_signal;    /* 1: a tile of the first list is announced to its dependents from the

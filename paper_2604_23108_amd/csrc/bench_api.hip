@@ -32,7 +32,7 @@ static int to_options(const mohge_ffn_options* in, const LayerDesc& L, FfnOption
   o->spin_limit = in->spin_limit;
   if (in->band_rows > 0) o->band = in->band_rows;
   o->group_major = in->group_major != 0;
-  o->steal = in->steal != 0;
+  o->steal = in->steal & 3;
   o->short_last = in->short_last != 0;
   o->defer_signal = in->defer_signal != 0;
   if (in->cycles) {

@@ -34,7 +34,8 @@ struct FfnOptions {
   int spin_limit = 0;         // polls a dependent tile waits: 0 = default (about a second), < 0 = give up at once
   int band = 4;               // row blocks per band of the tile order inside an expert
   int group_major = 0;        // 1: experts visited group by group, 0: by all-size sets
-  int steal = 1;              // workgroups whose XCD range is exhausted help the other ranges
+  int steal = 2;              // workgroups whose XCD range is exhausted help the other ranges: bit 0 in the first
+                              //   list of a fused launch, bit 1 in the second
   int short_last = 1;         // second list of a fused launch: the tiles with the shortest reduction last in every XCD range
   int defer_signal = 1;       // first list of a fused launch: a finished tile is announced once the workgroup's next tile
                               //   has its first stage (whose arrival proves the stores complete) instead of after a wait

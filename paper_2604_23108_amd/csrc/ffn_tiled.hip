@@ -1011,12 +1011,46 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
   // both ranges wait for them), then to the rest in list order.  Down phase: list order, the order
   // in which the up tiles they depend on were handed out.
   // A workgroup serves its own XCD's range until the counter runs past its end and then (steal)
-  // the other ranges in turn, so the launch ends when all tiles are done rather than when the
-  // slowest range is.  A stolen tile is an ordinary draw from that range's counter, so the
+  // whichever other range still has tiles, so the launch ends when all tiles are done rather than
+  // when the slowest range is.  (The number of rounds is bounded for form's sake: every round but
+  // the last exhausts a range, and counters only grow.)  A stolen tile is an ordinary draw from that range's counter, so the
   // argument about waiting below holds for it as well.
   int* pending = nullptr;      // ROLE 1: counter of the row block of the tile just finished, not yet added to
-  for (int k = 0; k < (a.steal ? kXcds : 1); ++k) {
-    const int cur = (home + k) % kXcds;
+  int cur = home;
+  for (int round = 0; round <= 4 * kXcds; ++round) {
+    if (round > 0) {
+      // Own range exhausted: look at the counters of all other ranges at once (one memory round
+      // trip: looking at them one after the other cost a round trip each at the moment when the
+      // workgroup has nothing to do, 15-30 us where the whole launch takes 230) and go to the first
+      // one, in ring order, that still has tiles.  (A counter is looked at before it is drawn
+      // from, so that an exhausted one is left alone.)
+      // (only where a compute unit sees several tiles of this list: with fewer, what a stolen tile
+      // saves at the end does not pay for fetching its operands into another XCD's L2)
+      if (!(a.steal & (PHASE == 0 ? 1 : 2)) || total < 4 * a.ncu) break;
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        int c[kXcds];
+#pragma unroll
+        for (int x = 0; x < kXcds; ++x)
+          c[x] = __hip_atomic_load(&a.hdr->counters[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int pick = -1;
+#pragma unroll
+        for (int k = kXcds - 1; k >= 1; --k) {
+          const int x = (home + k) % kXcds;
+          int b = a.hdr->xcd_begin[x], e = a.hdr->xcd_begin[x + 1];
+          if (b < 0) b = 0;
+          if (e > total) e = total;
+          int cx = 0;
+#pragma unroll
+          for (int y = 0; y < kXcds; ++y) cx = y == x ? c[y] : cx;
+          if (cx < e - b) pick = x;
+        }
+        *reinterpret_cast<volatile int*>(lds + kBcastOffset) = pick;
+      }
+      __syncthreads();
+      cur = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
+      if (cur < 0 || cur >= kXcds) break;
+    }
     int tbeg = a.hdr->xcd_begin[cur], tend = a.hdr->xcd_begin[cur + 1];
     if (tbeg < 0) tbeg = 0;
     if (tend > total) tend = total;
@@ -1024,13 +1058,7 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
     int ntail = PHASE == 0 ? a.hdr->tail[cur] : 0;
     ntail = ntail < 0 ? 0 : (ntail > n ? n : ntail);
     __syncthreads();         // everybody has read the last hand-over word
-    if (threadIdx.x == 0) {
-      int p0 = n;
-      // (a foreign range is looked at before it is drawn from, so that an exhausted counter is left alone)
-      if (k == 0 || __hip_atomic_load(&a.hdr->counters[cur], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < n)
-        p0 = atomicAdd(&a.hdr->counters[cur], 1);
-      *reinterpret_cast<volatile int*>(lds + kBcastOffset) = p0;
-    }
+    if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(lds + kBcastOffset) = atomicAdd(&a.hdr->counters[cur], 1);
     __syncthreads();
     int pos = __builtin_amdgcn_readfirstlane(*reinterpret_cast<volatile int*>(lds + kBcastOffset));
     while (pos >= 0 && pos < n) {
@@ -1142,7 +1170,7 @@ __global__ void __launch_bounds__(Shape<M0>::THREADS) ffn_fused_kernel(const Til
 void apply_options(TileArgs& t, const FfnOptions& o) {
   t.band = o.band > 0 ? o.band : 1;
   t.group_major = o.group_major != 0;
-  t.steal = o.steal != 0;
+  t.steal = o.steal;
   t.short_last = o.short_last != 0;
   t.defer_signal = o.defer_signal != 0;
   t.spin_limit = o.spin_limit == 0 ? kSpinLimit : o.spin_limit;
