@@ -50,26 +50,37 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// Phase 2 when every expert has a lane (N_e <= 64) and the group size is a power of two, so that a
-// group is an aligned run of N lanes: everything stays in registers.  Group maximum and sum are
-// butterflies over the N lanes (every lane of the group ends with the same bits), the group gate's
-// top-K_g and the expert top-k are rank counts against values fetched from other lanes (readlane
-// for a position all lanes agree on, a lane permutation for the partners inside the group), the
-// ascending output slots come from a ballot and a population count, the normalisation from a
-// wave-wide butterfly.  No LDS beyond the logits row, no barriers.
+// Phase 2 when the group size is a power of two (at most 64), so that a group is an aligned run
+// of N lanes: lane l holds experts l, l + 64, ... (NJ of them; NJ = 1 when every expert has a lane
+// of its own) and everything stays in registers.  Group maximum and sum are butterflies over the N
+// lanes (every lane of the group ends with the same bits), the group gate's top-K_g and the expert
+// top-k are rank counts against values fetched from other lanes (readlane for a position all lanes
+// agree on, a lane permutation for the partners inside the group), the ascending output slots
+// come from ballots and population counts, the normalisation from a wave-wide butterfly.  No LDS
+// beyond the logits row, no barriers.
 __device__ __forceinline__ float lane_value(float v, int uniform_lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), uniform_lane));
 }
 
+template <int NJ>
 __device__ __forceinline__ void route_select_small(const RouteArgs& a, const float* lg, int t0, int BT, int NW,
                                                    int w, int lane) {
   const int klimit = (a.mode == MOHGE_SELECT_GLOBAL) ? a.Ke : a.Ke / a.Kg;
   const int iters = (BT + NW - 1) / NW;
   const float NEG_INF = -__builtin_inff();
-  const int e = lane, N = a.N;
-  const bool valid = e < a.Ne;
-  const int g = valid ? e / N : 0, gb = g * N, li = e - gb;
-  const float bias = (a.bias && valid) ? a.bias[e] : 0.f;
+  const int N = a.N;
+  const int li = lane & (N - 1);             // position inside the group (groups are aligned lane runs)
+  const int lb = lane - li;                  // first lane of the group
+  int e[NJ], g[NJ];
+  bool valid[NJ];
+  float bias[NJ];
+#pragma unroll
+  for (int j = 0; j < NJ; ++j) {
+    e[j] = lane + 64 * j;
+    valid[j] = e[j] < a.Ne;
+    g[j] = valid[j] ? e[j] / N : 0;
+    bias[j] = (a.bias && valid[j]) ? a.bias[e[j]] : 0.f;
+  }
   for (int it = 0; it < iters; ++it) {
     const int tl = it * NW + w;
     const int t = t0 + tl;
@@ -77,7 +88,6 @@ __device__ __forceinline__ void route_select_small(const RouteArgs& a, const flo
     const float* lrow = lg + (size_t)(live ? tl : 0) * a.NOpad;
     // group gate: rank of each group's logit (ties to the lower id)
     const float zg = (lane < a.Ng) ? lrow[lane] : NEG_INF;
-    const float z = valid ? lrow[a.Ng + e] + bias : NEG_INF;
     int grank = 0;
     for (int g2 = 0; g2 < a.Ng; ++g2) {
       const float z2 = lane_value(zg, g2);
@@ -94,43 +104,76 @@ __device__ __forceinline__ void route_select_small(const RouteArgs& a, const flo
         if (slot < a.Kg) a.gidx[(size_t)t * a.Kg + slot] = lane;
       }
     }
-    const bool in = valid && ((gmask >> g) & 1ull);
-    // softmax inside the group: maximum and sum over its N lanes
-    float mx = in ? z : NEG_INF;
-    for (int off = 1; off < N; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
-    const float ex = in ? expf(z - mx) : 0.f;
-    float sum = ex;
-    for (int off = 1; off < N; off <<= 1) sum += __shfl_xor(sum, off, 64);
-    const float e1 = in ? ex / sum : 0.f;
-    const float gs_g = __shfl(gs_mine, g, 64);                // GS of this lane's group
-    const float e2 = in ? e1 * gs_g : 0.f;
-    const float key = in ? ((a.mode == MOHGE_SELECT_GLOBAL) ? e2 : z) : NEG_INF;
-    // expert top-k: rank among the candidates (ties to the lower id)
-    int rank = 0;
-    if (a.mode == MOHGE_SELECT_GLOBAL) {
-      for (int e2i = 0; e2i < a.Ne; ++e2i) {
-        const float k2 = lane_value(key, e2i);
-        rank += (k2 > key) || (k2 == key && e2i < e);
-      }
-    } else {
-      for (int i = 1; i < N; ++i) {
-        const int other = gb + ((li + i) & (N - 1));
-        const float k2 = __shfl(key, other, 64);
-        rank += (k2 > key) || (k2 == key && other < e);
-      }
+    float z[NJ], e1[NJ], e2[NJ], key[NJ];
+    bool in[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      z[j] = valid[j] ? lrow[a.Ng + e[j]] + bias[j] : NEG_INF;
+      in[j] = valid[j] && ((gmask >> g[j]) & 1ull);
+      // softmax inside the group: maximum and sum over its N lanes
+      float mx = in[j] ? z[j] : NEG_INF;
+      for (int off = 1; off < N; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+      const float ex = in[j] ? expf(z[j] - mx) : 0.f;
+      float sum = ex;
+      for (int off = 1; off < N; off <<= 1) sum += __shfl_xor(sum, off, 64);
+      e1[j] = in[j] ? ex / sum : 0.f;
+      const float gs_g = __shfl(gs_mine, g[j], 64);           // GS of this expert's group
+      e2[j] = in[j] ? e1[j] * gs_g : 0.f;
+      key[j] = in[j] ? ((a.mode == MOHGE_SELECT_GLOBAL) ? e2[j] : z[j]) : NEG_INF;
     }
-    const bool sel = in && rank < klimit;
-    const unsigned long long smask = __ballot(sel);
-    const float D = wave_sum(sel ? e2 : 0.f);
-    if (live && valid) {
-      if (a.es1) a.es1[(size_t)t * a.Ne + e] = e1;
-      if (sel) {
-        const int slot = __popcll(smask & ((1ull << lane) - 1ull));
-        if (slot < a.Ke) {
-          a.eidx[(size_t)t * a.Ke + slot] = e;
-          a.gates[(size_t)t * a.Ke + slot] = e2 / D;
+    // expert top-k: rank among the candidates (ties to the lower id)
+    int rank[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) rank[j] = 0;
+    if (a.mode == MOHGE_SELECT_GLOBAL) {
+      // the candidates are the members of the kept groups only (the mask is the same in every lane)
+      for (unsigned long long m = gmask; m != 0ull; m &= m - 1ull) {
+        const int e0 = (int)__builtin_ctzll(m) * N;            // first expert of a kept group
+        if (e0 >= a.Ne) break;
+        const int jj = e0 >> 6, l0 = e0 & 63;
+        float kj = key[0];
+#pragma unroll
+        for (int j = 1; j < NJ; ++j) kj = jj == j ? key[j] : kj;
+        for (int i = 0; i < N; ++i) {
+          const float k2 = lane_value(kj, l0 + i);
+          const int e2i = e0 + i;
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) rank[j] += (k2 > key[j]) || (k2 == key[j] && e2i < e[j]);
         }
       }
+    } else {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        for (int i = 1; i < N; ++i) {
+          const int other = lb + ((li + i) & (N - 1));        // lane of another member of the group
+          const float k2 = __shfl(key[j], other, 64);
+          rank[j] += (k2 > key[j]) || (k2 == key[j] && other < lane);
+        }
+    }
+    bool sel[NJ];
+    unsigned long long smask[NJ];
+    float dsum = 0.f;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      sel[j] = in[j] && rank[j] < klimit;
+      smask[j] = __ballot(sel[j]);
+      if (sel[j]) dsum += e2[j];
+    }
+    const float D = wave_sum(dsum);
+    int base = 0;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      if (live && valid[j]) {
+        if (a.es1) a.es1[(size_t)t * a.Ne + e[j]] = e1[j];
+        if (sel[j]) {
+          const int slot = base + __popcll(smask[j] & ((1ull << lane) - 1ull));
+          if (slot < a.Ke) {
+            a.eidx[(size_t)t * a.Ke + slot] = e[j];
+            a.gates[(size_t)t * a.Ke + slot] = e2[j] / D;
+          }
+        }
+      }
+      base += __popcll(smask[j]);
     }
   }
 }
@@ -139,8 +182,10 @@ __device__ __forceinline__ void route_select_small(const RouteArgs& a, const flo
 // LDS region for the per-wave rows.
 __device__ __forceinline__ void route_select(const RouteArgs& a, unsigned char* smem, const float* lg,
                                              int t0, int BT, int NW, int w, int lane) {
-  if (a.Ne <= 64 && (a.N & (a.N - 1)) == 0) {
-    route_select_small(a, lg, t0, BT, NW, w, lane);
+  if ((a.N & (a.N - 1)) == 0 && a.N <= 64) {
+    if (a.Ne <= 64) route_select_small<1>(a, lg, t0, BT, NW, w, lane);
+    else if (a.Ne <= 128) route_select_small<2>(a, lg, t0, BT, NW, w, lane);
+    else route_select_small<4>(a, lg, t0, BT, NW, w, lane);
     return;
   }
   // ---- phase 2: one wavefront per token, lane <-> expert ---------------------
