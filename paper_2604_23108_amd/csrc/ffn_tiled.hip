@@ -62,6 +62,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kStagesA = 2, kStagesB = 3;   // 32 KB parts: 2 token + 3 weight = all 160 KB of LDS
 constexpr int kWGM = 2, kWGN = 4;
+// LDS words for the hand-over between the tiles of a persistent workgroup: beyond the epilogue patches
+// (one per wave, at most 32 rows x 144 bytes), inside a stage buffer that is dead between two tiles
+constexpr int kHandoverOffset = (kWGM * kWGN * 32 * 144 + 4095) / 4096 * 4096;
 constexpr int kTileCost = 18;          // cost model of the schedule: fixed part of a tile's stage, in 64-row units
 
 // gate and up rows share a tile in the two up-projection modes
@@ -77,7 +80,8 @@ struct Shape {
   static constexpr int NCOLS_PER_TILE = is_up(MODE) ? kBN / 2 : kBN;
   // wave grid of the workgroup: 2 x 4 waves with 128 x 64 wave tiles (2 x 2 waves with
   // 128 x 128 wave tiles read a third fewer fragments per MFMA but measured slower in every
-  // mode, the weight gradients with their transposing reads included)
+  // mode, the weight gradients with their transposing reads included; 4 x 4 waves with 64 x 64
+  // wave tiles leave 128 registers a lane, spill, and measured 10 % slower)
   static constexpr int WGM = kWGM, WGN = kWGN;
   static constexpr int THREADS = 64 * WGM * WGN;
 };
@@ -497,8 +501,9 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   constexpr int B_LOADS = BN * CH / NT;
   // wave-wide load j of the token part fills tile rows [64j, 64j+64): only NACT of them matter
   // (token-major operands: a part is 64 tokens x 256 features, all of it is loaded)
-  constexpr int A_LOADS = TRA ? BM * CH / NT : NACT * (64 / (NWAVES * RPL));
-  static_assert(64 % (NWAVES * RPL) == 0 && B_LOADS * NWAVES * RPL == BN, "whole wave-wide loads");
+  // (NACT active fragments per wave cover the tile rows [0, NACT * 32 * WGM))
+  constexpr int A_LOADS = TRA ? BM * CH / NT : NACT * (32 * WGM / (NWAVES * RPL));
+  static_assert((32 * WGM) % (NWAVES * RPL) == 0 && B_LOADS * NWAVES * RPL == BN, "whole wave-wide loads");
   constexpr int PART = BM * ROWB;                 // 32 KB: one token part or one weight part
   constexpr int NM = NACT * NF;     // MFMAs per k-step
   constexpr int NR = NACT + NF;     // fragment reads per k-step
@@ -909,6 +914,22 @@ __device__ __forceinline__ void run_tile(const TileArgs& a, const TileRec rec, u
   }
 }
 
+// The instantiation of run_tile for the tile's row count: a wave's k-th fragment serves the tile
+// rows [32 * WGM * k, 32 * WGM * (k + 1)) together with the other wave rows.
+template <int MODE>
+__device__ __forceinline__ void run_tile_rows(const TileArgs& a, const TileRec& rec, unsigned char* lds, int lane,
+                                              int w, int* signal) {
+  constexpr int UNIT = 32 * Shape<MODE>::WGM, MF = kBM / UNIT;
+  static_assert(MF == 2 || MF == 4, "two or four token fragments per wave");
+  const int nact = (rec.rows + UNIT - 1) / UNIT;
+  if constexpr (MF == 4) {
+    if (nact == 4) { run_tile<MODE, 4>(a, rec, lds, lane, w, signal); return; }
+    if (nact == 3) { run_tile<MODE, 3>(a, rec, lds, lane, w, signal); return; }
+  }
+  if (nact >= 2) run_tile<MODE, 2>(a, rec, lds, lane, w, signal);
+  else run_tile<MODE, 1>(a, rec, lds, lane, w, signal);
+}
+
 // Persistent tile kernel: workgroup b serves XCD b % 8.  Its first tile is fixed (range start
 // + b / 8); further tiles are handed out by an atomic counter per range, so a workgroup that
 // drew cheap tiles simply takes more of them.  The counter is read one tile ahead (the
@@ -920,7 +941,7 @@ __global__ void __launch_bounds__(Shape<MODE>::THREADS) ffn_tile_kernel(const Ti
   extern __shared__ __align__(1024) unsigned char lds[];
   // LDS word for the hand-over: beyond the epilogue patches, inside a stage buffer that is
   // dead between a tile's last barrier and the first barrier of the next tile
-  constexpr int kBcastOffset = 40960;
+  constexpr int kBcastOffset = kHandoverOffset;
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
@@ -951,11 +972,7 @@ __global__ void __launch_bounds__(Shape<MODE>::THREADS) ffn_tile_kernel(const Ti
       }
     }
     if (ok) {
-      const int nact = (rec.rows + 63) / 64;
-      if (nact == 4) run_tile<MODE, 4>(a, rec, lds, lane, w);
-      else if (nact == 3) run_tile<MODE, 3>(a, rec, lds, lane, w);
-      else if (nact == 2) run_tile<MODE, 2>(a, rec, lds, lane, w);
-      else run_tile<MODE, 1>(a, rec, lds, lane, w);
+      run_tile_rows<MODE>(a, rec, lds, lane, w, nullptr);
     }
     __syncthreads();       // every wave is past its epilogue (and past reading the old word)
     if (threadIdx.x == 0) *reinterpret_cast<volatile int*>(lds + kBcastOffset) = t_next;
@@ -1003,7 +1020,7 @@ __device__ __forceinline__ void poison_tile(const TileArgs& a, const TileRec& re
 template <int MODE, int ROLE>
 __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* lds, int lane, int w) {
   constexpr int PHASE = ROLE == 1 ? 0 : 1;
-  constexpr int kBcastOffset = 40960;
+  constexpr int kBcastOffset = kHandoverOffset;
   const int home = blockIdx.x % kXcds;
   const int total = a.hdr->total;
   // The counter of a range hands out positions 0, 1, 2, ...  Up phase: the positions map to the
@@ -1084,7 +1101,6 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
         }
       }
       if (ok) {
-        const int nact = (rec.rows + 63) / 64;
         bool gave_up = false;
         if constexpr (ROLE == 2) {
           if (threadIdx.x == 0) {
@@ -1110,10 +1126,9 @@ __device__ __forceinline__ void fused_phase(const TileArgs& a, unsigned char* ld
           // the rows this tile depends on never became complete: its output is written as NaN, so
           // that nothing downstream can take it for a result (the header flag says why)
           poison_tile(a, rec);
-        } else if (nact == 4) run_tile<MODE, 4>(a, rec, lds, lane, w, pending);
-        else if (nact == 3) run_tile<MODE, 3>(a, rec, lds, lane, w, pending);
-        else if (nact == 2) run_tile<MODE, 2>(a, rec, lds, lane, w, pending);
-        else run_tile<MODE, 1>(a, rec, lds, lane, w, pending);
+        } else {
+          run_tile_rows<MODE>(a, rec, lds, lane, w, pending);
+        }
         // ROLE 1: this tile's row-block counter is added to by the workgroup's next tile once its
         // first stage has landed, or after the loop (a tile of ROLE 1 is never one that gave up);
         // without `defer_signal` at once, after a wait for this tile's stores
