@@ -378,6 +378,15 @@ def measure(args, name, backward, torch, M, BB, steps, warmup, full):
                           ("mohge_expert_ffn_train" if backward else "mohge_expert_ffn"),
                 "bound": "mfma", "achieved": ach / 1e12, "peak": PEAK_MFMA_BF16 / 1e12, "unit": "TFLOP/s",
                 "frac": ach / PEAK_MFMA_BF16}
+        # The bound of a launch is the resource whose peak allows it the least: with few rows per expert
+        # (the paper's layer shapes: every weight byte is used by one row block) moving the algorithmic
+        # bytes at the HBM peak takes longer than the multiply-adds at the matrix-core peak.
+        t_mfma, t_hbm = (flops_up + flops_down) / PEAK_MFMA_BF16, (bytes_up + bytes_down) / PEAK_HBM
+        if t_hbm > t_mfma and not backward:
+            ach_b = (bytes_up + bytes_down) / (call_ms[key] * 1e-3)
+            roof.update({"bound": "hbm", "achieved": ach_b / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                         "frac": ach_b / PEAK_HBM, "frac_of_mfma_peak": ach / PEAK_MFMA_BF16})
+        roof["least_time_ms"] = {"mfma": round(t_mfma * 1e3, 5), "hbm": round(t_hbm * 1e3, 5)}
     roof["traffic"], roof["traffic_source"] = measured_traffic(tag + ("_backward" if backward else ""))
     parts = {
         "step_ms_median": round(step_ms[len(step_ms) // 2], 5), "step_ms_min": round(step_ms[0], 5),

@@ -64,7 +64,8 @@ constexpr int kStagesA = 2, kStagesB = 3;   // 32 KB parts: 2 token + 3 weight =
 constexpr int kWGM = 2, kWGN = 4;
 // LDS words for the hand-over between the tiles of a persistent workgroup: beyond the epilogue patches
 // (one per wave, at most 32 rows x 144 bytes), inside a stage buffer that is dead between two tiles
-constexpr int kHandoverOffset = (kWGM * kWGN * 32 * 144 + 4095) / 4096 * 4096;
+constexpr int kHandoverOffset = (kWGM * kWGN * 32 * 144 / 4096 + 1) * 4096;
+static_assert(kHandoverOffset == 40960 && kHandoverOffset + 8 <= 2 * kBM * kBK * 2, "inside the second token part");
 constexpr int kTileCost = 18;          // cost model of the schedule: fixed part of a tile's stage, in 64-row units
 
 // gate and up rows share a tile in the two up-projection modes
